@@ -1,0 +1,179 @@
+/*
+ * nvfp4.h -- C ABI of the MI355X (gfx950) FP4 quantized linear layer.
+ *
+ * Implements the hot path of "FP4 All the Way: Fully Quantized Training of
+ * LLMs": the block quantization operation Q (Sec. 3: E2M1 elements in blocks
+ * that share one E4M3 or E8M0 scale; Sec. 3.2: round-to-nearest or stochastic
+ * rounding) and the three GEMMs of every linear layer (Eqs. 4-6).
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The library
+ *     never allocates, frees or keeps them.  Scratch memory comes in through a
+ *     `workspace` argument whose size the matching *_workspace_bytes() call
+ *     returns; the workspace may be reused by the next call on the same stream.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued asynchronously; no call synchronizes.
+ *   - Arguments are validated on the host before anything is launched; a bad
+ *     argument returns an error code and enqueues nothing.
+ *   - Tensor pointers must be 16-byte aligned, leading dimensions must keep
+ *     every row 16-byte aligned.
+ *   - Non-finite inputs give unspecified codes (no error).
+ *   - Row-major everywhere.  "codes" hold two 4-bit E2M1 codes per byte, the
+ *     element with the even index along the blocked axis in the low nibble.
+ *     Code bits: sign | exponent(2) | mantissa(1); magnitudes
+ *     {0, .5, 1, 1.5, 2, 3, 4, 6}.  "scales" hold one byte per block: E4M3
+ *     (bias 7, finite-only, sign bit never set) or E8M0 (2^(byte-127)).
+ *   - Value of a quantized element: (-1)^sign * magnitude * scale * g, where g
+ *     is the per-tensor fp32 scale (1 when the format has none).
+ */
+#ifndef NVFP4_H
+#define NVFP4_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    NVFP4_OK = 0,
+    NVFP4_EINVAL = 1,       /* null pointer, unknown enum value, bad axis or flag */
+    NVFP4_ESHAPE = 2,       /* non-positive size, or blocked axis not a multiple of the block */
+    NVFP4_EALIGN = 3,       /* pointer or leading dimension breaks 16-byte alignment */
+    NVFP4_EUNSUPPORTED = 4, /* format combination the library does not implement */
+    NVFP4_EWORKSPACE = 5,   /* workspace missing or too small */
+    NVFP4_EHIP = 6          /* the HIP runtime reported a launch error */
+} nvfp4_status;
+
+typedef enum { NVFP4_RTN = 0, NVFP4_SR = 1 } nvfp4_rounding;
+typedef enum { NVFP4_F32 = 0, NVFP4_BF16 = 1 } nvfp4_dtype;
+typedef enum { NVFP4_SCALE_E4M3 = 0, NVFP4_SCALE_E8M0 = 1 } nvfp4_scale_fmt;
+
+/* Block format (Sec. 3, Table 1).  NVFP4 = {16, E4M3, 1}; MXFP4 = {32, E8M0, 0};
+ * the block-size study of Sec. 3.1 / Fig. 2 adds {32|64|128, E4M3, 1}.
+ * block must be 16, 32, 64 or 128.  E8M0 scales take no tensor scale. */
+typedef struct {
+    int32_t block;
+    int32_t scale;        /* nvfp4_scale_fmt */
+    int32_t tensor_scale; /* 1: per-tensor fp32 scale g; 0: g = 1 */
+} nvfp4_format;
+
+/* nvfp4_quantize flags */
+#define NVFP4_PRESET_TSCALE 1u /* read g from *tensor_scale instead of computing it */
+
+const char *nvfp4_status_string(nvfp4_status s);
+
+/* Output sizes in bytes for a logical [rows, cols] tensor. */
+size_t nvfp4_codes_bytes(int64_t rows, int64_t cols);
+size_t nvfp4_scales_bytes(int64_t rows, int64_t cols, int axis, const nvfp4_format *f);
+
+/* Scratch sizes in bytes. */
+size_t nvfp4_quantize_workspace_bytes(int64_t rows, int64_t cols);
+size_t nvfp4_linear_fwd_workspace_bytes(int64_t M, int64_t N, int64_t K, const nvfp4_format *f);
+size_t nvfp4_linear_bwd_workspace_bytes(int64_t M, int64_t N, int64_t K, const nvfp4_format *f);
+
+/*
+ * Per-tensor scale g (not in the paper; it fixes only the element and block
+ * scale formats): g = max|x| / (6 * 448), so that the block holding the
+ * largest element gets the largest E4M3 scale.  g = 1 for an all-zero tensor;
+ * g is never below 2^-117.  Writes g to tensor_scale[0] (device fp32).
+ * x: [rows, cols] with leading dimension ld (elements), dtype dt.
+ * workspace: >= nvfp4_quantize_workspace_bytes(rows, cols).
+ */
+nvfp4_status nvfp4_tensor_scale(const void *x, nvfp4_dtype dt, int64_t rows, int64_t cols,
+                                int64_t ld, float *tensor_scale, void *workspace,
+                                size_t workspace_bytes, void *stream);
+
+/*
+ * Q of Eqs. 1-6: block-quantize x [rows, cols] (leading dimension ld).
+ * Blocks of f->block elements run along `axis`, which must be the contraction
+ * axis of the GEMM the result feeds:
+ *   axis 1 (along a row):    codes [rows, cols/2], scales [rows, cols/block]
+ *   axis 0 (down a column):  codes [cols, rows/2], scales [cols, rows/block]
+ *                            -- the output is the quantized TRANSPOSE, which is
+ *                            how Eqs. 2-3 consume W^T and a^T.
+ * The blocked length (cols for axis 1, rows for axis 0) must be a multiple of
+ * the block size.
+ *
+ * Per block (E4M3 scales): a = max|x|; scale byte = E4M3_RNE_sat(a * (1/(6g)));
+ * with s its value and d = s*g, element magnitudes are min(|x * (1/d)|, 6)
+ * rounded to the E2M1 grid; a zero scale byte gives zero magnitudes.
+ * Per block (E8M0 scales): byte = clamp(floor(log2 a) - 2 + 127, 0, 254),
+ * elements x * 2^(127-byte), same clamp and rounding.
+ * All of this in fp32, one rounding per operation.
+ *
+ * rounding (Sec. 3.2, Eqs. 4-6): NVFP4_RTN = nearest grid value, ties to the
+ * even code; NVFP4_SR = round up with probability equal to the relative
+ * distance from the lower neighbour, drawn from 16 bits of Philox4x32-10 with
+ * key = seed and counter = (row-major index of the element in x) >> 3; the
+ * draw does not depend on `axis`.  `seed` is ignored for RTN.
+ *
+ * tensor_scale: device fp32[1].  With f->tensor_scale == 0 it is written with
+ * 1.  Otherwise it is computed from x and written, unless flags has
+ * NVFP4_PRESET_TSCALE, in which case it is read (and used as max(g, 2^-117)).
+ * workspace: >= nvfp4_quantize_workspace_bytes(rows, cols); may be NULL with
+ * NVFP4_PRESET_TSCALE or a format without tensor scale.
+ */
+nvfp4_status nvfp4_quantize(const void *x, nvfp4_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                            int axis, nvfp4_rounding rounding, uint64_t seed,
+                            const nvfp4_format *f, uint8_t *codes, uint8_t *scales,
+                            float *tensor_scale, uint32_t flags, void *workspace,
+                            size_t workspace_bytes, void *stream);
+
+/*
+ * Block-scaled GEMM shared by Eqs. 4-6, operands stored with the contraction
+ * axis contiguous ("NT"):
+ *   out[i, j] = gA * gB * sum_k a[i, k] * b[j, k],   a = magnitude*scale of A, same for B
+ * A_codes [M, K/2], A_scales [M, K/block]; B_codes [N, K/2], B_scales [N, K/block].
+ * tensor_scales: device fp32[2] = {gA, gB}.
+ * out: [M, N] of out_dt with leading dimension ldc.  Products are exact;
+ * accumulation is fp32.
+ * K must be a multiple of the block and of 32; M, N >= 1.
+ */
+nvfp4_status nvfp4_gemm(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
+                        const uint8_t *A_codes, const uint8_t *A_scales, const uint8_t *B_codes,
+                        const uint8_t *B_scales, const float *tensor_scales, void *out,
+                        nvfp4_dtype out_dt, int64_t ldc, void *stream);
+
+/*
+ * Forward GEMM, Eq. 4:  Y[M, N] = Q_RtN(X[M, K]) * Q_RtN(W[N, K])^T, blocks along K.
+ * X, W dense row-major of in_dt; Y dense row-major of out_dt.
+ */
+nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, int64_t N,
+                              int64_t K, nvfp4_dtype in_dt, nvfp4_dtype out_dt,
+                              const nvfp4_format *f, void *workspace, size_t workspace_bytes,
+                              void *stream);
+
+/*
+ * Backward and update GEMMs, Eqs. 5-6, for upstream gradient dY[M, N]:
+ *   dX[M, K] = Q_SR(dY) * Q_RtN(W^T)^T     blocks along N; SR stream `seed`
+ *   dW[N, K] = Q_SR(dY^T) * Q_SR(X^T)^T    blocks along M; SR streams seed+1 (dY), seed+2 (X)
+ * Either of dX, dW may be NULL to skip that GEMM.
+ */
+nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void *dX, void *dW,
+                              int64_t M, int64_t N, int64_t K, nvfp4_dtype in_dt,
+                              nvfp4_dtype out_dt, const nvfp4_format *f, uint64_t seed,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Host-side evaluations of the scalar steps the kernels use (the same inline
+ * functions, compiled for the host).  They let a CPU-only test sweep the
+ * rounding logic against an independent implementation; they touch no GPU.
+ */
+uint8_t nvfp4_host_e4m3_encode(float r);            /* r >= 0 -> scale byte */
+float nvfp4_host_e4m3_decode(uint8_t byte);
+uint8_t nvfp4_host_round_rtn(float m);              /* m in [0, 6] -> magnitude code */
+uint8_t nvfp4_host_round_sr(float m, uint32_t u16); /* m in [0, 6], 16 random bits */
+void nvfp4_host_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
+uint32_t nvfp4_host_sr_bits(uint64_t seed, uint64_t element_index);
+uint8_t nvfp4_host_e8m0_encode(float a);            /* a > 0 -> shared-exponent byte */
+/* array forms: n inputs -> n outputs (host pointers) */
+void nvfp4_host_e4m3_encode_n(const float *r, int64_t n, uint8_t *out);
+void nvfp4_host_round_rtn_n(const float *m, int64_t n, uint8_t *out);
+void nvfp4_host_round_sr_n(const float *m, const uint32_t *u16, int64_t n, uint8_t *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NVFP4_H */

@@ -1,0 +1,239 @@
+"""ctypes binding of libnvfp4.so: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU, passes their
+device pointers and the current HIP stream to the C ABI declared in
+``include/nvfp4.h`` and returns torch tensors it allocated for the outputs.
+No arithmetic of the method happens in Python, and there is no fallback: if
+the library is missing, importing this module fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libnvfp4.so")
+
+RTN, SR = 0, 1
+F32, BF16 = 0, 1
+SCALE_E4M3, SCALE_E8M0 = 0, 1
+PRESET_TSCALE = 1
+
+OK, EINVAL, ESHAPE, EALIGN, EUNSUPPORTED, EWORKSPACE, EHIP = range(7)
+
+
+class _Format(C.Structure):
+    _fields_ = [("block", C.c_int32), ("scale", C.c_int32), ("tensor_scale", C.c_int32)]
+
+
+@dataclass(frozen=True)
+class Format:
+    block: int = 16
+    scale: int = SCALE_E4M3
+    tensor_scale: int = 1
+
+    def c(self) -> _Format:
+        return _Format(self.block, self.scale, self.tensor_scale)
+
+
+NVFP4 = Format(16, SCALE_E4M3, 1)
+MXFP4 = Format(32, SCALE_E8M0, 0)
+
+
+class Nvfp4Error(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {lib.nvfp4_status_string(code).decode()} (status {code})")
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    L = C.CDLL(LIB_PATH)
+    vp, i64, u64, u32, sz, ci = C.c_void_p, C.c_int64, C.c_uint64, C.c_uint32, C.c_size_t, C.c_int
+    fp = C.POINTER(_Format)
+    L.nvfp4_status_string.restype = C.c_char_p
+    L.nvfp4_status_string.argtypes = [ci]
+    L.nvfp4_codes_bytes.restype = sz
+    L.nvfp4_codes_bytes.argtypes = [i64, i64]
+    L.nvfp4_scales_bytes.restype = sz
+    L.nvfp4_scales_bytes.argtypes = [i64, i64, ci, fp]
+    L.nvfp4_quantize_workspace_bytes.restype = sz
+    L.nvfp4_quantize_workspace_bytes.argtypes = [i64, i64]
+    L.nvfp4_linear_fwd_workspace_bytes.restype = sz
+    L.nvfp4_linear_fwd_workspace_bytes.argtypes = [i64, i64, i64, fp]
+    L.nvfp4_linear_bwd_workspace_bytes.restype = sz
+    L.nvfp4_linear_bwd_workspace_bytes.argtypes = [i64, i64, i64, fp]
+    L.nvfp4_tensor_scale.restype = ci
+    L.nvfp4_tensor_scale.argtypes = [vp, ci, i64, i64, i64, vp, vp, sz, vp]
+    L.nvfp4_quantize.restype = ci
+    L.nvfp4_quantize.argtypes = [vp, ci, i64, i64, i64, ci, ci, u64, fp, vp, vp, vp, u32, vp, sz, vp]
+    L.nvfp4_gemm.restype = ci
+    L.nvfp4_gemm.argtypes = [i64, i64, i64, fp, vp, vp, vp, vp, vp, vp, ci, i64, vp]
+    L.nvfp4_linear_fwd.restype = ci
+    L.nvfp4_linear_fwd.argtypes = [vp, vp, vp, i64, i64, i64, ci, ci, fp, vp, sz, vp]
+    L.nvfp4_linear_bwd.restype = ci
+    L.nvfp4_linear_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, fp, u64, vp, sz, vp]
+    # host probes
+    L.nvfp4_host_e4m3_encode.restype = C.c_uint8
+    L.nvfp4_host_e4m3_encode.argtypes = [C.c_float]
+    L.nvfp4_host_e4m3_decode.restype = C.c_float
+    L.nvfp4_host_e4m3_decode.argtypes = [C.c_uint8]
+    L.nvfp4_host_round_rtn.restype = C.c_uint8
+    L.nvfp4_host_round_rtn.argtypes = [C.c_float]
+    L.nvfp4_host_round_sr.restype = C.c_uint8
+    L.nvfp4_host_round_sr.argtypes = [C.c_float, u32]
+    L.nvfp4_host_philox4x32_10.restype = None
+    L.nvfp4_host_philox4x32_10.argtypes = [vp, vp, vp]
+    L.nvfp4_host_sr_bits.restype = u32
+    L.nvfp4_host_sr_bits.argtypes = [u64, u64]
+    L.nvfp4_host_e8m0_encode.restype = C.c_uint8
+    L.nvfp4_host_e8m0_encode.argtypes = [C.c_float]
+    L.nvfp4_host_e4m3_encode_n.restype = None
+    L.nvfp4_host_e4m3_encode_n.argtypes = [vp, i64, vp]
+    L.nvfp4_host_round_rtn_n.restype = None
+    L.nvfp4_host_round_rtn_n.argtypes = [vp, i64, vp]
+    L.nvfp4_host_round_sr_n.restype = None
+    L.nvfp4_host_round_sr_n.argtypes = [vp, vp, i64, vp]
+    return L
+
+
+lib = _load()
+
+EXPORTS = (
+    "nvfp4_status_string", "nvfp4_codes_bytes", "nvfp4_scales_bytes",
+    "nvfp4_quantize_workspace_bytes", "nvfp4_linear_fwd_workspace_bytes",
+    "nvfp4_linear_bwd_workspace_bytes", "nvfp4_tensor_scale", "nvfp4_quantize", "nvfp4_gemm",
+    "nvfp4_linear_fwd", "nvfp4_linear_bwd", "nvfp4_host_e4m3_encode", "nvfp4_host_e4m3_decode",
+    "nvfp4_host_round_rtn", "nvfp4_host_round_sr", "nvfp4_host_philox4x32_10",
+    "nvfp4_host_sr_bits", "nvfp4_host_e8m0_encode", "nvfp4_host_e4m3_encode_n",
+    "nvfp4_host_round_rtn_n", "nvfp4_host_round_sr_n",
+)
+
+
+def _dtype_tag(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _torch_dtype(tag: int) -> torch.dtype:
+    return torch.float32 if tag == F32 else torch.bfloat16
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(code: int, where: str) -> None:
+    if code != OK:
+        raise Nvfp4Error(code, where)
+
+
+def _require_gpu(*ts: torch.Tensor) -> None:
+    for t in ts:
+        if t is not None and not t.is_cuda:
+            raise ValueError("tensors must live on the GPU")
+
+
+def tensor_scale(x: torch.Tensor) -> torch.Tensor:
+    """nvfp4_tensor_scale: g = max|x| / 2688 as a device fp32[1] tensor."""
+    _require_gpu(x)
+    assert x.dim() == 2 and x.stride(1) == 1
+    g = torch.empty(1, dtype=torch.float32, device=x.device)
+    ws = torch.empty(lib.nvfp4_quantize_workspace_bytes(*x.shape), dtype=torch.uint8, device=x.device)
+    _check(lib.nvfp4_tensor_scale(x.data_ptr(), _dtype_tag(x), x.shape[0], x.shape[1], x.stride(0),
+                                  g.data_ptr(), ws.data_ptr(), ws.numel(), _stream()), "nvfp4_tensor_scale")
+    return g
+
+
+def quantize(x: torch.Tensor, axis: int = 1, rounding: int = RTN, seed: int = 0,
+             fmt: Format = NVFP4, tensor_scale: torch.Tensor | None = None, out=None):
+    """nvfp4_quantize -> (codes u8 [outer, inner/2], scales u8 [outer, inner/block], g fp32[1]).
+
+    `tensor_scale` presets g (device fp32[1]); it is then used and returned as is.
+    `out` = (codes, scales, g) reuses caller-provided output tensors.
+    """
+    _require_gpu(x, tensor_scale)
+    assert x.dim() == 2 and (x.stride(1) == 1 or x.shape[1] <= 1)
+    rows, cols = x.shape
+    ld = x.stride(0) if rows > 1 else cols
+    outer, inner = (rows, cols) if axis == 1 else (cols, rows)
+    f = fmt.c()
+    if out is None:
+        codes = torch.empty((outer, inner // 2), dtype=torch.uint8, device=x.device)
+        scales = torch.empty((outer, inner // fmt.block), dtype=torch.uint8, device=x.device)
+        g = torch.empty(1, dtype=torch.float32, device=x.device) if tensor_scale is None else tensor_scale
+    else:
+        codes, scales, g = out
+        if tensor_scale is not None:
+            g = tensor_scale
+    flags = PRESET_TSCALE if tensor_scale is not None else 0
+    ws = torch.empty(lib.nvfp4_quantize_workspace_bytes(rows, cols), dtype=torch.uint8, device=x.device)
+    _check(lib.nvfp4_quantize(x.data_ptr(), _dtype_tag(x), rows, cols, ld, axis, rounding, seed,
+                              C.byref(f), codes.data_ptr(), scales.data_ptr(), g.data_ptr(), flags,
+                              ws.data_ptr(), ws.numel(), _stream()), "nvfp4_quantize")
+    return codes, scales, g
+
+
+def gemm(A, B, fmt: Format = NVFP4, out_dtype: torch.dtype = torch.float32, out=None) -> torch.Tensor:
+    """nvfp4_gemm: A = (codes [M,K/2], scales, g[1]), B = (codes [N,K/2], scales, g[1]) -> [M, N]."""
+    (ac, asc, ga), (bc, bsc, gb) = A, B
+    _require_gpu(ac, asc, ga, bc, bsc, gb)
+    M, N, K = ac.shape[0], bc.shape[0], ac.shape[1] * 2
+    ts = torch.cat([ga.reshape(1), gb.reshape(1)])
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype, device=ac.device)
+    f = fmt.c()
+    _check(lib.nvfp4_gemm(M, N, K, C.byref(f), ac.data_ptr(), asc.data_ptr(), bc.data_ptr(),
+                          bsc.data_ptr(), ts.data_ptr(), out.data_ptr(), _dtype_tag(out),
+                          out.stride(0), _stream()), "nvfp4_gemm")
+    return out
+
+
+def linear_fwd(X: torch.Tensor, W: torch.Tensor, fmt: Format = NVFP4,
+               out_dtype: torch.dtype = torch.float32, workspace: torch.Tensor | None = None,
+               out: torch.Tensor | None = None) -> torch.Tensor:
+    """nvfp4_linear_fwd (Eq. 4): Y[M,N] = Q_RtN(X[M,K]) Q_RtN(W[N,K])^T."""
+    _require_gpu(X, W)
+    assert X.is_contiguous() and W.is_contiguous() and X.dtype == W.dtype
+    M, K = X.shape
+    N = W.shape[0]
+    f = fmt.c()
+    if workspace is None:
+        workspace = torch.empty(lib.nvfp4_linear_fwd_workspace_bytes(M, N, K, C.byref(f)),
+                                dtype=torch.uint8, device=X.device)
+    Y = torch.empty((M, N), dtype=out_dtype, device=X.device) if out is None else out
+    _check(lib.nvfp4_linear_fwd(X.data_ptr(), W.data_ptr(), Y.data_ptr(), M, N, K, _dtype_tag(X),
+                                _dtype_tag(Y), C.byref(f), workspace.data_ptr(), workspace.numel(),
+                                _stream()), "nvfp4_linear_fwd")
+    return Y
+
+
+def linear_bwd(dY: torch.Tensor, X: torch.Tensor, W: torch.Tensor, seed: int, fmt: Format = NVFP4,
+               out_dtype: torch.dtype = torch.float32, workspace: torch.Tensor | None = None,
+               out=None):
+    """nvfp4_linear_bwd (Eqs. 5-6) -> (dX [M,K], dW [N,K])."""
+    _require_gpu(dY, X, W)
+    assert dY.is_contiguous() and X.is_contiguous() and W.is_contiguous()
+    M, N = dY.shape
+    K = X.shape[1]
+    f = fmt.c()
+    if workspace is None:
+        workspace = torch.empty(lib.nvfp4_linear_bwd_workspace_bytes(M, N, K, C.byref(f)),
+                                dtype=torch.uint8, device=dY.device)
+    if out is None:
+        dX = torch.empty((M, K), dtype=out_dtype, device=dY.device)
+        dW = torch.empty((N, K), dtype=out_dtype, device=dY.device)
+    else:
+        dX, dW = out
+    _check(lib.nvfp4_linear_bwd(dY.data_ptr(), X.data_ptr(), W.data_ptr(), dX.data_ptr(),
+                                dW.data_ptr(), M, N, K, _dtype_tag(dY), _dtype_tag(dX), C.byref(f),
+                                seed, workspace.data_ptr(), workspace.numel(), _stream()),
+           "nvfp4_linear_bwd")
+    return dX, dW

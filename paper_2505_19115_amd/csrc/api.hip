@@ -1,0 +1,345 @@
+// C ABI of the library (declared in include/nvfp4.h): argument validation on the host,
+// workspace layout, and the composition of kernels into the fused linear entries.
+#include <stdlib.h>
+#include <string.h>
+
+#include "kernels.h"
+#include "nvfp4_math.h"
+
+using namespace nvfp4;
+
+namespace {
+
+constexpr size_t WS_ALIGN = 256;
+constexpr size_t WS_HEADER = 256;  // tensor scales and maxima live at the front of a workspace
+
+inline size_t align_up(size_t n) { return (n + WS_ALIGN - 1) / WS_ALIGN * WS_ALIGN; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t elem_size(int dt) { return dt == NVFP4_BF16 ? 2 : 4; }
+inline bool valid_dtype(int dt) { return dt == NVFP4_F32 || dt == NVFP4_BF16; }
+
+nvfp4_status check_format(const nvfp4_format *f)
+{
+    if (!f) return NVFP4_EINVAL;
+    if (f->scale != NVFP4_SCALE_E4M3 && f->scale != NVFP4_SCALE_E8M0) return NVFP4_EINVAL;
+    if (f->tensor_scale != 0 && f->tensor_scale != 1) return NVFP4_EINVAL;
+    if (f->block != 16 && f->block != 32 && f->block != 64 && f->block != 128) return NVFP4_EUNSUPPORTED;
+    if (f->scale == NVFP4_SCALE_E8M0 && f->tensor_scale) return NVFP4_EUNSUPPORTED;
+    return NVFP4_OK;
+}
+
+// The gfx950 convert instruction is the default for round-to-nearest; the integer/fp32
+// formulation (the one the host probes evaluate) can be forced for cross-checking.
+bool use_hw_convert()
+{
+    const char *e = getenv("NVFP4_SOFT_CONVERT");
+    return !(e && e[0] == '1');
+}
+
+nvfp4_status check_tensor(const void *x, int dt, int64_t rows, int64_t cols, int64_t ld)
+{
+    if (!x) return NVFP4_EINVAL;
+    if (!valid_dtype(dt)) return NVFP4_EINVAL;
+    if (rows < 0 || cols < 0 || ld < cols) return NVFP4_ESHAPE;
+    if (!aligned16(x) || (ld * elem_size(dt)) % 16 != 0) return NVFP4_EALIGN;
+    return NVFP4_OK;
+}
+
+struct QuantPlan {
+    const void *x;
+    int dt;
+    int64_t rows, cols, ld;
+    int axis, rounding;
+    uint64_t seed;
+    uint8_t *codes, *scales;
+    const float *g_src;
+    float *g_out;
+    int g_mode;
+};
+
+hipError_t run_quantize(const QuantPlan &q, const nvfp4_format *f, hipStream_t st)
+{
+    QuantArgs a;
+    a.x = q.x;
+    a.rows = q.rows;
+    a.cols = q.cols;
+    a.ld = q.ld;
+    a.codes = q.codes;
+    a.scales = q.scales;
+    a.g_src = q.g_src;
+    a.g_out = q.g_out;
+    a.g_mode = q.g_mode;
+    a.seed = q.seed;
+    return launch_quantize(a, q.dt, q.axis, q.rounding, f->block, f->scale, use_hw_convert(), st);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *nvfp4_status_string(nvfp4_status s)
+{
+    switch (s) {
+    case NVFP4_OK: return "ok";
+    case NVFP4_EINVAL: return "invalid argument";
+    case NVFP4_ESHAPE: return "invalid shape";
+    case NVFP4_EALIGN: return "misaligned pointer or leading dimension";
+    case NVFP4_EUNSUPPORTED: return "unsupported format";
+    case NVFP4_EWORKSPACE: return "workspace missing or too small";
+    case NVFP4_EHIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+size_t nvfp4_codes_bytes(int64_t rows, int64_t cols)
+{
+    if (rows <= 0 || cols <= 0) return 0;
+    return (size_t)rows * (size_t)cols / 2;
+}
+
+size_t nvfp4_scales_bytes(int64_t rows, int64_t cols, int axis, const nvfp4_format *f)
+{
+    if (rows <= 0 || cols <= 0 || check_format(f) != NVFP4_OK || (axis != 0 && axis != 1)) return 0;
+    return axis == 1 ? (size_t)rows * (size_t)(cols / f->block) : (size_t)cols * (size_t)(rows / f->block);
+}
+
+size_t nvfp4_quantize_workspace_bytes(int64_t, int64_t) { return WS_HEADER; }
+
+size_t nvfp4_linear_fwd_workspace_bytes(int64_t M, int64_t N, int64_t K, const nvfp4_format *f)
+{
+    if (M <= 0 || N <= 0 || K <= 0 || check_format(f) != NVFP4_OK) return 0;
+    return WS_HEADER + align_up((size_t)M * K / 2) + align_up((size_t)M * (K / f->block)) +
+           align_up((size_t)N * K / 2) + align_up((size_t)N * (K / f->block));
+}
+
+size_t nvfp4_linear_bwd_workspace_bytes(int64_t M, int64_t N, int64_t K, const nvfp4_format *f)
+{
+    if (M <= 0 || N <= 0 || K <= 0 || check_format(f) != NVFP4_OK) return 0;
+    const size_t B = (size_t)f->block;
+    return WS_HEADER +
+           align_up((size_t)M * N / 2) + align_up((size_t)M * (N / B)) +  // dY blocked along N
+           align_up((size_t)K * N / 2) + align_up((size_t)K * (N / B)) +  // W^T blocked along N
+           align_up((size_t)N * M / 2) + align_up((size_t)N * (M / B)) +  // dY^T blocked along M
+           align_up((size_t)K * M / 2) + align_up((size_t)K * (M / B));   // X^T blocked along M
+}
+
+nvfp4_status nvfp4_tensor_scale(const void *x, nvfp4_dtype dt, int64_t rows, int64_t cols,
+                                int64_t ld, float *tensor_scale, void *workspace,
+                                size_t workspace_bytes, void *stream)
+{
+    nvfp4_status s = check_tensor(x, dt, rows, cols, ld);
+    if (s != NVFP4_OK) return s;
+    if (!tensor_scale) return NVFP4_EINVAL;
+    if (!workspace || workspace_bytes < WS_HEADER) return NVFP4_EWORKSPACE;
+    if (!aligned16(workspace)) return NVFP4_EALIGN;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    uint32_t *bits = reinterpret_cast<uint32_t *>(workspace);
+    if (launch_tensor_amax(x, dt, rows, cols, ld, bits, st) != hipSuccess) return NVFP4_EHIP;
+    if (launch_finalize_tensor_scale(bits, tensor_scale, st) != hipSuccess) return NVFP4_EHIP;
+    return NVFP4_OK;
+}
+
+nvfp4_status nvfp4_quantize(const void *x, nvfp4_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                            int axis, nvfp4_rounding rounding, uint64_t seed,
+                            const nvfp4_format *f, uint8_t *codes, uint8_t *scales,
+                            float *tensor_scale, uint32_t flags, void *workspace,
+                            size_t workspace_bytes, void *stream)
+{
+    nvfp4_status s = check_format(f);
+    if (s != NVFP4_OK) return s;
+    s = check_tensor(x, dt, rows, cols, ld);
+    if (s != NVFP4_OK) return s;
+    if (!codes || !scales || !tensor_scale) return NVFP4_EINVAL;
+    if (axis != 0 && axis != 1) return NVFP4_EINVAL;
+    if (rounding != NVFP4_RTN && rounding != NVFP4_SR) return NVFP4_EINVAL;
+    if (flags & ~NVFP4_PRESET_TSCALE) return NVFP4_EINVAL;
+    const int64_t inner = axis == 1 ? cols : rows;
+    if (inner % f->block != 0) return NVFP4_ESHAPE;
+    if (!aligned16(codes) || !aligned16(scales)) return NVFP4_EALIGN;
+    const bool preset = (flags & NVFP4_PRESET_TSCALE) != 0;
+    const bool need_amax = f->tensor_scale && !preset;
+    if (need_amax) {
+        if (!workspace || workspace_bytes < WS_HEADER) return NVFP4_EWORKSPACE;
+        if (!aligned16(workspace)) return NVFP4_EALIGN;
+    }
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+
+    QuantPlan q{x, dt, rows, cols, ld, axis, rounding, seed, codes, scales, tensor_scale, tensor_scale, G_NONE};
+    if (f->tensor_scale) {
+        if (preset) {
+            q.g_mode = G_PRESET;
+        } else {
+            uint32_t *bits = reinterpret_cast<uint32_t *>(workspace);
+            if (launch_tensor_amax(x, dt, rows, cols, ld, bits, st) != hipSuccess) return NVFP4_EHIP;
+            q.g_src = reinterpret_cast<const float *>(bits);
+            q.g_mode = G_FROM_AMAX;
+        }
+    }
+    if (rows == 0 || cols == 0) {
+        // nothing to encode; still report the scale an empty tensor gets (1, or the preset)
+        if (q.g_mode == G_FROM_AMAX)
+            return launch_finalize_tensor_scale(reinterpret_cast<const uint32_t *>(q.g_src), tensor_scale, st) == hipSuccess
+                       ? NVFP4_OK
+                       : NVFP4_EHIP;
+        return NVFP4_OK;
+    }
+    return run_quantize(q, f, st) == hipSuccess ? NVFP4_OK : NVFP4_EHIP;
+}
+
+nvfp4_status nvfp4_gemm(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
+                        const uint8_t *A_codes, const uint8_t *A_scales, const uint8_t *B_codes,
+                        const uint8_t *B_scales, const float *tensor_scales, void *out,
+                        nvfp4_dtype out_dt, int64_t ldc, void *stream)
+{
+    nvfp4_status s = check_format(f);
+    if (s != NVFP4_OK) return s;
+    if (!A_codes || !A_scales || !B_codes || !B_scales || !tensor_scales || !out) return NVFP4_EINVAL;
+    if (!valid_dtype(out_dt)) return NVFP4_EINVAL;
+    if (M < 0 || N < 0 || K <= 0 || ldc < N) return NVFP4_ESHAPE;
+    if (K % f->block != 0 || K % 32 != 0) return NVFP4_ESHAPE;
+    if (!aligned16(A_codes) || !aligned16(A_scales) || !aligned16(B_codes) || !aligned16(B_scales) ||
+        !aligned16(out))
+        return NVFP4_EALIGN;
+    if (f->scale != NVFP4_SCALE_E4M3) return NVFP4_EUNSUPPORTED;
+    if (M == 0 || N == 0) return NVFP4_OK;
+    GemmArgs g{M, N, K, A_codes, A_scales, B_codes, B_scales, tensor_scales, out, ldc};
+    return launch_gemm(g, f->block, f->scale, out_dt, reinterpret_cast<hipStream_t>(stream)) == hipSuccess
+               ? NVFP4_OK
+               : NVFP4_EHIP;
+}
+
+nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, int64_t N,
+                              int64_t K, nvfp4_dtype in_dt, nvfp4_dtype out_dt,
+                              const nvfp4_format *f, void *workspace, size_t workspace_bytes,
+                              void *stream)
+{
+    nvfp4_status s = check_format(f);
+    if (s != NVFP4_OK) return s;
+    if (!X || !W || !Y) return NVFP4_EINVAL;
+    if (!valid_dtype(in_dt) || !valid_dtype(out_dt)) return NVFP4_EINVAL;
+    if (M <= 0 || N <= 0 || K <= 0) return NVFP4_ESHAPE;
+    if (K % f->block != 0 || K % 32 != 0) return NVFP4_ESHAPE;
+    if (f->scale != NVFP4_SCALE_E4M3) return NVFP4_EUNSUPPORTED;
+    if (!aligned16(X) || !aligned16(W) || !aligned16(Y)) return NVFP4_EALIGN;
+    if (!workspace || workspace_bytes < nvfp4_linear_fwd_workspace_bytes(M, N, K, f)) return NVFP4_EWORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(workspace) & (WS_ALIGN - 1)) != 0) return NVFP4_EALIGN;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+
+    uint8_t *ws = reinterpret_cast<uint8_t *>(workspace);
+    float *ts = reinterpret_cast<float *>(ws);                 // {gX, gW}
+    uint32_t *amax = reinterpret_cast<uint32_t *>(ws + 64);    // two maxima
+    uint8_t *p = ws + WS_HEADER;
+    uint8_t *xc = p; p += align_up((size_t)M * K / 2);
+    uint8_t *xs = p; p += align_up((size_t)M * (K / f->block));
+    uint8_t *wc = p; p += align_up((size_t)N * K / 2);
+    uint8_t *wsc = p;
+
+    const int gm = f->tensor_scale ? G_FROM_AMAX : G_NONE;
+    if (f->tensor_scale) {
+        if (launch_tensor_amax(X, in_dt, M, K, K, amax + 0, st) != hipSuccess) return NVFP4_EHIP;
+        if (launch_tensor_amax(W, in_dt, N, K, K, amax + 1, st) != hipSuccess) return NVFP4_EHIP;
+    }
+    QuantPlan qx{X, in_dt, M, K, K, 1, NVFP4_RTN, 0, xc, xs, reinterpret_cast<const float *>(amax + 0), ts + 0, gm};
+    QuantPlan qw{W, in_dt, N, K, K, 1, NVFP4_RTN, 0, wc, wsc, reinterpret_cast<const float *>(amax + 1), ts + 1, gm};
+    if (run_quantize(qx, f, st) != hipSuccess) return NVFP4_EHIP;
+    if (run_quantize(qw, f, st) != hipSuccess) return NVFP4_EHIP;
+    GemmArgs g{M, N, K, xc, xs, wc, wsc, ts, Y, N};
+    return launch_gemm(g, f->block, f->scale, out_dt, st) == hipSuccess ? NVFP4_OK : NVFP4_EHIP;
+}
+
+nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void *dX, void *dW,
+                              int64_t M, int64_t N, int64_t K, nvfp4_dtype in_dt,
+                              nvfp4_dtype out_dt, const nvfp4_format *f, uint64_t seed,
+                              void *workspace, size_t workspace_bytes, void *stream)
+{
+    nvfp4_status s = check_format(f);
+    if (s != NVFP4_OK) return s;
+    if (!dY || (dX && !W) || (dW && !X)) return NVFP4_EINVAL;
+    if (!valid_dtype(in_dt) || !valid_dtype(out_dt)) return NVFP4_EINVAL;
+    if (M <= 0 || N <= 0 || K <= 0) return NVFP4_ESHAPE;
+    const int64_t B = f->block;
+    // dX contracts over N, dW over M; K is a leading dimension of X and W read down columns
+    if (dX && (N % B != 0 || N % 32 != 0)) return NVFP4_ESHAPE;
+    if (dW && (M % B != 0 || M % 32 != 0)) return NVFP4_ESHAPE;
+    if ((K * (int64_t)elem_size(in_dt)) % 16 != 0 || (N * (int64_t)elem_size(in_dt)) % 16 != 0) return NVFP4_EALIGN;
+    if (f->scale != NVFP4_SCALE_E4M3) return NVFP4_EUNSUPPORTED;
+    if (!aligned16(dY) || !aligned16(X) || !aligned16(W) || !aligned16(dX) || !aligned16(dW)) return NVFP4_EALIGN;
+    if (!workspace || workspace_bytes < nvfp4_linear_bwd_workspace_bytes(M, N, K, f)) return NVFP4_EWORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(workspace) & (WS_ALIGN - 1)) != 0) return NVFP4_EALIGN;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+
+    uint8_t *ws = reinterpret_cast<uint8_t *>(workspace);
+    float *ts = reinterpret_cast<float *>(ws);               // {g_dY, g_W, g_dY, g_X}
+    uint32_t *amax = reinterpret_cast<uint32_t *>(ws + 64);  // maxima of dY, W, X
+    uint8_t *p = ws + WS_HEADER;
+    uint8_t *dyc = p; p += align_up((size_t)M * N / 2);
+    uint8_t *dys = p; p += align_up((size_t)M * (N / B));
+    uint8_t *wtc = p; p += align_up((size_t)K * N / 2);
+    uint8_t *wts = p; p += align_up((size_t)K * (N / B));
+    uint8_t *dytc = p; p += align_up((size_t)N * M / 2);
+    uint8_t *dyts = p; p += align_up((size_t)N * (M / B));
+    uint8_t *xtc = p; p += align_up((size_t)K * M / 2);
+    uint8_t *xts = p;
+
+    const int gm = f->tensor_scale ? G_FROM_AMAX : G_NONE;
+    if (f->tensor_scale) {
+        if (launch_tensor_amax(dY, in_dt, M, N, N, amax + 0, st) != hipSuccess) return NVFP4_EHIP;
+    }
+    if (dX) {
+        if (f->tensor_scale && launch_tensor_amax(W, in_dt, N, K, K, amax + 1, st) != hipSuccess) return NVFP4_EHIP;
+        // Eq. 5: dX[M, K] = Q_SR(dY)[M, N] * Q_RtN(W^T)[K, N]^T
+        QuantPlan qa{dY, in_dt, M, N, N, 1, NVFP4_SR, seed, dyc, dys, reinterpret_cast<const float *>(amax + 0), ts + 0, gm};
+        QuantPlan qb{W, in_dt, N, K, K, 0, NVFP4_RTN, 0, wtc, wts, reinterpret_cast<const float *>(amax + 1), ts + 1, gm};
+        if (run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
+        if (run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
+        GemmArgs g{M, K, N, dyc, dys, wtc, wts, ts + 0, dX, K};
+        if (launch_gemm(g, f->block, f->scale, out_dt, st) != hipSuccess) return NVFP4_EHIP;
+    }
+    if (dW) {
+        if (f->tensor_scale && launch_tensor_amax(X, in_dt, M, K, K, amax + 2, st) != hipSuccess) return NVFP4_EHIP;
+        // Eq. 6: dW[N, K] = Q_SR(dY^T)[N, M] * Q_SR(X^T)[K, M]^T
+        QuantPlan qa{dY, in_dt, M, N, N, 0, NVFP4_SR, seed + 1, dytc, dyts, reinterpret_cast<const float *>(amax + 0), ts + 2, gm};
+        QuantPlan qb{X, in_dt, M, K, K, 0, NVFP4_SR, seed + 2, xtc, xts, reinterpret_cast<const float *>(amax + 2), ts + 3, gm};
+        if (run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
+        if (run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
+        GemmArgs g{N, K, M, dytc, dyts, xtc, xts, ts + 2, dW, K};
+        if (launch_gemm(g, f->block, f->scale, out_dt, st) != hipSuccess) return NVFP4_EHIP;
+    }
+    return NVFP4_OK;
+}
+
+// ---- host evaluations of the scalar steps (no GPU involved)
+
+uint8_t nvfp4_host_e4m3_encode(float r)
+{
+    float s;
+    return (uint8_t)e4m3_encode(r, &s);
+}
+float nvfp4_host_e4m3_decode(uint8_t byte) { return e4m3_decode(byte); }
+uint8_t nvfp4_host_round_rtn(float m) { return (uint8_t)round_rtn(m); }
+uint8_t nvfp4_host_round_sr(float m, uint32_t u16) { return (uint8_t)round_sr(m, u16); }
+void nvfp4_host_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    u32x4 d = philox4x32_10(ctr[0], ctr[1], ctr[2], ctr[3], key[0], key[1]);
+    out[0] = d.x; out[1] = d.y; out[2] = d.z; out[3] = d.w;
+}
+uint32_t nvfp4_host_sr_bits(uint64_t seed, uint64_t e) { return sr_bits_of(sr_draw(seed, e >> 3), (uint32_t)e & 7u); }
+uint8_t nvfp4_host_e8m0_encode(float a)
+{
+    float q;
+    return (uint8_t)e8m0_encode(a, &q);
+}
+void nvfp4_host_e4m3_encode_n(const float *r, int64_t n, uint8_t *out)
+{
+    for (int64_t t = 0; t < n; ++t) out[t] = nvfp4_host_e4m3_encode(r[t]);
+}
+void nvfp4_host_round_rtn_n(const float *m, int64_t n, uint8_t *out)
+{
+    for (int64_t t = 0; t < n; ++t) out[t] = nvfp4_host_round_rtn(m[t]);
+}
+void nvfp4_host_round_sr_n(const float *m, const uint32_t *u16, int64_t n, uint8_t *out)
+{
+    for (int64_t t = 0; t < n; ++t) out[t] = nvfp4_host_round_sr(m[t], u16[t]);
+}
+
+}  // extern "C"

@@ -1,0 +1,137 @@
+// Scalar steps of the FP4 block quantizer, shared by the HIP kernels and (compiled for the
+// host) by the nvfp4_host_* probes of the C ABI.  Formats: Sec. 3 / Table 1 of "FP4 All the
+// Way"; rounding modes: Sec. 3.2.  Every function is branch-light integer/fp32 arithmetic whose
+// result is fully determined by IEEE binary32 (no contraction: this header must be compiled
+// with -ffp-contract=off).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define NVFP4_HD __host__ __device__ __forceinline__
+
+namespace nvfp4 {
+
+NVFP4_HD uint32_t f2u(float f) { return __builtin_bit_cast(uint32_t, f); }
+NVFP4_HD float u2f(uint32_t u) { return __builtin_bit_cast(float, u); }
+NVFP4_HD uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+
+// Smallest per-tensor scale: keeps s*g (s >= 2^-9) a normal number with a finite reciprocal.
+NVFP4_HD float tensor_scale_floor() { return u2f((127u - 117u) << 23); }
+
+// g from the tensor maximum T (reading, not in the paper): T/(6*448); 1 for T == 0.
+NVFP4_HD float tensor_scale_from_amax(float T)
+{
+    if (T == 0.0f) return 1.0f;
+    float g = T / 2688.0f;
+    return g < tensor_scale_floor() ? tensor_scale_floor() : g;
+}
+
+// E4M3 (bias 7, 3 mantissa bits, finite-only, max 448) of r >= 0: round to nearest even,
+// saturate.  Returns the byte; *s receives the decoded value.
+//   normal range (r >= 2^-6): round the binary32 mantissa to 3 bits by integer add;
+//   below 2^-6 the step is 2^-9: adding 2^14 (whose ulp is 2^-9) lets the fp32 adder round.
+NVFP4_HD uint32_t e4m3_encode(float r, float *s)
+{
+    r = r < 448.0f ? r : 448.0f;
+    if (r < 0.015625f) {
+        float t = r + 16384.0f;
+        *s = t - 16384.0f;
+        return f2u(t) & 0xFu;
+    }
+    uint32_t b = f2u(r);
+    b += 0x7FFFFu + ((b >> 20) & 1u);
+    b &= 0xFFF00000u;
+    *s = u2f(b);
+    return (b >> 20) - (120u << 3);
+}
+
+NVFP4_HD float e4m3_decode(uint32_t byte)
+{
+    uint32_t e = (byte >> 3) & 15u, m = byte & 7u;
+    if (e == 0) return (float)m * 0.001953125f;  // m * 2^-9
+    return u2f(((e + 120u) << 23) | (m << 20));
+}
+
+// E8M0 shared exponent of a block with maximum a > 0 (MXFP4, Sec. 3): byte =
+// clamp(floor(log2 a) - 2 + 127, 0, 254); *q = 2^(127 - byte) maps the block onto E2M1's range.
+NVFP4_HD uint32_t e8m0_encode(float a, float *q)
+{
+    uint32_t bits = f2u(a);
+    int ex = (int)(bits >> 23);  // biased exponent; 0 for subnormal a
+    int fl;                      // floor(log2 a)
+    if (ex == 0)
+        fl = -127 - __builtin_clz(bits << 9);  // leading mantissa bit at position 22-clz
+    else
+        fl = ex - 127;
+    int biased = fl - 2 + 127;
+    biased = biased < 0 ? 0 : (biased > 254 ? 254 : biased);
+    int qe = 127 - biased + 127;  // biased exponent of q, in [0, 254]
+    *q = qe == 0 ? u2f(0x00400000u) /* 2^-127 */ : u2f((uint32_t)qe << 23);
+    return (uint32_t)biased;
+}
+
+// Round-to-nearest-even of m in [0, 6] onto the E2M1 magnitudes {0,.5,1,1.5,2,3,4,6}.
+// The grid step is 2^(e-1) with e = 0 for m < 2, 1 for [2,4), 2 for [4,6]; adding 2^(23+e-1)
+// makes the fp32 adder round m to a multiple of the step, ties to even, and leaves the
+// multiple in the low mantissa bits.  Even multiples are even codes, so this is ties-to-even
+// on codes as well.
+NVFP4_HD uint32_t round_rtn(float m)
+{
+    uint32_t e = umax(f2u(m) >> 23, 127u) - 127u;
+    uint32_t n = f2u(m + u2f((149u + e) << 23)) & 7u;
+    return n + (e << 1);
+}
+
+// Stochastic rounding of m in [0, 6] with a 16-bit uniform u: with lo <= m < hi the grid
+// neighbours and t = (m - lo)/(hi - lo), round up iff u + 1/2 < 65536 t.
+// fx = 65536 m/step is exact; with n = floor(m/step): 65536 t = fx - 65536 n, so the rule is
+// (65536 n + u) + 1/2 < fx, i.e. 65536 n + u < R with R = ceil(fx - 1/2), and the rounded
+// multiple of the step is floor((R + 65535 - u) / 65536).
+NVFP4_HD uint32_t round_sr(float m, uint32_t u16)
+{
+    uint32_t e = umax(f2u(m) >> 23, 127u) - 127u;
+    float fx = m * u2f((144u - e) << 23);
+    int R = (int)ceilf(fx - 0.5f);
+    uint32_t k = (uint32_t)(R + 65535 - (int)u16) >> 16;
+    return k + (e << 1);
+}
+
+// Philox4x32-10 (Salmon et al., SC'11).
+struct u32x4 {
+    uint32_t x, y, z, w;
+};
+
+NVFP4_HD u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                             uint32_t k1)
+{
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return u32x4{c0, c1, c2, c3};
+}
+
+// The 128 random bits shared by the 8 elements whose row-major indices are 8c .. 8c+7.
+NVFP4_HD u32x4 sr_draw(uint64_t seed, uint64_t c)
+{
+    return philox4x32_10((uint32_t)c, (uint32_t)(c >> 32), 0u, 0u, (uint32_t)seed,
+                         (uint32_t)(seed >> 32));
+}
+
+// 16 bits of element e & 7 out of its group's draw.
+NVFP4_HD uint32_t sr_bits_of(const u32x4 &d, uint32_t e_low3)
+{
+    uint32_t w = (e_low3 >> 1) == 0 ? d.x : (e_low3 >> 1) == 1 ? d.y : (e_low3 >> 1) == 2 ? d.z : d.w;
+    return (e_low3 & 1u) ? (w >> 16) : (w & 0xFFFFu);
+}
+
+}  // namespace nvfp4

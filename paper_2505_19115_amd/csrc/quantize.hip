@@ -1,0 +1,497 @@
+// Block quantizer kernels for gfx950: tensor maximum, row-blocked quantizer, column-blocked
+// (transposed-output) quantizer.  Implements the operation Q of Eqs. 1-6 of "FP4 All the Way"
+// for the formats of Sec. 3 / Table 1 and the two rounding modes of Sec. 3.2.
+//
+// Memory plan (the kernels are HBM-bound, so everything is about 16-byte coalesced access):
+//   rows kernel   : one lane = 8 consecutive elements of a row (one 16 B load for bf16), a
+//                   block of B elements = B/8 adjacent lanes, block maximum by DPP max across
+//                   those lanes, one 4 B store of 8 packed codes per lane.
+//   columns kernel: one lane = RPL consecutive rows x 8 consecutive columns held in registers
+//                   (RPL = 32 for bf16, 16 for fp32).  Lanes that are adjacent in the wave hold
+//                   vertically adjacent row groups of the same 8 columns, so a wave reads
+//                   >= 256 B contiguous per row and writes 64 B contiguous per output row of
+//                   the transposed code matrix without staging through LDS.
+#include "kernels.h"
+#include "nvfp4_math.h"
+
+namespace nvfp4 {
+
+// ------------------------------------------------------------------ small device helpers
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_max(float a)
+{
+    // a >= 0: unsigned order of the bit patterns is the float order
+    int o = __builtin_amdgcn_update_dpp(0, (int)f2u(a), CTRL, 0xF, 0xF, false);
+    uint32_t ou = (uint32_t)o;
+    return u2f(umax(f2u(a), ou));
+}
+
+// Maximum over groups of L adjacent lanes (L = 1, 2, 4, 8, 16; groups aligned to L).
+template <int L>
+__device__ __forceinline__ float group_max(float a)
+{
+    if (L >= 2) a = dpp_max<0xB1>(a);   // quad_perm [1,0,3,2]  : lane ^ 1
+    if (L >= 4) a = dpp_max<0x4E>(a);   // quad_perm [2,3,0,1]  : lane ^ 2
+    if (L >= 8) a = dpp_max<0x141>(a);  // row_half_mirror      : swaps the two quads of 8 lanes
+    if (L >= 16) a = dpp_max<0x140>(a); // row_mirror           : swaps the two halves of 16 lanes
+    return a;
+}
+
+template <int DT>
+struct Chunk;  // 8 consecutive elements as loaded from memory
+
+template <>
+struct Chunk<NVFP4_BF16> {
+    uint4 raw;
+    __device__ __forceinline__ void load(const void *x, int64_t off)
+    {
+        raw = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(x) + off);
+    }
+    __device__ __forceinline__ void load_partial(const void *x, int64_t off, int n)
+    {
+        const uint16_t *p = reinterpret_cast<const uint16_t *>(x) + off;
+        uint32_t w[4] = {0, 0, 0, 0};
+        for (int t = 0; t < n; ++t) w[t >> 1] |= (uint32_t)p[t] << (16 * (t & 1));
+        raw = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    __device__ __forceinline__ void zero() { raw = make_uint4(0, 0, 0, 0); }
+    __device__ __forceinline__ float get(int t) const
+    {
+        uint32_t w = t < 2 ? raw.x : t < 4 ? raw.y : t < 6 ? raw.z : raw.w;
+        return (t & 1) ? u2f(w & 0xFFFF0000u) : u2f(w << 16);
+    }
+};
+
+template <>
+struct Chunk<NVFP4_F32> {
+    float4 lo, hi;
+    __device__ __forceinline__ void load(const void *x, int64_t off)
+    {
+        const float4 *p = reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(x) + off);
+        lo = p[0];
+        hi = p[1];
+    }
+    __device__ __forceinline__ void load_partial(const void *x, int64_t off, int n)
+    {
+        const float *p = reinterpret_cast<const float *>(x) + off;
+        float v[8];
+        for (int t = 0; t < 8; ++t) v[t] = t < n ? p[t] : 0.0f;
+        lo = make_float4(v[0], v[1], v[2], v[3]);
+        hi = make_float4(v[4], v[5], v[6], v[7]);
+    }
+    __device__ __forceinline__ void zero()
+    {
+        lo = make_float4(0, 0, 0, 0);
+        hi = lo;
+    }
+    __device__ __forceinline__ float get(int t) const
+    {
+        switch (t) {
+        case 0: return lo.x;
+        case 1: return lo.y;
+        case 2: return lo.z;
+        case 3: return lo.w;
+        case 4: return hi.x;
+        case 5: return hi.y;
+        case 6: return hi.z;
+        default: return hi.w;
+        }
+    }
+};
+
+template <int DT>
+__device__ __forceinline__ float chunk_amax(const Chunk<DT> &c)
+{
+    float a = 0.0f;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) a = fmaxf(a, fabsf(c.get(t)));
+    return a;
+}
+
+// Per-tensor scale as the kernels see it: none, preset in memory, or the bit pattern of the
+// tensor maximum left by the amax kernel.
+__device__ __forceinline__ float resolve_g(const QuantArgs &P)
+{
+    if (P.g_mode == G_NONE) return 1.0f;
+    if (P.g_mode == G_PRESET) {
+        float g = *P.g_src;
+        return g < tensor_scale_floor() ? tensor_scale_floor() : g;
+    }
+    return tensor_scale_from_amax(u2f(*reinterpret_cast<const uint32_t *>(P.g_src)));
+}
+
+// Block scale byte and the multiplier q that maps the block onto the E2M1 range.
+// q = 0 for a block whose magnitudes are all zero.
+template <int SF>
+__device__ __forceinline__ uint32_t block_scale(float a, float g, float k, float *q)
+{
+    if (SF == NVFP4_SCALE_E4M3) {
+        float s;
+        uint32_t byte = e4m3_encode(a * k, &s);
+        float d = s * g;
+        *q = byte == 0 ? 0.0f : 1.0f / d;
+        return byte;
+    } else {
+        if (a == 0.0f) {
+            *q = 0.0f;
+            return 0u;
+        }
+        return e8m0_encode(a, q);
+    }
+}
+
+// One element: sign | magnitude code.
+template <int RND>
+__device__ __forceinline__ uint32_t quant_elem(float x, float q, uint32_t u16)
+{
+    float m = fabsf(x * q);
+    m = m < 6.0f ? m : 6.0f;
+    uint32_t mag = RND == NVFP4_RTN ? round_rtn(m) : round_sr(m, u16);
+    return mag | ((f2u(x) >> 28) & 8u);
+}
+
+// Two adjacent elements -> one byte via the gfx950 convert (RNE, saturating at +-6, sign
+// kept on zero), low nibble = first element.
+__device__ __forceinline__ uint32_t quant_pair_hw(float x0, float x1, float q)
+{
+    return __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, x0 * q, x1 * q, 1.0f, 0) & 0xFFu;
+}
+
+// ------------------------------------------------------------------ tensor maximum (Q0)
+
+__global__ __launch_bounds__(64) void zero_u32_kernel(uint32_t *p)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) *p = 0u;
+}
+
+// max|x| over a [rows, cols] tensor into *out (bit pattern, atomic unsigned max).
+// grid.x strides over the 8-element chunks of a row span, grid.y over row spans; for a dense
+// tensor the host passes rows = 1, cols = rows*cols.
+template <int DT>
+__global__ __launch_bounds__(256) void amax_kernel(const void *x, int64_t cols, int64_t ld,
+                                                   uint32_t *out)
+{
+    const int64_t row = blockIdx.y;
+    const int64_t nchunk = cols >> 3;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    float a = 0.0f;
+    int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    for (; c + 3 * stride < nchunk; c += 4 * stride) {
+        Chunk<DT> v0, v1, v2, v3;
+        v0.load(x, row * ld + c * 8);
+        v1.load(x, row * ld + (c + stride) * 8);
+        v2.load(x, row * ld + (c + 2 * stride) * 8);
+        v3.load(x, row * ld + (c + 3 * stride) * 8);
+        a = fmaxf(fmaxf(a, chunk_amax(v0)), fmaxf(chunk_amax(v1), fmaxf(chunk_amax(v2), chunk_amax(v3))));
+    }
+    for (; c < nchunk; c += stride) {
+        Chunk<DT> v;
+        v.load(x, row * ld + c * 8);
+        a = fmaxf(a, chunk_amax(v));
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0 && (cols & 7)) {
+        Chunk<DT> v;
+        v.load_partial(x, row * ld + nchunk * 8, (int)(cols & 7));
+        a = fmaxf(a, chunk_amax(v));
+    }
+    a = group_max<16>(a);
+    // 4 rows of 16 lanes per wave, 4 waves: finish through LDS
+    __shared__ uint32_t part[16];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if ((lane & 15) == 0) part[wave * 4 + (lane >> 4)] = f2u(a);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t m = 0;
+#pragma unroll
+        for (int t = 0; t < 16; ++t) m = umax(m, part[t]);
+        if (m != 0) atomicMax(out, m);
+    }
+}
+
+__global__ __launch_bounds__(64) void finalize_tensor_scale_kernel(const uint32_t *amax_bits,
+                                                                   float *g_out)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) *g_out = tensor_scale_from_amax(u2f(*amax_bits));
+}
+
+// ------------------------------------------------------------------ row-blocked quantizer
+
+constexpr int ROWS_UNROLL = 4;  // chunks per thread
+
+template <int DT, int B, int SF, int RND, bool HW>
+__global__ __launch_bounds__(256) void quantize_rows_kernel(QuantArgs P)
+{
+    constexpr int LPB = B / 8;  // lanes per block
+    const int64_t cpr = P.cols >> 3;
+    const int64_t total = P.rows * cpr;
+    const float g = resolve_g(P);
+    const float k = 1.0f / (6.0f * g);
+    if (blockIdx.x == 0 && threadIdx.x == 0) *P.g_out = g;
+
+    const int64_t base = (int64_t)blockIdx.x * (256 * ROWS_UNROLL) + threadIdx.x;
+    const bool dense = P.ld == P.cols;
+    Chunk<DT> v[ROWS_UNROLL];
+#pragma unroll
+    for (int u = 0; u < ROWS_UNROLL; ++u) {
+        const int64_t id = base + u * 256;
+        if (id < total) {
+            int64_t off = id * 8;
+            if (!dense) {
+                const int64_t i = id / cpr;
+                off = i * P.ld + (id - i * cpr) * 8;
+            }
+            v[u].load(P.x, off);
+        } else {
+            v[u].zero();
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < ROWS_UNROLL; ++u) {
+        const int64_t id = base + u * 256;
+        // a whole block is in or out of range together, so the lanes exchanged below are
+        // either all live or all holding zeros
+        const float a = group_max<LPB>(chunk_amax(v[u]));
+        float q;
+        const uint32_t sbyte = block_scale<SF>(a, g, k, &q);
+        uint32_t packed = 0;
+        if (RND == NVFP4_RTN && HW) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                packed |= quant_pair_hw(v[u].get(2 * t), v[u].get(2 * t + 1), q) << (8 * t);
+        } else {
+            u32x4 d = {0, 0, 0, 0};
+            if (RND == NVFP4_SR) d = sr_draw(P.seed, (uint64_t)id);  // element index = 8*id + t
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+                packed |= quant_elem<RND>(v[u].get(t), q, sr_bits_of(d, t)) << (4 * t);
+        }
+        if (id < total) {
+            reinterpret_cast<uint32_t *>(P.codes)[id] = packed;
+            if ((threadIdx.x & (LPB - 1)) == 0) P.scales[id / LPB] = (uint8_t)sbyte;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ column-blocked quantizer
+
+// Lane tile: RPL rows x 8 columns.  Wave tile: 128 rows x (8 * 64 * RPL / 128) columns, lanes
+// with consecutive ids stacked vertically.  Workgroup: 4 waves side by side.
+template <int DT>
+struct ColGeom {
+    static constexpr int RPL = DT == NVFP4_BF16 ? 32 : 16;
+    static constexpr int LANES_V = 128 / RPL;          // lanes stacked vertically
+    static constexpr int LANES_H = 64 / LANES_V;       // column groups per wave
+    static constexpr int WAVE_COLS = 8 * LANES_H;
+    static constexpr int WG_COLS = 4 * WAVE_COLS;
+    static constexpr int WG_ROWS = 128;
+};
+
+template <int DT, int B, int SF, int RND, bool HW>
+__global__ __launch_bounds__(256) void quantize_cols_kernel(QuantArgs P)
+{
+    using G = ColGeom<DT>;
+    constexpr int RPL = G::RPL;
+    constexpr int BL = B < RPL ? B : RPL;        // rows of one block held by this lane
+    constexpr int NB = RPL / BL;                 // blocks (or block parts) per lane per column
+    constexpr int LPB = B / BL;                  // lanes sharing one block
+
+    const float g = resolve_g(P);
+    const float k = 1.0f / (6.0f * g);
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *P.g_out = g;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lv = lane % G::LANES_V, lh = lane / G::LANES_V;
+    const int64_t row0 = (int64_t)blockIdx.y * G::WG_ROWS + lv * RPL;
+    const int64_t col0 = (int64_t)blockIdx.x * G::WG_COLS + wave * G::WAVE_COLS + lh * 8;
+    const int ncol = col0 >= P.cols ? 0 : (P.cols - col0 >= 8 ? 8 : (int)(P.cols - col0));
+
+    Chunk<DT> v[RPL];
+#pragma unroll
+    for (int r = 0; r < RPL; ++r) {
+        const int64_t i = row0 + r;
+        if (i < P.rows && ncol == 8)
+            v[r].load(P.x, i * P.ld + col0);
+        else if (i < P.rows && ncol > 0)
+            v[r].load_partial(P.x, i * P.ld + col0, ncol);
+        else
+            v[r].zero();
+    }
+
+    const int64_t rows_half = P.rows >> 1;
+    const int64_t nblk = P.rows / B;
+
+    // pass 1: block maxima -> scale bytes and multipliers, per column and per block part
+    float q[8][NB];
+    uint32_t sbytes[8][NB];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            float a = 0.0f;
+#pragma unroll
+            for (int r = 0; r < BL; ++r) a = fmaxf(a, fabsf(v[nb * BL + r].get(c)));
+            a = group_max<LPB>(a);
+            sbytes[c][nb] = block_scale<SF>(a, g, k, &q[c][nb]);
+        }
+    }
+
+    // pass 2: codes.  words[c][w] collects rows 8w..8w+7 of column c, one nibble per row.
+    uint32_t words[8][RPL / 8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+#pragma unroll
+        for (int w = 0; w < RPL / 8; ++w) words[c][w] = 0;
+
+    if (RND == NVFP4_RTN && HW) {
+#pragma unroll
+        for (int r = 0; r < RPL; r += 2)
+#pragma unroll
+            for (int c = 0; c < 8; ++c)
+                words[c][r / 8] |= quant_pair_hw(v[r].get(c), v[r + 1].get(c), q[c][r / BL]) << (4 * (r % 8));
+    } else {
+        // the 8 columns of a lane are 8 consecutive elements of a row; their random bits come
+        // from one draw when that group is aligned in the row-major numbering, else from two
+        const bool aligned = ((P.cols | col0) & 7) == 0;
+#pragma unroll
+        for (int r = 0; r < RPL; ++r) {
+            u32x4 d0 = {0, 0, 0, 0}, d1 = {0, 0, 0, 0};
+            uint32_t shift = 0;
+            if (RND == NVFP4_SR) {
+                const uint64_t e0 = (uint64_t)(row0 + r) * (uint64_t)P.cols + (uint64_t)col0;
+                d0 = sr_draw(P.seed, e0 >> 3);
+                shift = (uint32_t)e0 & 7u;
+                if (!aligned) d1 = sr_draw(P.seed, (e0 >> 3) + 1);
+            }
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                uint32_t u16 = 0;
+                if (RND == NVFP4_SR) {
+                    if (aligned) {
+                        u16 = sr_bits_of(d0, c);
+                    } else {
+                        const uint32_t pos = shift + c;
+                        u16 = pos < 8 ? sr_bits_of(d0, pos) : sr_bits_of(d1, pos - 8);
+                    }
+                }
+                words[c][r / 8] |= quant_elem<RND>(v[r].get(c), q[c][r / BL], u16) << (4 * (r % 8));
+            }
+        }
+    }
+
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        if (c < ncol) {
+            const int64_t col = col0 + c;
+            uint8_t *crow = P.codes + col * rows_half + (row0 >> 1);
+#pragma unroll
+            for (int h = 0; h < RPL / 16; ++h)
+                if (row0 + 16 * h < P.rows)
+                    *reinterpret_cast<uint2 *>(crow + 8 * h) = make_uint2(words[c][2 * h], words[c][2 * h + 1]);
+            if (lv % LPB == 0) {
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    if (row0 + nb * BL < P.rows)
+                        P.scales[col * nblk + (row0 + nb * BL) / B] = (uint8_t)sbytes[c][nb];
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ host-side launchers
+
+static inline hipError_t launch_status() { return hipGetLastError(); }
+
+hipError_t launch_tensor_amax(const void *x, int dt, int64_t rows, int64_t cols, int64_t ld,
+                              uint32_t *amax_bits, hipStream_t st)
+{
+    hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(64), 0, st, amax_bits);
+    int64_t span_rows = rows, span_cols = cols;
+    if (ld == cols) {
+        span_cols = rows * cols;
+        span_rows = 1;
+    }
+    const int64_t nchunk = span_cols >> 3;
+    int64_t gx = (nchunk + 256 * 4 - 1) / (256 * 4);
+    if (gx < 1) gx = 1;
+    const int64_t cap = span_rows == 1 ? 4096 : 64;
+    if (gx > cap) gx = cap;
+    // grid.y is limited to 65535: walk taller tensors in slabs
+    for (int64_t r0 = 0; r0 < span_rows; r0 += 65535) {
+        const int64_t nr = span_rows - r0 < 65535 ? span_rows - r0 : 65535;
+        const char *base = reinterpret_cast<const char *>(x) + r0 * ld * (dt == NVFP4_BF16 ? 2 : 4);
+        if (dt == NVFP4_BF16)
+            hipLaunchKernelGGL(amax_kernel<NVFP4_BF16>, dim3((unsigned)gx, (unsigned)nr), dim3(256), 0, st,
+                               base, span_cols, ld, amax_bits);
+        else
+            hipLaunchKernelGGL(amax_kernel<NVFP4_F32>, dim3((unsigned)gx, (unsigned)nr), dim3(256), 0, st,
+                               base, span_cols, ld, amax_bits);
+    }
+    return launch_status();
+}
+
+hipError_t launch_finalize_tensor_scale(const uint32_t *amax_bits, float *g_out, hipStream_t st)
+{
+    hipLaunchKernelGGL(finalize_tensor_scale_kernel, dim3(1), dim3(64), 0, st, amax_bits, g_out);
+    return launch_status();
+}
+
+template <int DT, int B, int SF, int RND, bool HW>
+static void launch_q(const QuantArgs &P, int axis, hipStream_t st)
+{
+    if (axis == 1) {
+        const int64_t total = P.rows * (P.cols >> 3);
+        const int64_t per = 256 * ROWS_UNROLL;
+        hipLaunchKernelGGL((quantize_rows_kernel<DT, B, SF, RND, HW>), dim3((unsigned)((total + per - 1) / per)),
+                           dim3(256), 0, st, P);
+    } else {
+        using G = ColGeom<DT>;
+        dim3 grid((unsigned)((P.cols + G::WG_COLS - 1) / G::WG_COLS),
+                  (unsigned)((P.rows + G::WG_ROWS - 1) / G::WG_ROWS));
+        hipLaunchKernelGGL((quantize_cols_kernel<DT, B, SF, RND, HW>), grid, dim3(256), 0, st, P);
+    }
+}
+
+template <int DT, int B, int SF>
+static void launch_q_rnd(const QuantArgs &P, int axis, int rounding, bool hw, hipStream_t st)
+{
+    if (rounding == NVFP4_SR)
+        launch_q<DT, B, SF, NVFP4_SR, false>(P, axis, st);
+    else if (hw)
+        launch_q<DT, B, SF, NVFP4_RTN, true>(P, axis, st);
+    else
+        launch_q<DT, B, SF, NVFP4_RTN, false>(P, axis, st);
+}
+
+template <int DT>
+static void launch_q_fmt(const QuantArgs &P, int axis, int rounding, int block, int sf, bool hw,
+                         hipStream_t st)
+{
+#define NVFP4_CASE(BB)                                                                   \
+    case BB:                                                                             \
+        if (sf == NVFP4_SCALE_E4M3)                                                      \
+            launch_q_rnd<DT, BB, NVFP4_SCALE_E4M3>(P, axis, rounding, hw, st);           \
+        else                                                                             \
+            launch_q_rnd<DT, BB, NVFP4_SCALE_E8M0>(P, axis, rounding, hw, st);           \
+        break;
+    switch (block) {
+        NVFP4_CASE(16)
+        NVFP4_CASE(32)
+        NVFP4_CASE(64)
+        NVFP4_CASE(128)
+    default: break;
+    }
+#undef NVFP4_CASE
+}
+
+hipError_t launch_quantize(const QuantArgs &P, int dt, int axis, int rounding, int block, int sf,
+                           bool hw_convert, hipStream_t st)
+{
+    if (dt == NVFP4_BF16)
+        launch_q_fmt<NVFP4_BF16>(P, axis, rounding, block, sf, hw_convert, st);
+    else
+        launch_q_fmt<NVFP4_F32>(P, axis, rounding, block, sf, hw_convert, st);
+    return launch_status();
+}
+
+}  // namespace nvfp4

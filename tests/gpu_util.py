@@ -1,0 +1,45 @@
+"""Helpers shared by the GPU parity tests."""
+import numpy as np
+import torch
+
+import oracle
+
+GPU_TO_ORACLE_FMT = {}
+
+
+def ofmt(fmt):
+    """binding.Format -> oracle.Format (same three integers, separate modules)."""
+    return oracle.Format(fmt.block, fmt.scale, fmt.tensor_scale)
+
+
+def to_np(t: torch.Tensor) -> np.ndarray:
+    return t.detach().cpu().numpy()
+
+
+def assert_quant_equal(got, want, what=""):
+    """Bit-exact comparison of (codes, scales, g)."""
+    gc, gs, gg = to_np(got[0]), to_np(got[1]), float(got[2].item())
+    wc, ws, wg = want
+    assert gg == wg, f"{what}: tensor scale {gg} != {wg}"
+    if not np.array_equal(gs, ws):
+        bad = np.argwhere(gs != ws)
+        raise AssertionError(f"{what}: {len(bad)} scale bytes differ, first at {bad[0]}: "
+                             f"{gs[tuple(bad[0])]:#x} != {ws[tuple(bad[0])]:#x}")
+    if not np.array_equal(gc, wc):
+        bad = np.argwhere(gc != wc)
+        raise AssertionError(f"{what}: {len(bad)} code bytes differ, first at {bad[0]}: "
+                             f"{gc[tuple(bad[0])]:#x} != {wc[tuple(bad[0])]:#x}")
+
+
+REL_TOL = 1e-5  # the stated bar: fp32 accumulation against the fp64 oracle
+
+
+def assert_gemm_close(Y: np.ndarray, ref: np.ndarray, ref_abs: np.ndarray, what="", tol=REL_TOL):
+    """|Y - ref| <= tol * sum_k |a||b| element-wise, and tol in Frobenius norm."""
+    Y = Y.astype(np.float64)
+    err = np.abs(Y - ref)
+    worst = (err / np.maximum(ref_abs, 1e-300)).max() if ref.size else 0.0
+    assert np.all(err <= tol * ref_abs + 1e-300), f"{what}: element error {worst:.3e} x sum|a||b|"
+    if ref.size:
+        fro = np.linalg.norm(Y - ref) / max(np.linalg.norm(ref), 1e-300)
+        assert fro <= tol, f"{what}: Frobenius relative error {fro:.3e}"

@@ -1,0 +1,171 @@
+"""GPU parity of nvfp4_gemm and the fused linear entries against the fp64 CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2505_19115_amd import synth
+from gpu_util import assert_gemm_close, assert_quant_equal, ofmt, to_np
+
+pytestmark = pytest.mark.gpu
+
+nv = None
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _binding():
+    global nv
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2505_19115_amd import binding
+    nv = binding
+    yield
+
+
+def dev(q):
+    """oracle-side (codes, scales, g) -> device tensors."""
+    c, s, g = q
+    return (torch.from_numpy(c).cuda(), torch.from_numpy(s).cuda(),
+            torch.tensor([g], dtype=torch.float32, device="cuda"))
+
+
+def random_operand(rng, rows, K, block=16, lo=0x01, hi=0x7F, g=1.0):
+    codes = rng.integers(0, 256, (rows, K // 2)).astype(np.uint8)
+    scales = rng.integers(lo, hi, (rows, K // block)).astype(np.uint8)
+    return codes, scales, g
+
+
+def check(A, B, fmt, what, out_dtype=torch.float32, tol=None):
+    print(f"[case] gemm {what} M={A[0].shape[0]} N={B[0].shape[0]} K={A[0].shape[1] * 2} fmt={fmt}", flush=True)
+    Y = nv.gemm(dev(A), dev(B), fmt, out_dtype)
+    torch.cuda.synchronize()
+    ref = oracle.gemm_nt(A, B, ofmt(fmt))
+    ref_abs = oracle.gemm_nt(A, B, ofmt(fmt), take_abs=True)
+    if out_dtype == torch.bfloat16:
+        # bf16 output: the fp32 result rounded once more (8 significant bits)
+        assert np.all(np.abs(to_np(Y.float()) - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * ref_abs), what
+    else:
+        assert_gemm_close(to_np(Y), ref, ref_abs, what, **({} if tol is None else {"tol": tol}))
+    return Y
+
+
+def test_config1_forward():
+    # Y = Q(X) Q(W)^T for X, W fp32 [256, 256] ~ N(0,1), quantized on the GPU
+    X = synth.normal(256, 256, 1.0, 1, torch.float32)
+    W = synth.normal(256, 256, 1.0, 2, torch.float32)
+    qa, qb = nv.quantize(X.cuda(), 1), nv.quantize(W.cuda(), 1)
+    A, B = oracle.quantize(X, 1), oracle.quantize(W, 1)
+    assert_quant_equal(qa, A, "X")
+    assert_quant_equal(qb, B, "W")
+    Y = nv.gemm(qa, qb)
+    torch.cuda.synchronize()
+    assert_gemm_close(to_np(Y), oracle.gemm_nt(A, B), oracle.gemm_nt(A, B, take_abs=True), "config1")
+    Yf = nv.linear_fwd(X.cuda(), W.cuda())
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Yf)
+
+
+def test_unit_scales_give_exact_integers():
+    # all scales 1, g = 1: every partial sum is a multiple of 1/4 below 2^24/4, so fp32
+    # accumulation is exact whatever the order and the result must EQUAL the integer product
+    rng = np.random.default_rng(0)
+    M, N, K = 200, 136, 1184
+    A = (rng.integers(0, 256, (M, K // 2)).astype(np.uint8), np.full((M, K // 16), 0x38, np.uint8), 1.0)
+    B = (rng.integers(0, 256, (N, K // 2)).astype(np.uint8), np.full((N, K // 16), 0x38, np.uint8), 1.0)
+    Y = to_np(nv.gemm(dev(A), dev(B)))
+    assert np.array_equal(Y.astype(np.float64), oracle.gemm_nt(A, B))
+
+
+@pytest.mark.parametrize("shape", [(256, 256, 256), (200, 136, 160), (1, 1, 32), (130, 257, 416), (384, 512, 1024)])
+def test_random_codes_and_scales(shape):
+    # every scale byte from the smallest subnormal to 448 next to each other, random codes
+    M, N, K = shape
+    rng = np.random.default_rng(M * 7 + N)
+    check(random_operand(rng, M, K, g=0.37), random_operand(rng, N, K, g=2.5e-3), nv.NVFP4, "random")
+
+
+def test_moderate_scales_tight():
+    # scales within a few binades (what real tensors give): no cancellation of huge terms
+    rng = np.random.default_rng(5)
+    check(random_operand(rng, 320, 2048, lo=0x30, hi=0x48), random_operand(rng, 192, 2048, lo=0x30, hi=0x48),
+          nv.NVFP4, "moderate")
+
+
+@pytest.mark.parametrize("block", [32, 64, 128])
+def test_wider_blocks(block):
+    fmt = nv.Format(block, nv.SCALE_E4M3, 1)
+    rng = np.random.default_rng(block)
+    check(random_operand(rng, 192, 640, block), random_operand(rng, 160, 640, block), fmt, f"block{block}")
+    X = synth.normal(128, 512, 1.0, 7, torch.bfloat16)
+    W = synth.normal(256, 512, 0.02, 8, torch.bfloat16)
+    check(oracle.quantize(X, 1, 0, 0, ofmt(fmt)), oracle.quantize(W, 1, 0, 0, ofmt(fmt)), fmt, f"block{block}-real")
+
+
+def test_bf16_output_and_leading_dimension():
+    rng = np.random.default_rng(9)
+    A, B = random_operand(rng, 96, 256, lo=0x30, hi=0x40), random_operand(rng, 80, 256, lo=0x30, hi=0x40)
+    check(A, B, nv.NVFP4, "bf16-out", out_dtype=torch.bfloat16)
+    out = torch.full((96, 128), -1.0, device="cuda")
+    nv.gemm(dev(A), dev(B), out=out[:, :80])
+    ref = oracle.gemm_nt(A, B)
+    assert_gemm_close(to_np(out[:, :80]), ref, oracle.gemm_nt(A, B, take_abs=True), "ldc")
+    assert torch.all(out[:, 80:] == -1.0)
+
+
+def test_7b_shape_sampled():
+    # gate projection of the 7B model, tokens = 4096: [4096, 4096] x [11008, 4096]^T; 4000
+    # sampled outputs are checked one by one, plus one full output row and column
+    M, N, K = 4096, 11008, 4096
+    X = synth.normal(M, K, 1.0, 31)
+    W = synth.normal(N, K, 0.02, 32)
+    A, B = oracle.quantize(X, 1), oracle.quantize(W, 1)
+    print("[case] gemm 7B gate sampled", flush=True)
+    Y = nv.gemm(dev(A), dev(B))
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(3)
+    ii = np.concatenate([rng.integers(0, M, 4000), np.full(N, 1234), np.arange(M)])
+    jj = np.concatenate([rng.integers(0, N, 4000), np.arange(N), np.full(M, 10007)])
+    ref = oracle.gemm_nt_sample(A, B, ii, jj)
+    ref_abs = oracle.gemm_nt_sample(A, B, ii, jj, take_abs=True)
+    assert_gemm_close(to_np(Y)[ii, jj], ref, ref_abs, "7b-gate")
+
+
+def test_linear_fwd_bwd_against_oracle():
+    # Eqs. 4-6 end to end on a small layer; operands are checked bit-exactly first, then the
+    # three products by tolerance
+    M, N, K = 256, 384, 512
+    X = synth.normal(M, K, 1.0, 41)
+    W = synth.normal(N, K, 0.02, 42)
+    dY = synth.gradient_like(M, N, 43)
+    seed = 1000
+    Xg, Wg, dYg = X.cuda(), W.cuda(), dY.cuda()
+    print("[case] linear fwd/bwd", flush=True)
+    Y = nv.linear_fwd(Xg, Wg)
+    dX, dW = nv.linear_bwd(dYg, Xg, Wg, seed)
+    torch.cuda.synchronize()
+    qx, qw = oracle.quantize(X, 1), oracle.quantize(W, 1)
+    assert_gemm_close(to_np(Y), oracle.gemm_nt(qx, qw), oracle.gemm_nt(qx, qw, take_abs=True), "Y")
+    qdy, qwt = oracle.quantize(dY, 1, oracle.SR, seed), oracle.quantize(W, 0)
+    assert_quant_equal(nv.quantize(dYg, 1, nv.SR, seed), qdy, "Q_SR(dY)")
+    assert_quant_equal(nv.quantize(Wg, 0), qwt, "Q_RtN(W^T)")
+    assert_gemm_close(to_np(dX), oracle.gemm_nt(qdy, qwt), oracle.gemm_nt(qdy, qwt, take_abs=True), "dX")
+    qdyt, qxt = oracle.quantize(dY, 0, oracle.SR, seed + 1), oracle.quantize(X, 0, oracle.SR, seed + 2)
+    assert_quant_equal(nv.quantize(dYg, 0, nv.SR, seed + 1), qdyt, "Q_SR(dY^T)")
+    assert_quant_equal(nv.quantize(Xg, 0, nv.SR, seed + 2), qxt, "Q_SR(X^T)")
+    assert_gemm_close(to_np(dW), oracle.gemm_nt(qdyt, qxt), oracle.gemm_nt(qdyt, qxt, take_abs=True), "dW")
+    # the oracle's own composition agrees too
+    odX, odW = oracle.linear_bwd(dY, X, W, seed)
+    assert np.allclose(to_np(dX), odX, rtol=1e-4, atol=1e-9) and np.allclose(to_np(dW), odW, rtol=1e-4, atol=1e-9)
+
+
+def test_linear_fp32_inputs_bf16_outputs():
+    M, N, K = 128, 96, 256
+    X = synth.normal(M, K, 1.0, 51, torch.float32)
+    W = synth.normal(N, K, 0.05, 52, torch.float32)
+    dY = synth.gradient_like(M, N, 53, dtype=torch.float32)
+    Y = nv.linear_fwd(X.cuda(), W.cuda(), out_dtype=torch.bfloat16)
+    dX, dW = nv.linear_bwd(dY.cuda(), X.cuda(), W.cuda(), 7, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    oY = oracle.linear_fwd(X, W)
+    odX, odW = oracle.linear_bwd(dY, X, W, 7)
+    for got, ref in ((Y, oY), (dX, odX), (dW, odW)):
+        assert np.all(np.abs(to_np(got.float()) - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * np.abs(ref).max())

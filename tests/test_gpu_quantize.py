@@ -1,0 +1,203 @@
+"""GPU parity of nvfp4_quantize / nvfp4_tensor_scale against the CPU oracle: codes, scale bytes
+and the tensor scale must be bit-identical on the same seeded inputs."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2505_19115_amd import synth
+from gpu_util import assert_quant_equal, ofmt, to_np
+
+pytestmark = pytest.mark.gpu
+
+nv = None
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _binding():
+    global nv
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2505_19115_amd import binding
+    nv = binding
+    yield
+
+
+def run_both(x_cpu, axis, rounding, seed, fmt, preset=None, what=""):
+    print(f"[case] {what} shape={tuple(x_cpu.shape)} dtype={x_cpu.dtype} axis={axis} rounding={rounding} "
+          f"seed={seed} fmt={fmt}", flush=True)
+    x = x_cpu.cuda()
+    ts = None if preset is None else torch.tensor([preset], dtype=torch.float32, device="cuda")
+    got = nv.quantize(x, axis, rounding, seed, fmt, tensor_scale=ts)
+    torch.cuda.synchronize()
+    want = oracle.quantize(x_cpu, axis, rounding, seed, ofmt(fmt), g=preset)
+    assert_quant_equal(got, want, what)
+    return got
+
+
+FORMATS = {
+    "nvfp4": lambda: nv.NVFP4,
+    "mxfp4": lambda: nv.MXFP4,
+    "e4m3_b32": lambda: nv.Format(32, nv.SCALE_E4M3, 1),
+    "e4m3_b64": lambda: nv.Format(64, nv.SCALE_E4M3, 1),
+    "e4m3_b128": lambda: nv.Format(128, nv.SCALE_E4M3, 1),
+}
+
+
+def test_config1_fp32_256(monkeypatch):
+    # X, W fp32 [256, 256] ~ N(0,1): row-blocked RtN as the forward GEMM consumes them
+    for seed in (1, 2):
+        x = synth.normal(256, 256, 1.0, seed, torch.float32)
+        run_both(x, 1, nv.RTN, 0, nv.NVFP4, what="config1")
+        run_both(x, 0, nv.RTN, 0, nv.NVFP4, what="config1-cols")
+        run_both(x, 1, nv.SR, 5, nv.NVFP4, what="config1-sr")
+        run_both(x, 0, nv.SR, 5, nv.NVFP4, what="config1-cols-sr")
+
+
+@pytest.mark.parametrize("fmt", list(FORMATS))
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("axis", [1, 0])
+@pytest.mark.parametrize("rounding", [0, 1])
+def test_all_formats_ragged_tiles(fmt, dtype, axis, rounding):
+    # several workgroup tiles in both directions plus ragged tails: 384 rows = 3 row tiles of
+    # 128; 1152 columns = 2.25 column tiles of 512 (bf16) and 4.5 of 256 (fp32)
+    f = FORMATS[fmt]()
+    x = synth.student_t_outliers(384, 1152, seed=11, dtype=dtype)
+    run_both(x, axis, rounding, 1234, f, what=f"{fmt}")
+
+
+@pytest.mark.parametrize("axis", [1, 0])
+@pytest.mark.parametrize("rounding", [0, 1])
+def test_ragged_rows_and_leading_dimension(axis, rounding):
+    # rows = 16 * 19 (one block short of the 32-row lane tile), cols = 16 * 65; the tensor is a
+    # window of a wider one, so rows are not contiguous
+    big = synth.student_t_outliers(304, 1200, seed=12, dtype=torch.bfloat16)
+    xg = big.cuda()[:, 8:8 + 1040]
+    x_cpu = big[:, 8:8 + 1040].contiguous()
+    print(f"[case] window axis={axis} rounding={rounding}", flush=True)
+    got = nv.quantize(xg, axis, rounding, 77, nv.NVFP4)
+    want = oracle.quantize(x_cpu, axis, rounding, 77)
+    assert_quant_equal(got, want, "window")
+
+
+@pytest.mark.parametrize("rounding", [0, 1])
+def test_columns_not_multiple_of_8(rounding):
+    # axis 0 only needs the row count to be a multiple of the block; 1003 columns leave a
+    # 3-column tail and misalign the 8-element random-number groups from row to row
+    big = synth.normal(160, 1008, 1.0, 13, torch.bfloat16)
+    xg = big.cuda()[:, :1003]
+    x_cpu = big[:, :1003].contiguous()
+    print(f"[case] cols=1003 rounding={rounding}", flush=True)
+    got = nv.quantize(xg, 0, rounding, 99, nv.NVFP4)
+    want = oracle.quantize(x_cpu, 0, rounding, 99)
+    assert_quant_equal(got, want, "cols1003")
+    big32 = synth.normal(48, 1004, 1.0, 14, torch.float32)
+    got = nv.quantize(big32.cuda()[:, :1001], 0, rounding, 5, nv.NVFP4)
+    assert_quant_equal(got, oracle.quantize(big32[:, :1001].contiguous(), 0, rounding, 5), "cols1001-f32")
+
+
+def test_software_rounding_path_equals_hardware_convert(monkeypatch):
+    x = synth.student_t_outliers(256, 1024, seed=15, dtype=torch.bfloat16)
+    hw = run_both(x, 1, nv.RTN, 0, nv.NVFP4, what="hw")
+    hw0 = run_both(x, 0, nv.RTN, 0, nv.NVFP4, what="hw-cols")
+    monkeypatch.setenv("NVFP4_SOFT_CONVERT", "1")
+    sw = run_both(x, 1, nv.RTN, 0, nv.NVFP4, what="soft")
+    sw0 = run_both(x, 0, nv.RTN, 0, nv.NVFP4, what="soft-cols")
+    assert torch.equal(hw[0], sw[0]) and torch.equal(hw0[0], sw0[0])
+
+
+def _blocks_with_leader(values, leader):
+    """Rows of 1024 = 64 blocks, each block [leader, 15 values]."""
+    n = (values.size + 14) // 15
+    n = (n + 63) // 64 * 64
+    v = np.concatenate([values, np.zeros(n * 15 - values.size, np.float32)])
+    x = np.empty((n, 16), np.float32)
+    x[:, 0] = leader
+    x[:, 1:] = v.reshape(n, 15)
+    return torch.from_numpy(x.reshape(-1, 1024))
+
+
+def test_every_fp32_value_rounds_like_the_oracle():
+    # blocks [6, v1 .. v15] with g preset to 1 have scale exactly 1, so the element codes are
+    # the rounding of the raw values: every binary32 pattern from 2^-3 to 6 (alternating sign)
+    # plus a strided sample of the smaller ones
+    lo, hi = int(np.float32(0.125).view(np.uint32)), int(np.float32(6.0).view(np.uint32))
+    v = np.concatenate([np.arange(lo, hi + 1, dtype=np.uint32),
+                        np.arange(0, lo, 8191, dtype=np.uint32)]).view(np.float32).copy()
+    v[1::2] *= -1
+    x = _blocks_with_leader(v, 6.0)
+    for rounding, seed in ((nv.RTN, 0), (nv.SR, 3)):
+        run_both(x, 1, rounding, seed, nv.NVFP4, preset=1.0, what="sweep")
+    # saturation: with g = 2^-10 every block scale saturates at 448 (d = 0.4375) and most
+    # scaled values exceed 6
+    w = np.arange(lo, int(np.float32(1e6).view(np.uint32)), 1021, dtype=np.uint32).view(np.float32).copy()
+    w[::2] *= -1
+    xs = _blocks_with_leader(w, 1e6)
+    for rounding, seed in ((nv.RTN, 0), (nv.SR, 4)):
+        run_both(xs, 1, rounding, seed, nv.NVFP4, preset=2.0 ** -10, what="saturate")
+
+
+def test_every_scale_value_encodes_like_the_oracle():
+    # g = fl(1/6) makes 6 g round to exactly 1, so the scale byte is E4M3(block maximum)
+    g = float(np.float32(1.0) / np.float32(6.0))
+    assert np.float32(6.0) * np.float32(g) == np.float32(1.0)
+    hi = int(np.float32(520.0).view(np.uint32))
+    a = np.arange(0, hi, 67, dtype=np.uint32).view(np.float32)
+    n = (a.size // 64) * 64
+    x = np.zeros((n, 16), np.float32)
+    x[:, 5] = a[:n]
+    x[::2, 5] *= -1
+    x[:, 9] = a[:n] * np.float32(0.37)
+    xt = torch.from_numpy(x.reshape(-1, 1024))
+    run_both(xt, 1, nv.RTN, 0, nv.NVFP4, preset=g, what="scale-sweep")
+    run_both(xt, 1, nv.SR, 8, nv.NVFP4, preset=g, what="scale-sweep-sr")
+
+
+def test_degenerate_inputs():
+    z = torch.zeros(32, 64, dtype=torch.bfloat16)
+    z[3, 7] = -0.0
+    for axis in (0, 1):
+        got = run_both(z, axis, nv.SR, 1, nv.NVFP4, what="zeros")
+        assert float(got[2].item()) == 1.0
+    one = torch.zeros(16, 16, dtype=torch.float32)
+    one[2, 3] = -3.0e-41  # subnormal maximum: the tensor scale hits its floor
+    run_both(one, 1, nv.RTN, 0, nv.NVFP4, what="subnormal")
+    run_both(one, 0, nv.RTN, 0, nv.NVFP4, what="subnormal-cols")
+    huge = synth.normal(32, 32, 1.0, 3, torch.float32) * 1e30
+    run_both(huge, 1, nv.RTN, 0, nv.NVFP4, what="huge")
+    run_both(huge, 0, nv.SR, 2, nv.MXFP4, what="huge-mx")
+    tiny = synth.normal(32, 64, 1.0, 4, torch.float32) * 1e-38
+    run_both(tiny, 1, nv.SR, 2, nv.MXFP4, what="tiny-mx")
+    # preset scale far too small: everything saturates
+    x = synth.normal(64, 64, 1.0, 5, torch.bfloat16)
+    run_both(x, 1, nv.RTN, 0, nv.NVFP4, preset=1e-6, what="preset-small")
+    run_both(x, 0, nv.SR, 6, nv.NVFP4, preset=10.0, what="preset-large")
+    # empty tensor: nothing written, scale 1
+    e = torch.empty(0, 64, dtype=torch.bfloat16, device="cuda")
+    c, s, g = nv.quantize(e, 1, nv.RTN, 0, nv.NVFP4)
+    torch.cuda.synchronize()
+    assert c.numel() == 0 and float(g.item()) == 1.0
+
+
+def test_tensor_scale_entry_and_determinism():
+    x = synth.student_t_outliers(1024, 2048, seed=21)
+    xg = x.cuda()
+    g = nv.tensor_scale(xg)
+    assert float(g.item()) == oracle.tensor_scale_from_amax(oracle.tensor_amax(x))
+    win = xg[:, 16:16 + 1000]
+    assert float(nv.tensor_scale(win).item()) == oracle.tensor_scale_from_amax(
+        oracle.tensor_amax(x[:, 16:16 + 1000].contiguous()))
+    a = nv.quantize(xg, 0, nv.SR, 42)
+    b = nv.quantize(xg, 0, nv.SR, 42)
+    c = nv.quantize(xg, 0, nv.SR, 43)
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    assert not torch.equal(a[0], c[0]) and torch.equal(a[1], c[1])
+
+
+@pytest.mark.parametrize("axis,rounding,seed", [(1, 0, 0), (0, 0, 0), (1, 1, 3), (0, 1, 7)])
+def test_full_size_quantizer_sweep_tensor(axis, rounding, seed):
+    # the benchmark's tensor: bf16 [8192, 8192], Student-t(3) * 0.02 with 0.1 % outliers x100,
+    # compared element by element (the oracle needs a few seconds per run)
+    x = synth.student_t_outliers(8192, 8192, seed=100)
+    run_both(x, axis, rounding, seed, nv.NVFP4, what="config2")
