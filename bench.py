@@ -1,0 +1,170 @@
+#!/usr/bin/env python3
+"""Benchmark of the NVFP4 quantized linear layer on one MI355X.
+
+One "step" = forward + backward + update (Eqs. 4-6 of the paper) of the three linear layers of
+a Llama2-7B SwiGLU MLP at 4096 tokens: every tensor-maximum pass, every row/column quantizer
+(RtN forward, Philox SR backward) and all nine block-scaled GEMMs, through the C ABI.  Inputs are
+synthetic (seeded Gaussians, gradient tensor with sparse outliers) and resident in HBM before
+the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+PEAK_F16_TFLOPS = 2500.0   # dense fp16/bf16 MFMA: the instruction the exact NVFP4 GEMM issues
+PEAK_FP4_TFLOPS = 10100.0  # dense FP4 MFMA: the denominator the headline metric names
+
+
+def event_time_ms(fn, iters, torch, warmup=2):
+    """Average milliseconds per call of fn(i), measured with events on the stream fn launches on."""
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for i in range(iters):
+        fn(i)
+    stop.record()
+    stop.synchronize()
+    return start.elapsed_time(stop) / iters
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
+                    help="HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc runs")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2505_19115_amd import binding as nv
+    from paper_2505_19115_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+    dev = "cuda"
+
+    # ---- workload: the 7B SwiGLU MLP's three linears, tokens = 4096 (batch 2 x seq 2048)
+    M = 4096
+    layers = [("gate", 11008, 4096), ("up", 11008, 4096), ("down", 4096, 11008)]
+    data = []
+    for idx, (name, N, K) in enumerate(layers):
+        X = synth.normal(M, K, 1.0, 100 + idx).to(dev)
+        W = synth.normal(N, K, 0.02, 200 + idx).to(dev)
+        dY = synth.gradient_like(M, N, 300 + idx).to(dev)
+        f = nv.NVFP4.c()
+        wf = torch.empty(nv.lib.nvfp4_linear_fwd_workspace_bytes(M, N, K, C.byref(f)), dtype=torch.uint8, device=dev)
+        wb = torch.empty(nv.lib.nvfp4_linear_bwd_workspace_bytes(M, N, K, C.byref(f)), dtype=torch.uint8, device=dev)
+        Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+        dX = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
+        dW = torch.empty((N, K), dtype=torch.bfloat16, device=dev)
+        data.append((name, N, K, X, W, dY, wf, wb, Y, dX, dW))
+    flop_per_step = sum(3 * 2 * M * N * K for _, N, K in layers)
+
+    def step(s):
+        for name, N, K, X, W, dY, wf, wb, Y, dX, dW in data:
+            nv.linear_fwd(X, W, workspace=wf, out=Y)
+            nv.linear_bwd(dY, X, W, seed=1000 + 3 * s, workspace=wb, out=(dX, dW))
+
+    for s in range(args.warmup):
+        step(s)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(args.warmup + s)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    tflops = flop_per_step / (elapsed / args.steps) / 1e12
+
+    # ---- dominant kernel: the block-scaled GEMM at the gate/up shape (same launch as in step)
+    name, N, K, X, W, dY, wf, wb, Y, dX, dW = data[0]
+    qa, qb = nv.quantize(X, 1), nv.quantize(W, 1)
+    gemm_ms = event_time_ms(lambda i: nv.gemm(qa, qb, out=Y), max(args.steps, 5), torch)
+    gemm_tflops = 2.0 * M * N * K / (gemm_ms * 1e-3) / 1e12
+    traffic = None
+    if os.path.exists(args.traffic_json):
+        try:
+            traffic = json.load(open(args.traffic_json)).get("gemm_gate_bytes_per_launch")
+        except Exception:
+            traffic = None
+    roofline = {"kernel": "gemm_nt_f16_kernel (gate: 4096x11008x4096)", "bound": "mfma",
+                "achieved": round(gemm_tflops, 2), "peak": PEAK_F16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(gemm_tflops / PEAK_F16_TFLOPS, 4),
+                "frac_of_fp4_peak": round(gemm_tflops / PEAK_FP4_TFLOPS, 4),
+                "avg_launch_ms": round(gemm_ms, 4), "traffic": traffic}
+
+    # ---- quantizer sweep tensor (second half of the metric): bf16 [8192, 8192].
+    # Four different tensors are cycled (512 MiB in total) so that the 256 MB last-level cache
+    # cannot serve the reads of the next call: the rate is an HBM rate.
+    NQ = 4
+    xqs = [synth.student_t_outliers(8192, 8192, seed=100 + i).to(dev) for i in range(NQ)]
+    gs = [nv.tensor_scale(x) for x in xqs]
+    nel = xqs[0].numel()
+    quant = {}
+    for label, axis, rnd in (("rows_rtn", 1, nv.RTN), ("rows_sr", 1, nv.SR), ("cols_rtn", 0, nv.RTN), ("cols_sr", 0, nv.SR)):
+        outs = [nv.quantize(xqs[i], axis, rnd, 1, tensor_scale=gs[i]) for i in range(NQ)]
+        ms = event_time_ms(lambda i: nv.quantize(xqs[i % NQ], axis, rnd, 1, tensor_scale=gs[i % NQ], out=outs[i % NQ]),
+                           12, torch, warmup=NQ)
+        gbs = nel * 2.5625 / (ms * 1e-3) / 1e9
+        quant[label] = {"ms": round(ms, 4), "GB/s": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
+    outs = [nv.quantize(xqs[i], 1, nv.RTN, 0) for i in range(NQ)]
+    ms = event_time_ms(lambda i: nv.quantize(xqs[i % NQ], 1, nv.RTN, 0, out=outs[i % NQ]), 12, torch, warmup=NQ)
+    gbs = nel * 4.5625 / (ms * 1e-3) / 1e9
+    quant["rows_rtn_with_amax_pass"] = {"ms": round(ms, 4), "GB/s": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
+    quant["bytes_per_element"] = {"preset_scale": 2.5625, "with_amax_pass": 4.5625}
+    del xqs, outs
+
+    # ---- the oracle on the host cores, bounded sample of the same workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        Ms = Ns = Ks = 2048
+        Xs, Ws, dYs = synth.normal(Ms, Ks, 1.0, 1), synth.normal(Ns, Ks, 0.02, 2), synth.gradient_like(Ms, Ns, 3)
+        t0 = time.perf_counter()
+        oracle.linear_fwd(Xs, Ws)
+        oracle.linear_bwd(dYs, Xs, Ws, 5)
+        dt = time.perf_counter() - t0
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        cores = min(cores, os.cpu_count() or cores)
+        cpu = {"value": round(3 * 2 * Ms * Ns * Ks / dt / 1e12, 6), "unit": "TFLOP/s", "cores": cores,
+               "kind": "oracle", "seconds": round(dt, 2),
+               "sample": f"one linear fwd+bwd (Eqs. 4-6), M=N=K={Ms}, NVFP4: 6 quantize calls + 3 fp64 GEMMs"}
+
+    line = {
+        "metric": "NVFP4 linear fwd+bwd TFLOP/s (% FP4 MFMA peak); quantize GB/s (% HBM peak)",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "e2m1 codes x e4m3 scales, expanded exactly to f16 for MFMA, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": "Llama2-7B SwiGLU MLP linears fwd+bwd (gate, up, down), tokens=4096: "
+                               "9 GEMMs + 18 quantize calls + tensor-maximum passes per step, bf16 in",
+                   "M": M, "layers": [[n, N, K] for n, N, K in layers], "format": "NVFP4 (block 16, E4M3, tensor scale)",
+                   "rounding": "fwd RtN; bwd/update SR (Philox4x32-10)"},
+        "frac_of_fp4_peak": round(tflops / PEAK_FP4_TFLOPS, 4),
+        "roofline": roofline, "quantize": quant, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

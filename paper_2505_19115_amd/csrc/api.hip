@@ -36,11 +36,12 @@ bool use_hw_convert()
     return !(e && e[0] == '1');
 }
 
+// An empty tensor (rows or cols 0) may come with a null data pointer.
 nvfp4_status check_tensor(const void *x, int dt, int64_t rows, int64_t cols, int64_t ld)
 {
-    if (!x) return NVFP4_EINVAL;
     if (!valid_dtype(dt)) return NVFP4_EINVAL;
     if (rows < 0 || cols < 0 || ld < cols) return NVFP4_ESHAPE;
+    if (!x && rows > 0 && cols > 0) return NVFP4_EINVAL;
     if (!aligned16(x) || (ld * elem_size(dt)) % 16 != 0) return NVFP4_EALIGN;
     return NVFP4_OK;
 }
@@ -149,7 +150,8 @@ nvfp4_status nvfp4_quantize(const void *x, nvfp4_dtype dt, int64_t rows, int64_t
     if (s != NVFP4_OK) return s;
     s = check_tensor(x, dt, rows, cols, ld);
     if (s != NVFP4_OK) return s;
-    if (!codes || !scales || !tensor_scale) return NVFP4_EINVAL;
+    const bool empty = rows == 0 || cols == 0;
+    if (!tensor_scale || (!empty && (!codes || !scales))) return NVFP4_EINVAL;
     if (axis != 0 && axis != 1) return NVFP4_EINVAL;
     if (rounding != NVFP4_RTN && rounding != NVFP4_SR) return NVFP4_EINVAL;
     if (flags & ~NVFP4_PRESET_TSCALE) return NVFP4_EINVAL;
@@ -175,7 +177,7 @@ nvfp4_status nvfp4_quantize(const void *x, nvfp4_dtype dt, int64_t rows, int64_t
             q.g_mode = G_FROM_AMAX;
         }
     }
-    if (rows == 0 || cols == 0) {
+    if (empty) {
         // nothing to encode; still report the scale an empty tensor gets (1, or the preset)
         if (q.g_mode == G_FROM_AMAX)
             return launch_finalize_tensor_scale(reinterpret_cast<const uint32_t *>(q.g_src), tensor_scale, st) == hipSuccess
