@@ -23,16 +23,22 @@ typedef float float16_t __attribute__((ext_vector_type(16)));
 
 constexpr int KT = 128;      // contraction elements per LDS tile
 constexpr int KTB = KT / 2;  // bytes of codes per row per tile
-constexpr int SROW = 8;      // LDS bytes reserved per row for the tile's scale bytes
+constexpr int SROW = 16;     // LDS bytes per row for the tile's scales: 8 fp16 values, one per 16 elements
 
-// 16-byte chunk c (0..3) of tile row r lives at chunk slot c ^ ((r >> 1) & 3): 8 consecutive
-// rows reading the same logical chunk then hit 8 different 16-byte bank groups.
+// LDS placement of the codes of one tile row r (64 bytes = 4 chunks of 16 = 8 quarters of 8):
+// chunk c sits in chunk slot c ^ ((r >> 1) & 3) and, inside the chunk, the two 8-byte quarters
+// swap places when bit 3 of r is set.  With that, 16 consecutive rows reading the same logical
+// quarter (one ds_read_b64 wavefront pass) touch 16 different 8-byte bank pairs, and a 16-byte
+// store of a whole chunk by 8 consecutive threads covers 128 contiguous bytes: no conflicts
+// either way (measured 128 B/clk/CU, the LDS peak).
 __device__ __forceinline__ int swz(int r, int c) { return r * KTB + ((c ^ ((r >> 1) & 3)) << 4); }
+__device__ __forceinline__ int swz_quarter(int r, int c, int sub) { return swz(r, c) + ((sub ^ ((r >> 3) & 1)) << 3); }
 
 // 8 codes (one dword) of one block -> 8 fp16 values times the block scale.
-// s2 = fp16 pair holding scale * 2^-8 twice.
-__device__ __forceinline__ half8_t dequant8(uint32_t w, half2_t s2)
+// s = fp16 holding scale * 2^-8; the convert multiplies the codes by 2^8.
+__device__ __forceinline__ half8_t dequant8(uint32_t w, _Float16 s)
 {
+    const half2_t s2 = {s, s};
     half2_t h0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 256.0f, 0) * s2;
     half2_t h1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 256.0f, 1) * s2;
     half2_t h2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 256.0f, 2) * s2;
@@ -43,14 +49,6 @@ __device__ __forceinline__ half8_t dequant8(uint32_t w, half2_t s2)
     return r;
 }
 
-// E4M3 byte -> fp16 pair of scale * 2^-8: the byte shifted into fp16's exponent/mantissa
-// fields is that value for normal and subnormal bytes alike (fp16 bias 15 = E4M3 bias 7 + 8).
-__device__ __forceinline__ half2_t scale_pair(uint32_t byte)
-{
-    uint32_t b = byte << 7;
-    return __builtin_bit_cast(half2_t, b | (b << 16));
-}
-
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
 {
     uint32_t u = f2u(f);
@@ -58,29 +56,49 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
     return (uint16_t)(u >> 16);
 }
 
-// Workgroup: 256 threads = 2 x 2 waves; a wave owns (32 TA) x (32 TB) outputs as TA x TB MFMA
-// tiles.  Per 128-wide K tile the 64 code bytes of each operand row sit in LDS as four
-// 16-byte chunks; lane (r = lane % 32, h = lane / 32) expands chunk 2p + h (p = 0, 1), and
-// its dword t feeds the t-th MFMA of that half tile.  A and B use the same assignment of
-// contraction indices to (lane half, slot), which is all the instruction requires.
-template <int B, int TA, int TB, int OUT_DT>
-__global__ __launch_bounds__(256) void gemm_nt_f16_kernel(GemmArgs P)
+// Tile geometry.  A workgroup is WM x WN waves; a wave owns (32 TA) x (32 TB) outputs as
+// TA x TB MFMA tiles.  The production shape is 2 x 4 waves of 4 x 2 tiles: 256 x 256 per
+// workgroup, 128 accumulator registers per wave, so TWO waves fit on every SIMD.  That is
+// the point of the shape: measured on gfx950, one wave alone issues a VALU instruction only
+// every ~8 cycles, two waves per SIMD reach the full rate of one per 4 cycles, and the
+// operand expansion costs 8 (TA + TB) / (TA TB) = 6 VALU instructions per 32-cycle MFMA.
+//
+// Per 128-wide K tile the 64 code bytes of each operand row sit in LDS as four 16-byte chunks
+// and its 8 block scales as fp16 values (scale * 2^-8; for blocks wider than 16 the value is
+// repeated).  Lane (r = lane % 32, h = lane / 32) owns chunk 2p + h (p = 0, 1) of its row:
+// two 8-byte "quarters" of 16 codes = one 16-element block each; dword t of a quarter feeds
+// one MFMA step.  A and B use the same assignment of contraction indices to (lane half,
+// slot), which is all the instruction requires.
+template <int B, int WM, int WN, int TA, int TB, int OUT_DT, bool KTAIL>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
 {
-    constexpr int BM = 64 * TA, BN = 64 * TB;
-    constexpr int SPT = KT / B;  // scale bytes per row per tile
-    __shared__ __attribute__((aligned(16))) uint8_t sA[BM * KTB];
-    __shared__ __attribute__((aligned(16))) uint8_t sB[BN * KTB];
-    __shared__ __attribute__((aligned(16))) uint8_t sSA[BM * SROW];
-    __shared__ __attribute__((aligned(16))) uint8_t sSB[BN * SROW];
+    constexpr int NT = 64 * WM * WN;
+    constexpr int BM = 32 * TA * WM, BN = 32 * TB * WN;
+    constexpr int SPT = KT / B;  // scale bytes per row per tile in global memory
+    constexpr int VALU_PER_MFMA = (8 * (TA + TB) + TA * TB - 1) / (TA * TB);
+    constexpr int A_BYTES = BM * KTB, B_BYTES = BN * KTB, SA_BYTES = BM * SROW, SB_BYTES = BN * SROW;
+    constexpr int STAGE = A_BYTES + B_BYTES + SA_BYTES + SB_BYTES;
+    constexpr int CA = BM * 4 / NT, CB = BN * 4 / NT;  // 16-byte chunks per thread per tile
+    static_assert(BM * 4 % NT == 0 && BN * 4 % NT == 0 && BM + BN <= NT * 2, "tile/thread mismatch");
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
     const int r = lane & 31, h = lane >> 5;
-    const int64_t m0 = (int64_t)blockIdx.y * BM, n0 = (int64_t)blockIdx.x * BN;
+    // consecutive workgroup ids land on different XCDs (8 of them, each with its own L2): give
+    // each XCD a contiguous band of the tile grid so that its workgroups share operand tiles
+    const int ntx = (int)((P.N + BN - 1) / BN), nty = (int)((P.M + BM - 1) / BM);
+    const int ntiles = ntx * nty;
+    int wg = blockIdx.x;
+    {
+        const int per = (ntiles + 7) / 8, xcd = wg & 7, slot = wg >> 3;
+        const int full = ntiles - (per - 1) * 8;  // XCDs that receive `per` tiles (others per-1)
+        wg = xcd < full ? xcd * per + slot : full * per + (xcd - full) * (per - 1) + slot;
+    }
+    const int64_t m0 = (int64_t)(wg / ntx) * BM, n0 = (int64_t)(wg % ntx) * BN;
     const int64_t Kb = P.K >> 1;          // code bytes per row
     const int64_t Ks = P.K / B;           // scale bytes per row
     const int nkt = (int)((P.K + KT - 1) / KT);
-    const bool vec_scales = (P.K % KT) == 0;
 
     float16_t acc[TA][TB];
 #pragma unroll
@@ -90,116 +108,250 @@ __global__ __launch_bounds__(256) void gemm_nt_f16_kernel(GemmArgs P)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
 
-    uint4 ga[TA], gb[TB];
-    uint64_t gsa = 0, gsb = 0;
-
-    auto fetch = [&](int kt) {
+    // ---- global -> registers -> LDS staging of one K tile.
+    // Rows past the matrix edge are clamped to the last row (their products land in outputs
+    // that are never stored), so the code loads carry no predicate.  A K tail (K not a
+    // multiple of 128) is handled through the scales alone: chunks past K are read from a
+    // clamped address and meet zero scales.
+    constexpr int NSR = (BM + BN + NT - 1) / NT;  // scale rows per thread
+    uint4 ga[CA], gb[CB];
+    uint64_t gs[NSR];
+    uint32_t offA[CA], offB[CB];  // byte offset of this thread's chunks inside a K tile column
+    int ldsA[CA], ldsB[CB];
 #pragma unroll
-        for (int u = 0; u < TA; ++u) {
-            const int qd = tid + 256 * u, row = qd >> 2, ch = qd & 3;
-            const int64_t kb = (int64_t)kt * KTB + ch * 16;
-            ga[u] = (m0 + row < P.M && kb < Kb)
-                        ? *reinterpret_cast<const uint4 *>(P.A_codes + (m0 + row) * Kb + kb)
-                        : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int u = 0; u < TB; ++u) {
-            const int qd = tid + 256 * u, row = qd >> 2, ch = qd & 3;
-            const int64_t kb = (int64_t)kt * KTB + ch * 16;
-            gb[u] = (n0 + row < P.N && kb < Kb)
-                        ? *reinterpret_cast<const uint4 *>(P.B_codes + (n0 + row) * Kb + kb)
-                        : make_uint4(0, 0, 0, 0);
-        }
-        auto fetch_scales = [&](const uint8_t *base, int64_t row_g, int64_t nrows) -> uint64_t {
-            uint64_t s = 0;
-            if (row_g < nrows) {
-                const uint8_t *p = base + row_g * Ks + (int64_t)kt * SPT;
-                if (vec_scales) {
-                    if (SPT == 8) s = *reinterpret_cast<const uint64_t *>(p);
-                    else if (SPT == 4) s = *reinterpret_cast<const uint32_t *>(p);
-                    else if (SPT == 2) s = *reinterpret_cast<const uint16_t *>(p);
-                    else s = *p;
-                } else {
-                    const int64_t left = Ks - (int64_t)kt * SPT;
-#pragma unroll
-                    for (int t = 0; t < SPT; ++t)
-                        if (t < left) s |= (uint64_t)p[t] << (8 * t);
-                }
-            }
-            return s;
-        };
-        if (tid < BM) gsa = fetch_scales(P.A_scales, m0 + tid, P.M);
-        if (tid < BN) gsb = fetch_scales(P.B_scales, n0 + tid, P.N);
-    };
-
-    auto stash = [&]() {
-#pragma unroll
-        for (int u = 0; u < TA; ++u) {
-            const int qd = tid + 256 * u;
-            *reinterpret_cast<uint4 *>(sA + swz(qd >> 2, qd & 3)) = ga[u];
-        }
-#pragma unroll
-        for (int u = 0; u < TB; ++u) {
-            const int qd = tid + 256 * u;
-            *reinterpret_cast<uint4 *>(sB + swz(qd >> 2, qd & 3)) = gb[u];
-        }
-        if (tid < BM) *reinterpret_cast<uint64_t *>(sSA + tid * SROW) = gsa;
-        if (tid < BN) *reinterpret_cast<uint64_t *>(sSB + tid * SROW) = gsb;
-    };
-
-    fetch(0);
-    for (int kt = 0; kt < nkt; ++kt) {
-        __syncthreads();
-        stash();
-        __syncthreads();
-        if (kt + 1 < nkt) fetch(kt + 1);
-
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            const int ch = 2 * p + h;  // this lane's chunk: tile elements 32 ch .. 32 ch + 31
-            uint4 ca[TA], cb[TB];
-            uint32_t sca[TA], scb[TB];  // the chunk's scale bytes (two for B = 16, else one)
-#pragma unroll
-            for (int a = 0; a < TA; ++a) {
-                const int row = wm * 32 * TA + 32 * a + r;
-                ca[a] = *reinterpret_cast<const uint4 *>(sA + swz(row, ch));
-                if (B == 16)
-                    sca[a] = *reinterpret_cast<const uint16_t *>(sSA + row * SROW + 2 * ch);
-                else
-                    sca[a] = sSA[row * SROW + (32 * ch) / B];
-            }
-#pragma unroll
-            for (int b = 0; b < TB; ++b) {
-                const int row = wn * 32 * TB + 32 * b + r;
-                cb[b] = *reinterpret_cast<const uint4 *>(sB + swz(row, ch));
-                if (B == 16)
-                    scb[b] = *reinterpret_cast<const uint16_t *>(sSB + row * SROW + 2 * ch);
-                else
-                    scb[b] = sSB[row * SROW + (32 * ch) / B];
-            }
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                half8_t fa[TA], fb[TB];
-#pragma unroll
-                for (int a = 0; a < TA; ++a) {
-                    const uint32_t w = t == 0 ? ca[a].x : t == 1 ? ca[a].y : t == 2 ? ca[a].z : ca[a].w;
-                    const uint32_t sb = (B == 16 && t >= 2) ? (sca[a] >> 8) : (sca[a] & 0xFFu);
-                    fa[a] = dequant8(w, scale_pair(sb));
-                }
-#pragma unroll
-                for (int b = 0; b < TB; ++b) {
-                    const uint32_t w = t == 0 ? cb[b].x : t == 1 ? cb[b].y : t == 2 ? cb[b].z : cb[b].w;
-                    const uint32_t sb = (B == 16 && t >= 2) ? (scb[b] >> 8) : (scb[b] & 0xFFu);
-                    fb[b] = dequant8(w, scale_pair(sb));
-                }
-#pragma unroll
-                for (int a = 0; a < TA; ++a)
-#pragma unroll
-                    for (int b = 0; b < TB; ++b)
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[a], fb[b], acc[a][b], 0, 0, 0);
-            }
-        }
+    for (int u = 0; u < CA; ++u) {
+        const int qd = tid + NT * u, row = qd >> 2, ch = qd & 3;
+        const int64_t gr = m0 + row < P.M ? m0 + row : P.M - 1;
+        offA[u] = (uint32_t)(gr * Kb + ch * 16);
+        ldsA[u] = swz(row, ch);
     }
+#pragma unroll
+    for (int u = 0; u < CB; ++u) {
+        const int qd = tid + NT * u, row = qd >> 2, ch = qd & 3;
+        const int64_t gr = n0 + row < P.N ? n0 + row : P.N - 1;
+        offB[u] = (uint32_t)(gr * Kb + ch * 16);
+        ldsB[u] = A_BYTES + swz(row, ch);
+    }
+    const bool swap_halves = ((tid >> 2) & 8) != 0;  // NT is a multiple of 64: same for all u
+    const uint8_t *srow_ptr[NSR];
+    bool srow_on[NSR];
+#pragma unroll
+    for (int u = 0; u < NSR; ++u) {
+        const int srow = tid + NT * u;
+        const bool isA = srow < BM;
+        int64_t gr = isA ? m0 + srow : n0 + (srow - BM);
+        const int64_t nrows = isA ? P.M : P.N;
+        gr = gr < nrows ? gr : nrows - 1;
+        srow_on[u] = srow < BM + BN;
+        srow_ptr[u] = (isA ? P.A_scales : P.B_scales) + gr * Ks;
+    }
+    const int64_t last_chunk = Kb - 16;
+    auto fetch = [&](int kt) {
+        const int64_t kb = (int64_t)kt * KTB;
+        const uint8_t *pa = P.A_codes + kb, *pb = P.B_codes + kb;
+        if (!KTAIL) {
+#pragma unroll
+            for (int u = 0; u < CA; ++u) ga[u] = *reinterpret_cast<const uint4 *>(pa + offA[u]);
+#pragma unroll
+            for (int u = 0; u < CB; ++u) gb[u] = *reinterpret_cast<const uint4 *>(pb + offB[u]);
+#pragma unroll
+            for (int u = 0; u < NSR; ++u) {
+                if (!srow_on[u]) continue;
+                const uint8_t *sp = srow_ptr[u] + (int64_t)kt * SPT;
+                if (SPT == 8) gs[u] = *reinterpret_cast<const uint64_t *>(sp);
+                else if (SPT == 4) gs[u] = *reinterpret_cast<const uint32_t *>(sp);
+                else if (SPT == 2) gs[u] = *reinterpret_cast<const uint16_t *>(sp);
+                else gs[u] = *sp;
+            }
+        } else {
+            // K tail present: clamp chunk addresses, assemble scale bytes one by one, zero past K
+#pragma unroll
+            for (int u = 0; u < CA; ++u) {
+                const int64_t c = kb + ((tid + NT * u) & 3) * 16;
+                ga[u] = *reinterpret_cast<const uint4 *>(pa + offA[u] - (c > last_chunk ? c - last_chunk : 0));
+            }
+#pragma unroll
+            for (int u = 0; u < CB; ++u) {
+                const int64_t c = kb + ((tid + NT * u) & 3) * 16;
+                gb[u] = *reinterpret_cast<const uint4 *>(pb + offB[u] - (c > last_chunk ? c - last_chunk : 0));
+            }
+            const int64_t left = Ks - (int64_t)kt * SPT;
+#pragma unroll
+            for (int u = 0; u < NSR; ++u) {
+                if (!srow_on[u]) continue;
+                const uint8_t *sp = srow_ptr[u] + (int64_t)kt * SPT;
+                uint64_t sv = 0;
+#pragma unroll
+                for (int t = 0; t < SPT; ++t)
+                    if (t < left) sv |= (uint64_t)sp[t] << (8 * t);
+                gs[u] = sv;
+            }
+        }
+    };
+    // LDS scale layout: [4 chunks of 32 elements][BM + BN rows] dwords, each dword = the fp16
+    // scales (byte << 7 = fp16(scale * 2^-8), exact for normal and subnormal E4M3 bytes alike
+    // because fp16's bias is E4M3's plus 8) of the chunk's two 16-element blocks; a wave reads
+    // 32 consecutive rows of one chunk.  For blocks wider than 16 the value is repeated.
+    auto stash = [&](int stage) {
+        uint8_t *base = lds + stage * STAGE;
+#pragma unroll
+        for (int u = 0; u < CA; ++u) {
+            const uint4 v = ga[u];
+            *reinterpret_cast<uint4 *>(base + ldsA[u]) = swap_halves ? make_uint4(v.z, v.w, v.x, v.y) : v;
+        }
+#pragma unroll
+        for (int u = 0; u < CB; ++u) {
+            const uint4 v = gb[u];
+            *reinterpret_cast<uint4 *>(base + ldsB[u]) = swap_halves ? make_uint4(v.z, v.w, v.x, v.y) : v;
+        }
+        uint32_t *sS = reinterpret_cast<uint32_t *>(base + A_BYTES + B_BYTES);
+#pragma unroll
+        for (int u = 0; u < NSR; ++u) {
+            if (!srow_on[u]) continue;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t b0 = (uint32_t)(gs[u] >> (8 * ((32 * j) / B))) & 0xFFu;
+                const uint32_t b1 = (uint32_t)(gs[u] >> (8 * ((32 * j + 16) / B))) & 0xFFu;
+                sS[j * (BM + BN) + tid + NT * u] = (b0 << 7) | (b1 << 23);
+            }
+        }
+    };
+
+    // ---- LDS -> registers.  A lane reads quarter (p, sub) of rows (frag base + r): its byte
+    // offset inside a row is one of four lane constants, the rest are immediates.
+    struct Quarter {
+        uint2 ca[TA], cb[TB];
+    };
+    struct Scales {  // two fp16 scales (first and second block of the lane's 32-element chunk)
+        uint32_t sa[TA], sb[TB];
+    };
+    int qoff[4];  // [2 p + sub]
+#pragma unroll
+    for (int q = 0; q < 4; ++q) qoff[q] = swz_quarter(r, 2 * (q >> 1) + h, q & 1);
+    const int soff = (h * (BM + BN) + r) * 4;
+    auto load_quarter = [&](int stage, int q, Quarter &Q) {
+        const uint8_t *sA = lds + stage * STAGE + qoff[q], *sB = sA + A_BYTES;
+#pragma unroll
+        for (int a = 0; a < TA; ++a)
+            Q.ca[a] = *reinterpret_cast<const uint2 *>(sA + (wm * 32 * TA + 32 * a) * KTB);
+#pragma unroll
+        for (int b = 0; b < TB; ++b)
+            Q.cb[b] = *reinterpret_cast<const uint2 *>(sB + (wn * 32 * TB + 32 * b) * KTB);
+    };
+    auto load_scales = [&](int stage, int p, Scales &S) {
+        const uint8_t *sS = lds + stage * STAGE + A_BYTES + B_BYTES + soff + 2 * p * (BM + BN) * 4;
+#pragma unroll
+        for (int a = 0; a < TA; ++a) S.sa[a] = *reinterpret_cast<const uint32_t *>(sS + (wm * 32 * TA + 32 * a) * 4);
+#pragma unroll
+        for (int b = 0; b < TB; ++b) S.sb[b] = *reinterpret_cast<const uint32_t *>(sS + (BM + wn * 32 * TB + 32 * b) * 4);
+    };
+    struct Frags {
+        half8_t a[TA], b[TB];
+    };
+    // operands of MFMA step (q, t): dword t of quarter q, scaled by the quarter's block scale
+    auto expand = [&](const Quarter &Q, const Scales &S, int q, int t, Frags &F) {
+#pragma unroll
+        for (int a = 0; a < TA; ++a) {
+            const half2_t sp = __builtin_bit_cast(half2_t, S.sa[a]);
+            F.a[a] = dequant8(t == 0 ? Q.ca[a].x : Q.ca[a].y, (q & 1) ? sp[1] : sp[0]);
+        }
+#pragma unroll
+        for (int b = 0; b < TB; ++b) {
+            const half2_t sp = __builtin_bit_cast(half2_t, S.sb[b]);
+            F.b[b] = dequant8(t == 0 ? Q.cb[b].x : Q.cb[b].y, (q & 1) ? sp[1] : sp[0]);
+        }
+    };
+    auto mma = [&](const Frags &F) {
+#pragma unroll
+        for (int a = 0; a < TA; ++a)
+#pragma unroll
+            for (int b = 0; b < TB; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(F.a[a], F.b[b], acc[a][b], 0, 0, 0);
+    };
+
+    // Software pipeline, continuous across K tiles (8 MFMA steps of TA*TB MFMAs per tile; the
+    // operands of step s+1 are expanded under the MFMAs of step s).  On entry to iteration kt
+    // the LDS stage kt & 1 holds tile kt; Qa holds its quarter 0, S0 the scales of its first
+    // half, F0 the operands of its first step.  Within the iteration:
+    //   top      global loads of tile kt+1 -> registers; LDS loads of quarter 1 and of S1
+    //   steps    quarter q+1 is loaded from LDS while quarter q is multiplied
+    //   step 5|6 tile kt+1 -> other LDS stage, ONE barrier, LDS loads of its quarter 0 / S0
+    //   step 7   already expands the first operands of tile kt+1.
+    // After the barrier nobody reads stage kt & 1 again (all four quarters are in registers),
+    // so the next iteration may overwrite it.
+    // The scheduling hints pin "one MFMA, then its share of the expansion work" so that VALU
+    // work is always queued behind an MFMA that holds the matrix pipe for 32 cycles.
+#define NVFP4_INTERLEAVE()                                                  \
+    _Pragma("unroll") for (int i = 0; i < TA * TB; ++i) {                   \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                  \
+        __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER_MFMA, 0);      \
+    }                                                                       \
+    __builtin_amdgcn_sched_barrier(0);
+#define NVFP4_STEP(Qn, Sn, qn, tn, Fn, Fc) \
+    expand(Qn, Sn, qn, tn, Fn);            \
+    mma(Fc);                               \
+    NVFP4_INTERLEAVE()
+
+    Quarter Qa, Qb;
+    Scales S0, S1;
+    Frags F0, F1;
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    load_quarter(0, 0, Qa);
+    load_scales(0, 0, S0);
+    expand(Qa, S0, 0, 0, F0);
+#define NVFP4_TILE(stage, kt)                     \
+    {                                             \
+        fetch((kt) + 1);                          \
+        load_quarter(stage, 1, Qb);               \
+        load_scales(stage, 1, S1);                \
+        __builtin_amdgcn_sched_barrier(0);        \
+        NVFP4_STEP(Qa, S0, 0, 1, F1, F0)          \
+        NVFP4_STEP(Qb, S0, 1, 0, F0, F1)          \
+        load_quarter(stage, 2, Qa);               \
+        NVFP4_STEP(Qb, S0, 1, 1, F1, F0)          \
+        NVFP4_STEP(Qa, S1, 2, 0, F0, F1)          \
+        load_quarter(stage, 3, Qb);               \
+        NVFP4_STEP(Qa, S1, 2, 1, F1, F0)          \
+        NVFP4_STEP(Qb, S1, 3, 0, F0, F1)          \
+        stash((stage) ^ 1);                       \
+        __syncthreads();                          \
+        load_quarter((stage) ^ 1, 0, Qa);         \
+        load_scales((stage) ^ 1, 0, S0);          \
+        __builtin_amdgcn_sched_barrier(0);        \
+        NVFP4_STEP(Qb, S1, 3, 1, F1, F0)          \
+        NVFP4_STEP(Qa, S0, 0, 0, F0, F1)          \
+    }
+    // two tiles per trip so that the LDS stage (and with it every LDS offset) is a constant
+    int kt = 0;
+    for (; kt + 2 < nkt; kt += 2) {
+        NVFP4_TILE(0, kt)
+        NVFP4_TILE(1, kt + 1)
+    }
+    if (kt + 1 < nkt) {
+        NVFP4_TILE(0, kt)
+        ++kt;
+    }
+#undef NVFP4_TILE
+    {
+        const int stage = kt & 1;  // the last tile
+        load_quarter(stage, 1, Qb);
+        load_scales(stage, 1, S1);
+        __builtin_amdgcn_sched_barrier(0);
+        NVFP4_STEP(Qa, S0, 0, 1, F1, F0)
+        NVFP4_STEP(Qb, S0, 1, 0, F0, F1)
+        load_quarter(stage, 2, Qa);
+        NVFP4_STEP(Qb, S0, 1, 1, F1, F0)
+        NVFP4_STEP(Qa, S1, 2, 0, F0, F1)
+        load_quarter(stage, 3, Qb);
+        NVFP4_STEP(Qa, S1, 2, 1, F1, F0)
+        NVFP4_STEP(Qb, S1, 3, 0, F0, F1)
+        NVFP4_STEP(Qb, S1, 3, 1, F1, F0)
+        mma(F1);
+    }
+#undef NVFP4_STEP
+#undef NVFP4_INTERLEAVE
 
     // epilogue: accumulator register v of lane (r, h) is row 8 (v / 4) + 4 h + v % 4, column r
     const float gg = P.tensor_scales[0] * P.tensor_scales[1];
@@ -222,25 +374,48 @@ __global__ __launch_bounds__(256) void gemm_nt_f16_kernel(GemmArgs P)
         }
 }
 
-template <int B, int TA, int TB>
+template <int B, int WM, int WN, int TA, int TB, bool KTAIL>
 static void launch_f16(const GemmArgs &P, int out_dt, hipStream_t st)
 {
-    constexpr int BM = 64 * TA, BN = 64 * TB;
-    dim3 grid((unsigned)((P.N + BN - 1) / BN), (unsigned)((P.M + BM - 1) / BM));
-    if (out_dt == NVFP4_F32)
-        hipLaunchKernelGGL((gemm_nt_f16_kernel<B, TA, TB, NVFP4_F32>), grid, dim3(256), 0, st, P);
+    constexpr int BM = 32 * TA * WM, BN = 32 * TB * WN;
+    constexpr int LDS_BYTES = 2 * ((BM + BN) * KTB + (BM + BN) * SROW);
+    const unsigned ntiles = (unsigned)(((P.N + BN - 1) / BN) * ((P.M + BM - 1) / BM));
+    if (out_dt == NVFP4_F32) {
+        auto k = gemm_nt_f16_kernel<B, WM, WN, TA, TB, NVFP4_F32, KTAIL>;
+        static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES), true);
+        (void)once;
+        hipLaunchKernelGGL(k, dim3(ntiles), dim3(64 * WM * WN), LDS_BYTES, st, P);
+    } else {
+        auto k = gemm_nt_f16_kernel<B, WM, WN, TA, TB, NVFP4_BF16, KTAIL>;
+        static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES), true);
+        (void)once;
+        hipLaunchKernelGGL(k, dim3(ntiles), dim3(64 * WM * WN), LDS_BYTES, st, P);
+    }
+}
+
+// Tile choice: 256 x 256 (8 waves) when the output has enough such tiles to occupy the 256
+// CUs, else 128 x 128 (4 waves, several workgroups per CU).
+template <int B>
+static void launch_f16_auto(const GemmArgs &P, int out_dt, hipStream_t st)
+{
+    const int64_t big = ((P.M + 255) / 256) * ((P.N + 255) / 256);
+    const bool ktail = (P.K % KT) != 0;  // the large tile is built for K % 128 == 0 only
+    if (big >= 128 && !ktail)
+        launch_f16<B, 2, 4, 4, 2, false>(P, out_dt, st);
+    else if (!ktail)
+        launch_f16<B, 2, 2, 2, 2, false>(P, out_dt, st);
     else
-        hipLaunchKernelGGL((gemm_nt_f16_kernel<B, TA, TB, NVFP4_BF16>), grid, dim3(256), 0, st, P);
+        launch_f16<B, 2, 2, 2, 2, true>(P, out_dt, st);
 }
 
 hipError_t launch_gemm(const GemmArgs &P, int block, int sf, int out_dt, hipStream_t st)
 {
     if (sf != NVFP4_SCALE_E4M3) return hipErrorNotSupported;
     switch (block) {
-    case 16: launch_f16<16, 2, 2>(P, out_dt, st); break;
-    case 32: launch_f16<32, 2, 2>(P, out_dt, st); break;
-    case 64: launch_f16<64, 2, 2>(P, out_dt, st); break;
-    case 128: launch_f16<128, 2, 2>(P, out_dt, st); break;
+    case 16: launch_f16_auto<16>(P, out_dt, st); break;
+    case 32: launch_f16_auto<32>(P, out_dt, st); break;
+    case 64: launch_f16_auto<64>(P, out_dt, st); break;
+    case 128: launch_f16_auto<128>(P, out_dt, st); break;
     default: return hipErrorNotSupported;
     }
     return hipGetLastError();
