@@ -104,12 +104,21 @@ size_t nvfp4_scales_bytes(int64_t rows, int64_t cols, int axis, const nvfp4_form
     return axis == 1 ? (size_t)rows * (size_t)(cols / f->block) : (size_t)cols * (size_t)(rows / f->block);
 }
 
-size_t nvfp4_quantize_workspace_bytes(int64_t, int64_t) { return WS_HEADER; }
+// bytes of per-workgroup partial maxima for one tensor (sized for the strided case, which
+// needs at least as many as the dense one)
+static size_t partials_bytes(int64_t rows, int64_t cols)
+{
+    if (rows <= 0 || cols <= 0) return WS_ALIGN;
+    return align_up(4 * (size_t)tensor_amax_partials(rows, cols, cols + 8));
+}
+
+size_t nvfp4_quantize_workspace_bytes(int64_t rows, int64_t cols) { return WS_HEADER + partials_bytes(rows, cols); }
 
 size_t nvfp4_linear_fwd_workspace_bytes(int64_t M, int64_t N, int64_t K, const nvfp4_format *f)
 {
     if (M <= 0 || N <= 0 || K <= 0 || check_format(f) != NVFP4_OK) return 0;
-    return WS_HEADER + align_up((size_t)M * K / 2) + align_up((size_t)M * (K / f->block)) +
+    const size_t part = partials_bytes(M, K) > partials_bytes(N, K) ? partials_bytes(M, K) : partials_bytes(N, K);
+    return WS_HEADER + part + align_up((size_t)M * K / 2) + align_up((size_t)M * (K / f->block)) +
            align_up((size_t)N * K / 2) + align_up((size_t)N * (K / f->block));
 }
 
@@ -117,7 +126,10 @@ size_t nvfp4_linear_bwd_workspace_bytes(int64_t M, int64_t N, int64_t K, const n
 {
     if (M <= 0 || N <= 0 || K <= 0 || check_format(f) != NVFP4_OK) return 0;
     const size_t B = (size_t)f->block;
-    return WS_HEADER +
+    size_t part = partials_bytes(M, N);
+    if (partials_bytes(N, K) > part) part = partials_bytes(N, K);
+    if (partials_bytes(M, K) > part) part = partials_bytes(M, K);
+    return WS_HEADER + part +
            align_up((size_t)M * N / 2) + align_up((size_t)M * (N / B)) +  // dY blocked along N
            align_up((size_t)K * N / 2) + align_up((size_t)K * (N / B)) +  // W^T blocked along N
            align_up((size_t)N * M / 2) + align_up((size_t)N * (M / B)) +  // dY^T blocked along M
@@ -131,12 +143,12 @@ nvfp4_status nvfp4_tensor_scale(const void *x, nvfp4_dtype dt, int64_t rows, int
     nvfp4_status s = check_tensor(x, dt, rows, cols, ld);
     if (s != NVFP4_OK) return s;
     if (!tensor_scale) return NVFP4_EINVAL;
-    if (!workspace || workspace_bytes < WS_HEADER) return NVFP4_EWORKSPACE;
+    if (!workspace || workspace_bytes < nvfp4_quantize_workspace_bytes(rows, cols)) return NVFP4_EWORKSPACE;
     if (!aligned16(workspace)) return NVFP4_EALIGN;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     uint32_t *bits = reinterpret_cast<uint32_t *>(workspace);
-    if (launch_tensor_amax(x, dt, rows, cols, ld, bits, st) != hipSuccess) return NVFP4_EHIP;
-    if (launch_finalize_tensor_scale(bits, tensor_scale, st) != hipSuccess) return NVFP4_EHIP;
+    uint32_t *partials = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(workspace) + WS_HEADER);
+    if (launch_tensor_amax(x, dt, rows, cols, ld, bits, partials, tensor_scale, st) != hipSuccess) return NVFP4_EHIP;
     return NVFP4_OK;
 }
 
@@ -161,7 +173,7 @@ nvfp4_status nvfp4_quantize(const void *x, nvfp4_dtype dt, int64_t rows, int64_t
     const bool preset = (flags & NVFP4_PRESET_TSCALE) != 0;
     const bool need_amax = f->tensor_scale && !preset;
     if (need_amax) {
-        if (!workspace || workspace_bytes < WS_HEADER) return NVFP4_EWORKSPACE;
+        if (!workspace || workspace_bytes < nvfp4_quantize_workspace_bytes(rows, cols)) return NVFP4_EWORKSPACE;
         if (!aligned16(workspace)) return NVFP4_EALIGN;
     }
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -172,19 +184,15 @@ nvfp4_status nvfp4_quantize(const void *x, nvfp4_dtype dt, int64_t rows, int64_t
             q.g_mode = G_PRESET;
         } else {
             uint32_t *bits = reinterpret_cast<uint32_t *>(workspace);
-            if (launch_tensor_amax(x, dt, rows, cols, ld, bits, st) != hipSuccess) return NVFP4_EHIP;
+            uint32_t *partials = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(workspace) + WS_HEADER);
+            // an empty tensor gets its scale (1) written here; otherwise the quantizer writes it
+            if (launch_tensor_amax(x, dt, rows, cols, ld, bits, partials, empty ? tensor_scale : nullptr, st) != hipSuccess)
+                return NVFP4_EHIP;
             q.g_src = reinterpret_cast<const float *>(bits);
             q.g_mode = G_FROM_AMAX;
         }
     }
-    if (empty) {
-        // nothing to encode; still report the scale an empty tensor gets (1, or the preset)
-        if (q.g_mode == G_FROM_AMAX)
-            return launch_finalize_tensor_scale(reinterpret_cast<const uint32_t *>(q.g_src), tensor_scale, st) == hipSuccess
-                       ? NVFP4_OK
-                       : NVFP4_EHIP;
-        return NVFP4_OK;
-    }
+    if (empty) return NVFP4_OK;  // nothing to encode
     return run_quantize(q, f, st) == hipSuccess ? NVFP4_OK : NVFP4_EHIP;
 }
 
@@ -230,7 +238,8 @@ nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, 
     uint8_t *ws = reinterpret_cast<uint8_t *>(workspace);
     float *ts = reinterpret_cast<float *>(ws);                 // {gX, gW}
     uint32_t *amax = reinterpret_cast<uint32_t *>(ws + 64);    // two maxima
-    uint8_t *p = ws + WS_HEADER;
+    uint32_t *partials = reinterpret_cast<uint32_t *>(ws + WS_HEADER);
+    uint8_t *p = ws + WS_HEADER + (partials_bytes(M, K) > partials_bytes(N, K) ? partials_bytes(M, K) : partials_bytes(N, K));
     uint8_t *xc = p; p += align_up((size_t)M * K / 2);
     uint8_t *xs = p; p += align_up((size_t)M * (K / f->block));
     uint8_t *wc = p; p += align_up((size_t)N * K / 2);
@@ -238,8 +247,8 @@ nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, 
 
     const int gm = f->tensor_scale ? G_FROM_AMAX : G_NONE;
     if (f->tensor_scale) {
-        if (launch_tensor_amax(X, in_dt, M, K, K, amax + 0, st) != hipSuccess) return NVFP4_EHIP;
-        if (launch_tensor_amax(W, in_dt, N, K, K, amax + 1, st) != hipSuccess) return NVFP4_EHIP;
+        if (launch_tensor_amax(X, in_dt, M, K, K, amax + 0, partials, nullptr, st) != hipSuccess) return NVFP4_EHIP;
+        if (launch_tensor_amax(W, in_dt, N, K, K, amax + 1, partials, nullptr, st) != hipSuccess) return NVFP4_EHIP;
     }
     QuantPlan qx{X, in_dt, M, K, K, 1, NVFP4_RTN, 0, xc, xs, reinterpret_cast<const float *>(amax + 0), ts + 0, gm};
     QuantPlan qw{W, in_dt, N, K, K, 1, NVFP4_RTN, 0, wc, wsc, reinterpret_cast<const float *>(amax + 1), ts + 1, gm};
@@ -273,7 +282,11 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
     uint8_t *ws = reinterpret_cast<uint8_t *>(workspace);
     float *ts = reinterpret_cast<float *>(ws);               // {g_dY, g_W, g_dY, g_X}
     uint32_t *amax = reinterpret_cast<uint32_t *>(ws + 64);  // maxima of dY, W, X
-    uint8_t *p = ws + WS_HEADER;
+    uint32_t *partials = reinterpret_cast<uint32_t *>(ws + WS_HEADER);
+    size_t part = partials_bytes(M, N);
+    if (partials_bytes(N, K) > part) part = partials_bytes(N, K);
+    if (partials_bytes(M, K) > part) part = partials_bytes(M, K);
+    uint8_t *p = ws + WS_HEADER + part;
     uint8_t *dyc = p; p += align_up((size_t)M * N / 2);
     uint8_t *dys = p; p += align_up((size_t)M * (N / B));
     uint8_t *wtc = p; p += align_up((size_t)K * N / 2);
@@ -285,10 +298,10 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
 
     const int gm = f->tensor_scale ? G_FROM_AMAX : G_NONE;
     if (f->tensor_scale) {
-        if (launch_tensor_amax(dY, in_dt, M, N, N, amax + 0, st) != hipSuccess) return NVFP4_EHIP;
+        if (launch_tensor_amax(dY, in_dt, M, N, N, amax + 0, partials, nullptr, st) != hipSuccess) return NVFP4_EHIP;
     }
     if (dX) {
-        if (f->tensor_scale && launch_tensor_amax(W, in_dt, N, K, K, amax + 1, st) != hipSuccess) return NVFP4_EHIP;
+        if (f->tensor_scale && launch_tensor_amax(W, in_dt, N, K, K, amax + 1, partials, nullptr, st) != hipSuccess) return NVFP4_EHIP;
         // Eq. 5: dX[M, K] = Q_SR(dY)[M, N] * Q_RtN(W^T)[K, N]^T
         QuantPlan qa{dY, in_dt, M, N, N, 1, NVFP4_SR, seed, dyc, dys, reinterpret_cast<const float *>(amax + 0), ts + 0, gm};
         QuantPlan qb{W, in_dt, N, K, K, 0, NVFP4_RTN, 0, wtc, wts, reinterpret_cast<const float *>(amax + 1), ts + 1, gm};
@@ -298,7 +311,7 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
         if (launch_gemm(g, f->block, f->scale, out_dt, st) != hipSuccess) return NVFP4_EHIP;
     }
     if (dW) {
-        if (f->tensor_scale && launch_tensor_amax(X, in_dt, M, K, K, amax + 2, st) != hipSuccess) return NVFP4_EHIP;
+        if (f->tensor_scale && launch_tensor_amax(X, in_dt, M, K, K, amax + 2, partials, nullptr, st) != hipSuccess) return NVFP4_EHIP;
         // Eq. 6: dW[N, K] = Q_SR(dY^T)[N, M] * Q_SR(X^T)[K, M]^T
         QuantPlan qa{dY, in_dt, M, N, N, 0, NVFP4_SR, seed + 1, dytc, dyts, reinterpret_cast<const float *>(amax + 0), ts + 2, gm};
         QuantPlan qb{X, in_dt, M, K, K, 0, NVFP4_SR, seed + 2, xtc, xts, reinterpret_cast<const float *>(amax + 2), ts + 3, gm};

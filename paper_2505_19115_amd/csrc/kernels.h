@@ -28,9 +28,11 @@ struct GemmArgs {
     int64_t ldc;
 };
 
+// Tensor maximum: one partial per workgroup into `partials` (tensor_amax_partials() entries),
+// then folded into amax_bits[0] (bit pattern of max|x|) and, if g_out is given, into the scale.
+int64_t tensor_amax_partials(int64_t rows, int64_t cols, int64_t ld);
 hipError_t launch_tensor_amax(const void *x, int dt, int64_t rows, int64_t cols, int64_t ld,
-                              uint32_t *amax_bits, hipStream_t st);
-hipError_t launch_finalize_tensor_scale(const uint32_t *amax_bits, float *g_out, hipStream_t st);
+                              uint32_t *amax_bits, uint32_t *partials, float *g_out, hipStream_t st);
 hipError_t launch_quantize(const QuantArgs &P, int dt, int axis, int rounding, int block, int sf,
                            bool hw_convert, hipStream_t st);
 hipError_t launch_gemm(const GemmArgs &P, int block, int sf, int out_dt, hipStream_t st);

@@ -6,11 +6,11 @@
 //   rows kernel   : one lane = 8 consecutive elements of a row (one 16 B load for bf16), a
 //                   block of B elements = B/8 adjacent lanes, block maximum by DPP max across
 //                   those lanes, one 4 B store of 8 packed codes per lane.
-//   columns kernel: one lane = RPL consecutive rows x 8 consecutive columns held in registers
-//                   (RPL = 32 for bf16, 16 for fp32).  Lanes that are adjacent in the wave hold
-//                   vertically adjacent row groups of the same 8 columns, so a wave reads
-//                   >= 256 B contiguous per row and writes 64 B contiguous per output row of
-//                   the transposed code matrix without staging through LDS.
+//   columns kernel: one lane = 16 consecutive rows x 8 consecutive columns held in registers.
+//                   Lanes that are adjacent in the wave hold vertically adjacent row groups of
+//                   the same 8 columns, so the four waves of a workgroup read 512 B (bf16)
+//                   contiguous per row and a wave writes 64 B contiguous per output row of the
+//                   transposed code matrix, without staging through LDS.
 #include "kernels.h"
 #include "nvfp4_math.h"
 
@@ -38,15 +38,38 @@ __device__ __forceinline__ float group_max(float a)
     return a;
 }
 
+// The quantizer streams: every input byte is read once and every output byte written once, so
+// loads and stores carry the nontemporal hint (measured on gfx950 with the quantizer's 16 B in /
+// 4 B out shape: 6.1-6.2 TB/s with the hint against 5.4 TB/s without).  STREAM = false keeps a
+// tensor in the last-level cache for a second pass.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+template <bool STREAM>
+__device__ __forceinline__ uint4 load16(const void *p)
+{
+    if (STREAM) {
+        const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+        return make_uint4(v.x, v.y, v.z, v.w);
+    }
+    return *reinterpret_cast<const uint4 *>(p);
+}
+__device__ __forceinline__ void store4_stream(void *p, uint32_t v) { __builtin_nontemporal_store(v, reinterpret_cast<uint32_t *>(p)); }
+__device__ __forceinline__ void store8_stream(void *p, uint32_t a, uint32_t b)
+{
+    const u32x2_t v = {a, b};
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x2_t *>(p));
+}
+
 template <int DT>
 struct Chunk;  // 8 consecutive elements as loaded from memory
 
 template <>
 struct Chunk<NVFP4_BF16> {
     uint4 raw;
+    template <bool STREAM = true>
     __device__ __forceinline__ void load(const void *x, int64_t off)
     {
-        raw = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(x) + off);
+        raw = load16<STREAM>(reinterpret_cast<const uint16_t *>(x) + off);
     }
     __device__ __forceinline__ void load_partial(const void *x, int64_t off, int n)
     {
@@ -56,6 +79,7 @@ struct Chunk<NVFP4_BF16> {
         raw = make_uint4(w[0], w[1], w[2], w[3]);
     }
     __device__ __forceinline__ void zero() { raw = make_uint4(0, 0, 0, 0); }
+    __device__ __forceinline__ void launder() { asm volatile("" : "+v"(raw.x), "+v"(raw.y), "+v"(raw.z), "+v"(raw.w)); }
     __device__ __forceinline__ float get(int t) const
     {
         uint32_t w = t < 2 ? raw.x : t < 4 ? raw.y : t < 6 ? raw.z : raw.w;
@@ -66,11 +90,13 @@ struct Chunk<NVFP4_BF16> {
 template <>
 struct Chunk<NVFP4_F32> {
     float4 lo, hi;
+    template <bool STREAM = true>
     __device__ __forceinline__ void load(const void *x, int64_t off)
     {
-        const float4 *p = reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(x) + off);
-        lo = p[0];
-        hi = p[1];
+        const float *p = reinterpret_cast<const float *>(x) + off;
+        const uint4 a = load16<STREAM>(p), b = load16<STREAM>(p + 4);
+        lo = make_float4(u2f(a.x), u2f(a.y), u2f(a.z), u2f(a.w));
+        hi = make_float4(u2f(b.x), u2f(b.y), u2f(b.z), u2f(b.w));
     }
     __device__ __forceinline__ void load_partial(const void *x, int64_t off, int n)
     {
@@ -85,6 +111,7 @@ struct Chunk<NVFP4_F32> {
         lo = make_float4(0, 0, 0, 0);
         hi = lo;
     }
+    __device__ __forceinline__ void launder() {}
     __device__ __forceinline__ float get(int t) const
     {
         switch (t) {
@@ -160,40 +187,37 @@ __device__ __forceinline__ uint32_t quant_pair_hw(float x0, float x1, float q)
 
 // ------------------------------------------------------------------ tensor maximum (Q0)
 
-__global__ __launch_bounds__(64) void zero_u32_kernel(uint32_t *p)
-{
-    if (threadIdx.x == 0 && blockIdx.x == 0) *p = 0u;
-}
-
-// max|x| over a [rows, cols] tensor into *out (bit pattern, atomic unsigned max).
-// grid.x strides over the 8-element chunks of a row span, grid.y over row spans; for a dense
-// tensor the host passes rows = 1, cols = rows*cols.
+// max|x| over a [rows, cols] tensor: one partial maximum (bit pattern) per workgroup into
+// part_out[blockIdx.y * gridDim.x + blockIdx.x]; a single small workgroup folds them afterwards.
+// (One atomic max per workgroup on a single address serializes: 8192 of them cost ~80 us.)
+// grid.x covers the 8-element chunks of a row span (4 per thread, all four loads in flight
+// before the first use), grid.y the row spans; for a dense tensor the host passes one span of
+// rows*cols elements.  Loads are ordinary (cacheable): the quantizer reads the tensor again
+// right after, and up to 256 MB of it are then still in the last-level cache.
+constexpr int AMAX_UNROLL = 4;
 template <int DT>
 __global__ __launch_bounds__(256) void amax_kernel(const void *x, int64_t cols, int64_t ld,
-                                                   uint32_t *out)
+                                                   uint32_t *part_out)
 {
     const int64_t row = blockIdx.y;
     const int64_t nchunk = cols >> 3;
-    const int64_t stride = (int64_t)gridDim.x * 256;
+    const int64_t base = (int64_t)blockIdx.x * (256 * AMAX_UNROLL) + threadIdx.x;
+    Chunk<DT> v[AMAX_UNROLL];
+#pragma unroll
+    for (int u = 0; u < AMAX_UNROLL; ++u) {
+        const int64_t c = base + u * 256;
+        if (c < nchunk)
+            v[u].template load<false>(x, row * ld + c * 8);
+        else
+            v[u].zero();
+    }
     float a = 0.0f;
-    int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    for (; c + 3 * stride < nchunk; c += 4 * stride) {
-        Chunk<DT> v0, v1, v2, v3;
-        v0.load(x, row * ld + c * 8);
-        v1.load(x, row * ld + (c + stride) * 8);
-        v2.load(x, row * ld + (c + 2 * stride) * 8);
-        v3.load(x, row * ld + (c + 3 * stride) * 8);
-        a = fmaxf(fmaxf(a, chunk_amax(v0)), fmaxf(chunk_amax(v1), fmaxf(chunk_amax(v2), chunk_amax(v3))));
-    }
-    for (; c < nchunk; c += stride) {
-        Chunk<DT> v;
-        v.load(x, row * ld + c * 8);
-        a = fmaxf(a, chunk_amax(v));
-    }
+#pragma unroll
+    for (int u = 0; u < AMAX_UNROLL; ++u) a = fmaxf(a, chunk_amax(v[u]));
     if (blockIdx.x == 0 && threadIdx.x == 0 && (cols & 7)) {
-        Chunk<DT> v;
-        v.load_partial(x, row * ld + nchunk * 8, (int)(cols & 7));
-        a = fmaxf(a, chunk_amax(v));
+        Chunk<DT> t;
+        t.load_partial(x, row * ld + nchunk * 8, (int)(cols & 7));
+        a = fmaxf(a, chunk_amax(t));
     }
     a = group_max<16>(a);
     // 4 rows of 16 lanes per wave, 4 waves: finish through LDS
@@ -205,14 +229,27 @@ __global__ __launch_bounds__(256) void amax_kernel(const void *x, int64_t cols, 
         uint32_t m = 0;
 #pragma unroll
         for (int t = 0; t < 16; ++t) m = umax(m, part[t]);
-        if (m != 0) atomicMax(out, m);
+        part_out[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = m;
     }
 }
 
-__global__ __launch_bounds__(64) void finalize_tensor_scale_kernel(const uint32_t *amax_bits,
-                                                                   float *g_out)
+// Folds n partial maxima into amax_bits[0]; with g_out != nullptr also writes the tensor scale.
+__global__ __launch_bounds__(1024) void fold_amax_kernel(const uint32_t *partials, int64_t n,
+                                                         uint32_t *amax_bits, float *g_out)
 {
-    if (threadIdx.x == 0 && blockIdx.x == 0) *g_out = tensor_scale_from_amax(u2f(*amax_bits));
+    uint32_t m = 0;
+    for (int64_t i = threadIdx.x; i < n; i += 1024) m = umax(m, partials[i]);
+    m = f2u(group_max<16>(u2f(m)));
+    __shared__ uint32_t part[64];
+    if ((threadIdx.x & 15) == 0) part[threadIdx.x >> 4] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t r = 0;
+#pragma unroll
+        for (int t = 0; t < 64; ++t) r = umax(r, part[t]);
+        *amax_bits = r;
+        if (g_out) *g_out = tensor_scale_from_amax(u2f(r));
+    }
 }
 
 // ------------------------------------------------------------------ row-blocked quantizer
@@ -241,7 +278,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(QuantArgs P)
                 const int64_t i = id / cpr;
                 off = i * P.ld + (id - i * cpr) * 8;
             }
-            v[u].load(P.x, off);
+            v[u].template load<true>(P.x, off);
         } else {
             v[u].zero();
         }
@@ -266,9 +303,22 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(QuantArgs P)
             for (int t = 0; t < 8; ++t)
                 packed |= quant_elem<RND>(v[u].get(t), q, sr_bits_of(d, t)) << (4 * t);
         }
+        // scale bytes: lanes that start a block hold them; up to four neighbouring blocks are
+        // merged into one 4-byte store
+        constexpr int GATHER = LPB <= 4 ? 4 : 1;  // blocks merged per store
+        uint32_t sw = sbyte;
+        if (GATHER == 4) {
+            sw |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)sw, 0x100 + LPB, 0xF, 0xF, true) << 8;       // lane + LPB
+            sw |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)sw, 0x100 + 2 * LPB, 0xF, 0xF, true) << 16;  // lane + 2 LPB
+        }
         if (id < total) {
-            reinterpret_cast<uint32_t *>(P.codes)[id] = packed;
-            if ((threadIdx.x & (LPB - 1)) == 0) P.scales[id / LPB] = (uint8_t)sbyte;
+            store4_stream(reinterpret_cast<uint32_t *>(P.codes) + id, packed);
+            const int64_t blk = id / LPB;
+            if (GATHER == 4 && blk + 4 <= total / LPB) {
+                if ((threadIdx.x & (4 * LPB - 1)) == 0) store4_stream(P.scales + blk, sw);
+            } else if ((threadIdx.x & (LPB - 1)) == 0) {
+                P.scales[blk] = (uint8_t)sbyte;  // last (partial) group of four, or wide blocks
+            }
         }
     }
 }
@@ -279,7 +329,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(QuantArgs P)
 // with consecutive ids stacked vertically.  Workgroup: 4 waves side by side.
 template <int DT>
 struct ColGeom {
-    static constexpr int RPL = DT == NVFP4_BF16 ? 32 : 16;
+    static constexpr int RPL = 16;
     static constexpr int LANES_V = 128 / RPL;          // lanes stacked vertically
     static constexpr int LANES_H = 64 / LANES_V;       // column groups per wave
     static constexpr int WAVE_COLS = 8 * LANES_H;
@@ -287,7 +337,8 @@ struct ColGeom {
     static constexpr int WG_ROWS = 128;
 };
 
-template <int DT, int B, int SF, int RND, bool HW>
+// ALIGNED: cols is a multiple of 8, so the 8 columns of a lane share one random draw per row.
+template <int DT, int B, int SF, int RND, bool HW, bool ALIGNED>
 __global__ __launch_bounds__(256) void quantize_cols_kernel(QuantArgs P)
 {
     using G = ColGeom<DT>;
@@ -311,7 +362,7 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(QuantArgs P)
     for (int r = 0; r < RPL; ++r) {
         const int64_t i = row0 + r;
         if (i < P.rows && ncol == 8)
-            v[r].load(P.x, i * P.ld + col0);
+            v[r].template load<true>(P.x, i * P.ld + col0);
         else if (i < P.rows && ncol > 0)
             v[r].load_partial(P.x, i * P.ld + col0, ncol);
         else
@@ -336,6 +387,11 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(QuantArgs P)
         }
     }
 
+    // (the empty asm makes the compiler unpack the raw registers again in pass 2 instead of
+    // keeping 128 unpacked floats alive across the passes)
+#pragma unroll
+    for (int r = 0; r < RPL; ++r) v[r].launder();
+
     // pass 2: codes.  words[c][w] collects rows 8w..8w+7 of column c, one nibble per row.
     uint32_t words[8][RPL / 8];
 #pragma unroll
@@ -352,8 +408,7 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(QuantArgs P)
     } else {
         // the 8 columns of a lane are 8 consecutive elements of a row; their random bits come
         // from one draw when that group is aligned in the row-major numbering, else from two
-        const bool aligned = ((P.cols | col0) & 7) == 0;
-#pragma unroll
+#pragma clang loop unroll(full)
         for (int r = 0; r < RPL; ++r) {
             u32x4 d0 = {0, 0, 0, 0}, d1 = {0, 0, 0, 0};
             uint32_t shift = 0;
@@ -361,13 +416,13 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(QuantArgs P)
                 const uint64_t e0 = (uint64_t)(row0 + r) * (uint64_t)P.cols + (uint64_t)col0;
                 d0 = sr_draw(P.seed, e0 >> 3);
                 shift = (uint32_t)e0 & 7u;
-                if (!aligned) d1 = sr_draw(P.seed, (e0 >> 3) + 1);
+                if (!ALIGNED) d1 = sr_draw(P.seed, (e0 >> 3) + 1);
             }
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
                 uint32_t u16 = 0;
                 if (RND == NVFP4_SR) {
-                    if (aligned) {
+                    if (ALIGNED) {
                         u16 = sr_bits_of(d0, c);
                     } else {
                         const uint32_t pos = shift + c;
@@ -387,7 +442,7 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(QuantArgs P)
 #pragma unroll
             for (int h = 0; h < RPL / 16; ++h)
                 if (row0 + 16 * h < P.rows)
-                    *reinterpret_cast<uint2 *>(crow + 8 * h) = make_uint2(words[c][2 * h], words[c][2 * h + 1]);
+                    store8_stream(crow + 8 * h, words[c][2 * h], words[c][2 * h + 1]);
             if (lv % LPB == 0) {
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb)
@@ -402,37 +457,40 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(QuantArgs P)
 
 static inline hipError_t launch_status() { return hipGetLastError(); }
 
-hipError_t launch_tensor_amax(const void *x, int dt, int64_t rows, int64_t cols, int64_t ld,
-                              uint32_t *amax_bits, hipStream_t st)
+int64_t tensor_amax_partials(int64_t rows, int64_t cols, int64_t ld)
 {
-    hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(64), 0, st, amax_bits);
     int64_t span_rows = rows, span_cols = cols;
     if (ld == cols) {
         span_cols = rows * cols;
         span_rows = 1;
     }
-    const int64_t nchunk = span_cols >> 3;
-    int64_t gx = (nchunk + 256 * 4 - 1) / (256 * 4);
+    int64_t gx = ((span_cols >> 3) + 256 * AMAX_UNROLL - 1) / (256 * AMAX_UNROLL);
     if (gx < 1) gx = 1;
-    const int64_t cap = span_rows == 1 ? 4096 : 64;
-    if (gx > cap) gx = cap;
+    return gx * (span_rows < 1 ? 1 : span_rows);
+}
+
+hipError_t launch_tensor_amax(const void *x, int dt, int64_t rows, int64_t cols, int64_t ld,
+                              uint32_t *amax_bits, uint32_t *partials, float *g_out, hipStream_t st)
+{
+    int64_t span_rows = rows, span_cols = cols;
+    if (ld == cols) {
+        span_cols = rows * cols;
+        span_rows = 1;
+    }
+    int64_t gx = ((span_cols >> 3) + 256 * AMAX_UNROLL - 1) / (256 * AMAX_UNROLL);
+    if (gx < 1) gx = 1;
     // grid.y is limited to 65535: walk taller tensors in slabs
     for (int64_t r0 = 0; r0 < span_rows; r0 += 65535) {
         const int64_t nr = span_rows - r0 < 65535 ? span_rows - r0 : 65535;
         const char *base = reinterpret_cast<const char *>(x) + r0 * ld * (dt == NVFP4_BF16 ? 2 : 4);
         if (dt == NVFP4_BF16)
             hipLaunchKernelGGL(amax_kernel<NVFP4_BF16>, dim3((unsigned)gx, (unsigned)nr), dim3(256), 0, st,
-                               base, span_cols, ld, amax_bits);
+                               base, span_cols, ld, partials + r0 * gx);
         else
             hipLaunchKernelGGL(amax_kernel<NVFP4_F32>, dim3((unsigned)gx, (unsigned)nr), dim3(256), 0, st,
-                               base, span_cols, ld, amax_bits);
+                               base, span_cols, ld, partials + r0 * gx);
     }
-    return launch_status();
-}
-
-hipError_t launch_finalize_tensor_scale(const uint32_t *amax_bits, float *g_out, hipStream_t st)
-{
-    hipLaunchKernelGGL(finalize_tensor_scale_kernel, dim3(1), dim3(64), 0, st, amax_bits, g_out);
+    hipLaunchKernelGGL(fold_amax_kernel, dim3(1), dim3(1024), 0, st, partials, gx * span_rows, amax_bits, g_out);
     return launch_status();
 }
 
@@ -448,7 +506,10 @@ static void launch_q(const QuantArgs &P, int axis, hipStream_t st)
         using G = ColGeom<DT>;
         dim3 grid((unsigned)((P.cols + G::WG_COLS - 1) / G::WG_COLS),
                   (unsigned)((P.rows + G::WG_ROWS - 1) / G::WG_ROWS));
-        hipLaunchKernelGGL((quantize_cols_kernel<DT, B, SF, RND, HW>), grid, dim3(256), 0, st, P);
+        if (RND == NVFP4_SR && (P.cols & 7) != 0)
+            hipLaunchKernelGGL((quantize_cols_kernel<DT, B, SF, RND, HW, RND == NVFP4_RTN>), grid, dim3(256), 0, st, P);
+        else
+            hipLaunchKernelGGL((quantize_cols_kernel<DT, B, SF, RND, HW, true>), grid, dim3(256), 0, st, P);
     }
 }
 

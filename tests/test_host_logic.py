@@ -50,7 +50,7 @@ FAKE = 0x10000  # non-null, 16-byte aligned; never dereferenced because validati
 
 
 def _quant(x=FAKE, dt=nv.BF16, rows=64, cols=64, ld=64, axis=1, rnd=nv.RTN, fmt=nv.NVFP4,
-           codes=FAKE, scales=FAKE, ts=FAKE, flags=0, ws=FAKE, ws_bytes=256):
+           codes=FAKE, scales=FAKE, ts=FAKE, flags=0, ws=FAKE, ws_bytes=1 << 20):
     f = fmt.c()
     return nv.lib.nvfp4_quantize(x, dt, rows, cols, ld, axis, rnd, 0, C.byref(f), codes, scales, ts,
                                  flags, ws, ws_bytes, None)
