@@ -45,6 +45,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--probe", action="store_true",
+                    help="run each kernel of interest a few times and exit (for rocprofv3 --pmc passes)")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
                     help="HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc runs")
     args = ap.parse_args()
@@ -60,6 +62,28 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
     dev = "cuda"
+
+    if args.probe:
+        # a plain copy of known size (128 MiB in, 128 MiB out) calibrates the byte counters;
+        # then the dominant GEMM and every quantizer kernel on the benchmark's tensors
+        src = torch.randn(8192, 8192, device=dev).to(torch.bfloat16)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        Xp, Wp = synth.normal(4096, 4096, 1.0, 100).to(dev), synth.normal(11008, 4096, 0.02, 200).to(dev)
+        qa, qb = nv.quantize(Xp, 1), nv.quantize(Wp, 1)
+        Yp = torch.empty((4096, 11008), dtype=torch.bfloat16, device=dev)
+        for _ in range(3):
+            nv.gemm(qa, qb, out=Yp)
+        xq = synth.student_t_outliers(8192, 8192, seed=100).to(dev)
+        g = nv.tensor_scale(xq)
+        for axis in (1, 0):
+            for rnd in (nv.RTN, nv.SR):
+                for _ in range(2):
+                    nv.quantize(xq, axis, rnd, 1, tensor_scale=g)
+        torch.cuda.synchronize()
+        print("probe done")
+        return 0
 
     # ---- workload: the 7B SwiGLU MLP's three linears, tokens = 4096 (batch 2 x seq 2048)
     M = 4096

@@ -325,23 +325,25 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(QuantArgs P)
 
 // ------------------------------------------------------------------ column-blocked quantizer
 
-// Lane tile: RPL rows x 8 columns.  Wave tile: 128 rows x (8 * 64 * RPL / 128) columns, lanes
-// with consecutive ids stacked vertically.  Workgroup: 4 waves side by side.
-template <int DT>
+// Lane tile: 16 rows x 8 columns.  Wave tile: (16 LV) rows x (8 * 64 / LV) columns, lanes with
+// consecutive ids stacked vertically; workgroup: 4 waves side by side.  LV = 8 gives 64-byte
+// runs per output row; measured on [8192, 8192] bf16: LV = 4 (32-byte runs) is 45 % slower,
+// LV = 16 (128-byte runs, 64-byte reads) no faster.
+template <int DT, int LV = 8>
 struct ColGeom {
     static constexpr int RPL = 16;
-    static constexpr int LANES_V = 128 / RPL;          // lanes stacked vertically
+    static constexpr int LANES_V = LV;                 // lanes stacked vertically
     static constexpr int LANES_H = 64 / LANES_V;       // column groups per wave
     static constexpr int WAVE_COLS = 8 * LANES_H;
     static constexpr int WG_COLS = 4 * WAVE_COLS;
-    static constexpr int WG_ROWS = 128;
+    static constexpr int WG_ROWS = RPL * LANES_V;
 };
 
 // ALIGNED: cols is a multiple of 8, so the 8 columns of a lane share one random draw per row.
-template <int DT, int B, int SF, int RND, bool HW, bool ALIGNED>
+template <int DT, int B, int SF, int RND, bool HW, bool ALIGNED, int LV = 8>
 __global__ __launch_bounds__(256) void quantize_cols_kernel(QuantArgs P)
 {
-    using G = ColGeom<DT>;
+    using G = ColGeom<DT, LV>;
     constexpr int RPL = G::RPL;
     constexpr int BL = B < RPL ? B : RPL;        // rows of one block held by this lane
     constexpr int NB = RPL / BL;                 // blocks (or block parts) per lane per column
