@@ -210,7 +210,7 @@ nvfp4_status nvfp4_gemm(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
     if (!aligned16(A_codes) || !aligned16(A_scales) || !aligned16(B_codes) || !aligned16(B_scales) ||
         !aligned16(out))
         return NVFP4_EALIGN;
-    if (f->scale != NVFP4_SCALE_E4M3) return NVFP4_EUNSUPPORTED;
+    if (f->scale == NVFP4_SCALE_E8M0 && f->block != 32) return NVFP4_EUNSUPPORTED;  // E8M0 GEMM: MXFP4 only
     if (M == 0 || N == 0) return NVFP4_OK;
     GemmArgs g{M, N, K, A_codes, A_scales, B_codes, B_scales, tensor_scales, out, ldc};
     return launch_gemm(g, f->block, f->scale, out_dt, reinterpret_cast<hipStream_t>(stream)) == hipSuccess
@@ -229,7 +229,7 @@ nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, 
     if (!valid_dtype(in_dt) || !valid_dtype(out_dt)) return NVFP4_EINVAL;
     if (M <= 0 || N <= 0 || K <= 0) return NVFP4_ESHAPE;
     if (K % f->block != 0 || K % 32 != 0) return NVFP4_ESHAPE;
-    if (f->scale != NVFP4_SCALE_E4M3) return NVFP4_EUNSUPPORTED;
+    if (f->scale == NVFP4_SCALE_E8M0 && f->block != 32) return NVFP4_EUNSUPPORTED;  // E8M0 GEMM: MXFP4 only
     if (!aligned16(X) || !aligned16(W) || !aligned16(Y)) return NVFP4_EALIGN;
     if (!workspace || workspace_bytes < nvfp4_linear_fwd_workspace_bytes(M, N, K, f)) return NVFP4_EWORKSPACE;
     if ((reinterpret_cast<uintptr_t>(workspace) & (WS_ALIGN - 1)) != 0) return NVFP4_EALIGN;
@@ -273,7 +273,7 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
     if (dX && (N % B != 0 || N % 32 != 0)) return NVFP4_ESHAPE;
     if (dW && (M % B != 0 || M % 32 != 0)) return NVFP4_ESHAPE;
     if ((K * (int64_t)elem_size(in_dt)) % 16 != 0 || (N * (int64_t)elem_size(in_dt)) % 16 != 0) return NVFP4_EALIGN;
-    if (f->scale != NVFP4_SCALE_E4M3) return NVFP4_EUNSUPPORTED;
+    if (f->scale == NVFP4_SCALE_E8M0 && f->block != 32) return NVFP4_EUNSUPPORTED;  // E8M0 GEMM: MXFP4 only
     if (!aligned16(dY) || !aligned16(X) || !aligned16(W) || !aligned16(dX) || !aligned16(dW)) return NVFP4_EALIGN;
     if (!workspace || workspace_bytes < nvfp4_linear_bwd_workspace_bytes(M, N, K, f)) return NVFP4_EWORKSPACE;
     if ((reinterpret_cast<uintptr_t>(workspace) & (WS_ALIGN - 1)) != 0) return NVFP4_EALIGN;

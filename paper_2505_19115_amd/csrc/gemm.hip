@@ -410,7 +410,7 @@ static void launch_f16_auto(const GemmArgs &P, int out_dt, hipStream_t st)
 
 hipError_t launch_gemm(const GemmArgs &P, int block, int sf, int out_dt, hipStream_t st)
 {
-    if (sf != NVFP4_SCALE_E4M3) return hipErrorNotSupported;
+    if (sf == NVFP4_SCALE_E8M0) return block == 32 ? launch_gemm_mxfp4(P, out_dt, st) : hipErrorNotSupported;
     switch (block) {
     case 16: launch_f16_auto<16>(P, out_dt, st); break;
     case 32: launch_f16_auto<32>(P, out_dt, st); break;

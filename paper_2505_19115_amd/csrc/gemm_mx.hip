@@ -1,0 +1,316 @@
+// MXFP4 GEMM on the CDNA4 scaled FP4 MFMA ("NT": both operands stored with the contraction
+// axis contiguous).  MXFP4 (Sec. 3 / Table 1 of "FP4 All the Way": E2M1 elements, blocks of 32,
+// E8M0 power-of-two scales) is exactly what v_mfma_scale_f32_32x32x64_f8f6f4 consumes: each
+// lane supplies 32 consecutive contraction elements (16 bytes of packed codes) of one row plus
+// one E8M0 byte for them, so the packed operands go from LDS straight into the instruction with
+// no expansion arithmetic at all:
+//     out[i, j] = gA gB sum_b 2^(eA[i,b] - 127) 2^(eB[j,b] - 127) sum_{k in b} cA[i,k] cB[j,k].
+// Products and the power-of-two scaling are exact; accumulation is fp32.
+//
+// Geometry: 256 threads = 2 x 2 waves, wave tile 128 x 128 (4 x 4 MFMA tiles, 256 accumulator
+// registers, one wave per SIMD), workgroup tile 256 x 256.  With no VALU work in the loop the
+// single-wave issue limit does not matter; what matters is LDS bandwidth (a 4 x 4 register tile
+// reads 8 KB per 16 MFMAs = 128 B/clk/CU at full MFMA rate, the LDS peak), hence the largest
+// register tile that fits.
+#include "kernels.h"
+#include "nvfp4_math.h"
+
+namespace nvfp4 {
+
+typedef int int8v_t __attribute__((ext_vector_type(8)));
+typedef float float16v_t __attribute__((ext_vector_type(16)));
+
+namespace mx {
+constexpr int NT = 256, BM = 256, BN = 256, TA = 4, TB = 4;
+}
+
+__device__ __forceinline__ uint16_t mx_bf16_rne(float f)
+{
+    uint32_t u = f2u(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// KT = contraction elements per LDS stage (256: four MFMA steps per barrier; 64: one step, any
+// K that is a multiple of 32, chunks past K are zero-filled).
+// LDS stage: codes [BM + BN rows][KT/2 bytes], 16-byte chunk c of row r at slot c ^ (r & (NCH-1))
+// (8 consecutive rows reading one logical chunk hit 8 different 16-byte bank groups); scales as
+// dwords [2 lane halves][BM + BN rows], byte s of a dword = the E8M0 byte of MFMA step s for that
+// lane half, so the instruction's byte select is a compile-time constant.
+template <int KT, int OUT_DT>
+__global__ __launch_bounds__(256) void gemm_nt_mxfp4_kernel(GemmArgs P)
+{
+    using namespace mx;
+    constexpr int ROWB = KT / 2;          // code bytes per row per stage
+    constexpr int NCH = ROWB / 16;        // 16-byte chunks per row (8 or 2)
+    constexpr int STEPS = KT / 64;        // MFMA steps per stage (4 or 1)
+    constexpr int CPT = (BM * NCH) / NT;  // chunks per thread per operand (8 or 2)
+    constexpr int CODES = (BM + BN) * ROWB;
+    constexpr int STAGE = CODES + 2 * (BM + BN) * 4;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int r = lane & 31, g = lane >> 5;
+    const int ntx = (int)((P.N + BN - 1) / BN), nty = (int)((P.M + BM - 1) / BM);
+    const int ntiles = ntx * nty;
+    int wg = blockIdx.x;
+    {
+        // consecutive workgroup ids land on different XCDs: give each XCD a contiguous band
+        const int per = (ntiles + 7) / 8, xcd = wg & 7, slot = wg >> 3;
+        const int full = ntiles - (per - 1) * 8;
+        wg = xcd < full ? xcd * per + slot : full * per + (xcd - full) * (per - 1) + slot;
+    }
+    const int64_t m0 = (int64_t)(wg / ntx) * BM, n0 = (int64_t)(wg % ntx) * BN;
+    const int64_t Kb = P.K >> 1, Ks = P.K >> 5;
+    const int nkt = (int)((P.K + KT - 1) / KT);
+
+    float16v_t acc[TA][TB];
+#pragma unroll
+    for (int a = 0; a < TA; ++a)
+#pragma unroll
+        for (int b = 0; b < TB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+
+    // ---- global -> registers -> LDS.  Rows past the edge are clamped to the last row (their
+    // products land in outputs that are never stored).
+    // KT = 256: the codes go from global memory straight into LDS (global_load_lds, 16 bytes per
+    // lane): a wave instruction fills 1 KB = 8 consecutive tile rows, lane i landing at byte 16 i,
+    // so the XOR swizzle is applied by choosing WHICH global chunk lane i fetches.  No staging
+    // registers, no LDS store instructions.  KT = 64 stages through registers (it must be able
+    // to zero-fill past K).
+    constexpr bool DMA = KT == 256;
+    uint4 ga[DMA ? 1 : CPT], gb[DMA ? 1 : CPT];
+    uint64_t gsa = 0, gsb = 0;
+    uint32_t offA[CPT], offB[CPT];
+    int ldsW[CPT];
+#pragma unroll
+    for (int u = 0; u < CPT; ++u) {
+        int row, c;
+        if (DMA) {
+            row = (wave * CPT + u) * 8 + (lane >> 3);
+            c = (lane & 7) ^ (row & 7);
+            ldsW[u] = (wave * CPT + u) * 1024;  // wave-uniform base of this instruction's 1 KB
+        } else {
+            const int qd = tid + NT * u;
+            row = qd / NCH;
+            c = qd % NCH;
+            ldsW[u] = row * ROWB + ((c ^ (row & (NCH - 1))) << 4);
+        }
+        const int64_t ar = m0 + row < P.M ? m0 + row : P.M - 1;
+        const int64_t br = n0 + row < P.N ? n0 + row : P.N - 1;
+        offA[u] = (uint32_t)(ar * Kb + c * 16);
+        offB[u] = (uint32_t)(br * Kb + c * 16);
+    }
+    typedef __attribute__((address_space(3))) void *lds_ptr_t;
+    typedef const __attribute__((address_space(1))) void *glb_ptr_t;
+    // wave-uniform 64-bit value -> scalar registers (keeps "uniform base + 32-bit lane offset"
+    // addressing instead of one 64-bit vector pointer per load)
+    auto uniform_ptr = [](const uint8_t *p) -> const uint8_t * {
+        const uint64_t v = reinterpret_cast<uint64_t>(p);
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+        return reinterpret_cast<const uint8_t *>(((uint64_t)hi << 32) | lo);
+    };
+    const int dma_base = __builtin_amdgcn_readfirstlane(wave * CPT * 1024);
+    auto dma_codes = [&](int kt, int stage) {
+        const uint8_t *pa = uniform_ptr(P.A_codes + (int64_t)kt * ROWB);
+        const uint8_t *pb = uniform_ptr(P.B_codes + (int64_t)kt * ROWB);
+#pragma unroll
+        for (int u = 0; u < CPT; ++u) {
+            const int dst = stage * STAGE + dma_base + u * 1024;
+            __builtin_amdgcn_global_load_lds((glb_ptr_t)(pa + offA[u]), (lds_ptr_t)(lds + dst), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((glb_ptr_t)(pb + offB[u]), (lds_ptr_t)(lds + BM * ROWB + dst), 16, 0, 0);
+        }
+    };
+    const int64_t sar = m0 + tid < P.M ? m0 + tid : P.M - 1;
+    const int64_t sbr = n0 + tid < P.N ? n0 + tid : P.N - 1;
+    auto fetch = [&](int kt) {
+        const int64_t kb = (int64_t)kt * ROWB;
+        if (!DMA) {
+#pragma unroll
+            for (int u = 0; u < CPT; ++u) {
+                const bool in = kb + ((tid + NT * u) % NCH) * 16 < Kb;  // zero codes past K
+                ga[u] = in ? *reinterpret_cast<const uint4 *>(P.A_codes + kb + offA[u]) : make_uint4(0, 0, 0, 0);
+                gb[u] = in ? *reinterpret_cast<const uint4 *>(P.B_codes + kb + offB[u]) : make_uint4(0, 0, 0, 0);
+            }
+        }
+        const uint8_t *pa = P.A_scales + sar * Ks + (int64_t)kt * (KT / 32);
+        const uint8_t *pb = P.B_scales + sbr * Ks + (int64_t)kt * (KT / 32);
+        if (KT == 256) {
+            gsa = *reinterpret_cast<const uint64_t *>(pa);
+            gsb = *reinterpret_cast<const uint64_t *>(pb);
+        } else {
+            const bool two = (int64_t)kt * 2 + 1 < Ks;
+            gsa = (uint64_t)pa[0] | (two ? (uint64_t)pa[1] << 8 : 0);
+            gsb = (uint64_t)pb[0] | (two ? (uint64_t)pb[1] << 8 : 0);
+        }
+    };
+    // scale bytes of a row, in block order b0 b1 ... -> dword of lane half 0 (blocks 0, 2, 4, 6)
+    // and dword of lane half 1 (blocks 1, 3, 5, 7)
+    auto split_scales = [&](uint64_t s, uint32_t &even, uint32_t &odd) {
+        const uint32_t lo = (uint32_t)s, hi = (uint32_t)(s >> 32);
+        even = __builtin_amdgcn_perm(hi, lo, 0x06040200u);
+        odd = __builtin_amdgcn_perm(hi, lo, 0x07050301u);
+    };
+    auto stash = [&](int stage) {
+        uint8_t *base = lds + stage * STAGE;
+        if (!DMA) {
+#pragma unroll
+            for (int u = 0; u < CPT; ++u) {
+                *reinterpret_cast<uint4 *>(base + ldsW[u]) = ga[u];
+                *reinterpret_cast<uint4 *>(base + BM * ROWB + ldsW[u]) = gb[u];
+            }
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's direct-to-LDS loads have landed
+        }
+        uint32_t *sS = reinterpret_cast<uint32_t *>(base + CODES);
+        uint32_t e, o;
+        split_scales(gsa, e, o);
+        sS[tid] = e;
+        sS[(BM + BN) + tid] = o;
+        split_scales(gsb, e, o);
+        sS[BM + tid] = e;
+        sS[(BM + BN) + BM + tid] = o;
+    };
+
+    // ---- LDS -> registers
+    struct Frags {
+        uint4 a[TA], b[TB];
+    };
+    struct Scales {
+        uint32_t a[TA], b[TB];
+    };
+    int rd[STEPS];  // byte offset of this lane's chunk of MFMA step s inside its row
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) rd[s] = r * ROWB + (((2 * s + g) ^ (r & (NCH - 1))) << 4);
+    auto load_frags = [&](int stage, int s, Frags &F) {
+        const uint8_t *p = lds + stage * STAGE + rd[s];
+#pragma unroll
+        for (int a = 0; a < TA; ++a) F.a[a] = *reinterpret_cast<const uint4 *>(p + (wm * 128 + 32 * a) * ROWB);
+#pragma unroll
+        for (int b = 0; b < TB; ++b) F.b[b] = *reinterpret_cast<const uint4 *>(p + (BM + wn * 128 + 32 * b) * ROWB);
+    };
+    auto load_scales = [&](int stage, Scales &S) {
+        const uint32_t *p = reinterpret_cast<const uint32_t *>(lds + stage * STAGE + CODES) + g * (BM + BN) + r;
+#pragma unroll
+        for (int a = 0; a < TA; ++a) S.a[a] = p[wm * 128 + 32 * a];
+#pragma unroll
+        for (int b = 0; b < TB; ++b) S.b[b] = p[BM + wn * 128 + 32 * b];
+    };
+#define NVFP4_MX_MMA(F, S, s)                                                                              \
+    _Pragma("unroll") for (int a = 0; a < TA; ++a) _Pragma("unroll") for (int b = 0; b < TB; ++b)          \
+    {                                                                                                      \
+        const int8v_t va = {(int)F.a[a].x, (int)F.a[a].y, (int)F.a[a].z, (int)F.a[a].w, 0, 0, 0, 0};       \
+        const int8v_t vb = {(int)F.b[b].x, (int)F.b[b].y, (int)F.b[b].z, (int)F.b[b].w, 0, 0, 0, 0};       \
+        acc[a][b] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(va, vb, acc[a][b], 4, 4, s, (int)S.a[a], s, \
+                                                                    (int)S.b[b]);                          \
+    }
+
+    Frags F0, F1;
+    Scales S0, S1;
+    if (DMA) dma_codes(0, 0);
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    load_frags(0, 0, F0);
+    load_scales(0, S0);
+
+    // One K tile: steps 0..STEPS-1 multiply while the fragments of the next step are read; the
+    // next tile goes to the other LDS stage before the last step, ONE barrier, and the first
+    // fragments / scales of the next tile are already in flight during the last step.
+    // Sc = scales of this tile, Sn = registers for the next tile's.
+#define NVFP4_MX_TILE(stage, kt, more, Sc, Sn)                  \
+    {                                                           \
+        if (more) {                                             \
+            if (DMA) dma_codes((kt) + 1, (stage) ^ 1);          \
+            fetch((kt) + 1);                                    \
+        }                                                       \
+        if (STEPS == 4) {                                       \
+            load_frags(stage, 1, F1);                           \
+            NVFP4_MX_MMA(F0, Sc, 0)                             \
+            load_frags(stage, 2, F0);                           \
+            NVFP4_MX_MMA(F1, Sc, 1)                             \
+            load_frags(stage, 3, F1);                           \
+            NVFP4_MX_MMA(F0, Sc, 2)                             \
+            if (more) {                                         \
+                stash((stage) ^ 1);                             \
+                __syncthreads();                                \
+                load_frags((stage) ^ 1, 0, F0);                 \
+                load_scales((stage) ^ 1, Sn);                   \
+            }                                                   \
+            NVFP4_MX_MMA(F1, Sc, 3)                             \
+        } else {                                                \
+            if (more) stash((stage) ^ 1);                       \
+            NVFP4_MX_MMA(F0, Sc, 0)                             \
+            if (more) {                                         \
+                __syncthreads();                                \
+                load_frags((stage) ^ 1, 0, F0);                 \
+                load_scales((stage) ^ 1, Sn);                   \
+            }                                                   \
+        }                                                       \
+    }
+    int kt = 0;
+    for (; kt + 2 < nkt; kt += 2) {
+        NVFP4_MX_TILE(0, kt, true, S0, S1)
+        NVFP4_MX_TILE(1, kt + 1, true, S1, S0)
+    }
+    if (kt + 1 < nkt) {
+        NVFP4_MX_TILE(0, kt, true, S0, S1)
+        ++kt;
+        NVFP4_MX_TILE(1, kt, false, S1, S0)
+    } else {
+        NVFP4_MX_TILE(0, kt, false, S0, S1)
+    }
+#undef NVFP4_MX_TILE
+#undef NVFP4_MX_MMA
+
+    // epilogue: accumulator register v of lane (r, g) is row 8 (v / 4) + 4 g + v % 4, column r
+    const float gg = P.tensor_scales[0] * P.tensor_scales[1];
+#pragma unroll
+    for (int a = 0; a < TA; ++a)
+#pragma unroll
+        for (int b = 0; b < TB; ++b) {
+            const int64_t col = n0 + wn * 128 + 32 * b + r;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int64_t row = m0 + wm * 128 + 32 * a + 8 * (v >> 2) + 4 * g + (v & 3);
+                if (row < P.M && col < P.N) {
+                    const float y = acc[a][b][v] * gg;
+                    if (OUT_DT == NVFP4_F32)
+                        reinterpret_cast<float *>(P.out)[row * P.ldc + col] = y;
+                    else
+                        reinterpret_cast<uint16_t *>(P.out)[row * P.ldc + col] = mx_bf16_rne(y);
+                }
+            }
+        }
+}
+
+template <int KT>
+static void launch_mx(const GemmArgs &P, int out_dt, hipStream_t st)
+{
+    constexpr int LDS_BYTES = 2 * ((mx::BM + mx::BN) * (KT / 2) + 2 * (mx::BM + mx::BN) * 4);
+    const unsigned ntiles = (unsigned)(((P.N + mx::BN - 1) / mx::BN) * ((P.M + mx::BM - 1) / mx::BM));
+    if (out_dt == NVFP4_F32) {
+        auto k = gemm_nt_mxfp4_kernel<KT, NVFP4_F32>;
+        static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES), true);
+        (void)once;
+        hipLaunchKernelGGL(k, dim3(ntiles), dim3(256), LDS_BYTES, st, P);
+    } else {
+        auto k = gemm_nt_mxfp4_kernel<KT, NVFP4_BF16>;
+        static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES), true);
+        (void)once;
+        hipLaunchKernelGGL(k, dim3(ntiles), dim3(256), LDS_BYTES, st, P);
+    }
+}
+
+hipError_t launch_gemm_mxfp4(const GemmArgs &P, int out_dt, hipStream_t st)
+{
+    if (P.K % 256 == 0)
+        launch_mx<256>(P, out_dt, st);
+    else
+        launch_mx<64>(P, out_dt, st);
+    return hipGetLastError();
+}
+
+}  // namespace nvfp4

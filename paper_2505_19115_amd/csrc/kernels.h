@@ -36,5 +36,6 @@ hipError_t launch_tensor_amax(const void *x, int dt, int64_t rows, int64_t cols,
 hipError_t launch_quantize(const QuantArgs &P, int dt, int axis, int rounding, int block, int sf,
                            bool hw_convert, hipStream_t st);
 hipError_t launch_gemm(const GemmArgs &P, int block, int sf, int out_dt, hipStream_t st);
+hipError_t launch_gemm_mxfp4(const GemmArgs &P, int out_dt, hipStream_t st);  // block 32, E8M0
 
 }  // namespace nvfp4

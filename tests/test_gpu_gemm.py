@@ -169,3 +169,72 @@ def test_linear_fp32_inputs_bf16_outputs():
     odX, odW = oracle.linear_bwd(dY, X, W, 7)
     for got, ref in ((Y, oY), (dX, odX), (dW, odW)):
         assert np.all(np.abs(to_np(got.float()) - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * np.abs(ref).max())
+
+
+# ---------------------------------------------------------------- MXFP4 (block 32, E8M0): native FP4 MFMA
+def mx_operand(rng, rows, K, lo=112, hi=142):
+    codes = rng.integers(0, 256, (rows, K // 2)).astype(np.uint8)
+    scales = rng.integers(lo, hi, (rows, K // 32)).astype(np.uint8)
+    return codes, scales, 1.0
+
+
+@pytest.mark.parametrize("shape", [(256, 256, 256), (200, 136, 512), (1, 1, 32), (130, 257, 96), (384, 512, 1024),
+                                   (300, 520, 1280), (64, 64, 160)])
+def test_mxfp4_random_codes_and_scales(shape):
+    M, N, K = shape
+    rng = np.random.default_rng(M + 3 * N + K)
+    check(mx_operand(rng, M, K), mx_operand(rng, N, K), nv.MXFP4, "mxfp4-random")
+
+
+def test_mxfp4_unit_scales_exact_and_extreme_scales():
+    rng = np.random.default_rng(77)
+    M, N, K = 160, 288, 768
+    A = (rng.integers(0, 256, (M, K // 2)).astype(np.uint8), np.full((M, K // 32), 127, np.uint8), 1.0)
+    B = (rng.integers(0, 256, (N, K // 2)).astype(np.uint8), np.full((N, K // 32), 127, np.uint8), 1.0)
+    Y = to_np(nv.gemm(dev(A), dev(B), nv.MXFP4))
+    assert np.array_equal(Y.astype(np.float64), oracle.gemm_nt(A, B, oracle.MXFP4))
+    # scale bytes far apart (2^-60 .. 2^+60 on one side, the inverse range on the other)
+    A2 = (A[0], rng.integers(67, 187, (M, K // 32)).astype(np.uint8), 1.0)
+    B2 = (B[0], rng.integers(67, 187, (N, K // 32)).astype(np.uint8), 1.0)
+    check(A2, B2, nv.MXFP4, "mxfp4-extreme")
+    # zero blocks: byte 0 with zero codes
+    A3 = (A[0].copy(), A2[1].copy(), 1.0)
+    A3[1][:, ::3] = 0
+    for j in range(0, K // 32, 3):
+        A3[0][:, j * 16:(j + 1) * 16] = 0
+    check(A3, B2, nv.MXFP4, "mxfp4-zero-blocks")
+
+
+def test_mxfp4_quantized_linear_fwd_bwd():
+    M, N, K = 256, 384, 512
+    X = synth.normal(M, K, 1.0, 61)
+    W = synth.normal(N, K, 0.02, 62)
+    dY = synth.gradient_like(M, N, 63)
+    fm, of = nv.MXFP4, oracle.MXFP4
+    print("[case] mxfp4 linear fwd/bwd", flush=True)
+    Y = nv.linear_fwd(X.cuda(), W.cuda(), fm)
+    dX, dW = nv.linear_bwd(dY.cuda(), X.cuda(), W.cuda(), 9, fm)
+    torch.cuda.synchronize()
+    qx, qw = oracle.quantize(X, 1, 0, 0, of), oracle.quantize(W, 1, 0, 0, of)
+    assert_quant_equal(nv.quantize(X.cuda(), 1, nv.RTN, 0, fm), qx, "mx Q(X)")
+    assert_gemm_close(to_np(Y), oracle.gemm_nt(qx, qw, of), oracle.gemm_nt(qx, qw, of, take_abs=True), "mx Y")
+    qdy, qwt = oracle.quantize(dY, 1, oracle.SR, 9, of), oracle.quantize(W, 0, 0, 0, of)
+    assert_gemm_close(to_np(dX), oracle.gemm_nt(qdy, qwt, of), oracle.gemm_nt(qdy, qwt, of, take_abs=True), "mx dX")
+    qdyt, qxt = oracle.quantize(dY, 0, oracle.SR, 10, of), oracle.quantize(X, 0, oracle.SR, 11, of)
+    assert_gemm_close(to_np(dW), oracle.gemm_nt(qdyt, qxt, of), oracle.gemm_nt(qdyt, qxt, of, take_abs=True), "mx dW")
+
+
+def test_mxfp4_7b_shape_sampled():
+    M, N, K = 4096, 11008, 4096
+    X = synth.normal(M, K, 1.0, 31)
+    W = synth.normal(N, K, 0.02, 32)
+    A, B = oracle.quantize(X, 1, 0, 0, oracle.MXFP4), oracle.quantize(W, 1, 0, 0, oracle.MXFP4)
+    print("[case] mxfp4 gemm 7B gate sampled", flush=True)
+    Y = nv.gemm(dev(A), dev(B), nv.MXFP4)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    ii = np.concatenate([rng.integers(0, M, 4000), np.full(N, 4095), np.arange(M)])
+    jj = np.concatenate([rng.integers(0, N, 4000), np.arange(N), np.full(M, 11007)])
+    ref = oracle.gemm_nt_sample(A, B, ii, jj, oracle.MXFP4)
+    ref_abs = oracle.gemm_nt_sample(A, B, ii, jj, oracle.MXFP4, take_abs=True)
+    assert_gemm_close(to_np(Y)[ii, jj], ref, ref_abs, "mx-7b-gate")
