@@ -85,17 +85,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int r = lane & 31, h = lane >> 5;
-    // consecutive workgroup ids land on different XCDs (8 of them, each with its own L2): give
-    // each XCD a contiguous band of the tile grid so that its workgroups share operand tiles
     const int ntx = (int)((P.N + BN - 1) / BN), nty = (int)((P.M + BM - 1) / BM);
-    const int ntiles = ntx * nty;
-    int wg = blockIdx.x;
-    {
-        const int per = (ntiles + 7) / 8, xcd = wg & 7, slot = wg >> 3;
-        const int full = ntiles - (per - 1) * 8;  // XCDs that receive `per` tiles (others per-1)
-        wg = xcd < full ? xcd * per + slot : full * per + (xcd - full) * (per - 1) + slot;
-    }
-    const int64_t m0 = (int64_t)(wg / ntx) * BM, n0 = (int64_t)(wg % ntx) * BN;
+    int ty, tx;
+    tile_coords(blockIdx.x, ntx, nty, ty, tx);
+    const int64_t m0 = (int64_t)ty * BM, n0 = (int64_t)tx * BN;
     const int64_t Kb = P.K >> 1;          // code bytes per row
     const int64_t Ks = P.K / B;           // scale bytes per row
     const int nkt = (int)((P.K + KT - 1) / KT);

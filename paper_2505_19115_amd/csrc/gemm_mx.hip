@@ -53,15 +53,9 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_kernel(GemmArgs P)
     const int wm = wave >> 1, wn = wave & 1;
     const int r = lane & 31, g = lane >> 5;
     const int ntx = (int)((P.N + BN - 1) / BN), nty = (int)((P.M + BM - 1) / BM);
-    const int ntiles = ntx * nty;
-    int wg = blockIdx.x;
-    {
-        // consecutive workgroup ids land on different XCDs: give each XCD a contiguous band
-        const int per = (ntiles + 7) / 8, xcd = wg & 7, slot = wg >> 3;
-        const int full = ntiles - (per - 1) * 8;
-        wg = xcd < full ? xcd * per + slot : full * per + (xcd - full) * (per - 1) + slot;
-    }
-    const int64_t m0 = (int64_t)(wg / ntx) * BM, n0 = (int64_t)(wg % ntx) * BN;
+    int ty, tx;
+    tile_coords(blockIdx.x, ntx, nty, ty, tx);
+    const int64_t m0 = (int64_t)ty * BM, n0 = (int64_t)tx * BN;
     const int64_t Kb = P.K >> 1, Ks = P.K >> 5;
     const int nkt = (int)((P.K + KT - 1) / KT);
 

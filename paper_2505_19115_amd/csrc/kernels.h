@@ -31,6 +31,24 @@ struct GemmArgs {
 // Tensor maximum: one partial per workgroup into `partials` (tensor_amax_partials() entries),
 // then folded into amax_bits[0] (bit pattern of max|x|) and, if g_out is given, into the scale.
 int64_t tensor_amax_partials(int64_t rows, int64_t cols, int64_t ld);
+// Workgroup id -> output tile (ty, tx) of an nty x ntx tile grid.
+// Consecutive workgroup ids land on different XCDs (8 of them, each with its own 4 MB L2), so
+// XCD x = id % 8 is given a contiguous band of a walk over the grid, and the walk itself goes
+// down panels of 4 tile rows column by column: the ~32 workgroups an XCD runs at a time then
+// cover about 4 x 8 tiles and share 12 operand strips in its L2 instead of 33.
+__device__ __forceinline__ void tile_coords(int wg, int ntx, int nty, int &ty, int &tx)
+{
+    const int ntiles = ntx * nty;
+    const int per = (ntiles + 7) / 8, xcd = wg & 7, slot = wg >> 3;
+    const int full = ntiles - (per - 1) * 8;  // XCDs that receive `per` tiles (the others per-1)
+    const int t = xcd < full ? xcd * per + slot : full * per + (xcd - full) * (per - 1) + slot;
+    constexpr int GH = 4;
+    const int panel = t / (GH * ntx), in_panel = t - panel * (GH * ntx);
+    const int rows = nty - panel * GH < GH ? nty - panel * GH : GH;  // the last panel may be short
+    tx = in_panel / rows;
+    ty = panel * GH + in_panel - tx * rows;
+}
+
 hipError_t launch_tensor_amax(const void *x, int dt, int64_t rows, int64_t cols, int64_t ld,
                               uint32_t *amax_bits, uint32_t *partials, float *g_out, hipStream_t st);
 hipError_t launch_quantize(const QuantArgs &P, int dt, int axis, int rounding, int block, int sf,
