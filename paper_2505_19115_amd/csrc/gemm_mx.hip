@@ -106,15 +106,26 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_kernel(GemmArgs P)
         const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
         return reinterpret_cast<const uint8_t *>(((uint64_t)hi << 32) | lo);
     };
-    const int dma_base = __builtin_amdgcn_readfirstlane(wave * CPT * 1024);
+    // The loads are issued through inline assembly on purpose: the compiler's wait-count pass
+    // treats a direct-to-LDS load as a possible writer of every LDS location and would put
+    // s_waitcnt vmcnt(0) in front of the next LDS read, i.e. expose the full global latency once
+    // per tile.  Here the destination stage is never read before the explicit wait + barrier below.
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_ptr_t)lds;
+    const uint32_t dma_base = __builtin_amdgcn_readfirstlane(lds0 + wave * CPT * 1024);
+    auto dma_one = [&](uint32_t lds_addr, uint32_t voff, const uint8_t *base) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :
+                     : "s"(lds_addr), "v"(voff), "s"(base)
+                     : "memory");
+    };
     auto dma_codes = [&](int kt, int stage) {
         const uint8_t *pa = uniform_ptr(P.A_codes + (int64_t)kt * ROWB);
         const uint8_t *pb = uniform_ptr(P.B_codes + (int64_t)kt * ROWB);
 #pragma unroll
         for (int u = 0; u < CPT; ++u) {
-            const int dst = stage * STAGE + dma_base + u * 1024;
-            __builtin_amdgcn_global_load_lds((glb_ptr_t)(pa + offA[u]), (lds_ptr_t)(lds + dst), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((glb_ptr_t)(pb + offB[u]), (lds_ptr_t)(lds + BM * ROWB + dst), 16, 0, 0);
+            const uint32_t dst = dma_base + stage * STAGE + u * 1024;
+            dma_one(dst, offA[u], pa);
+            dma_one(dst + BM * ROWB, offB[u], pb);
         }
     };
     const int64_t sar = m0 + tid < P.M ? m0 + tid : P.M - 1;
