@@ -225,26 +225,47 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_kernel(GemmArgs P)
     // next tile goes to the other LDS stage before the last step, ONE barrier, and the first
     // fragments / scales of the next tile are already in flight during the last step.
     // Sc = scales of this tile, Sn = registers for the next tile's.
+    // The compiler's scheduler, left alone, sinks every LDS read down to its first use (and the
+    // scale loads down to the wait), which exposes the LDS latency once per four MFMAs.  Fences
+    // pin the software pipeline; inside a step the eight fragment reads of the NEXT step are
+    // spread between the sixteen MFMAs of this one.
+#define NVFP4_MX_FENCE __builtin_amdgcn_sched_barrier(0);
+#define NVFP4_MX_MIX                                            \
+    _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_)            \
+    {                                                           \
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);      \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);      \
+    }
 #define NVFP4_MX_TILE(stage, kt, more, Sc, Sn)                  \
     {                                                           \
         if (more) {                                             \
             if (DMA) dma_codes((kt) + 1, (stage) ^ 1);          \
             fetch((kt) + 1);                                    \
         }                                                       \
+        NVFP4_MX_FENCE                                          \
         if (STEPS == 4) {                                       \
             load_frags(stage, 1, F1);                           \
             NVFP4_MX_MMA(F0, Sc, 0)                             \
+            NVFP4_MX_MIX                                        \
+            NVFP4_MX_FENCE                                      \
             load_frags(stage, 2, F0);                           \
             NVFP4_MX_MMA(F1, Sc, 1)                             \
+            NVFP4_MX_MIX                                        \
+            NVFP4_MX_FENCE                                      \
             load_frags(stage, 3, F1);                           \
             NVFP4_MX_MMA(F0, Sc, 2)                             \
+            NVFP4_MX_MIX                                        \
+            NVFP4_MX_FENCE                                      \
             if (more) {                                         \
                 stash((stage) ^ 1);                             \
                 __syncthreads();                                \
+                NVFP4_MX_FENCE                                  \
                 load_frags((stage) ^ 1, 0, F0);                 \
                 load_scales((stage) ^ 1, Sn);                   \
+                NVFP4_MX_FENCE                                  \
             }                                                   \
             NVFP4_MX_MMA(F1, Sc, 3)                             \
+            NVFP4_MX_FENCE                                      \
         } else {                                                \
             if (more) stash((stage) ^ 1);                       \
             NVFP4_MX_MMA(F0, Sc, 0)                             \
@@ -268,18 +289,25 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_kernel(GemmArgs P)
         NVFP4_MX_TILE(0, kt, false, S0, S1)
     }
 #undef NVFP4_MX_TILE
+#undef NVFP4_MX_MIX
+#undef NVFP4_MX_FENCE
 #undef NVFP4_MX_MMA
 
     // epilogue: accumulator register v of lane (r, g) is row 8 (v / 4) + 4 g + v % 4, column r
+    // The lane coordinates are re-derived from an opaque copy so that none of the output
+    // addressing is computed before the K loop and kept in registers across it.
+    int lane_e = lane, wave_e = wave;
+    asm volatile("" : "+v"(lane_e), "+v"(wave_e));
+    const int re = lane_e & 31, ge = lane_e >> 5, wme = wave_e >> 1, wne = wave_e & 1;
     const float gg = P.tensor_scales[0] * P.tensor_scales[1];
 #pragma unroll
     for (int a = 0; a < TA; ++a)
 #pragma unroll
         for (int b = 0; b < TB; ++b) {
-            const int64_t col = n0 + wn * 128 + 32 * b + r;
+            const int64_t col = n0 + wne * 128 + 32 * b + re;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int64_t row = m0 + wm * 128 + 32 * a + 8 * (v >> 2) + 4 * g + (v & 3);
+                const int64_t row = m0 + wme * 128 + 32 * a + 8 * (v >> 2) + 4 * ge + (v & 3);
                 if (row < P.M && col < P.N) {
                     const float y = acc[a][b][v] * gg;
                     if (OUT_DT == NVFP4_F32)
@@ -288,7 +316,306 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_kernel(GemmArgs P)
                         reinterpret_cast<uint16_t *>(P.out)[row * P.ldc + col] = mx_bf16_rne(y);
                 }
             }
+            __builtin_amdgcn_sched_barrier(0);  // one accumulator tile at a time: keeps the register peak low
         }
+}
+
+
+// ---------------------------------------------------------------------------------------------
+// Main kernel (K a multiple of 128 and at least 512, 16-byte aligned codes): four LDS stages of
+// 128 contraction elements, every byte written by direct global -> LDS loads, three K tiles in
+// flight, one barrier per tile, no VALU work in the loop except eight scale shifts per tile.
+//
+// What bounds the loop besides the MFMA pipe is the vector L1: it takes one request (at most 64
+// bytes) per clock, and a lane-per-row load costs one request per lane however few bytes it
+// fetches.  The codes need 512 requests per tile (64 bytes per row); the scales are therefore
+// fetched 16 bytes per row at a time = FOUR tiles' worth in one request, into a double-buffered
+// scale area, instead of one dword per row per tile.
+//
+// LDS: four code stages [512 rows][64 bytes] with the 16-byte chunk c of row r at slot
+// c ^ ((r >> 2) & 3) (sixteen consecutive rows reading one logical chunk cover all sixteen 16-byte
+// slots of the 256-byte bank period); two scale buffers [512 rows][16 bytes] (a group of four K
+// tiles each); 4 KB that absorbs the filler loads.  MFMA step s (0, 1) of lane half g multiplies
+// chunk 2 g + s of the tile: the lane shifts the tile's scale dword right by 16 g once and the
+// instruction's byte select is the compile-time s.
+//
+// The MFMA's first operand is the B (N-side) tile, so a lane's accumulator holds four consecutive
+// output COLUMNS of one row: the epilogue is one packed convert pair and one 8-byte (bf16) or
+// 16-byte (fp32) store per four outputs.
+namespace mxd {
+constexpr int KT = 128, ROWB = 64, NS = 4;
+constexpr int STAGE = (mx::BM + mx::BN) * ROWB;        // 32 KB of codes
+constexpr int SBUF = (mx::BM + mx::BN) * 16;           // 8 KB: the scales of four K tiles
+constexpr int SCALES0 = NS * STAGE, DUMP0 = SCALES0 + 2 * SBUF;
+constexpr int LDS_BYTES = DUMP0 + 4096;
+constexpr int PER_TILE = 9;  // direct-to-LDS instructions per wave per K tile: 4 + 4 codes, 1 scales or filler
+}  // namespace mxd
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float float2v_t __attribute__((ext_vector_type(2)));
+
+template <int OUT_DT>
+__global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
+{
+    using namespace mx;
+    using namespace mxd;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int r = lane & 31, g = lane >> 5;
+    const int ntx = (int)((P.N + BN - 1) / BN), nty = (int)((P.M + BM - 1) / BM);
+    int ty, tx;
+    tile_coords((int)blockIdx.x, ntx, nty, ty, tx);
+    const int64_t m0 = (int64_t)ty * BM, n0 = (int64_t)tx * BN;
+    const int64_t Kb = P.K >> 1, Ks = P.K >> 5;
+    const int nkt = (int)(P.K / KT);
+
+    float16v_t acc[TA][TB];
+#pragma unroll
+    for (int a = 0; a < TA; ++a)
+#pragma unroll
+        for (int b = 0; b < TB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+
+    // ---- global -> LDS.  A code instruction fills 1 KB = 16 consecutive tile rows, lane i landing
+    // at byte 16 i (row i / 4, slot i % 4), so the swizzle is applied by choosing WHICH global chunk
+    // the lane fetches.  Rows past the edge are clamped to the last row (their products land in
+    // outputs that are never stored).  Lane offsets are relative to the tile's first row, the
+    // 64-bit part of the address is wave-uniform.
+    const int64_t mrows = P.M - m0 < BM ? P.M - m0 : BM, nrows = P.N - n0 < BN ? P.N - n0 : BN;
+    uint32_t offA[4], offB[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int row = (wave * 4 + u) * 16 + (lane >> 2);
+        const int c = (lane & 3) ^ ((lane >> 4) & 3);
+        offA[u] = (uint32_t)((row < mrows ? row : mrows - 1) * Kb + c * 16);
+        offB[u] = (uint32_t)((row < nrows ? row : nrows - 1) * Kb + c * 16);
+    }
+    const int srow = wave * 64 + lane;
+    const uint32_t offSA = (uint32_t)((srow < mrows ? srow : mrows - 1) * Ks);
+    const uint32_t offSB = (uint32_t)((srow < nrows ? srow : nrows - 1) * Ks);
+    typedef __attribute__((address_space(3))) void *lds_ptr_t;
+    auto uniform_ptr = [](const uint8_t *p) -> const uint8_t * {
+        const uint64_t v = reinterpret_cast<uint64_t>(p);
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+        return reinterpret_cast<const uint8_t *>(((uint64_t)hi << 32) | lo);
+    };
+    // Issued through inline assembly on purpose: the compiler's wait-count pass treats a
+    // direct-to-LDS load as a possible writer of every LDS location and would wait for ALL of them
+    // before the next LDS read.  Here a stage is never read before the explicit counted wait and
+    // the barrier that follow its loads.
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_ptr_t)lds;
+    const uint32_t code_dst = __builtin_amdgcn_readfirstlane(lds0 + wave * 4096);
+    const uint32_t scale_dst = __builtin_amdgcn_readfirstlane(lds0 + SCALES0 + wave * 1024);
+    const uint32_t dump_dst = __builtin_amdgcn_readfirstlane(lds0 + DUMP0 + wave * 1024);
+    auto dma16 = [&](uint32_t lds_addr, uint32_t voff, const uint8_t *base) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(voff), "s"(base) : "memory");
+    };
+    const uint8_t *tileA = P.A_codes + m0 * Kb, *tileB = P.B_codes + n0 * Kb;
+    const uint8_t *tileSA = P.A_scales + m0 * Ks, *tileSB = P.B_scales + n0 * Ks;
+    auto dma_codes = [&](int kt) {
+        const uint32_t st = (uint32_t)(kt & (NS - 1)) * STAGE;
+        const uint8_t *pa = uniform_ptr(tileA + (int64_t)kt * ROWB), *pb = uniform_ptr(tileB + (int64_t)kt * ROWB);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            dma16(code_dst + st + u * 1024, offA[u], pa);
+            dma16(code_dst + st + BM * ROWB + u * 1024, offB[u], pb);
+        }
+    };
+    // Scale group G = the 16 scale bytes of a row that cover K tiles 4 G .. 4 G + 3; the window of the
+    // last group is moved back to end with the row (Ks >= 16), so no load passes the end of a row.
+    auto group_start = [&](int G) -> int { return 16 * G + 16 <= Ks ? 16 * G : (int)Ks - 16; };
+    // part 0: this wave's 64 A rows, part 1: its 64 B rows
+    auto dma_scales = [&](int G, int part) {
+        const uint8_t *base = (part ? tileSB : tileSA) + group_start(G);
+        dma16(scale_dst + (G & 1) * SBUF + part * (BM * 16), part ? offSB : offSA, uniform_ptr(base));
+    };
+    // keeps the number of loads per tile constant (the counted waits rely on it): one request, lands in the dump
+    auto dma_filler = [&]() { dma16(dump_dst, 0u, uniform_ptr(tileSA)); };
+
+    // ---- LDS -> registers
+    struct Frags {
+        uint4 a[TA], b[TB];
+    };
+    struct Scales {
+        uint32_t a[TA], b[TB];
+    };
+    const int sw = (r >> 2) & 3;
+    const int rdA = (wm * 128 + r) * ROWB, rdB = (BM + wn * 128 + r) * ROWB;
+    const int rdS = SCALES0 + (wm * 128 + r) * 16, rdT = SCALES0 + (BM + wn * 128 + r) * 16;
+    const int sh = 16 * g;
+    auto load_frags = [&](int kt, int s, Frags &F) {
+        const uint8_t *p = lds + (kt & (NS - 1)) * STAGE + (((2 * g + s) ^ sw) << 4);
+#pragma unroll
+        for (int a = 0; a < TA; ++a) F.a[a] = *reinterpret_cast<const uint4 *>(p + rdA + 32 * a * ROWB);
+#pragma unroll
+        for (int b = 0; b < TB; ++b) F.b[b] = *reinterpret_cast<const uint4 *>(p + rdB + 32 * b * ROWB);
+    };
+    // raw scale dwords of a tile (all four E8M0 bytes of the row); shifted into place when the tile starts
+    auto load_scales = [&](int kt, Scales &R) {
+        const int G = kt >> 2;
+        const uint8_t *p = lds + (G & 1) * SBUF + (4 * kt - group_start(G));
+#pragma unroll
+        for (int a = 0; a < TA; ++a) R.a[a] = *reinterpret_cast<const uint32_t *>(p + rdS + 512 * a);
+#pragma unroll
+        for (int b = 0; b < TB; ++b) R.b[b] = *reinterpret_cast<const uint32_t *>(p + rdT + 512 * b);
+    };
+    auto shift_scales = [&](const Scales &R, Scales &S) {
+#pragma unroll
+        for (int a = 0; a < TA; ++a) S.a[a] = R.a[a] >> sh;
+#pragma unroll
+        for (int b = 0; b < TB; ++b) S.b[b] = R.b[b] >> sh;
+    };
+    // first MFMA operand = B tile (its rows become accumulator rows), second = A tile
+#define NVFP4_MXD_MMA(F, S, s)                                                                            \
+    _Pragma("unroll") for (int a = 0; a < TA; ++a) _Pragma("unroll") for (int b = 0; b < TB; ++b)         \
+    {                                                                                                     \
+        const int8v_t va = {(int)F.a[a].x, (int)F.a[a].y, (int)F.a[a].z, (int)F.a[a].w, 0, 0, 0, 0};      \
+        const int8v_t vb = {(int)F.b[b].x, (int)F.b[b].y, (int)F.b[b].z, (int)F.b[b].w, 0, 0, 0, 0};      \
+        acc[a][b] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(vb, va, acc[a][b], 4, 4, s, (int)S.b[b], s, \
+                                                                    (int)S.a[a]);                         \
+    }
+    // wait until at most n direct-to-LDS instructions of this wave are still in flight
+#define NVFP4_MXD_WAIT(n) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(n) : "memory");
+#define NVFP4_MXD_FENCE __builtin_amdgcn_sched_barrier(0);
+    // sixteen MFMAs with the eight fragment reads issued just before them spread in between
+#define NVFP4_MXD_MIX                                           \
+    _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_)            \
+    {                                                           \
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);      \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);      \
+    }
+
+    Frags F0, F1;
+    Scales S, R;
+    // nine loads per batch, three batches: scale group 0 rides with tile 0
+    dma_scales(0, 0);
+    dma_scales(0, 1);
+    dma_codes(0);
+    dma_codes(1);
+    dma_filler();
+    dma_codes(2);
+    dma_filler();
+    NVFP4_MXD_WAIT(2 * PER_TILE)  // batch 0 (ten loads) has landed
+    __syncthreads();
+    load_frags(0, 0, F0);
+    load_scales(0, R);
+
+    // K tile kt (stage kt % 4).  The codes of tile kt + 3 go to the stage tile kt - 1 occupied (every
+    // wave finished reading it before the barrier it passed during tile kt - 1), and with them one
+    // half of the next scale group (tiles 0 and 1 of a group) or a filler; step 0 multiplies while
+    // step 1's fragments are read; then this wave's loads of tile kt + 1 (issued two tiles ago, the
+    // two newest batches stay in flight) are waited for, ONE barrier, and the first fragments and
+    // the scales of tile kt + 1 are in flight during step 1.  Every tile runs the same code: past the
+    // end fillers keep the counted wait exact and the barrier / reads of the tile after the last one
+    // are harmless.
+    for (int kt = 0; kt < nkt; ++kt) {
+        if (kt + 3 < nkt) {
+            dma_codes(kt + 3);
+        } else {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) dma_filler();
+        }
+        {
+            const int Gn = (kt >> 2) + 1;
+            if ((kt & 3) < 2 && 4 * Gn < nkt)
+                dma_scales(Gn, kt & 1);
+            else
+                dma_filler();
+        }
+        shift_scales(R, S);
+        NVFP4_MXD_FENCE
+        load_frags(kt, 1, F1);
+        NVFP4_MXD_MMA(F0, S, 0)
+        NVFP4_MXD_MIX
+        NVFP4_MXD_FENCE
+        NVFP4_MXD_WAIT(2 * PER_TILE)
+        __syncthreads();
+        NVFP4_MXD_FENCE
+        load_frags(kt + 1, 0, F0);
+        load_scales(kt + 1, R);
+        NVFP4_MXD_FENCE
+        NVFP4_MXD_MMA(F1, S, 1)
+        NVFP4_MXD_FENCE
+    }
+#undef NVFP4_MXD_MIX
+#undef NVFP4_MXD_FENCE
+#undef NVFP4_MXD_WAIT
+#undef NVFP4_MXD_MMA
+
+    // ---- epilogue: accumulator register v of lane (r, g) of tile (a, b) is output row 32 a + r,
+    // column 32 b + 8 (v / 4) + 4 g + v % 4.  The lane coordinates are re-derived from an opaque
+    // copy so that none of the output addressing is computed before the K loop and kept in
+    // registers across it.
+    int lane_e = lane, wave_e = wave;
+    asm volatile("" : "+v"(lane_e), "+v"(wave_e));
+    const int re = lane_e & 31, ge = lane_e >> 5, wme = wave_e >> 1, wne = wave_e & 1;
+    const float gg = P.tensor_scales[0] * P.tensor_scales[1];
+    constexpr int ESZ = OUT_DT == NVFP4_F32 ? 4 : 2;
+    const int64_t row0 = m0 + wme * 128 + re, col0 = n0 + wne * 128 + 4 * ge;
+    uint8_t *const out = reinterpret_cast<uint8_t *>(P.out);
+    const bool fast = m0 + BM <= P.M && n0 + BN <= P.N && (P.ldc & 3) == 0 && (reinterpret_cast<uintptr_t>(P.out) & 15) == 0;
+    if (fast) {
+#pragma unroll
+        for (int a = 0; a < TA; ++a) {
+            uint8_t *prow = out + ((row0 + 32 * a) * P.ldc + col0) * ESZ;
+#pragma unroll
+            for (int b = 0; b < TB; ++b)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float y0 = acc[a][b][4 * q] * gg, y1 = acc[a][b][4 * q + 1] * gg;
+                    const float y2 = acc[a][b][4 * q + 2] * gg, y3 = acc[a][b][4 * q + 3] * gg;
+                    uint8_t *dst = prow + (32 * b + 8 * q) * ESZ;
+                    if (OUT_DT == NVFP4_F32) {
+                        *reinterpret_cast<float4 *>(dst) = make_float4(y0, y1, y2, y3);
+                    } else {
+                        const float2v_t lo = {y0, y1}, hi = {y2, y3};
+                        const bf16x2_t blo = __builtin_convertvector(lo, bf16x2_t), bhi = __builtin_convertvector(hi, bf16x2_t);
+                        uint2 w;
+                        w.x = *reinterpret_cast<const uint32_t *>(&blo);
+                        w.y = *reinterpret_cast<const uint32_t *>(&bhi);
+                        *reinterpret_cast<uint2 *>(dst) = w;
+                    }
+                }
+            __builtin_amdgcn_sched_barrier(0);  // one accumulator row of tiles at a time keeps the register peak low
+        }
+    } else {
+#pragma unroll
+        for (int a = 0; a < TA; ++a)
+#pragma unroll
+            for (int b = 0; b < TB; ++b) {
+                const int64_t row = row0 + 32 * a;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int64_t col = col0 + 32 * b + 8 * (v >> 2) + (v & 3);
+                    if (row < P.M && col < P.N) {
+                        const float y = acc[a][b][v] * gg;
+                        if (OUT_DT == NVFP4_F32)
+                            reinterpret_cast<float *>(P.out)[row * P.ldc + col] = y;
+                        else
+                            reinterpret_cast<uint16_t *>(P.out)[row * P.ldc + col] = mx_bf16_rne(y);
+                    }
+                }
+            }
+    }
+}
+
+static void launch_mx_dma(const GemmArgs &P, int out_dt, hipStream_t st)
+{
+    const unsigned ntiles = (unsigned)(((P.N + mx::BN - 1) / mx::BN) * ((P.M + mx::BM - 1) / mx::BM));
+    if (out_dt == NVFP4_F32) {
+        auto k = gemm_nt_mxfp4_dma_kernel<NVFP4_F32>;
+        static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, mxd::LDS_BYTES), true);
+        (void)once;
+        hipLaunchKernelGGL(k, dim3(ntiles), dim3(256), mxd::LDS_BYTES, st, P);
+    } else {
+        auto k = gemm_nt_mxfp4_dma_kernel<NVFP4_BF16>;
+        static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, mxd::LDS_BYTES), true);
+        (void)once;
+        hipLaunchKernelGGL(k, dim3(ntiles), dim3(256), mxd::LDS_BYTES, st, P);
+    }
 }
 
 template <int KT>
@@ -311,7 +638,13 @@ static void launch_mx(const GemmArgs &P, int out_dt, hipStream_t st)
 
 hipError_t launch_gemm_mxfp4(const GemmArgs &P, int out_dt, hipStream_t st)
 {
-    if (P.K % 256 == 0)
+    const uintptr_t codes = reinterpret_cast<uintptr_t>(P.A_codes) | reinterpret_cast<uintptr_t>(P.B_codes);
+    const uintptr_t scales = reinterpret_cast<uintptr_t>(P.A_scales) | reinterpret_cast<uintptr_t>(P.B_scales);
+    // lane offsets of the direct-to-LDS loads are 32-bit and relative to the tile's first row
+    const bool offsets_fit = (P.K >> 1) * 256 < ((int64_t)1 << 31);
+    if (P.K % 128 == 0 && P.K >= 512 && (codes & 15) == 0 && (scales & 3) == 0 && offsets_fit)
+        launch_mx_dma(P, out_dt, st);
+    else if (P.K % 256 == 0)
         launch_mx<256>(P, out_dt, st);
     else
         launch_mx<64>(P, out_dt, st);

@@ -179,11 +179,33 @@ def mx_operand(rng, rows, K, lo=112, hi=142):
 
 
 @pytest.mark.parametrize("shape", [(256, 256, 256), (200, 136, 512), (1, 1, 32), (130, 257, 96), (384, 512, 1024),
-                                   (300, 520, 1280), (64, 64, 160)])
+                                   (300, 520, 1280), (64, 64, 160),
+                                   # K a multiple of 128: the four-stage direct-to-LDS kernel with 1, 2, 3, 4, 5 K tiles
+                                   (256, 512, 128), (1, 1, 128), (257, 300, 256), (130, 257, 384), (512, 256, 512),
+                                   (260, 252, 640)])
 def test_mxfp4_random_codes_and_scales(shape):
     M, N, K = shape
     rng = np.random.default_rng(M + 3 * N + K)
     check(mx_operand(rng, M, K), mx_operand(rng, N, K), nv.MXFP4, "mxfp4-random")
+
+
+@pytest.mark.parametrize("out_dtype", [torch.float32, torch.bfloat16])
+def test_mxfp4_output_paths(out_dtype):
+    # full tiles (vector stores), a window of a wider matrix (ldc > N), and an ldc that rules the
+    # vector stores out
+    rng = np.random.default_rng(91)
+    M, N, K = 512, 768, 896
+    A, B = mx_operand(rng, M, K, 120, 134), mx_operand(rng, N, K, 120, 134)
+    check(A, B, nv.MXFP4, "mxfp4-full-tiles", out_dtype=out_dtype)
+    ref, ref_abs = oracle.gemm_nt(A, B, oracle.MXFP4), oracle.gemm_nt(A, B, oracle.MXFP4, take_abs=True)
+    tol = {"tol": 2.0 ** -8} if out_dtype == torch.bfloat16 else {}
+    for ld in (N + 256, N + 1):
+        print(f"[case] mxfp4 gemm window ldc={ld} {out_dtype}", flush=True)
+        out = torch.full((M, ld), -1.0, device="cuda", dtype=out_dtype)
+        nv.gemm(dev(A), dev(B), nv.MXFP4, out=out[:, :N])
+        torch.cuda.synchronize()
+        assert_gemm_close(to_np(out[:, :N].float()), ref, ref_abs, f"ldc{ld}", **tol)
+        assert bool((out[:, N:] == -1.0).all()), "columns outside the window were written"
 
 
 def test_mxfp4_unit_scales_exact_and_extreme_scales():
