@@ -446,21 +446,18 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
     const int rdA = (wm * 128 + r) * ROWB, rdB = (BM + wn * 128 + r) * ROWB;
     const int rdS = SCALES0 + (wm * 128 + r) * 16, rdT = SCALES0 + (BM + wn * 128 + r) * 16;
     const int sh = 16 * g;
-    auto load_frags = [&](int kt, int s, Frags &F) {
+    // fragment i of both operands (rows 32 i + r of the wave's A and B parts) for MFMA step s of tile kt
+    auto load_frag = [&](int kt, int s, Frags &F, int i) {
         const uint8_t *p = lds + (kt & (NS - 1)) * STAGE + (((2 * g + s) ^ sw) << 4);
-#pragma unroll
-        for (int a = 0; a < TA; ++a) F.a[a] = *reinterpret_cast<const uint4 *>(p + rdA + 32 * a * ROWB);
-#pragma unroll
-        for (int b = 0; b < TB; ++b) F.b[b] = *reinterpret_cast<const uint4 *>(p + rdB + 32 * b * ROWB);
+        F.a[i] = *reinterpret_cast<const uint4 *>(p + rdA + 32 * i * ROWB);
+        F.b[i] = *reinterpret_cast<const uint4 *>(p + rdB + 32 * i * ROWB);
     };
     // raw scale dwords of a tile (all four E8M0 bytes of the row); shifted into place when the tile starts
-    auto load_scales = [&](int kt, Scales &R) {
+    auto load_scale = [&](int kt, Scales &R, int i) {
         const int G = kt >> 2;
         const uint8_t *p = lds + (G & 1) * SBUF + (4 * kt - group_start(G));
-#pragma unroll
-        for (int a = 0; a < TA; ++a) R.a[a] = *reinterpret_cast<const uint32_t *>(p + rdS + 512 * a);
-#pragma unroll
-        for (int b = 0; b < TB; ++b) R.b[b] = *reinterpret_cast<const uint32_t *>(p + rdT + 512 * b);
+        R.a[i] = *reinterpret_cast<const uint32_t *>(p + rdS + 512 * i);
+        R.b[i] = *reinterpret_cast<const uint32_t *>(p + rdT + 512 * i);
     };
     auto shift_scales = [&](const Scales &R, Scales &S) {
 #pragma unroll
@@ -468,25 +465,21 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
 #pragma unroll
         for (int b = 0; b < TB; ++b) S.b[b] = R.b[b] >> sh;
     };
-    // first MFMA operand = B tile (its rows become accumulator rows), second = A tile
-#define NVFP4_MXD_MMA(F, S, s)                                                                            \
-    _Pragma("unroll") for (int a = 0; a < TA; ++a) _Pragma("unroll") for (int b = 0; b < TB; ++b)         \
+    // four MFMAs: output rows of A fragment a against the four B fragments.  The first MFMA
+    // operand is the B tile (its rows become accumulator rows), the second the A tile.
+#define NVFP4_MXD_MMA_ROW(F, S, s, ia)                                                                    \
+    _Pragma("unroll") for (int b = 0; b < TB; ++b)                                                        \
     {                                                                                                     \
-        const int8v_t va = {(int)F.a[a].x, (int)F.a[a].y, (int)F.a[a].z, (int)F.a[a].w, 0, 0, 0, 0};      \
+        const int8v_t va = {(int)F.a[ia].x, (int)F.a[ia].y, (int)F.a[ia].z, (int)F.a[ia].w, 0, 0, 0, 0};      \
         const int8v_t vb = {(int)F.b[b].x, (int)F.b[b].y, (int)F.b[b].z, (int)F.b[b].w, 0, 0, 0, 0};      \
-        acc[a][b] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(vb, va, acc[a][b], 4, 4, s, (int)S.b[b], s, \
-                                                                    (int)S.a[a]);                         \
+        acc[ia][b] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(vb, va, acc[ia][b], 4, 4, s, (int)S.b[b], s, \
+                                                                    (int)S.a[ia]);                         \
     }
     // wait until at most n direct-to-LDS instructions of this wave are still in flight
 #define NVFP4_MXD_WAIT(n) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(n) : "memory");
+    // pins the software pipeline: the compiler's scheduler, left alone, sinks every LDS read down to
+    // its first use
 #define NVFP4_MXD_FENCE __builtin_amdgcn_sched_barrier(0);
-    // sixteen MFMAs with the eight fragment reads issued just before them spread in between
-#define NVFP4_MXD_MIX                                           \
-    _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_)            \
-    {                                                           \
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);      \
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);      \
-    }
 
     Frags F0, F1;
     Scales S, R;
@@ -500,50 +493,59 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
     dma_filler();
     NVFP4_MXD_WAIT(2 * PER_TILE)  // batch 0 (ten loads) has landed
     __syncthreads();
-    load_frags(0, 0, F0);
-    load_scales(0, R);
-
-    // K tile kt (stage kt % 4).  The codes of tile kt + 3 go to the stage tile kt - 1 occupied (every
-    // wave finished reading it before the barrier it passed during tile kt - 1), and with them one
-    // half of the next scale group (tiles 0 and 1 of a group) or a filler; step 0 multiplies while
-    // step 1's fragments are read; then this wave's loads of tile kt + 1 (issued two tiles ago, the
-    // two newest batches stay in flight) are waited for, ONE barrier, and the first fragments and
-    // the scales of tile kt + 1 are in flight during step 1.  Every tile runs the same code: past the
-    // end fillers keep the counted wait exact and the barrier / reads of the tile after the last one
-    // are harmless.
-    for (int kt = 0; kt < nkt; ++kt) {
-        if (kt + 3 < nkt) {
-            dma_codes(kt + 3);
-        } else {
 #pragma unroll
-            for (int u = 0; u < 8; ++u) dma_filler();
-        }
-        {
-            const int Gn = (kt >> 2) + 1;
-            if ((kt & 3) < 2 && 4 * Gn < nkt)
-                dma_scales(Gn, kt & 1);
-            else
-                dma_filler();
-        }
+    for (int i = 0; i < 4; ++i) {
+        load_frag(0, 0, F0, i);
+        load_scale(0, R, i);
+    }
+
+    // K tile kt (stage kt % 4), one wave per SIMD: every instruction that blocks at issue (a full
+    // LDS or load queue) starves the MFMA pipe, so LDS reads and loads are dealt out four MFMAs at
+    // a time.  Step 0 multiplies while step 1's fragments are read and the codes of tile kt + 3
+    // are requested (into the stage tile kt - 1 occupied: every wave finished reading it before the
+    // barrier it passed during tile kt - 1), with one half of the next scale group (tiles 0 and 1
+    // of a group) or a filler.  Then this wave's loads of tile kt + 1 (issued two tiles ago, the
+    // two newest batches stay in flight) are waited for, ONE barrier, and step 1 multiplies while
+    // the first fragments and the scales of tile kt + 1 are read.  Every tile runs the same code:
+    // past the end fillers keep the counted wait exact and the barrier / reads of the tile after
+    // the last one are harmless.
+    for (int kt = 0; kt < nkt; ++kt) {
+        const bool more = kt + 3 < nkt;
+        const uint32_t st3 = (uint32_t)((kt + 3) & (NS - 1)) * STAGE;
+        const uint8_t *pa = uniform_ptr(more ? tileA + (int64_t)(kt + 3) * ROWB : tileSA);
+        const uint8_t *pb = uniform_ptr(more ? tileB + (int64_t)(kt + 3) * ROWB : tileSA);
         shift_scales(R, S);
         NVFP4_MXD_FENCE
-        load_frags(kt, 1, F1);
-        NVFP4_MXD_MMA(F0, S, 0)
-        NVFP4_MXD_MIX
-        NVFP4_MXD_FENCE
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            load_frag(kt, 1, F1, i);
+            NVFP4_MXD_MMA_ROW(F0, S, 0, i)
+            NVFP4_MXD_FENCE
+            // (selects, not branches: the loop body must stay one basic block for the fences to hold)
+            dma16(more ? code_dst + st3 + i * 1024 : dump_dst, more ? offA[i] : 0u, pa);
+            dma16(more ? code_dst + st3 + BM * ROWB + i * 1024 : dump_dst, more ? offB[i] : 0u, pb);
+            NVFP4_MXD_FENCE
+        }
+        {
+            const int Gn = (kt >> 2) + 1, part = kt & 1;
+            const bool real = (kt & 3) < 2 && 4 * Gn < nkt;
+            const uint8_t *base = real ? (part ? tileSB : tileSA) + group_start(Gn) : tileSA;
+            dma16(real ? scale_dst + (Gn & 1) * SBUF + part * (BM * 16) : dump_dst, real ? (part ? offSB : offSA) : 0u, uniform_ptr(base));
+        }
         NVFP4_MXD_WAIT(2 * PER_TILE)
         __syncthreads();
         NVFP4_MXD_FENCE
-        load_frags(kt + 1, 0, F0);
-        load_scales(kt + 1, R);
-        NVFP4_MXD_FENCE
-        NVFP4_MXD_MMA(F1, S, 1)
-        NVFP4_MXD_FENCE
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            load_frag(kt + 1, 0, F0, i);
+            load_scale(kt + 1, R, i);
+            NVFP4_MXD_MMA_ROW(F1, S, 1, i)
+            NVFP4_MXD_FENCE
+        }
     }
-#undef NVFP4_MXD_MIX
 #undef NVFP4_MXD_FENCE
 #undef NVFP4_MXD_WAIT
-#undef NVFP4_MXD_MMA
+#undef NVFP4_MXD_MMA_ROW
 
     // ---- epilogue: accumulator register v of lane (r, g) of tile (a, b) is output row 32 a + r,
     // column 32 b + 8 (v / 4) + 4 g + v % 4.  The lane coordinates are re-derived from an opaque
