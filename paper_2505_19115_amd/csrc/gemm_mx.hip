@@ -465,15 +465,15 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
 #pragma unroll
         for (int b = 0; b < TB; ++b) S.b[b] = R.b[b] >> sh;
     };
-    // four MFMAs: output rows of A fragment a against the four B fragments.  The first MFMA
-    // operand is the B tile (its rows become accumulator rows), the second the A tile.
-#define NVFP4_MXD_MMA_ROW(F, S, s, ia)                                                                    \
-    _Pragma("unroll") for (int b = 0; b < TB; ++b)                                                        \
+    // one MFMA: output rows of A fragment ia against B fragment ib.  The first MFMA operand is the
+    // B tile (its rows become accumulator rows), the second the A tile.
+#define NVFP4_MXD_MMA(F, S, s, ia, ib)                                                                    \
     {                                                                                                     \
-        const int8v_t va = {(int)F.a[ia].x, (int)F.a[ia].y, (int)F.a[ia].z, (int)F.a[ia].w, 0, 0, 0, 0};      \
-        const int8v_t vb = {(int)F.b[b].x, (int)F.b[b].y, (int)F.b[b].z, (int)F.b[b].w, 0, 0, 0, 0};      \
-        acc[ia][b] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(vb, va, acc[ia][b], 4, 4, s, (int)S.b[b], s, \
-                                                                    (int)S.a[ia]);                         \
+        const int8v_t va = {(int)F.a[ia].x, (int)F.a[ia].y, (int)F.a[ia].z, (int)F.a[ia].w, 0, 0, 0, 0};  \
+        const int8v_t vb = {(int)F.b[ib].x, (int)F.b[ib].y, (int)F.b[ib].z, (int)F.b[ib].w, 0, 0, 0, 0};  \
+        acc[ia][ib] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(vb, va, acc[ia][ib], 4, 4, s, (int)S.b[ib], s, \
+                                                                      (int)S.a[ia]);                      \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
     }
     // wait until at most n direct-to-LDS instructions of this wave are still in flight
 #define NVFP4_MXD_WAIT(n) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(n) : "memory");
@@ -499,31 +499,39 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
         load_scale(0, R, i);
     }
 
-    // K tile kt (stage kt % 4), one wave per SIMD: every instruction that blocks at issue (a full
-    // LDS or load queue) starves the MFMA pipe, so LDS reads and loads are dealt out four MFMAs at
-    // a time.  Step 0 multiplies while step 1's fragments are read and the codes of tile kt + 3
-    // are requested (into the stage tile kt - 1 occupied: every wave finished reading it before the
-    // barrier it passed during tile kt - 1), with one half of the next scale group (tiles 0 and 1
-    // of a group) or a filler.  Then this wave's loads of tile kt + 1 (issued two tiles ago, the
-    // two newest batches stay in flight) are waited for, ONE barrier, and step 1 multiplies while
-    // the first fragments and the scales of tile kt + 1 are read.  Every tile runs the same code:
-    // past the end fillers keep the counted wait exact and the barrier / reads of the tile after
-    // the last one are harmless.
+    // K tile kt (stage kt % 4).  With one wave per SIMD nothing hides an instruction that takes long
+    // to issue, so exactly one LDS read or one load follows each MFMA and issues in its shadow
+    // (scheduling fences pin that order).  Step 0 multiplies while step 1's fragments are read
+    // and the codes of tile kt + 3 are requested (into the stage tile kt - 1 occupied: every wave
+    // finished reading it before the barrier it passed during tile kt - 1), then one half of the
+    // next scale group (tiles 0 and 1 of a group) or a filler.  This wave's loads of tile kt + 1
+    // (issued two tiles ago; the two newest batches stay in flight) are waited for, ONE barrier,
+    // and step 1 multiplies while the first fragments and the scales of tile kt + 1 are read.
+    // Every tile runs the same code: past the end the loads become one-request fillers (lane
+    // offsets masked to zero, landing in the free stage) that keep the counted wait exact, and
+    // the barrier / reads of the tile after the last one are harmless.
     for (int kt = 0; kt < nkt; ++kt) {
         const bool more = kt + 3 < nkt;
-        const uint32_t st3 = (uint32_t)((kt + 3) & (NS - 1)) * STAGE;
+        const uint32_t lanes = more ? ~0u : 0u;
+        const uint32_t dst3 = code_dst + (uint32_t)((kt + 3) & (NS - 1)) * STAGE;
         const uint8_t *pa = uniform_ptr(more ? tileA + (int64_t)(kt + 3) * ROWB : tileSA);
         const uint8_t *pb = uniform_ptr(more ? tileB + (int64_t)(kt + 3) * ROWB : tileSA);
         shift_scales(R, S);
         NVFP4_MXD_FENCE
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            load_frag(kt, 1, F1, i);
-            NVFP4_MXD_MMA_ROW(F0, S, 0, i)
+            const uint8_t *p = lds + (kt & (NS - 1)) * STAGE + (((2 * g + 1) ^ sw) << 4);
+            NVFP4_MXD_MMA(F0, S, 0, i, 0)
+            F1.a[i] = *reinterpret_cast<const uint4 *>(p + rdA + 32 * i * ROWB);
             NVFP4_MXD_FENCE
-            // (selects, not branches: the loop body must stay one basic block for the fences to hold)
-            dma16(more ? code_dst + st3 + i * 1024 : dump_dst, more ? offA[i] : 0u, pa);
-            dma16(more ? code_dst + st3 + BM * ROWB + i * 1024 : dump_dst, more ? offB[i] : 0u, pb);
+            NVFP4_MXD_MMA(F0, S, 0, i, 1)
+            F1.b[i] = *reinterpret_cast<const uint4 *>(p + rdB + 32 * i * ROWB);
+            NVFP4_MXD_FENCE
+            NVFP4_MXD_MMA(F0, S, 0, i, 2)
+            dma16(dst3 + i * 1024, offA[i] & lanes, pa);
+            NVFP4_MXD_FENCE
+            NVFP4_MXD_MMA(F0, S, 0, i, 3)
+            dma16(dst3 + BM * ROWB + i * 1024, offB[i] & lanes, pb);
             NVFP4_MXD_FENCE
         }
         {
@@ -537,15 +545,26 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
         NVFP4_MXD_FENCE
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            load_frag(kt + 1, 0, F0, i);
-            load_scale(kt + 1, R, i);
-            NVFP4_MXD_MMA_ROW(F1, S, 1, i)
+            const uint8_t *p = lds + ((kt + 1) & (NS - 1)) * STAGE + (((2 * g) ^ sw) << 4);
+            const int G = (kt + 1) >> 2;
+            const uint8_t *q = lds + (G & 1) * SBUF + (4 * (kt + 1) - group_start(G));
+            NVFP4_MXD_MMA(F1, S, 1, i, 0)
+            F0.a[i] = *reinterpret_cast<const uint4 *>(p + rdA + 32 * i * ROWB);
+            NVFP4_MXD_FENCE
+            NVFP4_MXD_MMA(F1, S, 1, i, 1)
+            F0.b[i] = *reinterpret_cast<const uint4 *>(p + rdB + 32 * i * ROWB);
+            NVFP4_MXD_FENCE
+            NVFP4_MXD_MMA(F1, S, 1, i, 2)
+            R.a[i] = *reinterpret_cast<const uint32_t *>(q + rdS + 512 * i);
+            NVFP4_MXD_FENCE
+            NVFP4_MXD_MMA(F1, S, 1, i, 3)
+            R.b[i] = *reinterpret_cast<const uint32_t *>(q + rdT + 512 * i);
             NVFP4_MXD_FENCE
         }
     }
 #undef NVFP4_MXD_FENCE
 #undef NVFP4_MXD_WAIT
-#undef NVFP4_MXD_MMA_ROW
+#undef NVFP4_MXD_MMA
 
     // ---- epilogue: accumulator register v of lane (r, g) of tile (a, b) is output row 32 a + r,
     // column 32 b + 8 (v / 4) + 4 g + v % 4.  The lane coordinates are re-derived from an opaque
