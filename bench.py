@@ -129,11 +129,45 @@ def main() -> int:
             traffic = json.load(open(args.traffic_json)).get("gemm_gate_bytes_per_launch")
         except Exception:
             traffic = None
+    # sustained rate of the two matrix instructions from a register-only loop (power-managed clock;
+    # depends on operand bit activity): the practical ceiling next to the published peak
+    sustained = {
+        "f16_random_operands": round(nv.probe_mfma_rate(nv.MFMA_F16, True), 1),
+        "f16_zero_operands": round(nv.probe_mfma_rate(nv.MFMA_F16, False), 1),
+        "fp4_random_operands": round(nv.probe_mfma_rate(nv.MFMA_FP4, True), 1),
+        "fp4_zero_operands": round(nv.probe_mfma_rate(nv.MFMA_FP4, False), 1),
+        "unit": "TFLOP/s", "how": "nvfp4_probe_mfma_rate: registers only, one workgroup per CU",
+    }
     roofline = {"kernel": "gemm_nt_f16_kernel (gate: 4096x11008x4096)", "bound": "mfma",
                 "achieved": round(gemm_tflops, 2), "peak": PEAK_F16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(gemm_tflops / PEAK_F16_TFLOPS, 4),
                 "frac_of_fp4_peak": round(gemm_tflops / PEAK_FP4_TFLOPS, 4),
+                "frac_of_sustained_f16": round(gemm_tflops / max(sustained["f16_random_operands"], 1e-9), 4),
                 "avg_launch_ms": round(gemm_ms, 4), "traffic": traffic}
+
+    # ---- MXFP4 (block 32, E8M0): the same GEMM on the FP4 matrix instruction, and the format sweep
+    # of the paper's Table 1 / Fig. 1 axes on the down-projection shape (forward linear, bf16 in/out)
+    qam, qbm = nv.quantize(X, 1, fmt=nv.MXFP4), nv.quantize(W, 1, fmt=nv.MXFP4)
+    mx_ms = event_time_ms(lambda i: nv.gemm(qam, qbm, nv.MXFP4, out=Y), max(args.steps, 5), torch)
+    mx_tflops = 2.0 * M * N * K / (mx_ms * 1e-3) / 1e12
+    mxfp4 = {"kernel": "gemm_nt_mxfp4_dma_kernel (gate: 4096x11008x4096)", "bound": "mfma",
+             "achieved": round(mx_tflops, 2), "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s",
+             "frac": round(mx_tflops / PEAK_FP4_TFLOPS, 4),
+             "frac_of_sustained_fp4": round(mx_tflops / max(sustained["fp4_random_operands"], 1e-9), 4),
+             "avg_launch_ms": round(mx_ms, 4)}
+    del qam, qbm
+    dname, dN, dK, dX_, dW_ = data[2][0], data[2][1], data[2][2], data[2][3], data[2][4]
+    sweep = {}
+    for label, fmt in (("nvfp4_b16_e4m3", nv.NVFP4), ("mxfp4_b32_e8m0", nv.MXFP4),
+                       ("b32_e4m3", nv.Format(32, nv.SCALE_E4M3, 1)), ("b64_e4m3", nv.Format(64, nv.SCALE_E4M3, 1)),
+                       ("b128_e4m3", nv.Format(128, nv.SCALE_E4M3, 1))):
+        f = fmt.c()
+        ws = torch.empty(nv.lib.nvfp4_linear_fwd_workspace_bytes(M, dN, dK, C.byref(f)), dtype=torch.uint8, device=dev)
+        Yd = data[2][8]
+        ms = event_time_ms(lambda i: nv.linear_fwd(dX_, dW_, fmt, workspace=ws, out=Yd), 5, torch)
+        sweep[label] = {"ms": round(ms, 4), "TFLOP/s": round(2.0 * M * dN * dK / (ms * 1e-3) / 1e12, 1)}
+        del ws
+    sweep["workload"] = f"linear forward (2 tensor-maximum passes, 2 quantize calls, 1 GEMM), {dname}: M={M} N={dN} K={dK}"
 
     # ---- quantizer sweep tensor (second half of the metric): bf16 [8192, 8192].
     # Four different tensors are cycled (512 MiB in total) so that the 256 MB last-level cache
@@ -160,7 +194,7 @@ def main() -> int:
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        Ms = Ns = Ks = 2048
+        Ms, Ns, Ks = 4096, 4096, 8192  # about 15 s of host work
         Xs, Ws, dYs = synth.normal(Ms, Ks, 1.0, 1), synth.normal(Ns, Ks, 0.02, 2), synth.gradient_like(Ms, Ns, 3)
         t0 = time.perf_counter()
         oracle.linear_fwd(Xs, Ws)
@@ -170,7 +204,7 @@ def main() -> int:
         cores = min(cores, os.cpu_count() or cores)
         cpu = {"value": round(3 * 2 * Ms * Ns * Ks / dt / 1e12, 6), "unit": "TFLOP/s", "cores": cores,
                "kind": "oracle", "seconds": round(dt, 2),
-               "sample": f"one linear fwd+bwd (Eqs. 4-6), M=N=K={Ms}, NVFP4: 6 quantize calls + 3 fp64 GEMMs"}
+               "sample": f"one linear fwd+bwd (Eqs. 4-6), M={Ms} N={Ns} K={Ks}, NVFP4: 6 quantize calls + 3 fp64 GEMMs"}
 
     line = {
         "metric": "NVFP4 linear fwd+bwd TFLOP/s (% FP4 MFMA peak); quantize GB/s (% HBM peak)",
@@ -184,7 +218,8 @@ def main() -> int:
                    "M": M, "layers": [[n, N, K] for n, N, K in layers], "format": "NVFP4 (block 16, E4M3, tensor scale)",
                    "rounding": "fwd RtN; bwd/update SR (Philox4x32-10)"},
         "frac_of_fp4_peak": round(tflops / PEAK_FP4_TFLOPS, 4),
-        "roofline": roofline, "quantize": quant, "cpu_baseline": cpu,
+        "roofline": roofline, "mfma_sustained": sustained, "mxfp4_gemm": mxfp4, "format_sweep": sweep,
+        "quantize": quant, "cpu_baseline": cpu,
     }
     print(json.dumps(line))
     return 0

@@ -157,6 +157,29 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
                               void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Diagnostic, not part of the method: the sustained rate of the matrix
+ * instruction a GEMM kernel issues, measured on the current device from a
+ * register-only loop (no LDS or global traffic) in that kernel's register-tile
+ * pattern, one workgroup per compute unit.  The published MFMA peaks assume the
+ * top clock; under a chip-wide matrix load the clock is power-managed and
+ * depends on how many operand bits toggle, so this is the practical ceiling a
+ * GEMM's achieved rate can be compared with.
+ *   kind             0: v_mfma_f32_32x32x16_f16 (exact NVFP4 / E4M3 GEMM)
+ *                    1: v_mfma_scale_f32_32x32x64_f8f6f4 on FP4 (MXFP4 GEMM)
+ *   random_operands  0: all-zero operand registers; 1: pseudo-random operand
+ *                    bits that change every step
+ *   iters            loop trips per wave, 1 .. 2^22
+ *   scratch          device memory, >= 4 * 512 * (number of compute units) bytes
+ *                    (the kernels write one float per thread there)
+ *   tflops           host pointer, receives TFLOP/s
+ * Blocks the calling thread until the measurement is done.  NVFP4_EINVAL for a
+ * bad kind / iters / null pointer, NVFP4_EWORKSPACE for a short scratch,
+ * NVFP4_EHIP if the runtime reports an error.
+ */
+nvfp4_status nvfp4_probe_mfma_rate(int kind, int random_operands, int iters, void *scratch,
+                                   size_t scratch_bytes, double *tflops, void *stream);
+
+/*
  * Host-side evaluations of the scalar steps the kernels use (the same inline
  * functions, compiled for the host).  They let a CPU-only test sweep the
  * rounding logic against an independent implementation; they touch no GPU.

@@ -98,6 +98,8 @@ def _load() -> C.CDLL:
     L.nvfp4_host_round_rtn_n.argtypes = [vp, i64, vp]
     L.nvfp4_host_round_sr_n.restype = None
     L.nvfp4_host_round_sr_n.argtypes = [vp, vp, i64, vp]
+    L.nvfp4_probe_mfma_rate.restype = C.c_int
+    L.nvfp4_probe_mfma_rate.argtypes = [C.c_int, C.c_int, C.c_int, vp, C.c_size_t, C.POINTER(C.c_double), vp]
     return L
 
 
@@ -110,7 +112,7 @@ EXPORTS = (
     "nvfp4_linear_fwd", "nvfp4_linear_bwd", "nvfp4_host_e4m3_encode", "nvfp4_host_e4m3_decode",
     "nvfp4_host_round_rtn", "nvfp4_host_round_sr", "nvfp4_host_philox4x32_10",
     "nvfp4_host_sr_bits", "nvfp4_host_e8m0_encode", "nvfp4_host_e4m3_encode_n",
-    "nvfp4_host_round_rtn_n", "nvfp4_host_round_sr_n",
+    "nvfp4_host_round_rtn_n", "nvfp4_host_round_sr_n", "nvfp4_probe_mfma_rate",
 )
 
 
@@ -237,3 +239,17 @@ def linear_bwd(dY: torch.Tensor, X: torch.Tensor, W: torch.Tensor, seed: int, fm
                                 seed, workspace.data_ptr(), workspace.numel(), _stream()),
            "nvfp4_linear_bwd")
     return dX, dW
+
+
+MFMA_F16, MFMA_FP4 = 0, 1
+
+
+def probe_mfma_rate(kind: int, random_operands: bool, iters: int = 20000) -> float:
+    """nvfp4_probe_mfma_rate -> sustained TFLOP/s of the matrix instruction on the current device."""
+    assert torch.cuda.is_available(), "the probe runs on the GPU"
+    cus = torch.cuda.get_device_properties(torch.cuda.current_device()).multi_processor_count
+    scratch = torch.empty(cus * 512, dtype=torch.float32, device="cuda")
+    out = C.c_double(0.0)
+    _check(lib.nvfp4_probe_mfma_rate(kind, int(bool(random_operands)), iters, scratch.data_ptr(),
+                                     scratch.numel() * 4, C.byref(out), _stream()), "nvfp4_probe_mfma_rate")
+    return out.value
