@@ -130,6 +130,9 @@ nvfp4_status nvfp4_quantize(const void *x, nvfp4_dtype dt, int64_t rows, int64_t
  * out: [M, N] of out_dt with leading dimension ldc.  Products are exact;
  * accumulation is fp32.
  * K must be a multiple of the block and of 32; M, N >= 1.
+ * Formats: E4M3 scales with blocks 16/32/64/128 (operands expanded exactly to
+ * fp16 for the matrix instruction), and E8M0 scales with block 32 (MXFP4, run
+ * on the FP4 matrix instruction as stored); other pairs: NVFP4_EUNSUPPORTED.
  */
 nvfp4_status nvfp4_gemm(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
                         const uint8_t *A_codes, const uint8_t *A_scales, const uint8_t *B_codes,
