@@ -20,6 +20,8 @@ namespace nvfp4 {
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float float2v_t __attribute__((ext_vector_type(2)));
 
 constexpr int KT = 128;      // contraction elements per LDS tile
 constexpr int KTB = KT / 2;  // bytes of codes per row per tile
@@ -259,7 +261,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
         for (int a = 0; a < TA; ++a)
 #pragma unroll
             for (int b = 0; b < TB; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(F.a[a], F.b[b], acc[a][b], 0, 0, 0);
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(F.b[b], F.a[a], acc[a][b], 0, 0, 0);
     };
 
     // Software pipeline, continuous across K tiles (8 MFMA steps of TA*TB MFMAs per tile; the
@@ -346,25 +348,58 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
 #undef NVFP4_STEP
 #undef NVFP4_INTERLEAVE
 
-    // epilogue: accumulator register v of lane (r, h) is row 8 (v / 4) + 4 h + v % 4, column r
+    // epilogue.  The MFMA's first operand is the B (N-side) fragment, so accumulator register v of
+    // lane (r, h) of tile (a, b) is output row 32 a + r, column 32 b + 8 (v / 4) + 4 h + v % 4: four
+    // consecutive columns of one row = one packed convert pair and one 8-byte (bf16) or 16-byte
+    // (fp32) store.  Full tiles with a suitably aligned output take that path; edge tiles store
+    // element by element.
     const float gg = P.tensor_scales[0] * P.tensor_scales[1];
+    constexpr int ESZ = OUT_DT == NVFP4_F32 ? 4 : 2;
+    const int64_t row0 = m0 + wm * 32 * TA + r, col0 = n0 + wn * 32 * TB + 4 * h;
+    const bool fast = m0 + BM <= P.M && n0 + BN <= P.N && (P.ldc & 3) == 0 && (reinterpret_cast<uintptr_t>(P.out) & 15) == 0;
+    if (fast) {
+        uint8_t *const out = reinterpret_cast<uint8_t *>(P.out);
 #pragma unroll
-    for (int a = 0; a < TA; ++a)
+        for (int a = 0; a < TA; ++a) {
+            uint8_t *prow = out + ((row0 + 32 * a) * P.ldc + col0) * ESZ;
 #pragma unroll
-        for (int b = 0; b < TB; ++b) {
-            const int64_t col = n0 + wn * 32 * TB + 32 * b + r;
+            for (int b = 0; b < TB; ++b)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int64_t row = m0 + wm * 32 * TA + 32 * a + 8 * (v >> 2) + 4 * h + (v & 3);
-                if (row < P.M && col < P.N) {
-                    const float y = acc[a][b][v] * gg;
-                    if (OUT_DT == NVFP4_F32)
-                        reinterpret_cast<float *>(P.out)[row * P.ldc + col] = y;
-                    else
-                        reinterpret_cast<uint16_t *>(P.out)[row * P.ldc + col] = f32_to_bf16_rne(y);
+                for (int q = 0; q < 4; ++q) {
+                    const float y0 = acc[a][b][4 * q] * gg, y1 = acc[a][b][4 * q + 1] * gg;
+                    const float y2 = acc[a][b][4 * q + 2] * gg, y3 = acc[a][b][4 * q + 3] * gg;
+                    uint8_t *dst = prow + (32 * b + 8 * q) * ESZ;
+                    if (OUT_DT == NVFP4_F32) {
+                        *reinterpret_cast<float4 *>(dst) = make_float4(y0, y1, y2, y3);
+                    } else {
+                        const float2v_t lo = {y0, y1}, hi = {y2, y3};
+                        const bf16x2_t blo = __builtin_convertvector(lo, bf16x2_t), bhi = __builtin_convertvector(hi, bf16x2_t);
+                        uint2 w;
+                        w.x = *reinterpret_cast<const uint32_t *>(&blo);
+                        w.y = *reinterpret_cast<const uint32_t *>(&bhi);
+                        *reinterpret_cast<uint2 *>(dst) = w;
+                    }
+                }
+        }
+    } else {
+#pragma unroll
+        for (int a = 0; a < TA; ++a)
+#pragma unroll
+            for (int b = 0; b < TB; ++b) {
+                const int64_t row = row0 + 32 * a;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int64_t col = col0 + 32 * b + 8 * (v >> 2) + (v & 3);
+                    if (row < P.M && col < P.N) {
+                        const float y = acc[a][b][v] * gg;
+                        if (OUT_DT == NVFP4_F32)
+                            reinterpret_cast<float *>(P.out)[row * P.ldc + col] = y;
+                        else
+                            reinterpret_cast<uint16_t *>(P.out)[row * P.ldc + col] = f32_to_bf16_rne(y);
+                    }
                 }
             }
-        }
+    }
 }
 
 template <int B, int WM, int WN, int TA, int TB, bool KTAIL>
