@@ -75,6 +75,9 @@ def main() -> int:
         Yp = torch.empty((4096, 11008), dtype=torch.bfloat16, device=dev)
         for _ in range(3):
             nv.gemm(qa, qb, out=Yp)
+        qam, qbm = nv.quantize(Xp, 1, fmt=nv.MXFP4), nv.quantize(Wp, 1, fmt=nv.MXFP4)
+        for _ in range(3):
+            nv.gemm(qam, qbm, nv.MXFP4, out=Yp)
         xq = synth.student_t_outliers(8192, 8192, seed=100).to(dev)
         g = nv.tensor_scale(xq)
         for axis in (1, 0):
@@ -123,12 +126,13 @@ def main() -> int:
     qa, qb = nv.quantize(X, 1), nv.quantize(W, 1)
     gemm_ms = event_time_ms(lambda i: nv.gemm(qa, qb, out=Y), max(args.steps, 5), torch)
     gemm_tflops = 2.0 * M * N * K / (gemm_ms * 1e-3) / 1e12
-    traffic = None
+    traffic = mx_traffic = None
     if os.path.exists(args.traffic_json):
         try:
-            traffic = json.load(open(args.traffic_json)).get("gemm_gate_bytes_per_launch")
+            tj = json.load(open(args.traffic_json))
+            traffic, mx_traffic = tj.get("gemm_gate_bytes_per_launch"), tj.get("mxfp4_gemm_gate_bytes_per_launch")
         except Exception:
-            traffic = None
+            traffic = mx_traffic = None
     # sustained rate of the two matrix instructions from a register-only loop (power-managed clock;
     # depends on operand bit activity): the practical ceiling next to the published peak
     sustained = {
@@ -154,7 +158,7 @@ def main() -> int:
              "achieved": round(mx_tflops, 2), "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s",
              "frac": round(mx_tflops / PEAK_FP4_TFLOPS, 4),
              "frac_of_sustained_fp4": round(mx_tflops / max(sustained["fp4_random_operands"], 1e-9), 4),
-             "avg_launch_ms": round(mx_ms, 4)}
+             "avg_launch_ms": round(mx_ms, 4), "traffic": mx_traffic}
     del qam, qbm
     dname, dN, dK, dX_, dW_ = data[2][0], data[2][1], data[2][2], data[2][3], data[2][4]
     sweep = {}
