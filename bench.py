@@ -73,10 +73,10 @@ def main() -> int:
         Xp, Wp = synth.normal(4096, 4096, 1.0, 100).to(dev), synth.normal(11008, 4096, 0.02, 200).to(dev)
         qa, qb = nv.quantize(Xp, 1), nv.quantize(Wp, 1)
         Yp = torch.empty((4096, 11008), dtype=torch.bfloat16, device=dev)
-        for _ in range(3):
+        for _ in range(10):
             nv.gemm(qa, qb, out=Yp)
         qam, qbm = nv.quantize(Xp, 1, fmt=nv.MXFP4), nv.quantize(Wp, 1, fmt=nv.MXFP4)
-        for _ in range(3):
+        for _ in range(10):
             nv.gemm(qam, qbm, nv.MXFP4, out=Yp)
         xq = synth.student_t_outliers(8192, 8192, seed=100).to(dev)
         g = nv.tensor_scale(xq)
