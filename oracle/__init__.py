@@ -84,6 +84,9 @@ def lib():
         L.orc_dequantize.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_int64, C.c_int64,
                                      C.POINTER(_Format), C.c_void_p]
         L.orc_gemm_nt.restype = None
+        L.orc_quant_noise.restype = None
+        L.orc_quant_noise.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_int,
+                                      C.POINTER(_Format), C.c_void_p, C.c_void_p, C.c_float, C.c_void_p]
         L.orc_gemm_nt.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.POINTER(_Format),
                                   C.c_void_p, C.c_void_p, C.c_float,
                                   C.c_void_p, C.c_void_p, C.c_float, C.c_int, C.c_void_p]
@@ -228,6 +231,19 @@ def dequantize(codes: np.ndarray, scales: np.ndarray, g: float, fmt: Format = NV
     lib().orc_dequantize(_p(np.ascontiguousarray(codes)), _p(np.ascontiguousarray(scales)),
                          g, outer, K, C.byref(f), _p(out))
     return out
+
+
+def quant_noise(x, q, axis: int = 1, fmt: Format = NVFP4):
+    """(sum x^2, sum (Q(x) - x)^2) in fp64 for q = (codes, scales, g) as quantize(x, axis, ...) returned
+    (Sec. 4: the monitored gradient-to-noise ratio is sqrt of their quotient)."""
+    a, tag = _as_input(x)
+    rows, cols = a.shape
+    codes, scales, g = q
+    out = np.zeros(2, np.float64)
+    f = fmt.c()
+    lib().orc_quant_noise(_p(a), tag, rows, cols, cols, axis, C.byref(f), _p(np.ascontiguousarray(codes)),
+                          _p(np.ascontiguousarray(scales)), g, _p(out))
+    return float(out[0]), float(out[1])
 
 
 def gemm_nt(A, B, fmt: Format = NVFP4, take_abs: bool = False) -> np.ndarray:

@@ -342,6 +342,37 @@ void orc_dequantize(const uint8_t *codes, const uint8_t *scales, float g, int64_
         }
 }
 
+/*
+ * Quantization-noise statistics behind the gradient-to-noise monitor of the
+ * noise-threshold section (Sec. 4): with eps = Q(x) - x the quantization
+ * error of a tensor of d elements, sigma_q^2 is its mean square, and the
+ * monitored ratio ||x|| / (sigma_q sqrt(d)) = sqrt(sum x^2 / sum eps^2) is
+ * compared with sqrt(3).  out[0] = sum x^2, out[1] = sum (Q(x) - x)^2, both
+ * accumulated in fp64 in row-major order of x; Q(x) is the exact value of the
+ * stored element (orc_dequantize's definition).  axis as in orc_quantize:
+ * axis 1 -> operand stored [rows, cols/2]; axis 0 -> stored [cols, rows/2].
+ */
+void orc_quant_noise(const void *x, int dtype, int64_t rows, int64_t cols, int64_t ld, int axis,
+                     const orc_format *f, const uint8_t *codes, const uint8_t *scales, float g,
+                     double out[2])
+{
+    const int64_t B = f->block;
+    const int64_t inner = axis == 1 ? cols : rows;
+    double sx = 0.0, se = 0.0;
+    for (int64_t i = 0; i < rows; ++i)
+        for (int64_t j = 0; j < cols; ++j) {
+            const int64_t o = axis == 1 ? i : j, n = axis == 1 ? j : i;
+            const uint8_t code = (codes[o * (inner / 2) + n / 2] >> (4 * (n & 1))) & 15;
+            const double q = (double)orc_e2m1_decode(code) * scale_value(scales[o * (inner / B) + n / B], f) *
+                             (f->tensor_scale ? (double)g : 1.0);
+            const double xv = (double)load_elem(x, dtype, i * ld + j);
+            sx += xv * xv;
+            se += (q - xv) * (q - xv);
+        }
+    out[0] = sx;
+    out[1] = se;
+}
+
 /* -------------------------------------------------------------------- GEMM */
 
 /*
