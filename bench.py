@@ -160,18 +160,37 @@ def main() -> int:
              "frac_of_sustained_fp4": round(mx_tflops / max(sustained["fp4_random_operands"], 1e-9), 4),
              "avg_launch_ms": round(mx_ms, 4), "traffic": mx_traffic}
     del qam, qbm
-    dname, dN, dK, dX_, dW_ = data[2][0], data[2][1], data[2][2], data[2][3], data[2][4]
+    # Format / block-size sweep (Table 1, Figs. 1-2 axes) on the down projection at 8192 tokens: forward
+    # (RtN) + backward (SR) of the linear layer per format, and the relative quantization MSE of the
+    # activation (RtN) and of the upstream gradient (SR) from the on-GPU noise statistics.
+    sM, sN, sK = 8192, 4096, 11008
+    sX, sW = synth.normal(sM, sK, 1.0, 500).to(dev), synth.normal(sN, sK, 0.02, 501).to(dev)
+    sdY = synth.gradient_like(sM, sN, 502).to(dev)
+    sY = torch.empty((sM, sN), dtype=torch.bfloat16, device=dev)
+    sdX, sdW = torch.empty((sM, sK), dtype=torch.bfloat16, device=dev), torch.empty((sN, sK), dtype=torch.bfloat16, device=dev)
     sweep = {}
     for label, fmt in (("nvfp4_b16_e4m3", nv.NVFP4), ("mxfp4_b32_e8m0", nv.MXFP4),
                        ("b32_e4m3", nv.Format(32, nv.SCALE_E4M3, 1)), ("b64_e4m3", nv.Format(64, nv.SCALE_E4M3, 1)),
                        ("b128_e4m3", nv.Format(128, nv.SCALE_E4M3, 1))):
         f = fmt.c()
-        ws = torch.empty(nv.lib.nvfp4_linear_fwd_workspace_bytes(M, dN, dK, C.byref(f)), dtype=torch.uint8, device=dev)
-        Yd = data[2][8]
-        ms = event_time_ms(lambda i: nv.linear_fwd(dX_, dW_, fmt, workspace=ws, out=Yd), 5, torch)
-        sweep[label] = {"ms": round(ms, 4), "TFLOP/s": round(2.0 * M * dN * dK / (ms * 1e-3) / 1e12, 1)}
-        del ws
-    sweep["workload"] = f"linear forward (2 tensor-maximum passes, 2 quantize calls, 1 GEMM), {dname}: M={M} N={dN} K={dK}"
+        wf = torch.empty(nv.lib.nvfp4_linear_fwd_workspace_bytes(sM, sN, sK, C.byref(f)), dtype=torch.uint8, device=dev)
+        wb = torch.empty(nv.lib.nvfp4_linear_bwd_workspace_bytes(sM, sN, sK, C.byref(f)), dtype=torch.uint8, device=dev)
+
+        def fwd_bwd(i):
+            nv.linear_fwd(sX, sW, fmt, workspace=wf, out=sY)
+            nv.linear_bwd(sdY, sX, sW, 7000 + 3 * i, fmt, workspace=wb, out=(sdX, sdW))
+
+        ms = event_time_ms(fwd_bwd, 4, torch)
+        nx = nv.quant_noise(sX, nv.quantize(sX, 1, nv.RTN, 0, fmt), 1, fmt).cpu().numpy()
+        ng = nv.quant_noise(sdY, nv.quantize(sdY, 1, nv.SR, 9, fmt), 1, fmt).cpu().numpy()
+        sweep[label] = {"fwd_bwd_ms": round(ms, 4), "TFLOP/s": round(3 * 2.0 * sM * sN * sK / (ms * 1e-3) / 1e12, 1),
+                        "rel_mse_activation_rtn": float(f"{nx[1] / nx[0]:.4e}"),
+                        "rel_mse_gradient_sr": float(f"{ng[1] / ng[0]:.4e}"),
+                        "gradient_to_noise_ratio": round(float((ng[0] / ng[1]) ** 0.5), 3)}
+        del wf, wb
+    sweep["workload"] = (f"linear fwd (RtN) + bwd (SR), down projection at 8192 tokens: M={sM} N={sN} K={sK}, bf16 in/out; "
+                         "rel_mse = sum (Q(x)-x)^2 / sum x^2; ratio = ||dY|| / (sigma_q sqrt(d)), threshold sqrt(3)")
+    del sX, sW, sdY, sY, sdX, sdW
 
     # ---- quantizer sweep tensor (second half of the metric): bf16 [8192, 8192].
     # Four different tensors are cycled (512 MiB in total) so that the 256 MB last-level cache
@@ -191,7 +210,15 @@ def main() -> int:
     ms = event_time_ms(lambda i: nv.quantize(xqs[i % NQ], 1, nv.RTN, 0, out=outs[i % NQ]), 12, torch, warmup=NQ)
     gbs = nel * 4.5625 / (ms * 1e-3) / 1e9
     quant["rows_rtn_with_amax_pass"] = {"ms": round(ms, 4), "GB/s": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
-    quant["bytes_per_element"] = {"preset_scale": 2.5625, "with_amax_pass": 4.5625}
+    for label, axis in (("noise_stats_rows", 1), ("noise_stats_cols", 0)):
+        qs = [nv.quantize(xqs[i], axis, nv.SR, 1, tensor_scale=gs[i]) for i in range(NQ)]
+        acc = torch.empty(2, dtype=torch.float64, device=dev)
+        nws = torch.empty(nv.lib.nvfp4_quant_noise_workspace_bytes(8192, 8192, axis), dtype=torch.uint8, device=dev)
+        ms = event_time_ms(lambda i: nv.quant_noise(xqs[i % NQ], qs[i % NQ], axis, out=acc, workspace=nws), 12, torch, warmup=NQ)
+        gbs = nel * 2.5625 / (ms * 1e-3) / 1e9
+        quant[label] = {"ms": round(ms, 4), "GB/s": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
+        del qs
+    quant["bytes_per_element"] = {"preset_scale": 2.5625, "with_amax_pass": 4.5625, "noise_stats": 2.5625}
     del xqs, outs
 
     # ---- the oracle on the host cores, bounded sample of the same workload

@@ -160,6 +160,30 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
                               void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Quantization-noise statistics of a quantized tensor against its source
+ * (noise-threshold section, Sec. 4: with eps = Q(x) - x the quantization error
+ * of a d-element gradient and sigma_q^2 its mean square, the paper monitors
+ * ||x|| / (sigma_q sqrt(d)) = sqrt(sum x^2 / sum eps^2) against sqrt(3); the
+ * same quotient inverted is the relative quantization MSE of a format):
+ *   sums[0] = sum x^2,   sums[1] = sum (Q(x) - x)^2     over all rows * cols elements,
+ * Q(x) = (-1)^sign * E2M1 magnitude * block scale * tensor scale of the stored element.
+ *   x, dt, rows, cols, ld, axis, f   as in nvfp4_quantize (device pointer)
+ *   codes, scales   device, the operand nvfp4_quantize wrote for this x, axis and format
+ *   tensor_scale    device fp32 scalar (read only when f->tensor_scale is 1)
+ *   sums            device double[2], 8-byte aligned
+ *   workspace       device, >= nvfp4_quant_noise_workspace_bytes(rows, cols, axis), 16-byte aligned
+ * Squares are summed in fp32 over 8 elements, everything above that in fp64 in
+ * a fixed order: the result is deterministic and agrees with an fp64 evaluation
+ * to about 1e-6 relative.  Asynchronous on `stream`.  An empty tensor gives {0, 0}.
+ * Errors: as nvfp4_quantize (NVFP4_EINVAL / ESHAPE / EALIGN / EUNSUPPORTED / EWORKSPACE / EHIP).
+ */
+size_t nvfp4_quant_noise_workspace_bytes(int64_t rows, int64_t cols, int axis);
+nvfp4_status nvfp4_quant_noise(const void *x, nvfp4_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                               int axis, const nvfp4_format *f, const uint8_t *codes,
+                               const uint8_t *scales, const float *tensor_scale, double *sums,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Diagnostic, not part of the method: the sustained rate of the matrix
  * instruction a GEMM kernel issues, measured on the current device from a
  * register-only loop (no LDS or global traffic) in that kernel's register-tile

@@ -98,6 +98,11 @@ def _load() -> C.CDLL:
     L.nvfp4_host_round_rtn_n.argtypes = [vp, i64, vp]
     L.nvfp4_host_round_sr_n.restype = None
     L.nvfp4_host_round_sr_n.argtypes = [vp, vp, i64, vp]
+    L.nvfp4_quant_noise_workspace_bytes.restype = C.c_size_t
+    L.nvfp4_quant_noise_workspace_bytes.argtypes = [i64, i64, C.c_int]
+    L.nvfp4_quant_noise.restype = C.c_int
+    L.nvfp4_quant_noise.argtypes = [vp, C.c_int, i64, i64, i64, C.c_int, C.POINTER(_Format), vp, vp, vp, vp, vp,
+                                    C.c_size_t, vp]
     L.nvfp4_probe_mfma_rate.restype = C.c_int
     L.nvfp4_probe_mfma_rate.argtypes = [C.c_int, C.c_int, C.c_int, vp, C.c_size_t, C.POINTER(C.c_double), vp]
     return L
@@ -113,6 +118,7 @@ EXPORTS = (
     "nvfp4_host_round_rtn", "nvfp4_host_round_sr", "nvfp4_host_philox4x32_10",
     "nvfp4_host_sr_bits", "nvfp4_host_e8m0_encode", "nvfp4_host_e4m3_encode_n",
     "nvfp4_host_round_rtn_n", "nvfp4_host_round_sr_n", "nvfp4_probe_mfma_rate",
+    "nvfp4_quant_noise_workspace_bytes", "nvfp4_quant_noise",
 )
 
 
@@ -253,3 +259,23 @@ def probe_mfma_rate(kind: int, random_operands: bool, iters: int = 20000) -> flo
     _check(lib.nvfp4_probe_mfma_rate(kind, int(bool(random_operands)), iters, scratch.data_ptr(),
                                      scratch.numel() * 4, C.byref(out), _stream()), "nvfp4_probe_mfma_rate")
     return out.value
+
+
+def quant_noise(x: torch.Tensor, q, axis: int = 1, fmt: Format = NVFP4, out: torch.Tensor | None = None,
+                workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """nvfp4_quant_noise (Sec. 4 monitor): device double[2] = (sum x^2, sum (Q(x) - x)^2) for q = (codes, scales, g)
+    as quantize(x, axis, ..., fmt) returned."""
+    _require_gpu(x)
+    assert x.dim() == 2 and x.stride(1) == 1
+    rows, cols = x.shape
+    codes, scales, g = q
+    f = fmt.c()
+    ws = workspace
+    if ws is None:
+        ws = torch.empty(max(lib.nvfp4_quant_noise_workspace_bytes(rows, cols, axis), 16), dtype=torch.uint8, device=x.device)
+    if out is None:
+        out = torch.empty(2, dtype=torch.float64, device=x.device)
+    _check(lib.nvfp4_quant_noise(x.data_ptr(), _dtype_tag(x), rows, cols, x.stride(0) if rows > 1 else cols, axis,
+                                 C.byref(f), codes.data_ptr(), scales.data_ptr(), g.data_ptr(), out.data_ptr(),
+                                 ws.data_ptr(), ws.numel(), _stream()), "nvfp4_quant_noise")
+    return out

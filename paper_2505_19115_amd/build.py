@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libnvfp4.so")
-SOURCES = ("quantize.hip", "gemm.hip", "gemm_mx.hip", "probe.hip", "api.hip")
+SOURCES = ("quantize.hip", "gemm.hip", "gemm_mx.hip", "probe.hip", "noise.hip", "api.hip")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

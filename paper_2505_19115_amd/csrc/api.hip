@@ -323,6 +323,36 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
     return NVFP4_OK;
 }
 
+size_t nvfp4_quant_noise_workspace_bytes(int64_t rows, int64_t cols, int axis)
+{
+    if (axis != 0 && axis != 1) return 0;
+    return align_up(16 * (size_t)quant_noise_partials(rows, cols, axis));
+}
+
+nvfp4_status nvfp4_quant_noise(const void *x, nvfp4_dtype dt, int64_t rows, int64_t cols, int64_t ld, int axis,
+                               const nvfp4_format *f, const uint8_t *codes, const uint8_t *scales,
+                               const float *tensor_scale, double *sums, void *workspace, size_t workspace_bytes,
+                               void *stream)
+{
+    nvfp4_status s = check_format(f);
+    if (s != NVFP4_OK) return s;
+    s = check_tensor(x, dt, rows, cols, ld);
+    if (s != NVFP4_OK) return s;
+    if (axis != 0 && axis != 1) return NVFP4_EINVAL;
+    const bool empty = rows == 0 || cols == 0;
+    if (!sums || (!empty && (!codes || !scales)) || (f->tensor_scale && !tensor_scale)) return NVFP4_EINVAL;
+    const int64_t inner = axis == 1 ? cols : rows;
+    if (inner % f->block != 0) return NVFP4_ESHAPE;
+    if (!aligned16(codes) || !aligned16(scales) || (reinterpret_cast<uintptr_t>(sums) & 7u) != 0) return NVFP4_EALIGN;
+    if (!workspace || workspace_bytes < nvfp4_quant_noise_workspace_bytes(rows, cols, axis)) return NVFP4_EWORKSPACE;
+    if (!aligned16(workspace)) return NVFP4_EALIGN;
+    return launch_quant_noise(x, dt, rows, cols, ld, axis, f->block, f->scale, codes, scales,
+                              f->tensor_scale ? tensor_scale : nullptr, reinterpret_cast<double *>(workspace), sums,
+                              reinterpret_cast<hipStream_t>(stream)) == hipSuccess
+               ? NVFP4_OK
+               : NVFP4_EHIP;
+}
+
 // ---- host evaluations of the scalar steps (no GPU involved)
 
 uint8_t nvfp4_host_e4m3_encode(float r)

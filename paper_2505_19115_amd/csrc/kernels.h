@@ -55,5 +55,10 @@ hipError_t launch_quantize(const QuantArgs &P, int dt, int axis, int rounding, i
                            bool hw_convert, hipStream_t st);
 hipError_t launch_gemm(const GemmArgs &P, int block, int sf, int out_dt, hipStream_t st);
 hipError_t launch_gemm_mxfp4(const GemmArgs &P, int out_dt, hipStream_t st);  // block 32, E8M0
+// Noise statistics: per-workgroup partial pairs (quant_noise_partials() of them), folded into sums[2].
+int64_t quant_noise_partials(int64_t rows, int64_t cols, int axis);
+hipError_t launch_quant_noise(const void *x, int dt, int64_t rows, int64_t cols, int64_t ld, int axis, int block, int sf,
+                              const uint8_t *codes, const uint8_t *scales, const float *g, double *partials, double *sums,
+                              hipStream_t st);
 
 }  // namespace nvfp4
