@@ -102,13 +102,14 @@ def main() -> int:
         Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
         dX = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
         dW = torch.empty((N, K), dtype=torch.bfloat16, device=dev)
-        data.append((name, N, K, X, W, dY, wf, wb, Y, dX, dW))
+        data.append((name, N, K, X, W, dY, wf, wb, Y, dX, dW, torch.empty(2, dtype=torch.float32, device=dev)))
     flop_per_step = sum(3 * 2 * M * N * K for _, N, K in layers)
 
     def step(s):
-        for name, N, K, X, W, dY, wf, wb, Y, dX, dW in data:
-            nv.linear_fwd(X, W, workspace=wf, out=Y)
-            nv.linear_bwd(dY, X, W, seed=1000 + 3 * s, workspace=wb, out=(dX, dW))
+        for name, N, K, X, W, dY, wf, wb, Y, dX, dW, sc in data:
+            # the forward call hands the per-tensor scales of X and W to the backward call
+            nv.linear_fwd(X, W, workspace=wf, out=Y, scales_out=sc)
+            nv.linear_bwd(dY, X, W, seed=1000 + 3 * s, workspace=wb, out=(dX, dW), xw_scales=sc)
 
     for s in range(args.warmup):
         step(s)
@@ -122,7 +123,7 @@ def main() -> int:
     tflops = flop_per_step / (elapsed / args.steps) / 1e12
 
     # ---- dominant kernel: the block-scaled GEMM at the gate/up shape (same launch as in step)
-    name, N, K, X, W, dY, wf, wb, Y, dX, dW = data[0]
+    name, N, K, X, W, dY, wf, wb, Y, dX, dW, _ = data[0]
     qa, qb = nv.quantize(X, 1), nv.quantize(W, 1)
     gemm_ms = event_time_ms(lambda i: nv.gemm(qa, qb, out=Y), max(args.steps, 5), torch)
     gemm_tflops = 2.0 * M * N * K / (gemm_ms * 1e-3) / 1e12
@@ -245,7 +246,7 @@ def main() -> int:
         "dtype": "e2m1 codes x e4m3 scales, expanded exactly to f16 for MFMA, f32 accumulate",
         "data": "synthetic",
         "config": {"workload": "Llama2-7B SwiGLU MLP linears fwd+bwd (gate, up, down), tokens=4096: "
-                               "9 GEMMs + 18 quantize calls + tensor-maximum passes per step, bf16 in",
+                               "9 GEMMs + 18 quantize calls + 9 tensor-maximum passes per step (X and W scales handed from forward to backward), bf16 in",
                    "M": M, "layers": [[n, N, K] for n, N, K in layers], "format": "NVFP4 (block 16, E4M3, tensor scale)",
                    "rounding": "fwd RtN; bwd/update SR (Philox4x32-10)"},
         "frac_of_fp4_peak": round(tflops / PEAK_FP4_TFLOPS, 4),

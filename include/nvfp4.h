@@ -142,22 +142,30 @@ nvfp4_status nvfp4_gemm(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
 /*
  * Forward GEMM, Eq. 4:  Y[M, N] = Q_RtN(X[M, K]) * Q_RtN(W[N, K])^T, blocks along K.
  * X, W dense row-major of in_dt; Y dense row-major of out_dt.
+ * xw_scales_out: NULL, or device fp32[2] that receives the per-tensor scales
+ * {gX, gW} this call derived from max|X| and max|W| (1, 1 for a format without
+ * tensor scale), to be handed to nvfp4_linear_bwd for the same X and W.
  */
 nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, int64_t N,
                               int64_t K, nvfp4_dtype in_dt, nvfp4_dtype out_dt,
                               const nvfp4_format *f, void *workspace, size_t workspace_bytes,
-                              void *stream);
+                              void *stream, float *xw_scales_out);
 
 /*
  * Backward and update GEMMs, Eqs. 5-6, for upstream gradient dY[M, N]:
  *   dX[M, K] = Q_SR(dY) * Q_RtN(W^T)^T     blocks along N; SR stream `seed`
  *   dW[N, K] = Q_SR(dY^T) * Q_SR(X^T)^T    blocks along M; SR streams seed+1 (dY), seed+2 (X)
  * Either of dX, dW may be NULL to skip that GEMM.
+ * xw_scales: NULL, or device fp32[2] = {gX, gW} as nvfp4_linear_fwd returned
+ * them for these X and W: the two tensor-maximum passes over X and W are then
+ * skipped (the per-tensor scale is a function of the tensor alone, so the
+ * results are identical).  Ignored for a format without tensor scale.
  */
 nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void *dX, void *dW,
                               int64_t M, int64_t N, int64_t K, nvfp4_dtype in_dt,
                               nvfp4_dtype out_dt, const nvfp4_format *f, uint64_t seed,
-                              void *workspace, size_t workspace_bytes, void *stream);
+                              void *workspace, size_t workspace_bytes, void *stream,
+                              const float *xw_scales);
 
 /*
  * Quantization-noise statistics of a quantized tensor against its source

@@ -74,9 +74,9 @@ def _load() -> C.CDLL:
     L.nvfp4_gemm.restype = ci
     L.nvfp4_gemm.argtypes = [i64, i64, i64, fp, vp, vp, vp, vp, vp, vp, ci, i64, vp]
     L.nvfp4_linear_fwd.restype = ci
-    L.nvfp4_linear_fwd.argtypes = [vp, vp, vp, i64, i64, i64, ci, ci, fp, vp, sz, vp]
+    L.nvfp4_linear_fwd.argtypes = [vp, vp, vp, i64, i64, i64, ci, ci, fp, vp, sz, vp, vp]
     L.nvfp4_linear_bwd.restype = ci
-    L.nvfp4_linear_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, fp, u64, vp, sz, vp]
+    L.nvfp4_linear_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, fp, u64, vp, sz, vp, vp]
     # host probes
     L.nvfp4_host_e4m3_encode.restype = C.c_uint8
     L.nvfp4_host_e4m3_encode.argtypes = [C.c_float]
@@ -206,8 +206,9 @@ def gemm(A, B, fmt: Format = NVFP4, out_dtype: torch.dtype = torch.float32, out=
 
 def linear_fwd(X: torch.Tensor, W: torch.Tensor, fmt: Format = NVFP4,
                out_dtype: torch.dtype = torch.float32, workspace: torch.Tensor | None = None,
-               out: torch.Tensor | None = None) -> torch.Tensor:
-    """nvfp4_linear_fwd (Eq. 4): Y[M,N] = Q_RtN(X[M,K]) Q_RtN(W[N,K])^T."""
+               out: torch.Tensor | None = None, scales_out: torch.Tensor | None = None) -> torch.Tensor:
+    """nvfp4_linear_fwd (Eq. 4): Y[M,N] = Q_RtN(X[M,K]) Q_RtN(W[N,K])^T.
+    scales_out: device fp32[2] that receives {gX, gW} for linear_bwd(..., xw_scales=...)."""
     _require_gpu(X, W)
     assert X.is_contiguous() and W.is_contiguous() and X.dtype == W.dtype
     M, K = X.shape
@@ -219,14 +220,16 @@ def linear_fwd(X: torch.Tensor, W: torch.Tensor, fmt: Format = NVFP4,
     Y = torch.empty((M, N), dtype=out_dtype, device=X.device) if out is None else out
     _check(lib.nvfp4_linear_fwd(X.data_ptr(), W.data_ptr(), Y.data_ptr(), M, N, K, _dtype_tag(X),
                                 _dtype_tag(Y), C.byref(f), workspace.data_ptr(), workspace.numel(),
-                                _stream()), "nvfp4_linear_fwd")
+                                _stream(), None if scales_out is None else scales_out.data_ptr()),
+           "nvfp4_linear_fwd")
     return Y
 
 
 def linear_bwd(dY: torch.Tensor, X: torch.Tensor, W: torch.Tensor, seed: int, fmt: Format = NVFP4,
                out_dtype: torch.dtype = torch.float32, workspace: torch.Tensor | None = None,
-               out=None):
-    """nvfp4_linear_bwd (Eqs. 5-6) -> (dX [M,K], dW [N,K])."""
+               out=None, xw_scales: torch.Tensor | None = None):
+    """nvfp4_linear_bwd (Eqs. 5-6) -> (dX [M,K], dW [N,K]).
+    xw_scales: device fp32[2] = {gX, gW} from linear_fwd(..., scales_out=...) for the same X and W."""
     _require_gpu(dY, X, W)
     assert dY.is_contiguous() and X.is_contiguous() and W.is_contiguous()
     M, N = dY.shape
@@ -242,7 +245,8 @@ def linear_bwd(dY: torch.Tensor, X: torch.Tensor, W: torch.Tensor, seed: int, fm
         dX, dW = out
     _check(lib.nvfp4_linear_bwd(dY.data_ptr(), X.data_ptr(), W.data_ptr(), dX.data_ptr(),
                                 dW.data_ptr(), M, N, K, _dtype_tag(dY), _dtype_tag(dX), C.byref(f),
-                                seed, workspace.data_ptr(), workspace.numel(), _stream()),
+                                seed, workspace.data_ptr(), workspace.numel(), _stream(),
+                                None if xw_scales is None else xw_scales.data_ptr()),
            "nvfp4_linear_bwd")
     return dX, dW
 

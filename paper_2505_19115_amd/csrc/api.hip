@@ -221,7 +221,7 @@ nvfp4_status nvfp4_gemm(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
 nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, int64_t N,
                               int64_t K, nvfp4_dtype in_dt, nvfp4_dtype out_dt,
                               const nvfp4_format *f, void *workspace, size_t workspace_bytes,
-                              void *stream)
+                              void *stream, float *xw_scales_out)
 {
     nvfp4_status s = check_format(f);
     if (s != NVFP4_OK) return s;
@@ -236,7 +236,8 @@ nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, 
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
 
     uint8_t *ws = reinterpret_cast<uint8_t *>(workspace);
-    float *ts = reinterpret_cast<float *>(ws);                 // {gX, gW}
+    // {gX, gW}: written by the quantizers (1 for a format without tensor scale), read by the GEMM
+    float *ts = xw_scales_out ? xw_scales_out : reinterpret_cast<float *>(ws);
     uint32_t *amax = reinterpret_cast<uint32_t *>(ws + 64);    // two maxima
     uint32_t *partials = reinterpret_cast<uint32_t *>(ws + WS_HEADER);
     uint8_t *p = ws + WS_HEADER + (partials_bytes(M, K) > partials_bytes(N, K) ? partials_bytes(M, K) : partials_bytes(N, K));
@@ -261,7 +262,7 @@ nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, 
 nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void *dX, void *dW,
                               int64_t M, int64_t N, int64_t K, nvfp4_dtype in_dt,
                               nvfp4_dtype out_dt, const nvfp4_format *f, uint64_t seed,
-                              void *workspace, size_t workspace_bytes, void *stream)
+                              void *workspace, size_t workspace_bytes, void *stream, const float *xw_scales)
 {
     nvfp4_status s = check_format(f);
     if (s != NVFP4_OK) return s;
@@ -297,24 +298,29 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
     uint8_t *xts = p;
 
     const int gm = f->tensor_scale ? G_FROM_AMAX : G_NONE;
+    // X and W: scales handed over from the forward call (used as given), else from their maxima
+    const bool known = f->tensor_scale && xw_scales != nullptr;
+    const int gm_xw = known ? G_PRESET : gm;
+    const float *gsrc_w = known ? xw_scales + 1 : reinterpret_cast<const float *>(amax + 1);
+    const float *gsrc_x = known ? xw_scales + 0 : reinterpret_cast<const float *>(amax + 2);
     if (f->tensor_scale) {
         if (launch_tensor_amax(dY, in_dt, M, N, N, amax + 0, partials, nullptr, st) != hipSuccess) return NVFP4_EHIP;
     }
     if (dX) {
-        if (f->tensor_scale && launch_tensor_amax(W, in_dt, N, K, K, amax + 1, partials, nullptr, st) != hipSuccess) return NVFP4_EHIP;
+        if (f->tensor_scale && !known && launch_tensor_amax(W, in_dt, N, K, K, amax + 1, partials, nullptr, st) != hipSuccess) return NVFP4_EHIP;
         // Eq. 5: dX[M, K] = Q_SR(dY)[M, N] * Q_RtN(W^T)[K, N]^T
         QuantPlan qa{dY, in_dt, M, N, N, 1, NVFP4_SR, seed, dyc, dys, reinterpret_cast<const float *>(amax + 0), ts + 0, gm};
-        QuantPlan qb{W, in_dt, N, K, K, 0, NVFP4_RTN, 0, wtc, wts, reinterpret_cast<const float *>(amax + 1), ts + 1, gm};
+        QuantPlan qb{W, in_dt, N, K, K, 0, NVFP4_RTN, 0, wtc, wts, gsrc_w, ts + 1, gm_xw};
         if (run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
         if (run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
         GemmArgs g{M, K, N, dyc, dys, wtc, wts, ts + 0, dX, K};
         if (launch_gemm(g, f->block, f->scale, out_dt, st) != hipSuccess) return NVFP4_EHIP;
     }
     if (dW) {
-        if (f->tensor_scale && launch_tensor_amax(X, in_dt, M, K, K, amax + 2, partials, nullptr, st) != hipSuccess) return NVFP4_EHIP;
+        if (f->tensor_scale && !known && launch_tensor_amax(X, in_dt, M, K, K, amax + 2, partials, nullptr, st) != hipSuccess) return NVFP4_EHIP;
         // Eq. 6: dW[N, K] = Q_SR(dY^T)[N, M] * Q_SR(X^T)[K, M]^T
         QuantPlan qa{dY, in_dt, M, N, N, 0, NVFP4_SR, seed + 1, dytc, dyts, reinterpret_cast<const float *>(amax + 0), ts + 2, gm};
-        QuantPlan qb{X, in_dt, M, K, K, 0, NVFP4_SR, seed + 2, xtc, xts, reinterpret_cast<const float *>(amax + 2), ts + 3, gm};
+        QuantPlan qb{X, in_dt, M, K, K, 0, NVFP4_SR, seed + 2, xtc, xts, gsrc_x, ts + 3, gm_xw};
         if (run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
         if (run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
         GemmArgs g{N, K, M, dytc, dyts, xtc, xts, ts + 2, dW, K};

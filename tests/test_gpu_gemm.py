@@ -171,6 +171,31 @@ def test_linear_fp32_inputs_bf16_outputs():
         assert np.all(np.abs(to_np(got.float()) - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * np.abs(ref).max())
 
 
+def test_backward_with_scales_handed_over_from_forward():
+    # the per-tensor scales of X and W are functions of the tensors alone: the backward call that is
+    # given the forward call's {gX, gW} skips two maximum passes and must produce the same bits
+    M, N, K = 256, 192, 320
+    X = synth.normal(M, K, 1.0, 71).cuda()
+    W = synth.normal(N, K, 0.02, 72).cuda()
+    dY = synth.gradient_like(M, N, 73).cuda()
+    for fmt in (nv.NVFP4, nv.MXFP4):
+        print(f"[case] scale hand-over fmt={fmt}", flush=True)
+        sc = torch.full((2,), -1.0, device="cuda")
+        Y0 = nv.linear_fwd(X, W, fmt)
+        Y1 = nv.linear_fwd(X, W, fmt, scales_out=sc)
+        assert torch.equal(Y0, Y1)
+        if fmt.tensor_scale:
+            gx, gw = float(nv.tensor_scale(X)), float(nv.tensor_scale(W))
+            assert sc.cpu().tolist() == [gx, gw]
+            assert gx == oracle.quantize(X.cpu(), 1)[2] and gw == oracle.quantize(W.cpu(), 1)[2]
+        else:
+            assert sc.cpu().tolist() == [1.0, 1.0]
+        a = nv.linear_bwd(dY, X, W, 5, fmt)
+        b = nv.linear_bwd(dY, X, W, 5, fmt, xw_scales=sc)
+        torch.cuda.synchronize()
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
 # ---------------------------------------------------------------- MXFP4 (block 32, E8M0): native FP4 MFMA
 def mx_operand(rng, rows, K, lo=112, hi=142):
     codes = rng.integers(0, 256, (rows, K // 2)).astype(np.uint8)

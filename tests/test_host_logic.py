@@ -90,13 +90,13 @@ def test_gemm_and_linear_argument_errors():
     assert g(f=nv.Format(64, nv.SCALE_E8M0, 0).c()) == nv.EUNSUPPORTED  # E8M0 GEMM exists for block 32 only
     assert g(M=0) == nv.OK           # empty product: nothing to do, nothing launched
     fw = lambda **k: nv.lib.nvfp4_linear_fwd(k.get("X", FAKE), FAKE, FAKE, 64, 64, k.get("K", 64), nv.BF16, nv.F32,
-                                             C.byref(f), k.get("ws", FAKE), k.get("wsb", 1 << 30), None)
+                                             C.byref(f), k.get("ws", FAKE), k.get("wsb", 1 << 30), None, None)
     assert fw(X=None) == nv.EINVAL
     assert fw(K=40) == nv.ESHAPE
     assert fw(ws=None) == nv.EWORKSPACE
     assert fw(wsb=16) == nv.EWORKSPACE
     bw = lambda **k: nv.lib.nvfp4_linear_bwd(k.get("dY", FAKE), FAKE, FAKE, FAKE, FAKE, k.get("M", 64), 64, 64,
-                                             nv.BF16, nv.F32, C.byref(f), 0, FAKE, k.get("wsb", 1 << 30), None)
+                                             nv.BF16, nv.F32, C.byref(f), 0, FAKE, k.get("wsb", 1 << 30), None, None)
     assert bw(dY=None) == nv.EINVAL
     assert bw(M=48) == nv.ESHAPE     # the update GEMM contracts over M
     assert bw(wsb=16) == nv.EWORKSPACE
