@@ -518,21 +518,24 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
         const uint8_t *pb = uniform_ptr(more ? tileB + (int64_t)(kt + 3) * ROWB : tileSA);
         shift_scales(R, S);
         NVFP4_MXD_FENCE
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        // step 0: MFMAs 0-7 each shadow one fragment read of step 1 (B fragments first: every row of
+        // MFMAs needs all four), MFMAs 8-15 each shadow one load of tile kt + 3; by the barrier the
+        // reads of this stage are long complete
+        {
             const uint8_t *p = lds + (kt & (NS - 1)) * STAGE + (((2 * g + 1) ^ sw) << 4);
-            NVFP4_MXD_MMA(F0, S, 0, i, 0)
-            F1.a[i] = *reinterpret_cast<const uint4 *>(p + rdA + 32 * i * ROWB);
-            NVFP4_MXD_FENCE
-            NVFP4_MXD_MMA(F0, S, 0, i, 1)
-            F1.b[i] = *reinterpret_cast<const uint4 *>(p + rdB + 32 * i * ROWB);
-            NVFP4_MXD_FENCE
-            NVFP4_MXD_MMA(F0, S, 0, i, 2)
-            dma16(dst3 + i * 1024, offA[i] & lanes, pa);
-            NVFP4_MXD_FENCE
-            NVFP4_MXD_MMA(F0, S, 0, i, 3)
-            dma16(dst3 + BM * ROWB + i * 1024, offB[i] & lanes, pb);
-            NVFP4_MXD_FENCE
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                NVFP4_MXD_MMA(F0, S, 0, j >> 2, j & 3)
+                if (j < 4)
+                    F1.b[j] = *reinterpret_cast<const uint4 *>(p + rdB + 32 * j * ROWB);
+                else if (j < 8)
+                    F1.a[j - 4] = *reinterpret_cast<const uint4 *>(p + rdA + 32 * (j - 4) * ROWB);
+                else if (j & 1)
+                    dma16(dst3 + BM * ROWB + ((j - 8) >> 1) * 1024, offB[(j - 8) >> 1] & lanes, pb);
+                else
+                    dma16(dst3 + ((j - 8) >> 1) * 1024, offA[(j - 8) >> 1] & lanes, pa);
+                NVFP4_MXD_FENCE
+            }
         }
         {
             const int Gn = (kt >> 2) + 1, part = kt & 1;
@@ -543,23 +546,24 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
         NVFP4_MXD_WAIT(2 * PER_TILE)
         __syncthreads();
         NVFP4_MXD_FENCE
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        // step 1: MFMAs 0-7 shadow the scale reads of tile kt + 1, MFMAs 8-15 its first fragments
+        {
             const uint8_t *p = lds + ((kt + 1) & (NS - 1)) * STAGE + (((2 * g) ^ sw) << 4);
             const int G = (kt + 1) >> 2;
             const uint8_t *q = lds + (G & 1) * SBUF + (4 * (kt + 1) - group_start(G));
-            NVFP4_MXD_MMA(F1, S, 1, i, 0)
-            F0.a[i] = *reinterpret_cast<const uint4 *>(p + rdA + 32 * i * ROWB);
-            NVFP4_MXD_FENCE
-            NVFP4_MXD_MMA(F1, S, 1, i, 1)
-            F0.b[i] = *reinterpret_cast<const uint4 *>(p + rdB + 32 * i * ROWB);
-            NVFP4_MXD_FENCE
-            NVFP4_MXD_MMA(F1, S, 1, i, 2)
-            R.a[i] = *reinterpret_cast<const uint32_t *>(q + rdS + 512 * i);
-            NVFP4_MXD_FENCE
-            NVFP4_MXD_MMA(F1, S, 1, i, 3)
-            R.b[i] = *reinterpret_cast<const uint32_t *>(q + rdT + 512 * i);
-            NVFP4_MXD_FENCE
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                NVFP4_MXD_MMA(F1, S, 1, j >> 2, j & 3)
+                if (j < 4)
+                    R.a[j] = *reinterpret_cast<const uint32_t *>(q + rdS + 512 * j);
+                else if (j < 8)
+                    R.b[j - 4] = *reinterpret_cast<const uint32_t *>(q + rdT + 512 * (j - 4));
+                else if (j < 12)
+                    F0.b[j - 8] = *reinterpret_cast<const uint4 *>(p + rdB + 32 * (j - 8) * ROWB);
+                else
+                    F0.a[j - 12] = *reinterpret_cast<const uint4 *>(p + rdA + 32 * (j - 12) * ROWB);
+                NVFP4_MXD_FENCE
+            }
         }
     }
 #undef NVFP4_MXD_FENCE
