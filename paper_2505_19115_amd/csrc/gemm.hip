@@ -27,14 +27,12 @@ constexpr int KT = 128;      // contraction elements per LDS tile
 constexpr int KTB = KT / 2;  // bytes of codes per row per tile
 constexpr int SROW = 16;     // LDS bytes per row for the tile's scales: 8 fp16 values, one per 16 elements
 
-// LDS placement of the codes of one tile row r (64 bytes = 4 chunks of 16 = 8 quarters of 8):
-// chunk c sits in chunk slot c ^ ((r >> 1) & 3) and, inside the chunk, the two 8-byte quarters
-// swap places when bit 3 of r is set.  With that, 16 consecutive rows reading the same logical
-// quarter (one ds_read_b64 wavefront pass) touch 16 different 8-byte bank pairs, and a 16-byte
-// store of a whole chunk by 8 consecutive threads covers 128 contiguous bytes: no conflicts
-// either way (measured 128 B/clk/CU, the LDS peak).
-__device__ __forceinline__ int swz(int r, int c) { return r * KTB + ((c ^ ((r >> 1) & 3)) << 4); }
-__device__ __forceinline__ int swz_quarter(int r, int c, int sub) { return swz(r, c) + ((sub ^ ((r >> 3) & 1)) << 3); }
+// LDS placement of the codes of one tile row r (64 bytes = 4 chunks of 16): chunk c sits in
+// chunk slot c ^ ((r >> 2) & 3).  Rows are 64 bytes apart, so 16 consecutive rows reading the same
+// logical chunk (one ds_read_b128 wavefront pass) cover all sixteen 16-byte slots of the 256-byte
+// bank period, and a 16-byte store of a whole chunk by 4 consecutive threads per row covers
+// contiguous bytes: no conflicts either way.
+__device__ __forceinline__ int swz(int r, int c) { return r * KTB + ((c ^ ((r >> 2) & 3)) << 4); }
 
 // 8 codes (one dword) of one block -> 8 fp16 values times the block scale.
 // s = fp16 holding scale * 2^-8; the convert multiplies the codes by 2^8.
@@ -108,26 +106,49 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
     // that are never stored), so the code loads carry no predicate.  A K tail (K not a
     // multiple of 128) is handled through the scales alone: chunks past K are read from a
     // clamped address and meet zero scales.
+    // Without a K tail the codes go from global memory straight into LDS (global_load_lds, 16
+    // bytes per lane): a wave instruction fills 1 KB = 16 consecutive tile rows, lane i landing at
+    // byte 16 i (row i / 4, slot i % 4), so the swizzle is applied by choosing WHICH global chunk
+    // the lane fetches.  No staging registers, no LDS store instructions for the codes.
+    constexpr bool DMA = !KTAIL;
     constexpr int NSR = (BM + BN + NT - 1) / NT;  // scale rows per thread
-    uint4 ga[CA], gb[CB];
+    uint4 ga[DMA ? 1 : CA], gb[DMA ? 1 : CB];
     uint64_t gs[NSR];
     uint32_t offA[CA], offB[CB];  // byte offset of this thread's chunks inside a K tile column
     int ldsA[CA], ldsB[CB];
 #pragma unroll
     for (int u = 0; u < CA; ++u) {
-        const int qd = tid + NT * u, row = qd >> 2, ch = qd & 3;
+        const int qd = tid + NT * u;
+        const int row = DMA ? (wave * CA + u) * 16 + (lane >> 2) : qd >> 2;
+        const int ch = DMA ? (lane & 3) ^ ((lane >> 4) & 3) : qd & 3;
         const int64_t gr = m0 + row < P.M ? m0 + row : P.M - 1;
         offA[u] = (uint32_t)(gr * Kb + ch * 16);
-        ldsA[u] = swz(row, ch);
+        ldsA[u] = DMA ? __builtin_amdgcn_readfirstlane((wave * CA + u) * 1024) : swz(row, ch);
     }
 #pragma unroll
     for (int u = 0; u < CB; ++u) {
-        const int qd = tid + NT * u, row = qd >> 2, ch = qd & 3;
+        const int qd = tid + NT * u;
+        const int row = DMA ? (wave * CB + u) * 16 + (lane >> 2) : qd >> 2;
+        const int ch = DMA ? (lane & 3) ^ ((lane >> 4) & 3) : qd & 3;
         const int64_t gr = n0 + row < P.N ? n0 + row : P.N - 1;
         offB[u] = (uint32_t)(gr * Kb + ch * 16);
-        ldsB[u] = A_BYTES + swz(row, ch);
+        ldsB[u] = DMA ? __builtin_amdgcn_readfirstlane(A_BYTES + (wave * CB + u) * 1024) : A_BYTES + swz(row, ch);
     }
-    const bool swap_halves = ((tid >> 2) & 8) != 0;  // NT is a multiple of 64: same for all u
+    typedef __attribute__((address_space(3))) void *lds_ptr_t;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_ptr_t)lds;
+    // wave-uniform 64-bit value -> scalar registers
+    auto uniform_ptr = [](const uint8_t *p) -> const uint8_t * {
+        const uint64_t v = reinterpret_cast<uint64_t>(p);
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+        return reinterpret_cast<const uint8_t *>(((uint64_t)hi << 32) | lo);
+    };
+    // Issued through inline assembly on purpose: the compiler's wait-count pass treats a
+    // direct-to-LDS load as a possible writer of every LDS location and would wait for it before
+    // the next LDS read.  Here the destination stage is not read before the explicit wait and the
+    // barrier in stash().
+    auto dma16 = [&](uint32_t lds_addr, uint32_t voff, const uint8_t *base) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(voff), "s"(base) : "memory");
+    };
     const uint8_t *srow_ptr[NSR];
     bool srow_on[NSR];
 #pragma unroll
@@ -141,14 +162,17 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
         srow_ptr[u] = (isA ? P.A_scales : P.B_scales) + gr * Ks;
     }
     const int64_t last_chunk = Kb - 16;
-    auto fetch = [&](int kt) {
+    // tile kt: codes -> LDS stage `stage` (direct) or staging registers; scale bytes -> registers
+    auto fetch = [&](int kt, int stage) {
         const int64_t kb = (int64_t)kt * KTB;
         const uint8_t *pa = P.A_codes + kb, *pb = P.B_codes + kb;
         if (!KTAIL) {
+            const uint8_t *ua = uniform_ptr(pa), *ub = uniform_ptr(pb);
+            const uint32_t dst = __builtin_amdgcn_readfirstlane(lds0 + stage * STAGE);
 #pragma unroll
-            for (int u = 0; u < CA; ++u) ga[u] = *reinterpret_cast<const uint4 *>(pa + offA[u]);
+            for (int u = 0; u < CA; ++u) dma16(dst + ldsA[u], offA[u], ua);
 #pragma unroll
-            for (int u = 0; u < CB; ++u) gb[u] = *reinterpret_cast<const uint4 *>(pb + offB[u]);
+            for (int u = 0; u < CB; ++u) dma16(dst + ldsB[u], offB[u], ub);
 #pragma unroll
             for (int u = 0; u < NSR; ++u) {
                 if (!srow_on[u]) continue;
@@ -189,15 +213,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
     // 32 consecutive rows of one chunk.  For blocks wider than 16 the value is repeated.
     auto stash = [&](int stage) {
         uint8_t *base = lds + stage * STAGE;
+        if (DMA) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's direct-to-LDS loads have landed
+        } else {
 #pragma unroll
-        for (int u = 0; u < CA; ++u) {
-            const uint4 v = ga[u];
-            *reinterpret_cast<uint4 *>(base + ldsA[u]) = swap_halves ? make_uint4(v.z, v.w, v.x, v.y) : v;
-        }
+            for (int u = 0; u < CA; ++u) *reinterpret_cast<uint4 *>(base + ldsA[u]) = ga[u];
 #pragma unroll
-        for (int u = 0; u < CB; ++u) {
-            const uint4 v = gb[u];
-            *reinterpret_cast<uint4 *>(base + ldsB[u]) = swap_halves ? make_uint4(v.z, v.w, v.x, v.y) : v;
+            for (int u = 0; u < CB; ++u) *reinterpret_cast<uint4 *>(base + ldsB[u]) = gb[u];
         }
         uint32_t *sS = reinterpret_cast<uint32_t *>(base + A_BYTES + B_BYTES);
 #pragma unroll
@@ -212,26 +234,27 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
         }
     };
 
-    // ---- LDS -> registers.  A lane reads quarter (p, sub) of rows (frag base + r): its byte
-    // offset inside a row is one of four lane constants, the rest are immediates.
-    struct Quarter {
-        uint2 ca[TA], cb[TB];
+    // ---- LDS -> registers.  A lane reads chunk 2 p + h (16 bytes = 32 codes = two blocks of 16,
+    // four MFMA steps) of rows (frag base + r): its byte offset inside a row is one of two lane
+    // constants, the rest are immediates.
+    struct Codes {
+        uint4 ca[TA], cb[TB];
     };
     struct Scales {  // two fp16 scales (first and second block of the lane's 32-element chunk)
         uint32_t sa[TA], sb[TB];
     };
-    int qoff[4];  // [2 p + sub]
+    int coff[2];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) qoff[q] = swz_quarter(r, 2 * (q >> 1) + h, q & 1);
+    for (int p = 0; p < 2; ++p) coff[p] = swz(r, 2 * p + h);
     const int soff = (h * (BM + BN) + r) * 4;
-    auto load_quarter = [&](int stage, int q, Quarter &Q) {
-        const uint8_t *sA = lds + stage * STAGE + qoff[q], *sB = sA + A_BYTES;
+    auto load_codes = [&](int stage, int p, Codes &Q) {
+        const uint8_t *sA = lds + stage * STAGE + coff[p], *sB = sA + A_BYTES;
 #pragma unroll
         for (int a = 0; a < TA; ++a)
-            Q.ca[a] = *reinterpret_cast<const uint2 *>(sA + (wm * 32 * TA + 32 * a) * KTB);
+            Q.ca[a] = *reinterpret_cast<const uint4 *>(sA + (wm * 32 * TA + 32 * a) * KTB);
 #pragma unroll
         for (int b = 0; b < TB; ++b)
-            Q.cb[b] = *reinterpret_cast<const uint2 *>(sB + (wn * 32 * TB + 32 * b) * KTB);
+            Q.cb[b] = *reinterpret_cast<const uint4 *>(sB + (wn * 32 * TB + 32 * b) * KTB);
     };
     auto load_scales = [&](int stage, int p, Scales &S) {
         const uint8_t *sS = lds + stage * STAGE + A_BYTES + B_BYTES + soff + 2 * p * (BM + BN) * 4;
@@ -243,17 +266,19 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
     struct Frags {
         half8_t a[TA], b[TB];
     };
-    // operands of MFMA step (q, t): dword t of quarter q, scaled by the quarter's block scale
-    auto expand = [&](const Quarter &Q, const Scales &S, int q, int t, Frags &F) {
+    // operands of MFMA step t (0..3) of a chunk: its dword t, scaled by the scale of the block
+    // (t / 2) that dword belongs to
+    auto expand = [&](const Codes &Q, const Scales &S, int t, Frags &F) {
+        auto dword = [&](const uint4 &v) { return t == 0 ? v.x : t == 1 ? v.y : t == 2 ? v.z : v.w; };
 #pragma unroll
         for (int a = 0; a < TA; ++a) {
             const half2_t sp = __builtin_bit_cast(half2_t, S.sa[a]);
-            F.a[a] = dequant8(t == 0 ? Q.ca[a].x : Q.ca[a].y, (q & 1) ? sp[1] : sp[0]);
+            F.a[a] = dequant8(dword(Q.ca[a]), t >= 2 ? sp[1] : sp[0]);
         }
 #pragma unroll
         for (int b = 0; b < TB; ++b) {
             const half2_t sp = __builtin_bit_cast(half2_t, S.sb[b]);
-            F.b[b] = dequant8(t == 0 ? Q.cb[b].x : Q.cb[b].y, (q & 1) ? sp[1] : sp[0]);
+            F.b[b] = dequant8(dword(Q.cb[b]), t >= 2 ? sp[1] : sp[0]);
         }
     };
     auto mma = [&](const Frags &F) {
@@ -266,14 +291,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
 
     // Software pipeline, continuous across K tiles (8 MFMA steps of TA*TB MFMAs per tile; the
     // operands of step s+1 are expanded under the MFMAs of step s).  On entry to iteration kt
-    // the LDS stage kt & 1 holds tile kt; Qa holds its quarter 0, S0 the scales of its first
-    // half, F0 the operands of its first step.  Within the iteration:
-    //   top      global loads of tile kt+1 -> registers; LDS loads of quarter 1 and of S1
-    //   steps    quarter q+1 is loaded from LDS while quarter q is multiplied
-    //   step 5|6 tile kt+1 -> other LDS stage, ONE barrier, LDS loads of its quarter 0 / S0
+    // the LDS stage kt & 1 holds tile kt; Ca holds the lanes' chunk of its first half, S0 the
+    // scales of that half, F0 the operands of its first step.  Within the iteration:
+    //   top      global loads of tile kt+1 -> registers; LDS loads of the second half (Cb, S1)
+    //   step 6   tile kt+1 -> other LDS stage, ONE barrier, LDS loads of its first half
     //   step 7   already expands the first operands of tile kt+1.
-    // After the barrier nobody reads stage kt & 1 again (all four quarters are in registers),
-    // so the next iteration may overwrite it.
+    // After the barrier nobody reads stage kt & 1 again (both halves are in registers), so the
+    // next iteration may overwrite it.
     // The scheduling hints pin "one MFMA, then its share of the expansion work" so that VALU
     // work is always queued behind an MFMA that holds the matrix pipe for 32 cycles.
 #define NVFP4_INTERLEAVE()                                                  \
@@ -282,41 +306,39 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
         __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER_MFMA, 0);      \
     }                                                                       \
     __builtin_amdgcn_sched_barrier(0);
-#define NVFP4_STEP(Qn, Sn, qn, tn, Fn, Fc) \
-    expand(Qn, Sn, qn, tn, Fn);            \
-    mma(Fc);                               \
+#define NVFP4_STEP(Qn, Sn, tn, Fn, Fc) \
+    expand(Qn, Sn, tn, Fn);            \
+    mma(Fc);                           \
     NVFP4_INTERLEAVE()
 
-    Quarter Qa, Qb;
+    Codes Ca, Cb;
     Scales S0, S1;
     Frags F0, F1;
-    fetch(0);
+    fetch(0, 0);
     stash(0);
     __syncthreads();
-    load_quarter(0, 0, Qa);
+    load_codes(0, 0, Ca);
     load_scales(0, 0, S0);
-    expand(Qa, S0, 0, 0, F0);
+    expand(Ca, S0, 0, F0);
 #define NVFP4_TILE(stage, kt)                     \
     {                                             \
-        fetch((kt) + 1);                          \
-        load_quarter(stage, 1, Qb);               \
+        fetch((kt) + 1, (stage) ^ 1);             \
+        load_codes(stage, 1, Cb);                 \
         load_scales(stage, 1, S1);                \
         __builtin_amdgcn_sched_barrier(0);        \
-        NVFP4_STEP(Qa, S0, 0, 1, F1, F0)          \
-        NVFP4_STEP(Qb, S0, 1, 0, F0, F1)          \
-        load_quarter(stage, 2, Qa);               \
-        NVFP4_STEP(Qb, S0, 1, 1, F1, F0)          \
-        NVFP4_STEP(Qa, S1, 2, 0, F0, F1)          \
-        load_quarter(stage, 3, Qb);               \
-        NVFP4_STEP(Qa, S1, 2, 1, F1, F0)          \
-        NVFP4_STEP(Qb, S1, 3, 0, F0, F1)          \
+        NVFP4_STEP(Ca, S0, 1, F1, F0)             \
+        NVFP4_STEP(Ca, S0, 2, F0, F1)             \
+        NVFP4_STEP(Ca, S0, 3, F1, F0)             \
+        NVFP4_STEP(Cb, S1, 0, F0, F1)             \
+        NVFP4_STEP(Cb, S1, 1, F1, F0)             \
+        NVFP4_STEP(Cb, S1, 2, F0, F1)             \
         stash((stage) ^ 1);                       \
         __syncthreads();                          \
-        load_quarter((stage) ^ 1, 0, Qa);         \
+        load_codes((stage) ^ 1, 0, Ca);           \
         load_scales((stage) ^ 1, 0, S0);          \
         __builtin_amdgcn_sched_barrier(0);        \
-        NVFP4_STEP(Qb, S1, 3, 1, F1, F0)          \
-        NVFP4_STEP(Qa, S0, 0, 0, F0, F1)          \
+        NVFP4_STEP(Cb, S1, 3, F1, F0)             \
+        NVFP4_STEP(Ca, S0, 0, F0, F1)             \
     }
     // two tiles per trip so that the LDS stage (and with it every LDS offset) is a constant
     int kt = 0;
@@ -331,18 +353,16 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
 #undef NVFP4_TILE
     {
         const int stage = kt & 1;  // the last tile
-        load_quarter(stage, 1, Qb);
+        load_codes(stage, 1, Cb);
         load_scales(stage, 1, S1);
         __builtin_amdgcn_sched_barrier(0);
-        NVFP4_STEP(Qa, S0, 0, 1, F1, F0)
-        NVFP4_STEP(Qb, S0, 1, 0, F0, F1)
-        load_quarter(stage, 2, Qa);
-        NVFP4_STEP(Qb, S0, 1, 1, F1, F0)
-        NVFP4_STEP(Qa, S1, 2, 0, F0, F1)
-        load_quarter(stage, 3, Qb);
-        NVFP4_STEP(Qa, S1, 2, 1, F1, F0)
-        NVFP4_STEP(Qb, S1, 3, 0, F0, F1)
-        NVFP4_STEP(Qb, S1, 3, 1, F1, F0)
+        NVFP4_STEP(Ca, S0, 1, F1, F0)
+        NVFP4_STEP(Ca, S0, 2, F0, F1)
+        NVFP4_STEP(Ca, S0, 3, F1, F0)
+        NVFP4_STEP(Cb, S1, 0, F0, F1)
+        NVFP4_STEP(Cb, S1, 1, F1, F0)
+        NVFP4_STEP(Cb, S1, 2, F0, F1)
+        NVFP4_STEP(Cb, S1, 3, F1, F0)
         mma(F1);
     }
 #undef NVFP4_STEP
