@@ -66,9 +66,9 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
 // Per 128-wide K tile the 64 code bytes of each operand row sit in LDS as four 16-byte chunks
 // and its 8 block scales as fp16 values (scale * 2^-8; for blocks wider than 16 the value is
 // repeated).  Lane (r = lane % 32, h = lane / 32) owns chunk 2p + h (p = 0, 1) of its row:
-// two 8-byte "quarters" of 16 codes = one 16-element block each; dword t of a quarter feeds
-// one MFMA step.  A and B use the same assignment of contraction indices to (lane half,
-// slot), which is all the instruction requires.
+// 32 codes = two 16-element blocks; dword t (0..3) of the chunk feeds one MFMA step and
+// belongs to block t / 2.  A and B use the same assignment of contraction indices to (lane
+// half, step), which is all the instruction requires.
 template <int B, int WM, int WN, int TA, int TB, int OUT_DT, bool KTAIL>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
 {
