@@ -7,11 +7,11 @@
 //     out[i, j] = gA gB sum_b 2^(eA[i,b] - 127) 2^(eB[j,b] - 127) sum_{k in b} cA[i,k] cB[j,k].
 // Products and the power-of-two scaling are exact; accumulation is fp32.
 //
-// Geometry: 256 threads = 2 x 2 waves, wave tile 128 x 128 (4 x 4 MFMA tiles, 256 accumulator
-// registers, one wave per SIMD), workgroup tile 256 x 256.  With no VALU work in the loop the
-// single-wave issue limit does not matter; what matters is LDS bandwidth (a 4 x 4 register tile
-// reads 8 KB per 16 MFMAs = 128 B/clk/CU at full MFMA rate, the LDS peak), hence the largest
-// register tile that fits.
+// Geometry of both kernels: 256 threads = 2 x 2 waves, wave tile 128 x 128 (4 x 4 MFMA tiles, all
+// 256 accumulator registers, one wave per SIMD), workgroup tile 256 x 256: with no VALU work in
+// the loop what matters is bytes moved per MFMA (a 4 x 4 register tile reads 8 KB of LDS per 16
+// MFMAs), hence the largest register tile that fits.  The MFMA's first operand is the B (N-side)
+// tile, so a lane's accumulator holds four consecutive output COLUMNS of one row.
 #include "kernels.h"
 #include "nvfp4_math.h"
 
@@ -19,6 +19,8 @@ namespace nvfp4 {
 
 typedef int int8v_t __attribute__((ext_vector_type(8)));
 typedef float float16v_t __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float float2v_t __attribute__((ext_vector_type(2)));
 
 namespace mx {
 constexpr int NT = 256, BM = 256, BN = 256, TA = 4, TB = 4;
@@ -31,22 +33,87 @@ __device__ __forceinline__ uint16_t mx_bf16_rne(float f)
     return (uint16_t)(u >> 16);
 }
 
-// KT = contraction elements per LDS stage (256: four MFMA steps per barrier; 64: one step, any
-// K that is a multiple of 32, chunks past K are zero-filled).
-// LDS stage: codes [BM + BN rows][KT/2 bytes], 16-byte chunk c of row r at slot c ^ (r & (NCH-1))
-// (8 consecutive rows reading one logical chunk hit 8 different 16-byte bank groups); scales as
-// dwords [2 lane halves][BM + BN rows], byte s of a dword = the E8M0 byte of MFMA step s for that
-// lane half, so the instruction's byte select is a compile-time constant.
-template <int KT, int OUT_DT>
+// Epilogue of both kernels: accumulator register v of lane (r, g) of tile (a, b) is output row
+// 32 a + r, column 32 b + 8 (v / 4) + 4 g + v % 4.  Full tiles with a suitably aligned output get
+// one packed convert pair and one 8-byte (bf16) or 16-byte (fp32) store per four outputs; edge
+// tiles store element by element.  The lane coordinates are re-derived from an opaque copy so
+// that none of the output addressing is computed before the K loop and kept in registers across it.
+template <int OUT_DT>
+__device__ __forceinline__ void mx_store_tile(const GemmArgs &P, float16v_t (&acc)[mx::TA][mx::TB], int64_t m0, int64_t n0,
+                                              int lane, int wave)
+{
+    using namespace mx;
+    int lane_e = lane, wave_e = wave;
+    asm volatile("" : "+v"(lane_e), "+v"(wave_e));
+    const int re = lane_e & 31, ge = lane_e >> 5, wme = wave_e >> 1, wne = wave_e & 1;
+    const float gg = P.tensor_scales[0] * P.tensor_scales[1];
+    constexpr int ESZ = OUT_DT == NVFP4_F32 ? 4 : 2;
+    const int64_t row0 = m0 + wme * 128 + re, col0 = n0 + wne * 128 + 4 * ge;
+    uint8_t *const out = reinterpret_cast<uint8_t *>(P.out);
+    const bool fast = m0 + BM <= P.M && n0 + BN <= P.N && (P.ldc & 3) == 0 && (reinterpret_cast<uintptr_t>(P.out) & 15) == 0;
+    if (fast) {
+#pragma unroll
+        for (int a = 0; a < TA; ++a) {
+            uint8_t *prow = out + ((row0 + 32 * a) * P.ldc + col0) * ESZ;
+#pragma unroll
+            for (int b = 0; b < TB; ++b)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float y0 = acc[a][b][4 * q] * gg, y1 = acc[a][b][4 * q + 1] * gg;
+                    const float y2 = acc[a][b][4 * q + 2] * gg, y3 = acc[a][b][4 * q + 3] * gg;
+                    uint8_t *dst = prow + (32 * b + 8 * q) * ESZ;
+                    if (OUT_DT == NVFP4_F32) {
+                        *reinterpret_cast<float4 *>(dst) = make_float4(y0, y1, y2, y3);
+                    } else {
+                        const float2v_t lo = {y0, y1}, hi = {y2, y3};
+                        const bf16x2_t blo = __builtin_convertvector(lo, bf16x2_t), bhi = __builtin_convertvector(hi, bf16x2_t);
+                        uint2 w;
+                        w.x = *reinterpret_cast<const uint32_t *>(&blo);
+                        w.y = *reinterpret_cast<const uint32_t *>(&bhi);
+                        *reinterpret_cast<uint2 *>(dst) = w;
+                    }
+                }
+            __builtin_amdgcn_sched_barrier(0);  // one accumulator row of tiles at a time keeps the register peak low
+        }
+    } else {
+#pragma unroll
+        for (int a = 0; a < TA; ++a)
+#pragma unroll
+            for (int b = 0; b < TB; ++b) {
+                const int64_t row = row0 + 32 * a;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int64_t col = col0 + 32 * b + 8 * (v >> 2) + (v & 3);
+                    if (row < P.M && col < P.N) {
+                        const float y = acc[a][b][v] * gg;
+                        if (OUT_DT == NVFP4_F32)
+                            reinterpret_cast<float *>(P.out)[row * P.ldc + col] = y;
+                        else
+                            reinterpret_cast<uint16_t *>(P.out)[row * P.ldc + col] = mx_bf16_rne(y);
+                    }
+                }
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Fallback kernel: any K that is a multiple of 32, any operand alignment.  K tile 64 = one MFMA
+// step, two LDS stages, everything staged through registers (chunks past K are zero-filled, rows
+// past the edge clamped to the last row: their products land in outputs that are never stored).
+// LDS stage: codes [512 rows][32 bytes], the two 16-byte chunks of row r swapped when r is odd;
+// scales as dwords [2 lane halves][512 rows], byte 0 = the E8M0 byte of the lane half's block.
+namespace mxf {
+constexpr int KT = 64, ROWB = 32;
+constexpr int CODES = (mx::BM + mx::BN) * ROWB;
+constexpr int STAGE = CODES + 2 * (mx::BM + mx::BN) * 4;
+constexpr int LDS_BYTES = 2 * STAGE;
+}  // namespace mxf
+
+template <int OUT_DT>
 __global__ __launch_bounds__(256) void gemm_nt_mxfp4_kernel(GemmArgs P)
 {
     using namespace mx;
-    constexpr int ROWB = KT / 2;          // code bytes per row per stage
-    constexpr int NCH = ROWB / 16;        // 16-byte chunks per row (8 or 2)
-    constexpr int STEPS = KT / 64;        // MFMA steps per stage (4 or 1)
-    constexpr int CPT = (BM * NCH) / NT;  // chunks per thread per operand (8 or 2)
-    constexpr int CODES = (BM + BN) * ROWB;
-    constexpr int STAGE = CODES + 2 * (BM + BN) * 4;
+    using namespace mxf;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -54,7 +121,7 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_kernel(GemmArgs P)
     const int r = lane & 31, g = lane >> 5;
     const int ntx = (int)((P.N + BN - 1) / BN), nty = (int)((P.M + BM - 1) / BM);
     int ty, tx;
-    tile_coords(blockIdx.x, ntx, nty, ty, tx);
+    tile_coords((int)blockIdx.x, ntx, nty, ty, tx);
     const int64_t m0 = (int64_t)ty * BM, n0 = (int64_t)tx * BN;
     const int64_t Kb = P.K >> 1, Ks = P.K >> 5;
     const int nkt = (int)((P.K + KT - 1) / KT);
@@ -67,259 +134,99 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_kernel(GemmArgs P)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
 
-    // ---- global -> registers -> LDS.  Rows past the edge are clamped to the last row (their
-    // products land in outputs that are never stored).
-    // KT = 256: the codes go from global memory straight into LDS (global_load_lds, 16 bytes per
-    // lane): a wave instruction fills 1 KB = 8 consecutive tile rows, lane i landing at byte 16 i,
-    // so the XOR swizzle is applied by choosing WHICH global chunk lane i fetches.  No staging
-    // registers, no LDS store instructions.  KT = 64 stages through registers (it must be able
-    // to zero-fill past K).
-    constexpr bool DMA = KT == 256;
-    uint4 ga[DMA ? 1 : CPT], gb[DMA ? 1 : CPT];
-    uint64_t gsa = 0, gsb = 0;
-    uint32_t offA[CPT], offB[CPT];
-    int ldsW[CPT];
+    // ---- global -> registers -> LDS: thread t stages chunks t and t + 256 (row = chunk / 2) of each operand
+    uint4 ga[2], gb[2];
+    uint32_t gsa = 0, gsb = 0;
+    const uint8_t *pA[2], *pB[2];
+    int ldsW[2], chunk[2];
 #pragma unroll
-    for (int u = 0; u < CPT; ++u) {
-        int row, c;
-        if (DMA) {
-            row = (wave * CPT + u) * 8 + (lane >> 3);
-            c = (lane & 7) ^ (row & 7);
-            ldsW[u] = (wave * CPT + u) * 1024;  // wave-uniform base of this instruction's 1 KB
-        } else {
-            const int qd = tid + NT * u;
-            row = qd / NCH;
-            c = qd % NCH;
-            ldsW[u] = row * ROWB + ((c ^ (row & (NCH - 1))) << 4);
-        }
-        const int64_t ar = m0 + row < P.M ? m0 + row : P.M - 1;
-        const int64_t br = n0 + row < P.N ? n0 + row : P.N - 1;
-        offA[u] = (uint32_t)(ar * Kb + c * 16);
-        offB[u] = (uint32_t)(br * Kb + c * 16);
+    for (int u = 0; u < 2; ++u) {
+        const int qd = tid + NT * u, row = qd >> 1, c = qd & 1;
+        const int64_t ar = m0 + row < P.M ? m0 + row : P.M - 1, br = n0 + row < P.N ? n0 + row : P.N - 1;
+        pA[u] = P.A_codes + ar * Kb + c * 16;
+        pB[u] = P.B_codes + br * Kb + c * 16;
+        chunk[u] = c;
+        ldsW[u] = row * ROWB + ((c ^ (row & 1)) << 4);
     }
-    typedef __attribute__((address_space(3))) void *lds_ptr_t;
-    typedef const __attribute__((address_space(1))) void *glb_ptr_t;
-    // wave-uniform 64-bit value -> scalar registers (keeps "uniform base + 32-bit lane offset"
-    // addressing instead of one 64-bit vector pointer per load)
-    auto uniform_ptr = [](const uint8_t *p) -> const uint8_t * {
-        const uint64_t v = reinterpret_cast<uint64_t>(p);
-        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-        return reinterpret_cast<const uint8_t *>(((uint64_t)hi << 32) | lo);
+    const int64_t sar = m0 + tid < P.M ? m0 + tid : P.M - 1, sbr = n0 + tid < P.N ? n0 + tid : P.N - 1;
+    auto load16u = [](const uint8_t *p) -> uint4 {  // any alignment
+        uint4 v;
+        __builtin_memcpy(&v, p, 16);
+        return v;
     };
-    // The loads are issued through inline assembly on purpose: the compiler's wait-count pass
-    // treats a direct-to-LDS load as a possible writer of every LDS location and would put
-    // s_waitcnt vmcnt(0) in front of the next LDS read, i.e. expose the full global latency once
-    // per tile.  Here the destination stage is never read before the explicit wait + barrier below.
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_ptr_t)lds;
-    const uint32_t dma_base = __builtin_amdgcn_readfirstlane(lds0 + wave * CPT * 1024);
-    auto dma_one = [&](uint32_t lds_addr, uint32_t voff, const uint8_t *base) {
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                     :
-                     : "s"(lds_addr), "v"(voff), "s"(base)
-                     : "memory");
-    };
-    auto dma_codes = [&](int kt, int stage) {
-        const uint8_t *pa = uniform_ptr(P.A_codes + (int64_t)kt * ROWB);
-        const uint8_t *pb = uniform_ptr(P.B_codes + (int64_t)kt * ROWB);
-#pragma unroll
-        for (int u = 0; u < CPT; ++u) {
-            const uint32_t dst = dma_base + stage * STAGE + u * 1024;
-            dma_one(dst, offA[u], pa);
-            dma_one(dst + BM * ROWB, offB[u], pb);
-        }
-    };
-    const int64_t sar = m0 + tid < P.M ? m0 + tid : P.M - 1;
-    const int64_t sbr = n0 + tid < P.N ? n0 + tid : P.N - 1;
     auto fetch = [&](int kt) {
         const int64_t kb = (int64_t)kt * ROWB;
-        if (!DMA) {
 #pragma unroll
-            for (int u = 0; u < CPT; ++u) {
-                const bool in = kb + ((tid + NT * u) % NCH) * 16 < Kb;  // zero codes past K
-                ga[u] = in ? *reinterpret_cast<const uint4 *>(P.A_codes + kb + offA[u]) : make_uint4(0, 0, 0, 0);
-                gb[u] = in ? *reinterpret_cast<const uint4 *>(P.B_codes + kb + offB[u]) : make_uint4(0, 0, 0, 0);
-            }
+        for (int u = 0; u < 2; ++u) {
+            const bool in = kb + chunk[u] * 16 < Kb;  // zero codes past K
+            ga[u] = in ? load16u(pA[u] + kb) : make_uint4(0, 0, 0, 0);
+            gb[u] = in ? load16u(pB[u] + kb) : make_uint4(0, 0, 0, 0);
         }
-        const uint8_t *pa = P.A_scales + sar * Ks + (int64_t)kt * (KT / 32);
-        const uint8_t *pb = P.B_scales + sbr * Ks + (int64_t)kt * (KT / 32);
-        if (KT == 256) {
-            gsa = *reinterpret_cast<const uint64_t *>(pa);
-            gsb = *reinterpret_cast<const uint64_t *>(pb);
-        } else {
-            const bool two = (int64_t)kt * 2 + 1 < Ks;
-            gsa = (uint64_t)pa[0] | (two ? (uint64_t)pa[1] << 8 : 0);
-            gsb = (uint64_t)pb[0] | (two ? (uint64_t)pb[1] << 8 : 0);
-        }
-    };
-    // scale bytes of a row, in block order b0 b1 ... -> dword of lane half 0 (blocks 0, 2, 4, 6)
-    // and dword of lane half 1 (blocks 1, 3, 5, 7)
-    auto split_scales = [&](uint64_t s, uint32_t &even, uint32_t &odd) {
-        const uint32_t lo = (uint32_t)s, hi = (uint32_t)(s >> 32);
-        even = __builtin_amdgcn_perm(hi, lo, 0x06040200u);
-        odd = __builtin_amdgcn_perm(hi, lo, 0x07050301u);
+        const uint8_t *sa = P.A_scales + sar * Ks + (int64_t)kt * 2, *sb = P.B_scales + sbr * Ks + (int64_t)kt * 2;
+        const bool two = (int64_t)kt * 2 + 1 < Ks;
+        gsa = (uint32_t)sa[0] | (two ? (uint32_t)sa[1] << 8 : 0u);
+        gsb = (uint32_t)sb[0] | (two ? (uint32_t)sb[1] << 8 : 0u);
     };
     auto stash = [&](int stage) {
         uint8_t *base = lds + stage * STAGE;
-        if (!DMA) {
 #pragma unroll
-            for (int u = 0; u < CPT; ++u) {
-                *reinterpret_cast<uint4 *>(base + ldsW[u]) = ga[u];
-                *reinterpret_cast<uint4 *>(base + BM * ROWB + ldsW[u]) = gb[u];
-            }
-        } else {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's direct-to-LDS loads have landed
+        for (int u = 0; u < 2; ++u) {
+            *reinterpret_cast<uint4 *>(base + ldsW[u]) = ga[u];
+            *reinterpret_cast<uint4 *>(base + BM * ROWB + ldsW[u]) = gb[u];
         }
         uint32_t *sS = reinterpret_cast<uint32_t *>(base + CODES);
-        uint32_t e, o;
-        split_scales(gsa, e, o);
-        sS[tid] = e;
-        sS[(BM + BN) + tid] = o;
-        split_scales(gsb, e, o);
-        sS[BM + tid] = e;
-        sS[(BM + BN) + BM + tid] = o;
+        sS[tid] = gsa & 0xFFu;
+        sS[(BM + BN) + tid] = gsa >> 8;
+        sS[BM + tid] = gsb & 0xFFu;
+        sS[(BM + BN) + BM + tid] = gsb >> 8;
     };
 
-    // ---- LDS -> registers
+    // ---- LDS -> registers -> MFMA: lane (r, g) multiplies chunk g of its rows
     struct Frags {
         uint4 a[TA], b[TB];
+        uint32_t sa[TA], sb[TB];
     };
-    struct Scales {
-        uint32_t a[TA], b[TB];
+    const int rd = r * ROWB + ((g ^ (r & 1)) << 4);
+    auto load_frags = [&](int stage, Frags &F) {
+        const uint8_t *p = lds + stage * STAGE + rd;
+        const uint32_t *q = reinterpret_cast<const uint32_t *>(lds + stage * STAGE + CODES) + g * (BM + BN) + r;
+#pragma unroll
+        for (int a = 0; a < TA; ++a) {
+            F.a[a] = *reinterpret_cast<const uint4 *>(p + (wm * 128 + 32 * a) * ROWB);
+            F.sa[a] = q[wm * 128 + 32 * a];
+        }
+#pragma unroll
+        for (int b = 0; b < TB; ++b) {
+            F.b[b] = *reinterpret_cast<const uint4 *>(p + (BM + wn * 128 + 32 * b) * ROWB);
+            F.sb[b] = q[BM + wn * 128 + 32 * b];
+        }
     };
-    int rd[STEPS];  // byte offset of this lane's chunk of MFMA step s inside its row
+    auto mma = [&](const Frags &F) {
 #pragma unroll
-    for (int s = 0; s < STEPS; ++s) rd[s] = r * ROWB + (((2 * s + g) ^ (r & (NCH - 1))) << 4);
-    auto load_frags = [&](int stage, int s, Frags &F) {
-        const uint8_t *p = lds + stage * STAGE + rd[s];
+        for (int a = 0; a < TA; ++a)
 #pragma unroll
-        for (int a = 0; a < TA; ++a) F.a[a] = *reinterpret_cast<const uint4 *>(p + (wm * 128 + 32 * a) * ROWB);
-#pragma unroll
-        for (int b = 0; b < TB; ++b) F.b[b] = *reinterpret_cast<const uint4 *>(p + (BM + wn * 128 + 32 * b) * ROWB);
+            for (int b = 0; b < TB; ++b) {
+                const int8v_t va = {(int)F.a[a].x, (int)F.a[a].y, (int)F.a[a].z, (int)F.a[a].w, 0, 0, 0, 0};
+                const int8v_t vb = {(int)F.b[b].x, (int)F.b[b].y, (int)F.b[b].z, (int)F.b[b].w, 0, 0, 0, 0};
+                acc[a][b] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(vb, va, acc[a][b], 4, 4, 0, (int)F.sb[b], 0, (int)F.sa[a]);
+            }
     };
-    auto load_scales = [&](int stage, Scales &S) {
-        const uint32_t *p = reinterpret_cast<const uint32_t *>(lds + stage * STAGE + CODES) + g * (BM + BN) + r;
-#pragma unroll
-        for (int a = 0; a < TA; ++a) S.a[a] = p[wm * 128 + 32 * a];
-#pragma unroll
-        for (int b = 0; b < TB; ++b) S.b[b] = p[BM + wn * 128 + 32 * b];
-    };
-#define NVFP4_MX_MMA(F, S, s)                                                                              \
-    _Pragma("unroll") for (int a = 0; a < TA; ++a) _Pragma("unroll") for (int b = 0; b < TB; ++b)          \
-    {                                                                                                      \
-        const int8v_t va = {(int)F.a[a].x, (int)F.a[a].y, (int)F.a[a].z, (int)F.a[a].w, 0, 0, 0, 0};       \
-        const int8v_t vb = {(int)F.b[b].x, (int)F.b[b].y, (int)F.b[b].z, (int)F.b[b].w, 0, 0, 0, 0};       \
-        acc[a][b] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(va, vb, acc[a][b], 4, 4, s, (int)S.a[a], s, \
-                                                                    (int)S.b[b]);                          \
-    }
 
-    Frags F0, F1;
-    Scales S0, S1;
-    if (DMA) dma_codes(0, 0);
+    Frags F;
     fetch(0);
     stash(0);
     __syncthreads();
-    load_frags(0, 0, F0);
-    load_scales(0, S0);
-
-    // One K tile: steps 0..STEPS-1 multiply while the fragments of the next step are read; the
-    // next tile goes to the other LDS stage before the last step, ONE barrier, and the first
-    // fragments / scales of the next tile are already in flight during the last step.
-    // Sc = scales of this tile, Sn = registers for the next tile's.
-    // The compiler's scheduler, left alone, sinks every LDS read down to its first use (and the
-    // scale loads down to the wait), which exposes the LDS latency once per four MFMAs.  Fences
-    // pin the software pipeline; inside a step the eight fragment reads of the NEXT step are
-    // spread between the sixteen MFMAs of this one.
-#define NVFP4_MX_FENCE __builtin_amdgcn_sched_barrier(0);
-#define NVFP4_MX_MIX                                            \
-    _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_)            \
-    {                                                           \
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);      \
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);      \
+    for (int kt = 0; kt < nkt; ++kt) {
+        const int stage = kt & 1;
+        const bool more = kt + 1 < nkt;
+        if (more) fetch(kt + 1);
+        load_frags(stage, F);
+        if (more) stash(stage ^ 1);  // the other stage: last read before the previous barrier
+        mma(F);
+        __syncthreads();
     }
-#define NVFP4_MX_TILE(stage, kt, more, Sc, Sn)                  \
-    {                                                           \
-        if (more) {                                             \
-            if (DMA) dma_codes((kt) + 1, (stage) ^ 1);          \
-            fetch((kt) + 1);                                    \
-        }                                                       \
-        NVFP4_MX_FENCE                                          \
-        if (STEPS == 4) {                                       \
-            load_frags(stage, 1, F1);                           \
-            NVFP4_MX_MMA(F0, Sc, 0)                             \
-            NVFP4_MX_MIX                                        \
-            NVFP4_MX_FENCE                                      \
-            load_frags(stage, 2, F0);                           \
-            NVFP4_MX_MMA(F1, Sc, 1)                             \
-            NVFP4_MX_MIX                                        \
-            NVFP4_MX_FENCE                                      \
-            load_frags(stage, 3, F1);                           \
-            NVFP4_MX_MMA(F0, Sc, 2)                             \
-            NVFP4_MX_MIX                                        \
-            NVFP4_MX_FENCE                                      \
-            if (more) {                                         \
-                stash((stage) ^ 1);                             \
-                __syncthreads();                                \
-                NVFP4_MX_FENCE                                  \
-                load_frags((stage) ^ 1, 0, F0);                 \
-                load_scales((stage) ^ 1, Sn);                   \
-                NVFP4_MX_FENCE                                  \
-            }                                                   \
-            NVFP4_MX_MMA(F1, Sc, 3)                             \
-            NVFP4_MX_FENCE                                      \
-        } else {                                                \
-            if (more) stash((stage) ^ 1);                       \
-            NVFP4_MX_MMA(F0, Sc, 0)                             \
-            if (more) {                                         \
-                __syncthreads();                                \
-                load_frags((stage) ^ 1, 0, F0);                 \
-                load_scales((stage) ^ 1, Sn);                   \
-            }                                                   \
-        }                                                       \
-    }
-    int kt = 0;
-    for (; kt + 2 < nkt; kt += 2) {
-        NVFP4_MX_TILE(0, kt, true, S0, S1)
-        NVFP4_MX_TILE(1, kt + 1, true, S1, S0)
-    }
-    if (kt + 1 < nkt) {
-        NVFP4_MX_TILE(0, kt, true, S0, S1)
-        ++kt;
-        NVFP4_MX_TILE(1, kt, false, S1, S0)
-    } else {
-        NVFP4_MX_TILE(0, kt, false, S0, S1)
-    }
-#undef NVFP4_MX_TILE
-#undef NVFP4_MX_MIX
-#undef NVFP4_MX_FENCE
-#undef NVFP4_MX_MMA
-
-    // epilogue: accumulator register v of lane (r, g) is row 8 (v / 4) + 4 g + v % 4, column r
-    // The lane coordinates are re-derived from an opaque copy so that none of the output
-    // addressing is computed before the K loop and kept in registers across it.
-    int lane_e = lane, wave_e = wave;
-    asm volatile("" : "+v"(lane_e), "+v"(wave_e));
-    const int re = lane_e & 31, ge = lane_e >> 5, wme = wave_e >> 1, wne = wave_e & 1;
-    const float gg = P.tensor_scales[0] * P.tensor_scales[1];
-#pragma unroll
-    for (int a = 0; a < TA; ++a)
-#pragma unroll
-        for (int b = 0; b < TB; ++b) {
-            const int64_t col = n0 + wne * 128 + 32 * b + re;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int64_t row = m0 + wme * 128 + 32 * a + 8 * (v >> 2) + 4 * ge + (v & 3);
-                if (row < P.M && col < P.N) {
-                    const float y = acc[a][b][v] * gg;
-                    if (OUT_DT == NVFP4_F32)
-                        reinterpret_cast<float *>(P.out)[row * P.ldc + col] = y;
-                    else
-                        reinterpret_cast<uint16_t *>(P.out)[row * P.ldc + col] = mx_bf16_rne(y);
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);  // one accumulator tile at a time: keeps the register peak low
-        }
+    mx_store_tile<OUT_DT>(P, acc, m0, n0, lane, wave);
 }
-
 
 // ---------------------------------------------------------------------------------------------
 // Main kernel (K a multiple of 128 and at least 512, 16-byte aligned codes): four LDS stages of
@@ -350,9 +257,6 @@ constexpr int SCALES0 = NS * STAGE, DUMP0 = SCALES0 + 2 * SBUF;
 constexpr int LDS_BYTES = DUMP0 + 4096;
 constexpr int PER_TILE = 9;  // direct-to-LDS instructions per wave per K tile: 4 + 4 codes, 1 scales or filler
 }  // namespace mxd
-
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-typedef float float2v_t __attribute__((ext_vector_type(2)));
 
 template <int OUT_DT>
 __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
@@ -570,61 +474,7 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
 #undef NVFP4_MXD_WAIT
 #undef NVFP4_MXD_MMA
 
-    // ---- epilogue: accumulator register v of lane (r, g) of tile (a, b) is output row 32 a + r,
-    // column 32 b + 8 (v / 4) + 4 g + v % 4.  The lane coordinates are re-derived from an opaque
-    // copy so that none of the output addressing is computed before the K loop and kept in
-    // registers across it.
-    int lane_e = lane, wave_e = wave;
-    asm volatile("" : "+v"(lane_e), "+v"(wave_e));
-    const int re = lane_e & 31, ge = lane_e >> 5, wme = wave_e >> 1, wne = wave_e & 1;
-    const float gg = P.tensor_scales[0] * P.tensor_scales[1];
-    constexpr int ESZ = OUT_DT == NVFP4_F32 ? 4 : 2;
-    const int64_t row0 = m0 + wme * 128 + re, col0 = n0 + wne * 128 + 4 * ge;
-    uint8_t *const out = reinterpret_cast<uint8_t *>(P.out);
-    const bool fast = m0 + BM <= P.M && n0 + BN <= P.N && (P.ldc & 3) == 0 && (reinterpret_cast<uintptr_t>(P.out) & 15) == 0;
-    if (fast) {
-#pragma unroll
-        for (int a = 0; a < TA; ++a) {
-            uint8_t *prow = out + ((row0 + 32 * a) * P.ldc + col0) * ESZ;
-#pragma unroll
-            for (int b = 0; b < TB; ++b)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float y0 = acc[a][b][4 * q] * gg, y1 = acc[a][b][4 * q + 1] * gg;
-                    const float y2 = acc[a][b][4 * q + 2] * gg, y3 = acc[a][b][4 * q + 3] * gg;
-                    uint8_t *dst = prow + (32 * b + 8 * q) * ESZ;
-                    if (OUT_DT == NVFP4_F32) {
-                        *reinterpret_cast<float4 *>(dst) = make_float4(y0, y1, y2, y3);
-                    } else {
-                        const float2v_t lo = {y0, y1}, hi = {y2, y3};
-                        const bf16x2_t blo = __builtin_convertvector(lo, bf16x2_t), bhi = __builtin_convertvector(hi, bf16x2_t);
-                        uint2 w;
-                        w.x = *reinterpret_cast<const uint32_t *>(&blo);
-                        w.y = *reinterpret_cast<const uint32_t *>(&bhi);
-                        *reinterpret_cast<uint2 *>(dst) = w;
-                    }
-                }
-            __builtin_amdgcn_sched_barrier(0);  // one accumulator row of tiles at a time keeps the register peak low
-        }
-    } else {
-#pragma unroll
-        for (int a = 0; a < TA; ++a)
-#pragma unroll
-            for (int b = 0; b < TB; ++b) {
-                const int64_t row = row0 + 32 * a;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int64_t col = col0 + 32 * b + 8 * (v >> 2) + (v & 3);
-                    if (row < P.M && col < P.N) {
-                        const float y = acc[a][b][v] * gg;
-                        if (OUT_DT == NVFP4_F32)
-                            reinterpret_cast<float *>(P.out)[row * P.ldc + col] = y;
-                        else
-                            reinterpret_cast<uint16_t *>(P.out)[row * P.ldc + col] = mx_bf16_rne(y);
-                    }
-                }
-            }
-    }
+    mx_store_tile<OUT_DT>(P, acc, m0, n0, lane, wave);
 }
 
 static void launch_mx_dma(const GemmArgs &P, int out_dt, hipStream_t st)
@@ -643,21 +493,19 @@ static void launch_mx_dma(const GemmArgs &P, int out_dt, hipStream_t st)
     }
 }
 
-template <int KT>
-static void launch_mx(const GemmArgs &P, int out_dt, hipStream_t st)
+static void launch_mx_fallback(const GemmArgs &P, int out_dt, hipStream_t st)
 {
-    constexpr int LDS_BYTES = 2 * ((mx::BM + mx::BN) * (KT / 2) + 2 * (mx::BM + mx::BN) * 4);
     const unsigned ntiles = (unsigned)(((P.N + mx::BN - 1) / mx::BN) * ((P.M + mx::BM - 1) / mx::BM));
     if (out_dt == NVFP4_F32) {
-        auto k = gemm_nt_mxfp4_kernel<KT, NVFP4_F32>;
-        static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES), true);
+        auto k = gemm_nt_mxfp4_kernel<NVFP4_F32>;
+        static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, mxf::LDS_BYTES), true);
         (void)once;
-        hipLaunchKernelGGL(k, dim3(ntiles), dim3(256), LDS_BYTES, st, P);
+        hipLaunchKernelGGL(k, dim3(ntiles), dim3(256), mxf::LDS_BYTES, st, P);
     } else {
-        auto k = gemm_nt_mxfp4_kernel<KT, NVFP4_BF16>;
-        static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES), true);
+        auto k = gemm_nt_mxfp4_kernel<NVFP4_BF16>;
+        static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, mxf::LDS_BYTES), true);
         (void)once;
-        hipLaunchKernelGGL(k, dim3(ntiles), dim3(256), LDS_BYTES, st, P);
+        hipLaunchKernelGGL(k, dim3(ntiles), dim3(256), mxf::LDS_BYTES, st, P);
     }
 }
 
@@ -669,10 +517,8 @@ hipError_t launch_gemm_mxfp4(const GemmArgs &P, int out_dt, hipStream_t st)
     const bool offsets_fit = (P.K >> 1) * 256 < ((int64_t)1 << 31);
     if (P.K % 128 == 0 && P.K >= 512 && (codes & 15) == 0 && (scales & 3) == 0 && offsets_fit)
         launch_mx_dma(P, out_dt, st);
-    else if (P.K % 256 == 0)
-        launch_mx<256>(P, out_dt, st);
     else
-        launch_mx<64>(P, out_dt, st);
+        launch_mx_fallback(P, out_dt, st);
     return hipGetLastError();
 }
 
