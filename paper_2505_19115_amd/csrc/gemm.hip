@@ -121,8 +121,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
         const int qd = tid + NT * u;
         const int row = DMA ? (wave * CA + u) * 16 + (lane >> 2) : qd >> 2;
         const int ch = DMA ? (lane & 3) ^ ((lane >> 4) & 3) : qd & 3;
-        const int64_t gr = m0 + row < P.M ? m0 + row : P.M - 1;
-        offA[u] = (uint32_t)(gr * Kb + ch * 16);
+        const int64_t lr = m0 + row < P.M ? row : P.M - 1 - m0;  // row inside the tile, clamped
+        offA[u] = (uint32_t)(lr * Kb + ch * 16);                  // (relative to the tile's first row: 32 bits suffice)
         ldsA[u] = DMA ? __builtin_amdgcn_readfirstlane((wave * CA + u) * 1024) : swz(row, ch);
     }
 #pragma unroll
@@ -130,8 +130,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
         const int qd = tid + NT * u;
         const int row = DMA ? (wave * CB + u) * 16 + (lane >> 2) : qd >> 2;
         const int ch = DMA ? (lane & 3) ^ ((lane >> 4) & 3) : qd & 3;
-        const int64_t gr = n0 + row < P.N ? n0 + row : P.N - 1;
-        offB[u] = (uint32_t)(gr * Kb + ch * 16);
+        const int64_t lr = n0 + row < P.N ? row : P.N - 1 - n0;
+        offB[u] = (uint32_t)(lr * Kb + ch * 16);
         ldsB[u] = DMA ? __builtin_amdgcn_readfirstlane(A_BYTES + (wave * CB + u) * 1024) : A_BYTES + swz(row, ch);
     }
     typedef __attribute__((address_space(3))) void *lds_ptr_t;
@@ -165,7 +165,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
     // tile kt: codes -> LDS stage `stage` (direct) or staging registers; scale bytes -> registers
     auto fetch = [&](int kt, int stage) {
         const int64_t kb = (int64_t)kt * KTB;
-        const uint8_t *pa = P.A_codes + kb, *pb = P.B_codes + kb;
+        const uint8_t *pa = P.A_codes + m0 * Kb + kb, *pb = P.B_codes + n0 * Kb + kb;
         if (!KTAIL) {
             const uint8_t *ua = uniform_ptr(pa), *ub = uniform_ptr(pb);
             const uint32_t dst = __builtin_amdgcn_readfirstlane(lds0 + stage * STAGE);
@@ -458,6 +458,8 @@ static void launch_f16_auto(const GemmArgs &P, int out_dt, hipStream_t st)
 
 hipError_t launch_gemm(const GemmArgs &P, int block, int sf, int out_dt, hipStream_t st)
 {
+    // lane offsets inside a 256-row tile are 32-bit
+    if ((P.K >> 1) * 256 >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
     if (sf == NVFP4_SCALE_E8M0) return block == 32 ? launch_gemm_mxfp4(P, out_dt, st) : hipErrorNotSupported;
     switch (block) {
     case 16: launch_f16_auto<16>(P, out_dt, st); break;
