@@ -17,7 +17,7 @@
  *
  * Where the paper is silent (how a block scale is derived, the per-tensor
  * scale, tie-breaking, saturation, the random-number source) the readings are
- * the ones listed next to each function; they are collected in the design doc.
+ * the ones stated next to each function.
  *
  * Arithmetic contract: all scale arithmetic is IEEE-754 binary32 with
  * round-to-nearest-even, one rounding per written operation, no fused
