@@ -122,6 +122,16 @@ def main() -> int:
     ms_per_step = elapsed * 1e3 / args.steps
     tflops = flop_per_step / (elapsed / args.steps) / 1e12
 
+    # the same step in MXFP4 (block 32, E8M0; the GEMMs then run on the FP4 matrix instruction)
+    def step_mx(s):
+        for name, N, K, X, W, dY, wf, wb, Y, dX, dW, sc in data:
+            nv.linear_fwd(X, W, nv.MXFP4, workspace=wf, out=Y)
+            nv.linear_bwd(dY, X, W, 2000 + 3 * s, nv.MXFP4, workspace=wb, out=(dX, dW))
+
+    mx_step_ms = event_time_ms(step_mx, max(args.steps // 2, 3), torch)
+    mx_step = {"ms_per_step": round(mx_step_ms, 3), "TFLOP/s": round(flop_per_step / (mx_step_ms * 1e-3) / 1e12, 1),
+               "frac_of_fp4_peak": round(flop_per_step / (mx_step_ms * 1e-3) / 1e12 / PEAK_FP4_TFLOPS, 4)}
+
     # ---- dominant kernel: the block-scaled GEMM at the gate/up shape (same launch as in step)
     name, N, K, X, W, dY, wf, wb, Y, dX, dW, _ = data[0]
     qa, qb = nv.quantize(X, 1), nv.quantize(W, 1)
@@ -250,7 +260,7 @@ def main() -> int:
                    "M": M, "layers": [[n, N, K] for n, N, K in layers], "format": "NVFP4 (block 16, E4M3, tensor scale)",
                    "rounding": "fwd RtN; bwd/update SR (Philox4x32-10)"},
         "frac_of_fp4_peak": round(tflops / PEAK_FP4_TFLOPS, 4),
-        "roofline": roofline, "mfma_sustained": sustained, "mxfp4_gemm": mxfp4, "format_sweep": sweep,
+        "roofline": roofline, "mfma_sustained": sustained, "mxfp4_gemm": mxfp4, "mxfp4_step": mx_step, "format_sweep": sweep,
         "quantize": quant, "cpu_baseline": cpu,
     }
     print(json.dumps(line))

@@ -129,7 +129,7 @@ nvfp4_status nvfp4_quantize(const void *x, nvfp4_dtype dt, int64_t rows, int64_t
  * tensor_scales: device fp32[2] = {gA, gB}.
  * out: [M, N] of out_dt with leading dimension ldc.  Products are exact;
  * accumulation is fp32.
- * K must be a multiple of the block and of 32; M, N >= 1.
+ * K must be a multiple of the block and of 32, at most 2^23; M, N >= 1.
  * Formats: E4M3 scales with blocks 16/32/64/128 (operands expanded exactly to
  * fp16 for the matrix instruction), and E8M0 scales with block 32 (MXFP4, run
  * on the FP4 matrix instruction as stored); other pairs: NVFP4_EUNSUPPORTED.

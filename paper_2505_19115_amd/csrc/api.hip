@@ -12,6 +12,7 @@ namespace {
 
 constexpr size_t WS_ALIGN = 256;
 constexpr size_t WS_HEADER = 256;  // tensor scales and maxima live at the front of a workspace
+constexpr int64_t MAX_CONTRACTION = (int64_t)1 << 23;  // the GEMM kernels keep 32-bit byte offsets inside a 256-row tile
 
 inline size_t align_up(size_t n) { return (n + WS_ALIGN - 1) / WS_ALIGN * WS_ALIGN; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -205,7 +206,7 @@ nvfp4_status nvfp4_gemm(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
     if (s != NVFP4_OK) return s;
     if (!A_codes || !A_scales || !B_codes || !B_scales || !tensor_scales || !out) return NVFP4_EINVAL;
     if (!valid_dtype(out_dt)) return NVFP4_EINVAL;
-    if (M < 0 || N < 0 || K <= 0 || ldc < N) return NVFP4_ESHAPE;
+    if (M < 0 || N < 0 || K <= 0 || K > MAX_CONTRACTION || ldc < N) return NVFP4_ESHAPE;
     if (K % f->block != 0 || K % 32 != 0) return NVFP4_ESHAPE;
     if (!aligned16(A_codes) || !aligned16(A_scales) || !aligned16(B_codes) || !aligned16(B_scales) ||
         !aligned16(out))
@@ -227,7 +228,7 @@ nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, 
     if (s != NVFP4_OK) return s;
     if (!X || !W || !Y) return NVFP4_EINVAL;
     if (!valid_dtype(in_dt) || !valid_dtype(out_dt)) return NVFP4_EINVAL;
-    if (M <= 0 || N <= 0 || K <= 0) return NVFP4_ESHAPE;
+    if (M <= 0 || N <= 0 || K <= 0 || K > MAX_CONTRACTION) return NVFP4_ESHAPE;
     if (K % f->block != 0 || K % 32 != 0) return NVFP4_ESHAPE;
     if (f->scale == NVFP4_SCALE_E8M0 && f->block != 32) return NVFP4_EUNSUPPORTED;  // E8M0 GEMM: MXFP4 only
     if (!aligned16(X) || !aligned16(W) || !aligned16(Y)) return NVFP4_EALIGN;
@@ -271,8 +272,8 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
     if (M <= 0 || N <= 0 || K <= 0) return NVFP4_ESHAPE;
     const int64_t B = f->block;
     // dX contracts over N, dW over M; K is a leading dimension of X and W read down columns
-    if (dX && (N % B != 0 || N % 32 != 0)) return NVFP4_ESHAPE;
-    if (dW && (M % B != 0 || M % 32 != 0)) return NVFP4_ESHAPE;
+    if (dX && (N % B != 0 || N % 32 != 0 || N > MAX_CONTRACTION)) return NVFP4_ESHAPE;
+    if (dW && (M % B != 0 || M % 32 != 0 || M > MAX_CONTRACTION)) return NVFP4_ESHAPE;
     if ((K * (int64_t)elem_size(in_dt)) % 16 != 0 || (N * (int64_t)elem_size(in_dt)) % 16 != 0) return NVFP4_EALIGN;
     if (f->scale == NVFP4_SCALE_E8M0 && f->block != 32) return NVFP4_EUNSUPPORTED;  // E8M0 GEMM: MXFP4 only
     if (!aligned16(dY) || !aligned16(X) || !aligned16(W) || !aligned16(dX) || !aligned16(dW)) return NVFP4_EALIGN;

@@ -171,6 +171,17 @@ def test_linear_fp32_inputs_bf16_outputs():
         assert np.all(np.abs(to_np(got.float()) - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * np.abs(ref).max())
 
 
+def test_gemm_is_deterministic():
+    # fixed accumulation order, no atomics: two launches give the same bits, for both matrix-instruction paths
+    rng = np.random.default_rng(123)
+    for fmt, mk in ((nv.NVFP4, lambda rows: random_operand(rng, rows, 1024)), (nv.MXFP4, lambda rows: mx_operand(rng, rows, 1024))):
+        A, B = dev(mk(520)), dev(mk(392))
+        print(f"[case] gemm determinism fmt={fmt}", flush=True)
+        y0, y1 = nv.gemm(A, B, fmt), nv.gemm(A, B, fmt)
+        torch.cuda.synchronize()
+        assert torch.equal(y0, y1)
+
+
 def test_backward_with_scales_handed_over_from_forward():
     # the per-tensor scales of X and W are functions of the tensors alone: the backward call that is
     # given the forward call's {gX, gW} skips two maximum passes and must produce the same bits

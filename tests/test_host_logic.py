@@ -89,6 +89,7 @@ def test_gemm_and_linear_argument_errors():
     assert g(out=FAKE + 4) == nv.EALIGN
     assert g(f=nv.Format(64, nv.SCALE_E8M0, 0).c()) == nv.EUNSUPPORTED  # E8M0 GEMM exists for block 32 only
     assert g(M=0) == nv.OK           # empty product: nothing to do, nothing launched
+    assert g(K=(1 << 23) + 32) == nv.ESHAPE  # contraction length beyond the kernels' 32-bit tile offsets
     fw = lambda **k: nv.lib.nvfp4_linear_fwd(k.get("X", FAKE), FAKE, FAKE, 64, 64, k.get("K", 64), nv.BF16, nv.F32,
                                              C.byref(f), k.get("ws", FAKE), k.get("wsb", 1 << 30), None, None)
     assert fw(X=None) == nv.EINVAL
