@@ -171,6 +171,27 @@ def test_linear_fp32_inputs_bf16_outputs():
         assert np.all(np.abs(to_np(got.float()) - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * np.abs(ref).max())
 
 
+@pytest.mark.parametrize("fmt_name", ["NVFP4", "MXFP4"])
+@pytest.mark.parametrize("shape", [(4096, 4096, 11008), (11008, 4096, 4096)], ids=["down-or-dX", "dW"])
+def test_7b_backward_gemm_shapes_sampled(shape, fmt_name):
+    # the other two GEMM shapes of the benchmark step (K = 11008: 86 K tiles; 11008 output rows), the kernels
+    # and launch configuration bench.py times, checked on sampled outputs the oracle computes one by one
+    M, N, K = shape
+    fmt, of = getattr(nv, fmt_name), getattr(oracle, fmt_name)
+    A = oracle.quantize(synth.normal(M, K, 1.0, 81), 1, 0, 0, of)
+    B = oracle.quantize(synth.normal(N, K, 0.02, 82), 1, 0, 0, of)
+    print(f"[case] gemm {fmt_name} {shape} sampled", flush=True)
+    Y = nv.gemm(dev(A), dev(B), fmt, torch.bfloat16)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(6)
+    ii = np.concatenate([rng.integers(0, M, 3000), np.full(256, M - 1), np.arange(0, M, 97)])
+    jj = np.concatenate([rng.integers(0, N, 3000), np.arange(N - 256, N), np.full(len(range(0, M, 97)), N - 1)])
+    ref = oracle.gemm_nt_sample(A, B, ii, jj, of)
+    ref_abs = oracle.gemm_nt_sample(A, B, ii, jj, of, take_abs=True)
+    got = to_np(Y.float())[ii, jj]
+    assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * ref_abs)  # bf16 output: one more rounding
+
+
 def test_gemm_is_deterministic():
     # fixed accumulation order, no atomics: two launches give the same bits, for both matrix-instruction paths
     rng = np.random.default_rng(123)

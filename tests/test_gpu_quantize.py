@@ -201,3 +201,16 @@ def test_full_size_quantizer_sweep_tensor(axis, rounding, seed):
     # compared element by element (the oracle needs a few seconds per run)
     x = synth.student_t_outliers(8192, 8192, seed=100)
     run_both(x, axis, rounding, seed, nv.NVFP4, what="config2")
+
+
+@pytest.mark.parametrize("what,shape,axis,rounding,fmt", [
+    ("dY rows SR (dX operand)", (4096, 11008), 1, 1, "NVFP4"),
+    ("dY columns SR (dW operand)", (4096, 11008), 0, 1, "NVFP4"),
+    ("W columns RtN (W^T operand)", (11008, 4096), 0, 0, "NVFP4"),
+    ("X columns SR, MXFP4", (4096, 4096), 0, 1, "MXFP4"),
+])
+def test_full_size_7b_backward_operands(what, shape, axis, rounding, fmt):
+    # the tensors the benchmark step quantizes for its backward GEMMs, element by element
+    rows, cols = shape
+    x = synth.gradient_like(rows, cols, 300) if what.startswith("dY") else synth.normal(rows, cols, 0.02, 200)
+    run_both(x, axis, rounding, 1000, getattr(nv, fmt), what=what)
