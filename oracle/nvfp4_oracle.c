@@ -153,8 +153,12 @@ uint8_t orc_round_rtn(float m)
  * to neighboring values"): with lo <= m < hi the neighbouring grid values and
  * t = (m - lo)/(hi - lo), the result is hi with probability t (to 2^-17) and lo
  * otherwise, so that the expected result is m (the E[eps] = 0 property used in
- * Sec. 4).  The draw is a 16-bit uniform u: round up iff u + 1/2 < 65536 t.
- * A value on the grid (t = 0) and the saturated value 6 never move. */
+ * Sec. 4).  The draw is a 16-bit uniform u: round up iff u + 1/2 <= 65536 t,
+ * which is the classic formulation "add uniformly random bits below the kept
+ * digit, then truncate" with the draw centred on the 16-bit grid (reading: the
+ * paper fixes neither the number of random bits nor which way the one exact
+ * tie u + 1/2 = 65536 t goes).  A value on the grid (t = 0) and the saturated
+ * value 6 never move. */
 uint8_t orc_round_sr(float m, uint32_t u16)
 {
     int lo = 0;
@@ -163,7 +167,7 @@ uint8_t orc_round_sr(float m, uint32_t u16)
     if (lo == 7) return 7;
     float vlo = orc_e2m1_decode((uint8_t)lo), vhi = orc_e2m1_decode((uint8_t)(lo + 1));
     float t = (m - vlo) / (vhi - vlo); /* both operations exact in binary32 */
-    int up = ((float)u16 + 0.5f) < t * 65536.0f;
+    int up = ((float)u16 + 0.5f) <= t * 65536.0f;
     return (uint8_t)(lo + up);
 }
 

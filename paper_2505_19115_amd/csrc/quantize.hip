@@ -185,6 +185,26 @@ __device__ __forceinline__ uint32_t quant_pair_hw(float x0, float x1, float q)
     return __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, x0 * q, x1 * q, 1.0f, 0) & 0xFFu;
 }
 
+// Stochastic rounding of one element through the gfx950 convert, which takes a pair: the
+// element sits in slot SLOT (0: low nibble, random bits seed[31:10]; 1: high nibble, seed[30:9]),
+// the other slot holds +0 (never rounded up: code 0).  Byte BYTE of acc is replaced and the
+// other bytes kept, so two accumulators (one per slot) are filled and OR-ed.  Saturation at
+// +-6 and the sign (also of a zero) are the convert's own.
+// Written as inline assembly with the accumulator tied to the destination: the compiler's
+// builtin for this instruction does not tie its "old" operand, which loses the other bytes.
+template <int SLOT, int BYTE>
+__device__ __forceinline__ uint32_t sr_elem_hw(uint32_t acc, float y, uint32_t u16)
+{
+    typedef float float2_t __attribute__((ext_vector_type(2)));
+    const float2_t v = SLOT == 0 ? float2_t{y, 0.0f} : float2_t{0.0f, y};
+    const uint32_t seed = SLOT == 0 ? sr_seed_first(u16) : sr_seed_second(u16);
+    if (BYTE == 0) asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, 1.0" : "+v"(acc) : "v"(v), "v"(seed));
+    if (BYTE == 1) asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, 1.0 op_sel:[0,0,1,0]" : "+v"(acc) : "v"(v), "v"(seed));
+    if (BYTE == 2) asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, 1.0 op_sel:[0,0,0,1]" : "+v"(acc) : "v"(v), "v"(seed));
+    if (BYTE == 3) asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, 1.0 op_sel:[0,0,1,1]" : "+v"(acc) : "v"(v), "v"(seed));
+    return acc;
+}
+
 // ------------------------------------------------------------------ tensor maximum (Q0)
 
 // max|x| over a [rows, cols] tensor: one partial maximum (bit pattern) per workgroup into
@@ -296,6 +316,15 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(QuantArgs P)
 #pragma unroll
             for (int t = 0; t < 4; ++t)
                 packed |= quant_pair_hw(v[u].get(2 * t), v[u].get(2 * t + 1), q) << (8 * t);
+        } else if (RND == NVFP4_SR && HW) {
+            const u32x4 d = sr_draw(P.seed, (uint64_t)id);  // element index = 8*id + t
+            uint32_t lo = 0, hi = 0;
+#define NVFP4_SR_PAIR(t)                                                                    \
+    lo = sr_elem_hw<0, t>(lo, v[u].get(2 * t) * q, sr_bits_of(d, 2 * t));                   \
+    hi = sr_elem_hw<1, t>(hi, v[u].get(2 * t + 1) * q, sr_bits_of(d, 2 * t + 1));
+            NVFP4_SR_PAIR(0) NVFP4_SR_PAIR(1) NVFP4_SR_PAIR(2) NVFP4_SR_PAIR(3)
+#undef NVFP4_SR_PAIR
+            packed = lo | hi;
         } else {
             u32x4 d = {0, 0, 0, 0};
             if (RND == NVFP4_SR) d = sr_draw(P.seed, (uint64_t)id);  // element index = 8*id + t
@@ -338,6 +367,42 @@ struct ColGeom {
     static constexpr int WG_COLS = 4 * WAVE_COLS;
     static constexpr int WG_ROWS = RPL * LANES_V;
 };
+
+// 16 bits of the column c of a lane's 8 in row-major element order: from draw d0 when the 8
+// columns are aligned to a draw (shift = 0), else from d0 or d1.
+template <bool ALIGNED>
+__device__ __forceinline__ uint32_t col_bits(const u32x4 &d0, const u32x4 &d1, uint32_t shift, int c)
+{
+    if (ALIGNED) return sr_bits_of(d0, c);
+    const uint32_t pos = shift + c;
+    return pos < 8 ? sr_bits_of(d0, pos) : sr_bits_of(d1, pos - 8);
+}
+
+// Stochastic rounding of a lane's 16 x 8 tile through the hardware convert, two rows at a time
+// (the byte select of the convert must be a constant, hence the recursion over row pairs).
+template <int DT, int RND, bool ALIGNED, int BL, int R>
+__device__ __forceinline__ void col_sr_hw(const QuantArgs &P, Chunk<DT> (&v)[16], float (&q)[8][16 / BL],
+                                          int64_t row0, int64_t col0, uint32_t (&weven)[8][2],
+                                          uint32_t (&wodd)[8][2])
+{
+    if constexpr (R < 16) {
+        const uint64_t e0 = (uint64_t)(row0 + R) * (uint64_t)P.cols + (uint64_t)col0;
+        const uint64_t e1 = e0 + (uint64_t)P.cols;
+        const u32x4 z = {0, 0, 0, 0};
+        const u32x4 a0 = sr_draw(P.seed, e0 >> 3), b0 = sr_draw(P.seed, e1 >> 3);
+        const u32x4 a1 = ALIGNED ? z : sr_draw(P.seed, (e0 >> 3) + 1);
+        const u32x4 b1 = ALIGNED ? z : sr_draw(P.seed, (e1 >> 3) + 1);
+        const uint32_t sa = (uint32_t)e0 & 7u, sb = (uint32_t)e1 & 7u;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            weven[c][R / 8] = sr_elem_hw<0, (R % 8) / 2>(weven[c][R / 8], v[R].get(c) * q[c][R / BL],
+                                                         col_bits<ALIGNED>(a0, a1, sa, c));
+            wodd[c][R / 8] = sr_elem_hw<1, (R % 8) / 2>(wodd[c][R / 8], v[R + 1].get(c) * q[c][(R + 1) / BL],
+                                                        col_bits<ALIGNED>(b0, b1, sb, c));
+        }
+        col_sr_hw<DT, RND, ALIGNED, BL, R + 2>(P, v, q, row0, col0, weven, wodd);
+    }
+}
 
 // ALIGNED: cols is a multiple of 8, so the 8 columns of a lane share one random draw per row.
 template <int DT, int B, int SF, int RND, bool HW, bool ALIGNED, int LV = 8>
@@ -407,6 +472,19 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(QuantArgs P)
 #pragma unroll
             for (int c = 0; c < 8; ++c)
                 words[c][r / 8] |= quant_pair_hw(v[r].get(c), v[r + 1].get(c), q[c][r / BL]) << (4 * (r % 8));
+    } else if (RND == NVFP4_SR && HW) {
+        // rows 2p and 2p+1 of a column share a byte: even rows go through slot 0, odd rows
+        // through slot 1 of the convert, into two sets of words that are OR-ed at the end
+        uint32_t wodd[8][RPL / 8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+#pragma unroll
+            for (int w = 0; w < RPL / 8; ++w) wodd[c][w] = 0;
+        col_sr_hw<DT, RND, ALIGNED, BL, 0>(P, v, q, row0, col0, words, wodd);
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+#pragma unroll
+            for (int w = 0; w < RPL / 8; ++w) words[c][w] |= wodd[c][w];
     } else {
         // the 8 columns of a lane are 8 consecutive elements of a row; their random bits come
         // from one draw when that group is aligned in the row-major numbering, else from two
@@ -518,7 +596,9 @@ static void launch_q(const QuantArgs &P, int axis, hipStream_t st)
 template <int DT, int B, int SF>
 static void launch_q_rnd(const QuantArgs &P, int axis, int rounding, bool hw, hipStream_t st)
 {
-    if (rounding == NVFP4_SR)
+    if (rounding == NVFP4_SR && hw)
+        launch_q<DT, B, SF, NVFP4_SR, true>(P, axis, st);
+    else if (rounding == NVFP4_SR)
         launch_q<DT, B, SF, NVFP4_SR, false>(P, axis, st);
     else if (hw)
         launch_q<DT, B, SF, NVFP4_RTN, true>(P, axis, st);

@@ -214,3 +214,27 @@ def test_full_size_7b_backward_operands(what, shape, axis, rounding, fmt):
     rows, cols = shape
     x = synth.gradient_like(rows, cols, 300) if what.startswith("dY") else synth.normal(rows, cols, 0.02, 200)
     run_both(x, axis, rounding, 1000, getattr(nv, fmt), what=what)
+
+
+@pytest.mark.parametrize("axis", [1, 0])
+def test_sr_exact_ties_between_draw_and_position(axis):
+    # every element sits exactly where its own draw ties with its position between the grid
+    # neighbours (65536 t = u + 1/2), offset by -1, 0 or +1 draws, in every binade of the grid;
+    # one 6.0 per block and a preset tensor scale of 1 make the block multiplier exactly 1
+    rows, cols, seed = 96, 128, 11
+    u = oracle.sr_bits_range(seed, 0, rows * cols).astype(np.float64).reshape(rows, cols)
+    rng = np.random.default_rng(4)
+    lo_step = np.array([(0.0, 0.5), (0.5, 0.5), (1.0, 0.5), (1.5, 0.5), (2.0, 1.0), (3.0, 1.0), (4.0, 2.0)])
+    pick = lo_step[rng.integers(0, len(lo_step), (rows, cols))]
+    off = rng.integers(-1, 2, (rows, cols))
+    pos = np.clip(u + off, 0, 65535) + 0.5
+    x = pick[..., 0] + pick[..., 1] * pos / 65536
+    x *= rng.choice([-1.0, 1.0], (rows, cols))
+    if axis == 1:
+        x[:, ::16] = 6.0
+    else:
+        x[::16, :] = 6.0
+    x32 = x.astype(np.float32)
+    assert np.array_equal(x32.astype(np.float64), x)
+    got = run_both(torch.from_numpy(x32), axis, nv.SR, seed, nv.NVFP4, preset=1.0, what="sr-ties")
+    assert np.all(to_np(got[1]) == 0x38)  # every block scale is 1.0

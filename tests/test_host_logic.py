@@ -144,7 +144,10 @@ def test_host_round_sr_matches_oracle():
     assert np.array_equal(got, oracle.round_sr(m, u))
     uu = np.arange(65536, dtype=np.uint32)
     for mv in [0.0, 1e-30, 0.1, 0.25, 0.4999999, 0.5, 0.75, 1.0, 1.2, 1.9999999, 2.0, 2.4, 3.0, 3.999999, 4.0, 5.0,
-               5.9999995, 6.0, 2.0 ** -17 * 0.5, 0.5 + 2.0 ** -18, 4 + 2.0 ** -16]:
+               5.9999995, 6.0, 2.0 ** -17 * 0.5, 0.5 + 2.0 ** -18, 4 + 2.0 ** -16,
+               # exact ties between the position and a centred draw, one per binade of the grid
+               0.5 * 100.5 / 65536, 0.5 + 0.5 * 7.5 / 65536, 1.5 + 0.5 * 65535.5 / 65536, 2 + 100.5 / 65536,
+               3 + 0.5 / 65536, 4 + 2 * 32767.5 / 65536]:
         mm = np.full(65536, mv, np.float32)
         nv.lib.nvfp4_host_round_sr_n(_p(mm), _p(uu), 65536, _p(got[:65536]))
         assert np.array_equal(got[:65536], oracle.round_sr(mm, uu)), mv

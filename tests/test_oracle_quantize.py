@@ -66,6 +66,19 @@ def test_sr_support_and_exact_probability():
         assert np.all(oracle.round_sr(np.full(65536, GRID[c], np.float32), u) == c)
 
 
+def test_sr_tie_between_draw_and_position_rounds_up():
+    # reading (the paper fixes neither the number of random bits nor this tie): a value whose
+    # position between its neighbours falls exactly on a centred draw, 65536 t = u + 1/2, goes up
+    # for that draw.  m = lo + step * 100.5 / 65536: draws 0..100 go up, 101.. stay.
+    u = np.arange(65536, dtype=np.uint32)
+    for lo, step in ((0.0, 0.5), (0.5, 0.5), (1.5, 0.5), (2.0, 1.0), (3.0, 1.0), (4.0, 2.0)):
+        m = np.float32(lo + step * 100.5 / 65536)
+        assert float(m) == lo + step * 100.5 / 65536  # exactly representable
+        got = oracle.round_sr(np.full(65536, m, np.float32), u)
+        base = int(np.searchsorted(GRID, lo))
+        assert np.all(got[:101] == base + 1) and np.all(got[101:] == base)
+
+
 def test_sr_probability_matches_distance_everywhere():
     rng = np.random.default_rng(3)
     u = np.arange(65536, dtype=np.uint32)
