@@ -122,6 +122,24 @@ nvfp4_status nvfp4_quantize(const void *x, nvfp4_dtype dt, int64_t rows, int64_t
                             size_t workspace_bytes, void *stream);
 
 /*
+ * Both orientations of one tensor in one pass over it: Eqs. 5-6 use the output
+ * gradient blocked along N (for dX) and along M (for dW), Eqs. 4-5 use W blocked
+ * along K and along N.  The results are exactly those of
+ *   nvfp4_quantize(x, ..., axis 1, rounding, seed_rows, ...) -> codes_rows [rows, cols/2], scales_rows [rows, cols/block]
+ *   nvfp4_quantize(x, ..., axis 0, rounding, seed_cols, ...) -> codes_cols [cols, rows/2], scales_cols [cols, rows/block]
+ * with one shared per-tensor scale (same rule, flags and workspace as
+ * nvfp4_quantize).  rows and cols must both be multiples of the block size.
+ * Blocks of 16 and 32 with 16-byte aligned rows of x run as one fused kernel
+ * (x is read once); other cases run the two single-orientation kernels.
+ * All output pointers device memory, 16-byte aligned, owned by the caller.
+ */
+nvfp4_status nvfp4_quantize_dual(const void *x, nvfp4_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                                 nvfp4_rounding rounding, uint64_t seed_rows, uint64_t seed_cols,
+                                 const nvfp4_format *f, uint8_t *codes_rows, uint8_t *scales_rows,
+                                 uint8_t *codes_cols, uint8_t *scales_cols, float *tensor_scale,
+                                 uint32_t flags, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Block-scaled GEMM shared by Eqs. 4-6, operands stored with the contraction
  * axis contiguous ("NT"):
  *   out[i, j] = gA * gB * sum_k a[i, k] * b[j, k],   a = magnitude*scale of A, same for B

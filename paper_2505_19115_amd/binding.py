@@ -71,6 +71,8 @@ def _load() -> C.CDLL:
     L.nvfp4_tensor_scale.argtypes = [vp, ci, i64, i64, i64, vp, vp, sz, vp]
     L.nvfp4_quantize.restype = ci
     L.nvfp4_quantize.argtypes = [vp, ci, i64, i64, i64, ci, ci, u64, fp, vp, vp, vp, u32, vp, sz, vp]
+    L.nvfp4_quantize_dual.restype = ci
+    L.nvfp4_quantize_dual.argtypes = [vp, ci, i64, i64, i64, ci, u64, u64, fp, vp, vp, vp, vp, vp, u32, vp, sz, vp]
     L.nvfp4_gemm.restype = ci
     L.nvfp4_gemm.argtypes = [i64, i64, i64, fp, vp, vp, vp, vp, vp, vp, ci, i64, vp]
     L.nvfp4_linear_fwd.restype = ci
@@ -113,7 +115,7 @@ lib = _load()
 EXPORTS = (
     "nvfp4_status_string", "nvfp4_codes_bytes", "nvfp4_scales_bytes",
     "nvfp4_quantize_workspace_bytes", "nvfp4_linear_fwd_workspace_bytes",
-    "nvfp4_linear_bwd_workspace_bytes", "nvfp4_tensor_scale", "nvfp4_quantize", "nvfp4_gemm",
+    "nvfp4_linear_bwd_workspace_bytes", "nvfp4_tensor_scale", "nvfp4_quantize", "nvfp4_quantize_dual", "nvfp4_gemm",
     "nvfp4_linear_fwd", "nvfp4_linear_bwd", "nvfp4_host_e4m3_encode", "nvfp4_host_e4m3_decode",
     "nvfp4_host_round_rtn", "nvfp4_host_round_sr", "nvfp4_host_philox4x32_10",
     "nvfp4_host_sr_bits", "nvfp4_host_e8m0_encode", "nvfp4_host_e4m3_encode_n",
@@ -187,6 +189,36 @@ def quantize(x: torch.Tensor, axis: int = 1, rounding: int = RTN, seed: int = 0,
                               C.byref(f), codes.data_ptr(), scales.data_ptr(), g.data_ptr(), flags,
                               ws.data_ptr(), ws.numel(), _stream()), "nvfp4_quantize")
     return codes, scales, g
+
+
+def quantize_dual(x: torch.Tensor, rounding: int = RTN, seed_rows: int = 0, seed_cols: int = 0,
+                  fmt: Format = NVFP4, tensor_scale: torch.Tensor | None = None, out=None):
+    """nvfp4_quantize_dual -> ((codes [rows, cols/2], scales [rows, cols/block], g),
+    (codes [cols, rows/2], scales [cols, rows/block], g)): both orientations, one shared g.
+
+    `out` = (codes_rows, scales_rows, codes_cols, scales_cols, g) reuses caller-provided tensors.
+    """
+    _require_gpu(x, tensor_scale)
+    assert x.dim() == 2 and (x.stride(1) == 1 or x.shape[1] <= 1)
+    rows, cols = x.shape
+    ld = x.stride(0) if rows > 1 else cols
+    f = fmt.c()
+    if out is None:
+        cr = torch.empty((rows, cols // 2), dtype=torch.uint8, device=x.device)
+        sr = torch.empty((rows, cols // fmt.block), dtype=torch.uint8, device=x.device)
+        cc = torch.empty((cols, rows // 2), dtype=torch.uint8, device=x.device)
+        sc = torch.empty((cols, rows // fmt.block), dtype=torch.uint8, device=x.device)
+        g = torch.empty(1, dtype=torch.float32, device=x.device) if tensor_scale is None else tensor_scale
+    else:
+        cr, sr, cc, sc, g = out
+        if tensor_scale is not None:
+            g = tensor_scale
+    flags = PRESET_TSCALE if tensor_scale is not None else 0
+    ws = torch.empty(lib.nvfp4_quantize_workspace_bytes(rows, cols), dtype=torch.uint8, device=x.device)
+    _check(lib.nvfp4_quantize_dual(x.data_ptr(), _dtype_tag(x), rows, cols, ld, rounding, seed_rows, seed_cols,
+                                   C.byref(f), cr.data_ptr(), sr.data_ptr(), cc.data_ptr(), sc.data_ptr(),
+                                   g.data_ptr(), flags, ws.data_ptr(), ws.numel(), _stream()), "nvfp4_quantize_dual")
+    return (cr, sr, g), (cc, sc, g)
 
 
 def gemm(A, B, fmt: Format = NVFP4, out_dtype: torch.dtype = torch.float32, out=None) -> torch.Tensor:

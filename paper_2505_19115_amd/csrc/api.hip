@@ -197,6 +197,63 @@ nvfp4_status nvfp4_quantize(const void *x, nvfp4_dtype dt, int64_t rows, int64_t
     return run_quantize(q, f, st) == hipSuccess ? NVFP4_OK : NVFP4_EHIP;
 }
 
+nvfp4_status nvfp4_quantize_dual(const void *x, nvfp4_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                                 nvfp4_rounding rounding, uint64_t seed_rows, uint64_t seed_cols,
+                                 const nvfp4_format *f, uint8_t *codes_rows, uint8_t *scales_rows,
+                                 uint8_t *codes_cols, uint8_t *scales_cols, float *tensor_scale,
+                                 uint32_t flags, void *workspace, size_t workspace_bytes, void *stream)
+{
+    nvfp4_status s = check_format(f);
+    if (s != NVFP4_OK) return s;
+    s = check_tensor(x, dt, rows, cols, ld);
+    if (s != NVFP4_OK) return s;
+    const bool empty = rows == 0 || cols == 0;
+    if (!tensor_scale || (!empty && (!codes_rows || !scales_rows || !codes_cols || !scales_cols))) return NVFP4_EINVAL;
+    if (rounding != NVFP4_RTN && rounding != NVFP4_SR) return NVFP4_EINVAL;
+    if (flags & ~NVFP4_PRESET_TSCALE) return NVFP4_EINVAL;
+    if (rows % f->block != 0 || cols % f->block != 0) return NVFP4_ESHAPE;
+    if (!aligned16(codes_rows) || !aligned16(scales_rows) || !aligned16(codes_cols) || !aligned16(scales_cols))
+        return NVFP4_EALIGN;
+    const bool preset = (flags & NVFP4_PRESET_TSCALE) != 0;
+    const bool need_amax = f->tensor_scale && !preset;
+    if (need_amax) {
+        if (!workspace || workspace_bytes < nvfp4_quantize_workspace_bytes(rows, cols)) return NVFP4_EWORKSPACE;
+        if (!aligned16(workspace)) return NVFP4_EALIGN;
+    }
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+
+    DualArgs d;
+    d.c.x = x;
+    d.c.rows = rows;
+    d.c.cols = cols;
+    d.c.ld = ld;
+    d.c.codes = codes_cols;
+    d.c.scales = scales_cols;
+    d.c.g_src = tensor_scale;
+    d.c.g_out = tensor_scale;
+    d.c.g_mode = G_NONE;
+    d.c.seed = seed_cols;
+    d.codes_r = codes_rows;
+    d.scales_r = scales_rows;
+    d.seed_r = seed_rows;
+    d.g_out2 = nullptr;
+    if (f->tensor_scale) {
+        if (preset) {
+            d.c.g_mode = G_PRESET;
+        } else {
+            uint32_t *bits = reinterpret_cast<uint32_t *>(workspace);
+            uint32_t *partials = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(workspace) + WS_HEADER);
+            if (launch_tensor_amax(x, dt, rows, cols, ld, bits, partials, empty ? tensor_scale : nullptr, st) != hipSuccess)
+                return NVFP4_EHIP;
+            d.c.g_src = reinterpret_cast<const float *>(bits);
+            d.c.g_mode = G_FROM_AMAX;
+        }
+    }
+    if (empty) return NVFP4_OK;
+    return launch_quantize_dual(d, dt, rounding, f->block, f->scale, use_hw_convert(), st) == hipSuccess ? NVFP4_OK
+                                                                                                        : NVFP4_EHIP;
+}
+
 nvfp4_status nvfp4_gemm(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
                         const uint8_t *A_codes, const uint8_t *A_scales, const uint8_t *B_codes,
                         const uint8_t *B_scales, const float *tensor_scales, void *out,
@@ -307,12 +364,32 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
     if (f->tensor_scale) {
         if (launch_tensor_amax(dY, in_dt, M, N, N, amax + 0, partials, nullptr, st) != hipSuccess) return NVFP4_EHIP;
     }
+    // with both GEMMs wanted, dY is read once for its two orientations (streams seed, seed+1)
+    const bool dual = dX && dW && quantize_dual_fused(in_dt, M, N, N, f->block, use_hw_convert());
+    if (dual) {
+        DualArgs d;
+        d.c.x = dY;
+        d.c.rows = M;
+        d.c.cols = N;
+        d.c.ld = N;
+        d.c.codes = dytc;
+        d.c.scales = dyts;
+        d.c.g_src = reinterpret_cast<const float *>(amax + 0);
+        d.c.g_out = ts + 0;
+        d.c.g_mode = gm;
+        d.c.seed = seed + 1;
+        d.codes_r = dyc;
+        d.scales_r = dys;
+        d.seed_r = seed;
+        d.g_out2 = ts + 2;
+        if (launch_quantize_dual(d, in_dt, NVFP4_SR, f->block, f->scale, true, st) != hipSuccess) return NVFP4_EHIP;
+    }
     if (dX) {
         if (f->tensor_scale && !known && launch_tensor_amax(W, in_dt, N, K, K, amax + 1, partials, nullptr, st) != hipSuccess) return NVFP4_EHIP;
         // Eq. 5: dX[M, K] = Q_SR(dY)[M, N] * Q_RtN(W^T)[K, N]^T
         QuantPlan qa{dY, in_dt, M, N, N, 1, NVFP4_SR, seed, dyc, dys, reinterpret_cast<const float *>(amax + 0), ts + 0, gm};
         QuantPlan qb{W, in_dt, N, K, K, 0, NVFP4_RTN, 0, wtc, wts, gsrc_w, ts + 1, gm_xw};
-        if (run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
+        if (!dual && run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
         if (run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
         GemmArgs g{M, K, N, dyc, dys, wtc, wts, ts + 0, dX, K};
         if (launch_gemm(g, f->block, f->scale, out_dt, st) != hipSuccess) return NVFP4_EHIP;
@@ -322,7 +399,7 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
         // Eq. 6: dW[N, K] = Q_SR(dY^T)[N, M] * Q_SR(X^T)[K, M]^T
         QuantPlan qa{dY, in_dt, M, N, N, 0, NVFP4_SR, seed + 1, dytc, dyts, reinterpret_cast<const float *>(amax + 0), ts + 2, gm};
         QuantPlan qb{X, in_dt, M, K, K, 0, NVFP4_SR, seed + 2, xtc, xts, gsrc_x, ts + 3, gm_xw};
-        if (run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
+        if (!dual && run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
         if (run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
         GemmArgs g{N, K, M, dytc, dyts, xtc, xts, ts + 2, dW, K};
         if (launch_gemm(g, f->block, f->scale, out_dt, st) != hipSuccess) return NVFP4_EHIP;

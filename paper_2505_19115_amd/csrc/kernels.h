@@ -20,6 +20,16 @@ struct QuantArgs {
     uint64_t seed;
 };
 
+// Both orientations of one tensor: c describes the tensor and the column-blocked outputs
+// (codes [cols, rows/2], scales [cols, rows/B], seed); the row-blocked outputs come beside it.
+struct DualArgs {
+    QuantArgs c;
+    uint8_t *codes_r;   // [rows, cols/2]
+    uint8_t *scales_r;  // [rows, cols/B]
+    uint64_t seed_r;
+    float *g_out2;      // optional second destination of the tensor scale (fused kernel only)
+};
+
 struct GemmArgs {
     int64_t M, N, K;
     const uint8_t *A_codes, *A_scales, *B_codes, *B_scales;
@@ -53,6 +63,11 @@ hipError_t launch_tensor_amax(const void *x, int dt, int64_t rows, int64_t cols,
                               uint32_t *amax_bits, uint32_t *partials, float *g_out, hipStream_t st);
 hipError_t launch_quantize(const QuantArgs &P, int dt, int axis, int rounding, int block, int sf,
                            bool hw_convert, hipStream_t st);
+// Row-blocked and column-blocked quantization of one tensor; one fused kernel when
+// quantize_dual_fused() holds, else the two single-orientation kernels.
+bool quantize_dual_fused(int dt, int64_t rows, int64_t cols, int64_t ld, int block, bool hw_convert);
+hipError_t launch_quantize_dual(const DualArgs &D, int dt, int rounding, int block, int sf, bool hw_convert,
+                                hipStream_t st);
 hipError_t launch_gemm(const GemmArgs &P, int block, int sf, int out_dt, hipStream_t st);
 hipError_t launch_gemm_mxfp4(const GemmArgs &P, int out_dt, hipStream_t st);  // block 32, E8M0
 // Noise statistics: per-workgroup partial pairs (quant_noise_partials() of them), folded into sums[2].

@@ -404,6 +404,10 @@ __device__ __forceinline__ void col_sr_hw(const QuantArgs &P, Chunk<DT> (&v)[16]
     }
 }
 
+template <int DT, int B, int SF, int RND, bool HW, bool ALIGNED, int LV>
+__device__ __forceinline__ void cols_tile(const QuantArgs &P, Chunk<DT> (&v)[16], float g, float k, int64_t row0,
+                                          int64_t col0, int ncol, int lv);
+
 // ALIGNED: cols is a multiple of 8, so the 8 columns of a lane share one random draw per row.
 template <int DT, int B, int SF, int RND, bool HW, bool ALIGNED, int LV = 8>
 __global__ __launch_bounds__(256) void quantize_cols_kernel(QuantArgs P)
@@ -435,7 +439,20 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(QuantArgs P)
         else
             v[r].zero();
     }
+    cols_tile<DT, B, SF, RND, HW, ALIGNED, LV>(P, v, g, k, row0, col0, ncol, lv);
+}
 
+// The column-blocked quantization of one lane tile (16 rows x 8 columns in v): block maxima,
+// scale bytes, codes, and the stores into the transposed outputs.
+template <int DT, int B, int SF, int RND, bool HW, bool ALIGNED, int LV>
+__device__ __forceinline__ void cols_tile(const QuantArgs &P, Chunk<DT> (&v)[16], float g, float k, int64_t row0,
+                                          int64_t col0, int ncol, int lv)
+{
+    using G = ColGeom<DT, LV>;
+    constexpr int RPL = G::RPL;
+    constexpr int BL = B < RPL ? B : RPL;
+    constexpr int NB = RPL / BL;
+    constexpr int LPB = B / BL;
     const int64_t rows_half = P.rows >> 1;
     const int64_t nblk = P.rows / B;
 
@@ -528,6 +545,132 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(QuantArgs P)
                 for (int nb = 0; nb < NB; ++nb)
                     if (row0 + nb * BL < P.rows)
                         P.scales[col * nblk + (row0 + nb * BL) / B] = (uint8_t)sbytes[c][nb];
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ both orientations in one pass
+
+// Eqs. 5-6 use the output gradient twice, blocked along N for dX and along M for dW; Eqs. 4-5
+// do the same with W.  This kernel reads the tensor once and writes both quantizations, each
+// identical to what the single-orientation kernels produce (same scale rule, same convert, same
+// draws: seed_r for the row-blocked output, P.seed for the column-blocked one).
+// Geometry of the columns kernel (lane = 16 rows x 8 columns, workgroup = 128 rows x 256
+// columns).  A row block of B = 16 or 32 columns spans 2 or 4 lanes that are 8 apart in the wave
+// (DPP row rotate / swizzle for the maximum).  The row-blocked codes of the tile (128 rows x 128
+// bytes) and its scale bytes are staged in LDS and written out 16 bytes per lane, so both outputs
+// leave in full lines although the lanes hold the data column-wise.
+// Host guarantees: rows % B == 0, cols % B == 0 (so a lane's 16 x 8 tile is entirely inside or
+// outside the tensor), 16-byte aligned rows of x.
+template <int DT, int B, int SF, int RND>
+__global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
+{
+    using G = ColGeom<DT, 8>;
+    static_assert(B == 16 || B == 32, "row blocks must fit the 8 column groups of a wave");
+    constexpr int LPBR = B / 8;                  // lanes sharing one row block
+    constexpr int ROW_BYTES = G::WG_COLS / 2;    // 128 code bytes per tile row
+    constexpr int ROW_SC = G::WG_COLS / B;       // scale bytes per tile row
+    __shared__ __align__(16) uint32_t lds_codes[G::WG_ROWS * ROW_BYTES / 4];
+    __shared__ __align__(16) uint8_t lds_scales[G::WG_ROWS * 16];
+
+    const QuantArgs &P = D.c;
+    const float g = resolve_g(P);
+    const float k = 1.0f / (6.0f * g);
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+        *P.g_out = g;
+        if (D.g_out2) *D.g_out2 = g;
+    }
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lv = lane % G::LANES_V, lh = lane / G::LANES_V;
+    const int64_t wrow0 = (int64_t)blockIdx.y * G::WG_ROWS, wcol0 = (int64_t)blockIdx.x * G::WG_COLS;
+    const int64_t row0 = wrow0 + lv * 16;
+    const int64_t col0 = wcol0 + wave * G::WAVE_COLS + lh * 8;
+    const bool inside = row0 < P.rows && col0 < P.cols;
+
+    Chunk<DT> v[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        if (inside)
+            v[r].template load<true>(P.x, (row0 + r) * P.ld + col0);
+        else
+            v[r].zero();
+    }
+
+    // row-blocked side: one block scale and 8 codes per row of the lane tile
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        float a = chunk_amax(v[r]);
+        a = dpp_max<0x128>(a);  // row_ror:8 : lane ^ 8, the neighbouring column group
+        if (LPBR == 4) {
+            const uint32_t o = (uint32_t)__builtin_amdgcn_ds_swizzle((int)f2u(a), 0x401F);  // lane ^ 16
+            a = u2f(umax(f2u(a), o));
+        }
+        float q;
+        const uint32_t sbyte = block_scale<SF>(a, g, k, &q);
+        uint32_t packed = 0;
+        if (RND == NVFP4_RTN) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                packed |= quant_pair_hw(v[r].get(2 * t), v[r].get(2 * t + 1), q) << (8 * t);
+        } else {
+            const uint64_t e0 = (uint64_t)(row0 + r) * (uint64_t)P.cols + (uint64_t)col0;
+            const u32x4 d = sr_draw(D.seed_r, e0 >> 3);
+            uint32_t lo = 0, hi = 0;
+#define NVFP4_SR_PAIR(t)                                                                    \
+    lo = sr_elem_hw<0, t>(lo, v[r].get(2 * t) * q, sr_bits_of(d, 2 * t));                   \
+    hi = sr_elem_hw<1, t>(hi, v[r].get(2 * t + 1) * q, sr_bits_of(d, 2 * t + 1));
+            NVFP4_SR_PAIR(0) NVFP4_SR_PAIR(1) NVFP4_SR_PAIR(2) NVFP4_SR_PAIR(3)
+#undef NVFP4_SR_PAIR
+            packed = lo | hi;
+        }
+        // tile row R = 16 lv + r holds 32 dwords; dword w is stored at w ^ (4 lv): the 16-byte
+        // chunk c of the row sits at chunk c ^ lv, which spreads the 8 rows a wave writes at a
+        // time over the banks
+        const int R = lv * 16 + r;
+        lds_codes[R * (ROW_BYTES / 4) + ((wave * 8 + lh) ^ (lv << 2))] = packed;
+        if ((lh & (LPBR - 1)) == 0) lds_scales[R * 16 + (wave * G::WAVE_COLS + lh * 8) / B] = (uint8_t)sbyte;
+    }
+
+    // (unpack the raw registers again below instead of keeping 128 floats alive)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) v[r].launder();
+
+    // column-blocked side: exactly the columns kernel's tile
+    cols_tile<DT, B, SF, RND, true, true, 8>(P, v, g, k, row0, col0, inside ? 8 : 0, lv);
+
+    __syncthreads();
+    const int64_t cpr = P.cols >> 1;
+    const bool wide = (cpr & 15) == 0;  // rows of the code matrix are 16-byte aligned
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int id = threadIdx.x + 256 * i, R = id >> 3, c = id & 7;
+        const int64_t row = wrow0 + R, col = wcol0 + c * 32;
+        if (row < P.rows && col < P.cols) {
+            const uint4 w = *reinterpret_cast<const uint4 *>(&lds_codes[R * (ROW_BYTES / 4) + ((c ^ (R >> 4)) << 2)]);
+            uint8_t *dst = D.codes_r + row * cpr + (col >> 1);
+            if (col + 32 <= P.cols && wide) {
+                const u32x4_t o = {w.x, w.y, w.z, w.w};
+                __builtin_nontemporal_store(o, reinterpret_cast<u32x4_t *>(dst));
+            } else {
+                store8_stream(dst, w.x, w.y);
+                if (col + 32 <= P.cols) store8_stream(dst + 8, w.z, w.w);
+            }
+        }
+    }
+    if (threadIdx.x < G::WG_ROWS) {
+        const int R = threadIdx.x;
+        const int64_t row = wrow0 + R, nsc = P.cols / B, s0 = wcol0 / B;
+        if (row < P.rows && s0 < nsc) {
+            uint8_t *dst = D.scales_r + row * nsc + s0;
+            const uint32_t *src = reinterpret_cast<const uint32_t *>(&lds_scales[R * 16]);
+            if (s0 + ROW_SC <= nsc && nsc % ROW_SC == 0) {
+                store8_stream(dst, src[0], src[1]);
+                if (ROW_SC == 16) store8_stream(dst + 8, src[2], src[3]);
+            } else {
+                const int n = (int)(nsc - s0 < ROW_SC ? nsc - s0 : ROW_SC);
+                for (int j = 0; j < n; ++j) dst[j] = lds_scales[R * 16 + j];
             }
         }
     }
@@ -635,6 +778,53 @@ hipError_t launch_quantize(const QuantArgs &P, int dt, int axis, int rounding, i
     else
         launch_q_fmt<NVFP4_F32>(P, axis, rounding, block, sf, hw_convert, st);
     return launch_status();
+}
+
+template <int DT, int B, int SF>
+static void launch_dual_rnd(const DualArgs &D, int rounding, hipStream_t st)
+{
+    using G = ColGeom<DT>;
+    dim3 grid((unsigned)((D.c.cols + G::WG_COLS - 1) / G::WG_COLS), (unsigned)((D.c.rows + G::WG_ROWS - 1) / G::WG_ROWS));
+    if (rounding == NVFP4_SR)
+        hipLaunchKernelGGL((quantize_dual_kernel<DT, B, SF, NVFP4_SR>), grid, dim3(256), 0, st, D);
+    else
+        hipLaunchKernelGGL((quantize_dual_kernel<DT, B, SF, NVFP4_RTN>), grid, dim3(256), 0, st, D);
+}
+
+template <int DT>
+static void launch_dual_fmt(const DualArgs &D, int rounding, int block, int sf, hipStream_t st)
+{
+    if (block == 16 && sf == NVFP4_SCALE_E4M3) launch_dual_rnd<DT, 16, NVFP4_SCALE_E4M3>(D, rounding, st);
+    else if (block == 16) launch_dual_rnd<DT, 16, NVFP4_SCALE_E8M0>(D, rounding, st);
+    else if (sf == NVFP4_SCALE_E4M3) launch_dual_rnd<DT, 32, NVFP4_SCALE_E4M3>(D, rounding, st);
+    else launch_dual_rnd<DT, 32, NVFP4_SCALE_E8M0>(D, rounding, st);
+}
+
+bool quantize_dual_fused(int dt, int64_t rows, int64_t cols, int64_t ld, int block, bool hw_convert)
+{
+    const int64_t esz = dt == NVFP4_BF16 ? 2 : 4;
+    return hw_convert && (block == 16 || block == 32) && rows % block == 0 && cols % block == 0 &&
+           (ld * esz) % 16 == 0 && cols < (int64_t(1) << 31) && rows < (int64_t(1) << 31);
+}
+
+hipError_t launch_quantize_dual(const DualArgs &D, int dt, int rounding, int block, int sf, bool hw_convert,
+                                hipStream_t st)
+{
+    if (quantize_dual_fused(dt, D.c.rows, D.c.cols, D.c.ld, block, hw_convert)) {
+        if (dt == NVFP4_BF16)
+            launch_dual_fmt<NVFP4_BF16>(D, rounding, block, sf, st);
+        else
+            launch_dual_fmt<NVFP4_F32>(D, rounding, block, sf, st);
+        return launch_status();
+    }
+    // other block sizes and ragged shapes: the two single-orientation kernels
+    QuantArgs r = D.c;
+    r.codes = D.codes_r;
+    r.scales = D.scales_r;
+    r.seed = D.seed_r;
+    hipError_t e = launch_quantize(r, dt, 1, rounding, block, sf, hw_convert, st);
+    if (e != hipSuccess) return e;
+    return launch_quantize(D.c, dt, 0, rounding, block, sf, hw_convert, st);
 }
 
 }  // namespace nvfp4

@@ -76,6 +76,26 @@ def test_quantize_argument_errors():
     assert _quant(ws_bytes=2) == nv.EWORKSPACE
 
 
+def test_quantize_dual_argument_errors():
+    def dual(x=FAKE, dt=nv.BF16, rows=64, cols=64, ld=64, rnd=nv.SR, fmt=nv.NVFP4, cr=FAKE, sr=FAKE, cc=FAKE,
+             sc=FAKE, ts=FAKE, flags=0, ws=FAKE, ws_bytes=1 << 20):
+        f = fmt.c()
+        return nv.lib.nvfp4_quantize_dual(x, dt, rows, cols, ld, rnd, 1, 2, C.byref(f), cr, sr, cc, sc, ts, flags,
+                                          ws, ws_bytes, None)
+    assert dual(x=None) == nv.EINVAL
+    assert dual(cc=None) == nv.EINVAL
+    assert dual(sr=None) == nv.EINVAL
+    assert dual(rnd=2) == nv.EINVAL
+    assert dual(flags=2) == nv.EINVAL
+    assert dual(rows=72) == nv.ESHAPE                     # both axes are blocked
+    assert dual(cols=72, ld=72) == nv.ESHAPE
+    assert dual(rows=96, cols=96, ld=96, fmt=nv.Format(64, 0, 1)) == nv.ESHAPE
+    assert dual(cr=FAKE + 4) == nv.EALIGN
+    assert dual(ws=None) == nv.EWORKSPACE
+    assert dual(fmt=nv.Format(16, nv.SCALE_E8M0, 1)) == nv.EUNSUPPORTED
+    assert dual(rows=0, cr=None, sr=None, cc=None, sc=None, ws=None, fmt=nv.MXFP4) == nv.OK  # empty: nothing launched
+
+
 def test_gemm_and_linear_argument_errors():
     f = nv.NVFP4.c()
     g = lambda **k: nv.lib.nvfp4_gemm(k.get("M", 64), k.get("N", 64), k.get("K", 64), C.byref(k.get("f", f)),
