@@ -102,14 +102,16 @@ def main() -> int:
         Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
         dX = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
         dW = torch.empty((N, K), dtype=torch.bfloat16, device=dev)
-        data.append((name, N, K, X, W, dY, wf, wb, Y, dX, dW, torch.empty(2, dtype=torch.float32, device=dev)))
+        saved = torch.empty(nv.linear_saved_bytes(M, N, K), dtype=torch.uint8, device=dev)
+        data.append((name, N, K, X, W, dY, wf, wb, Y, dX, dW, saved))
     flop_per_step = sum(3 * 2 * M * N * K for _, N, K in layers)
 
     def step(s):
-        for name, N, K, X, W, dY, wf, wb, Y, dX, dW, sc in data:
-            # the forward call hands the per-tensor scales of X and W to the backward call
-            nv.linear_fwd(X, W, workspace=wf, out=Y, scales_out=sc)
-            nv.linear_bwd(dY, X, W, seed=1000 + 3 * s, workspace=wb, out=(dX, dW), xw_scales=sc)
+        for name, N, K, X, W, dY, wf, wb, Y, dX, dW, saved in data:
+            # the forward call's passes over X and W also leave Q_SR(X^T), Q_RtN(W^T) and the
+            # per-tensor scales for the backward call, which then reads only dY (once)
+            nv.linear_fwd(X, W, workspace=wf, out=Y, saved=saved, bwd_seed=1000 + 3 * s)
+            nv.linear_bwd(dY, None, None, seed=1000 + 3 * s, workspace=wb, out=(dX, dW), saved=saved, K=K)
 
     for s in range(args.warmup):
         step(s)
@@ -124,9 +126,9 @@ def main() -> int:
 
     # the same step in MXFP4 (block 32, E8M0; the GEMMs then run on the FP4 matrix instruction)
     def step_mx(s):
-        for name, N, K, X, W, dY, wf, wb, Y, dX, dW, sc in data:
-            nv.linear_fwd(X, W, nv.MXFP4, workspace=wf, out=Y)
-            nv.linear_bwd(dY, X, W, 2000 + 3 * s, nv.MXFP4, workspace=wb, out=(dX, dW))
+        for name, N, K, X, W, dY, wf, wb, Y, dX, dW, saved in data:
+            nv.linear_fwd(X, W, nv.MXFP4, workspace=wf, out=Y, saved=saved, bwd_seed=2000 + 3 * s)
+            nv.linear_bwd(dY, None, None, 2000 + 3 * s, nv.MXFP4, workspace=wb, out=(dX, dW), saved=saved, K=K)
 
     mx_step_ms = event_time_ms(step_mx, max(args.steps // 2, 3), torch)
     mx_step = {"ms_per_step": round(mx_step_ms, 3), "TFLOP/s": round(flop_per_step / (mx_step_ms * 1e-3) / 1e12, 1),
@@ -186,10 +188,11 @@ def main() -> int:
         f = fmt.c()
         wf = torch.empty(nv.lib.nvfp4_linear_fwd_workspace_bytes(sM, sN, sK, C.byref(f)), dtype=torch.uint8, device=dev)
         wb = torch.empty(nv.lib.nvfp4_linear_bwd_workspace_bytes(sM, sN, sK, C.byref(f)), dtype=torch.uint8, device=dev)
+        ssaved = torch.empty(nv.linear_saved_bytes(sM, sN, sK, fmt), dtype=torch.uint8, device=dev)
 
         def fwd_bwd(i):
-            nv.linear_fwd(sX, sW, fmt, workspace=wf, out=sY)
-            nv.linear_bwd(sdY, sX, sW, 7000 + 3 * i, fmt, workspace=wb, out=(sdX, sdW))
+            nv.linear_fwd(sX, sW, fmt, workspace=wf, out=sY, saved=ssaved, bwd_seed=7000 + 3 * i)
+            nv.linear_bwd(sdY, None, None, 7000 + 3 * i, fmt, workspace=wb, out=(sdX, sdW), saved=ssaved, K=sK)
 
         ms = event_time_ms(fwd_bwd, 4, torch)
         nx = nv.quant_noise(sX, nv.quantize(sX, 1, nv.RTN, 0, fmt), 1, fmt).cpu().numpy()
@@ -256,7 +259,7 @@ def main() -> int:
         "dtype": "e2m1 codes x e4m3 scales, expanded exactly to f16 for MFMA, f32 accumulate",
         "data": "synthetic",
         "config": {"workload": "Llama2-7B SwiGLU MLP linears fwd+bwd (gate, up, down), tokens=4096: "
-                               "9 GEMMs + 18 quantize calls + 9 tensor-maximum passes per step (X and W scales handed from forward to backward), bf16 in",
+                               "9 GEMMs + 9 dual-orientation quantize passes (X, W in the forward call, which saves Q_SR(X^T), Q_RtN(W^T) and the scales for the backward call; dY in the backward call) + 9 tensor-maximum passes per step, bf16 in",
                    "M": M, "layers": [[n, N, K] for n, N, K in layers], "format": "NVFP4 (block 16, E4M3, tensor scale)",
                    "rounding": "fwd RtN; bwd/update SR (Philox4x32-10)"},
         "frac_of_fp4_peak": round(tflops / PEAK_FP4_TFLOPS, 4),

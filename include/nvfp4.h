@@ -72,6 +72,8 @@ size_t nvfp4_scales_bytes(int64_t rows, int64_t cols, int axis, const nvfp4_form
 size_t nvfp4_quantize_workspace_bytes(int64_t rows, int64_t cols);
 size_t nvfp4_linear_fwd_workspace_bytes(int64_t M, int64_t N, int64_t K, const nvfp4_format *f);
 size_t nvfp4_linear_bwd_workspace_bytes(int64_t M, int64_t N, int64_t K, const nvfp4_format *f);
+/* Size of the buffer through which nvfp4_linear_fwd hands Q(X^T), Q(W^T) and the tensor scales to nvfp4_linear_bwd. */
+size_t nvfp4_linear_saved_bytes(int64_t M, int64_t N, int64_t K, const nvfp4_format *f);
 
 /*
  * Per-tensor scale g (not in the paper; it fixes only the element and block
@@ -125,16 +127,18 @@ nvfp4_status nvfp4_quantize(const void *x, nvfp4_dtype dt, int64_t rows, int64_t
  * Both orientations of one tensor in one pass over it: Eqs. 5-6 use the output
  * gradient blocked along N (for dX) and along M (for dW), Eqs. 4-5 use W blocked
  * along K and along N.  The results are exactly those of
- *   nvfp4_quantize(x, ..., axis 1, rounding, seed_rows, ...) -> codes_rows [rows, cols/2], scales_rows [rows, cols/block]
- *   nvfp4_quantize(x, ..., axis 0, rounding, seed_cols, ...) -> codes_cols [cols, rows/2], scales_cols [cols, rows/block]
+ *   nvfp4_quantize(x, ..., axis 1, rounding_rows, seed_rows, ...) -> codes_rows [rows, cols/2], scales_rows [rows, cols/block]
+ *   nvfp4_quantize(x, ..., axis 0, rounding_cols, seed_cols, ...) -> codes_cols [cols, rows/2], scales_cols [cols, rows/block]
  * with one shared per-tensor scale (same rule, flags and workspace as
  * nvfp4_quantize).  rows and cols must both be multiples of the block size.
  * Blocks of 16 and 32 with 16-byte aligned rows of x run as one fused kernel
- * (x is read once); other cases run the two single-orientation kernels.
+ * (x is read once), except SR rows with RtN columns; other cases run the two
+ * single-orientation kernels.
  * All output pointers device memory, 16-byte aligned, owned by the caller.
  */
 nvfp4_status nvfp4_quantize_dual(const void *x, nvfp4_dtype dt, int64_t rows, int64_t cols, int64_t ld,
-                                 nvfp4_rounding rounding, uint64_t seed_rows, uint64_t seed_cols,
+                                 nvfp4_rounding rounding_rows, uint64_t seed_rows,
+                                 nvfp4_rounding rounding_cols, uint64_t seed_cols,
                                  const nvfp4_format *f, uint8_t *codes_rows, uint8_t *scales_rows,
                                  uint8_t *codes_cols, uint8_t *scales_cols, float *tensor_scale,
                                  uint32_t flags, void *workspace, size_t workspace_bytes, void *stream);
@@ -163,11 +167,19 @@ nvfp4_status nvfp4_gemm(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
  * xw_scales_out: NULL, or device fp32[2] that receives the per-tensor scales
  * {gX, gW} this call derived from max|X| and max|W| (1, 1 for a format without
  * tensor scale), to be handed to nvfp4_linear_bwd for the same X and W.
+ * saved: NULL, or device memory of >= nvfp4_linear_saved_bytes(M, N, K, f)
+ * bytes, 256-byte aligned, owned by the caller and kept until the backward call:
+ * the passes that quantize X and W for Eq. 4 then also write what Eqs. 5-6 need
+ * of them -- Q_SR(X^T) (blocks along M, SR stream bwd_seed + 2), Q_RtN(W^T)
+ * (blocks along N) and {gX, gW} -- so that nvfp4_linear_bwd, given the same
+ * `saved` and seed == bwd_seed, reads neither X nor W.  Requires M and N to be
+ * multiples of the block size and of 32 (NVFP4_ESHAPE otherwise).  Y is the
+ * same with and without `saved`.  bwd_seed is ignored when saved is NULL.
  */
 nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, int64_t N,
                               int64_t K, nvfp4_dtype in_dt, nvfp4_dtype out_dt,
                               const nvfp4_format *f, void *workspace, size_t workspace_bytes,
-                              void *stream, float *xw_scales_out);
+                              void *stream, float *xw_scales_out, void *saved, uint64_t bwd_seed);
 
 /*
  * Backward and update GEMMs, Eqs. 5-6, for upstream gradient dY[M, N]:
@@ -178,12 +190,16 @@ nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, 
  * them for these X and W: the two tensor-maximum passes over X and W are then
  * skipped (the per-tensor scale is a function of the tensor alone, so the
  * results are identical).  Ignored for a format without tensor scale.
+ * saved: NULL, or what nvfp4_linear_fwd wrote for the same M, N, K, format and
+ * bwd_seed == seed: X, W and xw_scales are then not read (they may be NULL) and
+ * the results are identical to those of the call without `saved`.
+ * With both dX and dW requested, dY is read once for its two quantizations.
  */
 nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void *dX, void *dW,
                               int64_t M, int64_t N, int64_t K, nvfp4_dtype in_dt,
                               nvfp4_dtype out_dt, const nvfp4_format *f, uint64_t seed,
                               void *workspace, size_t workspace_bytes, void *stream,
-                              const float *xw_scales);
+                              const float *xw_scales, const void *saved);
 
 /*
  * Quantization-noise statistics of a quantized tensor against its source

@@ -72,13 +72,15 @@ def _load() -> C.CDLL:
     L.nvfp4_quantize.restype = ci
     L.nvfp4_quantize.argtypes = [vp, ci, i64, i64, i64, ci, ci, u64, fp, vp, vp, vp, u32, vp, sz, vp]
     L.nvfp4_quantize_dual.restype = ci
-    L.nvfp4_quantize_dual.argtypes = [vp, ci, i64, i64, i64, ci, u64, u64, fp, vp, vp, vp, vp, vp, u32, vp, sz, vp]
+    L.nvfp4_quantize_dual.argtypes = [vp, ci, i64, i64, i64, ci, u64, ci, u64, fp, vp, vp, vp, vp, vp, u32, vp, sz, vp]
     L.nvfp4_gemm.restype = ci
     L.nvfp4_gemm.argtypes = [i64, i64, i64, fp, vp, vp, vp, vp, vp, vp, ci, i64, vp]
     L.nvfp4_linear_fwd.restype = ci
-    L.nvfp4_linear_fwd.argtypes = [vp, vp, vp, i64, i64, i64, ci, ci, fp, vp, sz, vp, vp]
+    L.nvfp4_linear_fwd.argtypes = [vp, vp, vp, i64, i64, i64, ci, ci, fp, vp, sz, vp, vp, vp, u64]
     L.nvfp4_linear_bwd.restype = ci
-    L.nvfp4_linear_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, fp, u64, vp, sz, vp, vp]
+    L.nvfp4_linear_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, fp, u64, vp, sz, vp, vp, vp]
+    L.nvfp4_linear_saved_bytes.restype = sz
+    L.nvfp4_linear_saved_bytes.argtypes = [i64, i64, i64, fp]
     # host probes
     L.nvfp4_host_e4m3_encode.restype = C.c_uint8
     L.nvfp4_host_e4m3_encode.argtypes = [C.c_float]
@@ -115,7 +117,7 @@ lib = _load()
 EXPORTS = (
     "nvfp4_status_string", "nvfp4_codes_bytes", "nvfp4_scales_bytes",
     "nvfp4_quantize_workspace_bytes", "nvfp4_linear_fwd_workspace_bytes",
-    "nvfp4_linear_bwd_workspace_bytes", "nvfp4_tensor_scale", "nvfp4_quantize", "nvfp4_quantize_dual", "nvfp4_gemm",
+    "nvfp4_linear_bwd_workspace_bytes", "nvfp4_linear_saved_bytes", "nvfp4_tensor_scale", "nvfp4_quantize", "nvfp4_quantize_dual", "nvfp4_gemm",
     "nvfp4_linear_fwd", "nvfp4_linear_bwd", "nvfp4_host_e4m3_encode", "nvfp4_host_e4m3_decode",
     "nvfp4_host_round_rtn", "nvfp4_host_round_sr", "nvfp4_host_philox4x32_10",
     "nvfp4_host_sr_bits", "nvfp4_host_e8m0_encode", "nvfp4_host_e4m3_encode_n",
@@ -191,8 +193,8 @@ def quantize(x: torch.Tensor, axis: int = 1, rounding: int = RTN, seed: int = 0,
     return codes, scales, g
 
 
-def quantize_dual(x: torch.Tensor, rounding: int = RTN, seed_rows: int = 0, seed_cols: int = 0,
-                  fmt: Format = NVFP4, tensor_scale: torch.Tensor | None = None, out=None):
+def quantize_dual(x: torch.Tensor, rounding_rows: int = RTN, seed_rows: int = 0, rounding_cols: int = RTN,
+                  seed_cols: int = 0, fmt: Format = NVFP4, tensor_scale: torch.Tensor | None = None, out=None):
     """nvfp4_quantize_dual -> ((codes [rows, cols/2], scales [rows, cols/block], g),
     (codes [cols, rows/2], scales [cols, rows/block], g)): both orientations, one shared g.
 
@@ -215,7 +217,7 @@ def quantize_dual(x: torch.Tensor, rounding: int = RTN, seed_rows: int = 0, seed
             g = tensor_scale
     flags = PRESET_TSCALE if tensor_scale is not None else 0
     ws = torch.empty(lib.nvfp4_quantize_workspace_bytes(rows, cols), dtype=torch.uint8, device=x.device)
-    _check(lib.nvfp4_quantize_dual(x.data_ptr(), _dtype_tag(x), rows, cols, ld, rounding, seed_rows, seed_cols,
+    _check(lib.nvfp4_quantize_dual(x.data_ptr(), _dtype_tag(x), rows, cols, ld, rounding_rows, seed_rows, rounding_cols, seed_cols,
                                    C.byref(f), cr.data_ptr(), sr.data_ptr(), cc.data_ptr(), sc.data_ptr(),
                                    g.data_ptr(), flags, ws.data_ptr(), ws.numel(), _stream()), "nvfp4_quantize_dual")
     return (cr, sr, g), (cc, sc, g)
@@ -238,9 +240,12 @@ def gemm(A, B, fmt: Format = NVFP4, out_dtype: torch.dtype = torch.float32, out=
 
 def linear_fwd(X: torch.Tensor, W: torch.Tensor, fmt: Format = NVFP4,
                out_dtype: torch.dtype = torch.float32, workspace: torch.Tensor | None = None,
-               out: torch.Tensor | None = None, scales_out: torch.Tensor | None = None) -> torch.Tensor:
+               out: torch.Tensor | None = None, scales_out: torch.Tensor | None = None,
+               saved: torch.Tensor | None = None, bwd_seed: int = 0) -> torch.Tensor:
     """nvfp4_linear_fwd (Eq. 4): Y[M,N] = Q_RtN(X[M,K]) Q_RtN(W[N,K])^T.
-    scales_out: device fp32[2] that receives {gX, gW} for linear_bwd(..., xw_scales=...)."""
+    scales_out: device fp32[2] that receives {gX, gW} for linear_bwd(..., xw_scales=...).
+    saved: device u8 buffer of linear_saved_bytes(M, N, K, fmt) that receives Q_SR(X^T), Q_RtN(W^T) and the
+    scales for linear_bwd(..., seed=bwd_seed, saved=saved)."""
     _require_gpu(X, W)
     assert X.is_contiguous() and W.is_contiguous() and X.dtype == W.dtype
     M, K = X.shape
@@ -252,20 +257,24 @@ def linear_fwd(X: torch.Tensor, W: torch.Tensor, fmt: Format = NVFP4,
     Y = torch.empty((M, N), dtype=out_dtype, device=X.device) if out is None else out
     _check(lib.nvfp4_linear_fwd(X.data_ptr(), W.data_ptr(), Y.data_ptr(), M, N, K, _dtype_tag(X),
                                 _dtype_tag(Y), C.byref(f), workspace.data_ptr(), workspace.numel(),
-                                _stream(), None if scales_out is None else scales_out.data_ptr()),
+                                _stream(), None if scales_out is None else scales_out.data_ptr(),
+                                None if saved is None else saved.data_ptr(), bwd_seed),
            "nvfp4_linear_fwd")
     return Y
 
 
 def linear_bwd(dY: torch.Tensor, X: torch.Tensor, W: torch.Tensor, seed: int, fmt: Format = NVFP4,
                out_dtype: torch.dtype = torch.float32, workspace: torch.Tensor | None = None,
-               out=None, xw_scales: torch.Tensor | None = None):
+               out=None, xw_scales: torch.Tensor | None = None, saved: torch.Tensor | None = None,
+               K: int | None = None):
     """nvfp4_linear_bwd (Eqs. 5-6) -> (dX [M,K], dW [N,K]).
-    xw_scales: device fp32[2] = {gX, gW} from linear_fwd(..., scales_out=...) for the same X and W."""
-    _require_gpu(dY, X, W)
-    assert dY.is_contiguous() and X.is_contiguous() and W.is_contiguous()
+    xw_scales: device fp32[2] = {gX, gW} from linear_fwd(..., scales_out=...) for the same X and W.
+    saved: what linear_fwd(..., saved=..., bwd_seed=seed) wrote; X and W may then be None (pass K)."""
+    _require_gpu(dY, *[t for t in (X, W) if t is not None])
+    assert dY.is_contiguous() and (X is None or X.is_contiguous()) and (W is None or W.is_contiguous())
+    assert saved is not None or (X is not None and W is not None)
     M, N = dY.shape
-    K = X.shape[1]
+    K = K if K is not None else (X.shape[1] if X is not None else W.shape[1])
     f = fmt.c()
     if workspace is None:
         workspace = torch.empty(lib.nvfp4_linear_bwd_workspace_bytes(M, N, K, C.byref(f)),
@@ -275,12 +284,19 @@ def linear_bwd(dY: torch.Tensor, X: torch.Tensor, W: torch.Tensor, seed: int, fm
         dW = torch.empty((N, K), dtype=out_dtype, device=dY.device)
     else:
         dX, dW = out
-    _check(lib.nvfp4_linear_bwd(dY.data_ptr(), X.data_ptr(), W.data_ptr(), dX.data_ptr(),
+    _check(lib.nvfp4_linear_bwd(dY.data_ptr(), None if X is None else X.data_ptr(),
+                                None if W is None else W.data_ptr(), dX.data_ptr(),
                                 dW.data_ptr(), M, N, K, _dtype_tag(dY), _dtype_tag(dX), C.byref(f),
                                 seed, workspace.data_ptr(), workspace.numel(), _stream(),
-                                None if xw_scales is None else xw_scales.data_ptr()),
+                                None if xw_scales is None else xw_scales.data_ptr(),
+                                None if saved is None else saved.data_ptr()),
            "nvfp4_linear_bwd")
     return dX, dW
+
+
+def linear_saved_bytes(M: int, N: int, K: int, fmt: Format = NVFP4) -> int:
+    f = fmt.c()
+    return lib.nvfp4_linear_saved_bytes(M, N, K, C.byref(f))
 
 
 MFMA_F16, MFMA_FP4 = 0, 1

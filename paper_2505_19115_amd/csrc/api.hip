@@ -75,6 +75,32 @@ hipError_t run_quantize(const QuantPlan &q, const nvfp4_format *f, hipStream_t s
     return launch_quantize(a, q.dt, q.axis, q.rounding, f->block, f->scale, use_hw_convert(), st);
 }
 
+// What nvfp4_linear_fwd leaves for nvfp4_linear_bwd: {gX, gW}, then the transposed operands.
+struct SavedLayout {
+    float *g;
+    uint8_t *xtc, *xts, *wtc, *wts;
+};
+
+SavedLayout saved_layout(void *saved, int64_t M, int64_t N, int64_t K, int64_t B)
+{
+    uint8_t *p = reinterpret_cast<uint8_t *>(saved);
+    SavedLayout L;
+    L.g = reinterpret_cast<float *>(p);
+    p += WS_HEADER;
+    L.xtc = p; p += align_up((size_t)K * M / 2);
+    L.xts = p; p += align_up((size_t)K * (M / B));
+    L.wtc = p; p += align_up((size_t)K * N / 2);
+    L.wts = p;
+    return L;
+}
+
+__global__ void place_scales_kernel(float *ts, const float *g_xw)
+{
+    // {g_dY, gW, g_dY, gX}: the two pairs the backward GEMMs read
+    if (threadIdx.x == 0) ts[1] = g_xw[1];
+    if (threadIdx.x == 1) ts[3] = g_xw[0];
+}
+
 }  // namespace
 
 extern "C" {
@@ -121,6 +147,14 @@ size_t nvfp4_linear_fwd_workspace_bytes(int64_t M, int64_t N, int64_t K, const n
     const size_t part = partials_bytes(M, K) > partials_bytes(N, K) ? partials_bytes(M, K) : partials_bytes(N, K);
     return WS_HEADER + part + align_up((size_t)M * K / 2) + align_up((size_t)M * (K / f->block)) +
            align_up((size_t)N * K / 2) + align_up((size_t)N * (K / f->block));
+}
+
+size_t nvfp4_linear_saved_bytes(int64_t M, int64_t N, int64_t K, const nvfp4_format *f)
+{
+    if (M <= 0 || N <= 0 || K <= 0 || check_format(f) != NVFP4_OK) return 0;
+    const size_t B = (size_t)f->block;
+    return WS_HEADER + align_up((size_t)K * M / 2) + align_up((size_t)K * (M / B)) +  // X^T blocked along M
+           align_up((size_t)K * N / 2) + align_up((size_t)K * (N / B));               // W^T blocked along N
 }
 
 size_t nvfp4_linear_bwd_workspace_bytes(int64_t M, int64_t N, int64_t K, const nvfp4_format *f)
@@ -198,7 +232,8 @@ nvfp4_status nvfp4_quantize(const void *x, nvfp4_dtype dt, int64_t rows, int64_t
 }
 
 nvfp4_status nvfp4_quantize_dual(const void *x, nvfp4_dtype dt, int64_t rows, int64_t cols, int64_t ld,
-                                 nvfp4_rounding rounding, uint64_t seed_rows, uint64_t seed_cols,
+                                 nvfp4_rounding rounding_rows, uint64_t seed_rows,
+                                 nvfp4_rounding rounding_cols, uint64_t seed_cols,
                                  const nvfp4_format *f, uint8_t *codes_rows, uint8_t *scales_rows,
                                  uint8_t *codes_cols, uint8_t *scales_cols, float *tensor_scale,
                                  uint32_t flags, void *workspace, size_t workspace_bytes, void *stream)
@@ -209,7 +244,8 @@ nvfp4_status nvfp4_quantize_dual(const void *x, nvfp4_dtype dt, int64_t rows, in
     if (s != NVFP4_OK) return s;
     const bool empty = rows == 0 || cols == 0;
     if (!tensor_scale || (!empty && (!codes_rows || !scales_rows || !codes_cols || !scales_cols))) return NVFP4_EINVAL;
-    if (rounding != NVFP4_RTN && rounding != NVFP4_SR) return NVFP4_EINVAL;
+    if (rounding_rows != NVFP4_RTN && rounding_rows != NVFP4_SR) return NVFP4_EINVAL;
+    if (rounding_cols != NVFP4_RTN && rounding_cols != NVFP4_SR) return NVFP4_EINVAL;
     if (flags & ~NVFP4_PRESET_TSCALE) return NVFP4_EINVAL;
     if (rows % f->block != 0 || cols % f->block != 0) return NVFP4_ESHAPE;
     if (!aligned16(codes_rows) || !aligned16(scales_rows) || !aligned16(codes_cols) || !aligned16(scales_cols))
@@ -250,8 +286,9 @@ nvfp4_status nvfp4_quantize_dual(const void *x, nvfp4_dtype dt, int64_t rows, in
         }
     }
     if (empty) return NVFP4_OK;
-    return launch_quantize_dual(d, dt, rounding, f->block, f->scale, use_hw_convert(), st) == hipSuccess ? NVFP4_OK
-                                                                                                        : NVFP4_EHIP;
+    return launch_quantize_dual(d, dt, rounding_rows, rounding_cols, f->block, f->scale, use_hw_convert(), st) == hipSuccess
+               ? NVFP4_OK
+               : NVFP4_EHIP;
 }
 
 nvfp4_status nvfp4_gemm(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
@@ -279,7 +316,7 @@ nvfp4_status nvfp4_gemm(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
 nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, int64_t N,
                               int64_t K, nvfp4_dtype in_dt, nvfp4_dtype out_dt,
                               const nvfp4_format *f, void *workspace, size_t workspace_bytes,
-                              void *stream, float *xw_scales_out)
+                              void *stream, float *xw_scales_out, void *saved, uint64_t bwd_seed)
 {
     nvfp4_status s = check_format(f);
     if (s != NVFP4_OK) return s;
@@ -291,6 +328,12 @@ nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, 
     if (!aligned16(X) || !aligned16(W) || !aligned16(Y)) return NVFP4_EALIGN;
     if (!workspace || workspace_bytes < nvfp4_linear_fwd_workspace_bytes(M, N, K, f)) return NVFP4_EWORKSPACE;
     if ((reinterpret_cast<uintptr_t>(workspace) & (WS_ALIGN - 1)) != 0) return NVFP4_EALIGN;
+    if (saved) {
+        // X^T is blocked along M and W^T along N, and those are the backward GEMMs' contractions
+        if (M % f->block != 0 || M % 32 != 0 || N % f->block != 0 || N % 32 != 0) return NVFP4_ESHAPE;
+        if (M > MAX_CONTRACTION || N > MAX_CONTRACTION) return NVFP4_ESHAPE;
+        if ((reinterpret_cast<uintptr_t>(saved) & (WS_ALIGN - 1)) != 0) return NVFP4_EALIGN;
+    }
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
 
     uint8_t *ws = reinterpret_cast<uint8_t *>(workspace);
@@ -309,10 +352,22 @@ nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, 
         if (launch_tensor_amax(X, in_dt, M, K, K, amax + 0, partials, nullptr, st) != hipSuccess) return NVFP4_EHIP;
         if (launch_tensor_amax(W, in_dt, N, K, K, amax + 1, partials, nullptr, st) != hipSuccess) return NVFP4_EHIP;
     }
-    QuantPlan qx{X, in_dt, M, K, K, 1, NVFP4_RTN, 0, xc, xs, reinterpret_cast<const float *>(amax + 0), ts + 0, gm};
-    QuantPlan qw{W, in_dt, N, K, K, 1, NVFP4_RTN, 0, wc, wsc, reinterpret_cast<const float *>(amax + 1), ts + 1, gm};
-    if (run_quantize(qx, f, st) != hipSuccess) return NVFP4_EHIP;
-    if (run_quantize(qw, f, st) != hipSuccess) return NVFP4_EHIP;
+    if (saved) {
+        // one pass over X and one over W also leave what Eqs. 5-6 need of them: Q_SR(X^T) with
+        // the backward call's third stream, and Q_RtN(W^T)
+        const SavedLayout L = saved_layout(saved, M, N, K, f->block);
+        DualArgs dx{{X, M, K, K, L.xtc, L.xts, reinterpret_cast<const float *>(amax + 0), ts + 0, gm, bwd_seed + 2},
+                    xc, xs, 0, L.g + 0};
+        DualArgs dw{{W, N, K, K, L.wtc, L.wts, reinterpret_cast<const float *>(amax + 1), ts + 1, gm, 0},
+                    wc, wsc, 0, L.g + 1};
+        if (launch_quantize_dual(dx, in_dt, NVFP4_RTN, NVFP4_SR, f->block, f->scale, use_hw_convert(), st) != hipSuccess) return NVFP4_EHIP;
+        if (launch_quantize_dual(dw, in_dt, NVFP4_RTN, NVFP4_RTN, f->block, f->scale, use_hw_convert(), st) != hipSuccess) return NVFP4_EHIP;
+    } else {
+        QuantPlan qx{X, in_dt, M, K, K, 1, NVFP4_RTN, 0, xc, xs, reinterpret_cast<const float *>(amax + 0), ts + 0, gm};
+        QuantPlan qw{W, in_dt, N, K, K, 1, NVFP4_RTN, 0, wc, wsc, reinterpret_cast<const float *>(amax + 1), ts + 1, gm};
+        if (run_quantize(qx, f, st) != hipSuccess) return NVFP4_EHIP;
+        if (run_quantize(qw, f, st) != hipSuccess) return NVFP4_EHIP;
+    }
     GemmArgs g{M, N, K, xc, xs, wc, wsc, ts, Y, N};
     return launch_gemm(g, f->block, f->scale, out_dt, st) == hipSuccess ? NVFP4_OK : NVFP4_EHIP;
 }
@@ -320,17 +375,20 @@ nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, 
 nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void *dX, void *dW,
                               int64_t M, int64_t N, int64_t K, nvfp4_dtype in_dt,
                               nvfp4_dtype out_dt, const nvfp4_format *f, uint64_t seed,
-                              void *workspace, size_t workspace_bytes, void *stream, const float *xw_scales)
+                              void *workspace, size_t workspace_bytes, void *stream, const float *xw_scales,
+                              const void *saved)
 {
     nvfp4_status s = check_format(f);
     if (s != NVFP4_OK) return s;
-    if (!dY || (dX && !W) || (dW && !X)) return NVFP4_EINVAL;
+    if (!dY || (!saved && ((dX && !W) || (dW && !X)))) return NVFP4_EINVAL;
+    if (saved && (reinterpret_cast<uintptr_t>(saved) & (WS_ALIGN - 1)) != 0) return NVFP4_EALIGN;
     if (!valid_dtype(in_dt) || !valid_dtype(out_dt)) return NVFP4_EINVAL;
     if (M <= 0 || N <= 0 || K <= 0) return NVFP4_ESHAPE;
     const int64_t B = f->block;
     // dX contracts over N, dW over M; K is a leading dimension of X and W read down columns
     if (dX && (N % B != 0 || N % 32 != 0 || N > MAX_CONTRACTION)) return NVFP4_ESHAPE;
     if (dW && (M % B != 0 || M % 32 != 0 || M > MAX_CONTRACTION)) return NVFP4_ESHAPE;
+    if (saved && (M % B != 0 || N % B != 0)) return NVFP4_ESHAPE;  // the shapes nvfp4_linear_fwd accepted
     if ((K * (int64_t)elem_size(in_dt)) % 16 != 0 || (N * (int64_t)elem_size(in_dt)) % 16 != 0) return NVFP4_EALIGN;
     if (f->scale == NVFP4_SCALE_E8M0 && f->block != 32) return NVFP4_EUNSUPPORTED;  // E8M0 GEMM: MXFP4 only
     if (!aligned16(dY) || !aligned16(X) || !aligned16(W) || !aligned16(dX) || !aligned16(dW)) return NVFP4_EALIGN;
@@ -354,6 +412,15 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
     uint8_t *dyts = p; p += align_up((size_t)N * (M / B));
     uint8_t *xtc = p; p += align_up((size_t)K * M / 2);
     uint8_t *xts = p;
+    if (saved) {
+        // Q_RtN(W^T) and Q_SR(X^T) as the forward call left them (its bwd_seed must equal seed)
+        const SavedLayout L = saved_layout(const_cast<void *>(saved), M, N, K, B);
+        wtc = L.wtc;
+        wts = L.wts;
+        xtc = L.xtc;
+        xts = L.xts;
+        hipLaunchKernelGGL(place_scales_kernel, dim3(1), dim3(64), 0, st, ts, L.g);
+    }
 
     const int gm = f->tensor_scale ? G_FROM_AMAX : G_NONE;
     // X and W: scales handed over from the forward call (used as given), else from their maxima
@@ -382,25 +449,25 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
         d.scales_r = dys;
         d.seed_r = seed;
         d.g_out2 = ts + 2;
-        if (launch_quantize_dual(d, in_dt, NVFP4_SR, f->block, f->scale, true, st) != hipSuccess) return NVFP4_EHIP;
+        if (launch_quantize_dual(d, in_dt, NVFP4_SR, NVFP4_SR, f->block, f->scale, true, st) != hipSuccess) return NVFP4_EHIP;
     }
     if (dX) {
-        if (f->tensor_scale && !known && launch_tensor_amax(W, in_dt, N, K, K, amax + 1, partials, nullptr, st) != hipSuccess) return NVFP4_EHIP;
+        if (f->tensor_scale && !known && !saved && launch_tensor_amax(W, in_dt, N, K, K, amax + 1, partials, nullptr, st) != hipSuccess) return NVFP4_EHIP;
         // Eq. 5: dX[M, K] = Q_SR(dY)[M, N] * Q_RtN(W^T)[K, N]^T
         QuantPlan qa{dY, in_dt, M, N, N, 1, NVFP4_SR, seed, dyc, dys, reinterpret_cast<const float *>(amax + 0), ts + 0, gm};
         QuantPlan qb{W, in_dt, N, K, K, 0, NVFP4_RTN, 0, wtc, wts, gsrc_w, ts + 1, gm_xw};
         if (!dual && run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
-        if (run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
+        if (!saved && run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
         GemmArgs g{M, K, N, dyc, dys, wtc, wts, ts + 0, dX, K};
         if (launch_gemm(g, f->block, f->scale, out_dt, st) != hipSuccess) return NVFP4_EHIP;
     }
     if (dW) {
-        if (f->tensor_scale && !known && launch_tensor_amax(X, in_dt, M, K, K, amax + 2, partials, nullptr, st) != hipSuccess) return NVFP4_EHIP;
+        if (f->tensor_scale && !known && !saved && launch_tensor_amax(X, in_dt, M, K, K, amax + 2, partials, nullptr, st) != hipSuccess) return NVFP4_EHIP;
         // Eq. 6: dW[N, K] = Q_SR(dY^T)[N, M] * Q_SR(X^T)[K, M]^T
         QuantPlan qa{dY, in_dt, M, N, N, 0, NVFP4_SR, seed + 1, dytc, dyts, reinterpret_cast<const float *>(amax + 0), ts + 2, gm};
         QuantPlan qb{X, in_dt, M, K, K, 0, NVFP4_SR, seed + 2, xtc, xts, gsrc_x, ts + 3, gm_xw};
         if (!dual && run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
-        if (run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
+        if (!saved && run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
         GemmArgs g{N, K, M, dytc, dyts, xtc, xts, ts + 2, dW, K};
         if (launch_gemm(g, f->block, f->scale, out_dt, st) != hipSuccess) return NVFP4_EHIP;
     }

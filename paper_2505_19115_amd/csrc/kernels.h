@@ -27,7 +27,7 @@ struct DualArgs {
     uint8_t *codes_r;   // [rows, cols/2]
     uint8_t *scales_r;  // [rows, cols/B]
     uint64_t seed_r;
-    float *g_out2;      // optional second destination of the tensor scale (fused kernel only)
+    float *g_out2;      // optional second destination of the tensor scale
 };
 
 struct GemmArgs {
@@ -66,8 +66,8 @@ hipError_t launch_quantize(const QuantArgs &P, int dt, int axis, int rounding, i
 // Row-blocked and column-blocked quantization of one tensor; one fused kernel when
 // quantize_dual_fused() holds, else the two single-orientation kernels.
 bool quantize_dual_fused(int dt, int64_t rows, int64_t cols, int64_t ld, int block, bool hw_convert);
-hipError_t launch_quantize_dual(const DualArgs &D, int dt, int rounding, int block, int sf, bool hw_convert,
-                                hipStream_t st);
+hipError_t launch_quantize_dual(const DualArgs &D, int dt, int rnd_rows, int rnd_cols, int block, int sf,
+                                bool hw_convert, hipStream_t st);
 hipError_t launch_gemm(const GemmArgs &P, int block, int sf, int out_dt, hipStream_t st);
 hipError_t launch_gemm_mxfp4(const GemmArgs &P, int out_dt, hipStream_t st);  // block 32, E8M0
 // Noise statistics: per-workgroup partial pairs (quant_noise_partials() of them), folded into sums[2].

@@ -555,7 +555,9 @@ __device__ __forceinline__ void cols_tile(const QuantArgs &P, Chunk<DT> (&v)[16]
 // Eqs. 5-6 use the output gradient twice, blocked along N for dX and along M for dW; Eqs. 4-5
 // do the same with W.  This kernel reads the tensor once and writes both quantizations, each
 // identical to what the single-orientation kernels produce (same scale rule, same convert, same
-// draws: seed_r for the row-blocked output, P.seed for the column-blocked one).
+// draws: seed_r for the row-blocked output, P.seed for the column-blocked one), each with its
+// own rounding mode (X is needed round-to-nearest along K for Eq. 4 and stochastically rounded
+// along M for Eq. 6).
 // Geometry of the columns kernel (lane = 16 rows x 8 columns, workgroup = 128 rows x 256
 // columns).  A row block of B = 16 or 32 columns spans 2 or 4 lanes that are 8 apart in the wave
 // (DPP row rotate / swizzle for the maximum).  The row-blocked codes of the tile (128 rows x 128
@@ -563,7 +565,7 @@ __device__ __forceinline__ void cols_tile(const QuantArgs &P, Chunk<DT> (&v)[16]
 // leave in full lines although the lanes hold the data column-wise.
 // Host guarantees: rows % B == 0, cols % B == 0 (so a lane's 16 x 8 tile is entirely inside or
 // outside the tensor), 16-byte aligned rows of x.
-template <int DT, int B, int SF, int RND>
+template <int DT, int B, int SF, int RND_R, int RND_C>
 __global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
 {
     using G = ColGeom<DT, 8>;
@@ -610,7 +612,7 @@ __global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
         float q;
         const uint32_t sbyte = block_scale<SF>(a, g, k, &q);
         uint32_t packed = 0;
-        if (RND == NVFP4_RTN) {
+        if (RND_R == NVFP4_RTN) {
 #pragma unroll
             for (int t = 0; t < 4; ++t)
                 packed |= quant_pair_hw(v[r].get(2 * t), v[r].get(2 * t + 1), q) << (8 * t);
@@ -638,7 +640,7 @@ __global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
     for (int r = 0; r < 16; ++r) v[r].launder();
 
     // column-blocked side: exactly the columns kernel's tile
-    cols_tile<DT, B, SF, RND, true, true, 8>(P, v, g, k, row0, col0, inside ? 8 : 0, lv);
+    cols_tile<DT, B, SF, RND_C, true, true, 8>(P, v, g, k, row0, col0, inside ? 8 : 0, lv);
 
     __syncthreads();
     const int64_t cpr = P.cols >> 1;
@@ -781,23 +783,25 @@ hipError_t launch_quantize(const QuantArgs &P, int dt, int axis, int rounding, i
 }
 
 template <int DT, int B, int SF>
-static void launch_dual_rnd(const DualArgs &D, int rounding, hipStream_t st)
+static void launch_dual_rnd(const DualArgs &D, int rnd_r, int rnd_c, hipStream_t st)
 {
     using G = ColGeom<DT>;
     dim3 grid((unsigned)((D.c.cols + G::WG_COLS - 1) / G::WG_COLS), (unsigned)((D.c.rows + G::WG_ROWS - 1) / G::WG_ROWS));
-    if (rounding == NVFP4_SR)
-        hipLaunchKernelGGL((quantize_dual_kernel<DT, B, SF, NVFP4_SR>), grid, dim3(256), 0, st, D);
+    if (rnd_r == NVFP4_SR && rnd_c == NVFP4_SR)
+        hipLaunchKernelGGL((quantize_dual_kernel<DT, B, SF, NVFP4_SR, NVFP4_SR>), grid, dim3(256), 0, st, D);
+    else if (rnd_r == NVFP4_RTN && rnd_c == NVFP4_SR)
+        hipLaunchKernelGGL((quantize_dual_kernel<DT, B, SF, NVFP4_RTN, NVFP4_SR>), grid, dim3(256), 0, st, D);
     else
-        hipLaunchKernelGGL((quantize_dual_kernel<DT, B, SF, NVFP4_RTN>), grid, dim3(256), 0, st, D);
+        hipLaunchKernelGGL((quantize_dual_kernel<DT, B, SF, NVFP4_RTN, NVFP4_RTN>), grid, dim3(256), 0, st, D);
 }
 
 template <int DT>
-static void launch_dual_fmt(const DualArgs &D, int rounding, int block, int sf, hipStream_t st)
+static void launch_dual_fmt(const DualArgs &D, int rnd_r, int rnd_c, int block, int sf, hipStream_t st)
 {
-    if (block == 16 && sf == NVFP4_SCALE_E4M3) launch_dual_rnd<DT, 16, NVFP4_SCALE_E4M3>(D, rounding, st);
-    else if (block == 16) launch_dual_rnd<DT, 16, NVFP4_SCALE_E8M0>(D, rounding, st);
-    else if (sf == NVFP4_SCALE_E4M3) launch_dual_rnd<DT, 32, NVFP4_SCALE_E4M3>(D, rounding, st);
-    else launch_dual_rnd<DT, 32, NVFP4_SCALE_E8M0>(D, rounding, st);
+    if (block == 16 && sf == NVFP4_SCALE_E4M3) launch_dual_rnd<DT, 16, NVFP4_SCALE_E4M3>(D, rnd_r, rnd_c, st);
+    else if (block == 16) launch_dual_rnd<DT, 16, NVFP4_SCALE_E8M0>(D, rnd_r, rnd_c, st);
+    else if (sf == NVFP4_SCALE_E4M3) launch_dual_rnd<DT, 32, NVFP4_SCALE_E4M3>(D, rnd_r, rnd_c, st);
+    else launch_dual_rnd<DT, 32, NVFP4_SCALE_E8M0>(D, rnd_r, rnd_c, st);
 }
 
 bool quantize_dual_fused(int dt, int64_t rows, int64_t cols, int64_t ld, int block, bool hw_convert)
@@ -807,14 +811,15 @@ bool quantize_dual_fused(int dt, int64_t rows, int64_t cols, int64_t ld, int blo
            (ld * esz) % 16 == 0 && cols < (int64_t(1) << 31) && rows < (int64_t(1) << 31);
 }
 
-hipError_t launch_quantize_dual(const DualArgs &D, int dt, int rounding, int block, int sf, bool hw_convert,
+hipError_t launch_quantize_dual(const DualArgs &D, int dt, int rnd_r, int rnd_c, int block, int sf, bool hw_convert,
                                 hipStream_t st)
 {
-    if (quantize_dual_fused(dt, D.c.rows, D.c.cols, D.c.ld, block, hw_convert)) {
+    // (SR rows with RtN columns is a combination no equation asks for: two kernels)
+    if (quantize_dual_fused(dt, D.c.rows, D.c.cols, D.c.ld, block, hw_convert) && !(rnd_r == NVFP4_SR && rnd_c == NVFP4_RTN)) {
         if (dt == NVFP4_BF16)
-            launch_dual_fmt<NVFP4_BF16>(D, rounding, block, sf, st);
+            launch_dual_fmt<NVFP4_BF16>(D, rnd_r, rnd_c, block, sf, st);
         else
-            launch_dual_fmt<NVFP4_F32>(D, rounding, block, sf, st);
+            launch_dual_fmt<NVFP4_F32>(D, rnd_r, rnd_c, block, sf, st);
         return launch_status();
     }
     // other block sizes and ragged shapes: the two single-orientation kernels
@@ -822,9 +827,12 @@ hipError_t launch_quantize_dual(const DualArgs &D, int dt, int rounding, int blo
     r.codes = D.codes_r;
     r.scales = D.scales_r;
     r.seed = D.seed_r;
-    hipError_t e = launch_quantize(r, dt, 1, rounding, block, sf, hw_convert, st);
+    r.g_out = D.c.g_out;
+    hipError_t e = launch_quantize(r, dt, 1, rnd_r, block, sf, hw_convert, st);
     if (e != hipSuccess) return e;
-    return launch_quantize(D.c, dt, 0, rounding, block, sf, hw_convert, st);
+    e = launch_quantize(D.c, dt, 0, rnd_c, block, sf, hw_convert, st);
+    if (e != hipSuccess || !D.g_out2) return e;
+    return hipMemcpyAsync(D.g_out2, D.c.g_out, sizeof(float), hipMemcpyDeviceToDevice, st);
 }
 
 }  // namespace nvfp4

@@ -227,6 +227,33 @@ def test_backward_with_scales_handed_over_from_forward():
         torch.cuda.synchronize()
         assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
 
+@pytest.mark.parametrize("fmtname", ["nvfp4", "mxfp4", "e4m3_b64"])
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_backward_from_operands_saved_by_forward(fmtname, dtype):
+    # the forward call's passes over X and W also write Q_SR(X^T) and Q_RtN(W^T) (Eqs. 5-6 operands);
+    # the backward call given that buffer reads neither X nor W and must produce the same bits as
+    # the call that quantizes them itself -- and those are checked against the oracle
+    fmt = {"nvfp4": nv.NVFP4, "mxfp4": nv.MXFP4, "e4m3_b64": nv.Format(64, nv.SCALE_E4M3, 1)}[fmtname]
+    for M, N, K, seed in ((256, 192, 320, 5), (384, 640, 128, 9)):
+        print(f"[case] saved operands fmt={fmtname} dtype={dtype} M={M} N={N} K={K}", flush=True)
+        X = synth.normal(M, K, 1.0, 81, dtype).cuda()
+        W = synth.normal(N, K, 0.02, 82, dtype).cuda()
+        dY = synth.gradient_like(M, N, 83, dtype=dtype).cuda()
+        saved = torch.empty(nv.linear_saved_bytes(M, N, K, fmt), dtype=torch.uint8, device="cuda")
+        Y0 = nv.linear_fwd(X, W, fmt)
+        Y1 = nv.linear_fwd(X, W, fmt, saved=saved, bwd_seed=seed)
+        assert torch.equal(Y0, Y1)
+        a = nv.linear_bwd(dY, X, W, seed, fmt)
+        b = nv.linear_bwd(dY, None, None, seed, fmt, saved=saved, K=K)
+        torch.cuda.synchronize()
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+        of = ofmt(fmt)
+        Xc, Wc, dYc = X.cpu(), W.cpu(), dY.cpu()
+        qdy, qwt = oracle.quantize(dYc, 1, oracle.SR, seed, of), oracle.quantize(Wc, 0, oracle.RTN, 0, of)
+        assert_gemm_close(to_np(b[0]), oracle.gemm_nt(qdy, qwt, of), oracle.gemm_nt(qdy, qwt, of, take_abs=True), "saved dX")
+        qdyt, qxt = oracle.quantize(dYc, 0, oracle.SR, seed + 1, of), oracle.quantize(Xc, 0, oracle.SR, seed + 2, of)
+        assert_gemm_close(to_np(b[1]), oracle.gemm_nt(qdyt, qxt, of), oracle.gemm_nt(qdyt, qxt, of, take_abs=True), "saved dW")
+
 
 # ---------------------------------------------------------------- MXFP4 (block 32, E8M0): native FP4 MFMA
 def mx_operand(rng, rows, K, lo=112, hi=142):

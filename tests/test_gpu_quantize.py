@@ -242,21 +242,22 @@ def test_sr_exact_ties_between_draw_and_position(axis):
 
 @pytest.mark.parametrize("fmt", list(FORMATS))
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
-@pytest.mark.parametrize("rounding", [0, 1])
+@pytest.mark.parametrize("rounding", ["rtn-rtn", "sr-sr", "rtn-sr", "sr-rtn"])
 def test_dual_orientation_matches_oracle(fmt, dtype, rounding):
     # Eqs. 5-6 use dY blocked along N and along M: one pass must give exactly the two
     # single-orientation results (blocks 16/32 run fused, 64/128 as two kernels); sizes span
     # several 128 x 256 tiles with ragged last tiles in both directions
     f = FORMATS[fmt]()
     B = f.block
+    rr, rc = {"rtn-rtn": (0, 0), "sr-sr": (1, 1), "rtn-sr": (0, 1), "sr-rtn": (1, 0)}[rounding]
     for rows, cols, preset in ((2 * B, 2 * B, None), (128 + 3 * B, 512 + 5 * B, None), (384, 256, 0.37)):
         x = synth.student_t_outliers(rows, cols, 40 + rows, dtype=dtype)
         print(f"[case] dual {fmt} {dtype} rounding={rounding} shape=({rows},{cols}) preset={preset}", flush=True)
         ts = None if preset is None else torch.tensor([preset], dtype=torch.float32, device="cuda")
-        qr, qc = nv.quantize_dual(x.cuda(), rounding, 21, 22, f, tensor_scale=ts)
+        qr, qc = nv.quantize_dual(x.cuda(), rr, 21, rc, 22, f, tensor_scale=ts)
         torch.cuda.synchronize()
-        assert_quant_equal(qr, oracle.quantize(x, 1, rounding, 21, ofmt(f), g=preset), "dual rows")
-        assert_quant_equal(qc, oracle.quantize(x, 0, rounding, 22, ofmt(f), g=preset), "dual cols")
+        assert_quant_equal(qr, oracle.quantize(x, 1, rr, 21, ofmt(f), g=preset), "dual rows")
+        assert_quant_equal(qc, oracle.quantize(x, 0, rc, 22, ofmt(f), g=preset), "dual cols")
 
 
 def test_dual_orientation_strided_and_full_size():
@@ -264,7 +265,7 @@ def test_dual_orientation_strided_and_full_size():
     base = synth.student_t_outliers(160, 400, 9)
     x = base[:, 16:16 + 368]
     xg = base.cuda()[:, 16:16 + 368]
-    qr, qc = nv.quantize_dual(xg, nv.SR, 5, 6, nv.NVFP4)
+    qr, qc = nv.quantize_dual(xg, nv.SR, 5, nv.SR, 6, nv.NVFP4)
     torch.cuda.synchronize()
     xc = x.contiguous()
     assert_quant_equal(qr, oracle.quantize(xc, 1, nv.SR, 5, oracle.NVFP4), "dual strided rows")
@@ -272,7 +273,7 @@ def test_dual_orientation_strided_and_full_size():
     dY = synth.gradient_like(4096, 11008, 77).cuda()
     for f in (nv.NVFP4, nv.MXFP4):
         g = nv.tensor_scale(dY) if f.tensor_scale else None
-        qr, qc = nv.quantize_dual(dY, nv.SR, 1, 2, f, tensor_scale=g)
+        qr, qc = nv.quantize_dual(dY, nv.SR, 1, nv.SR, 2, f, tensor_scale=g)
         r1 = nv.quantize(dY, 1, nv.SR, 1, f, tensor_scale=g)
         c1 = nv.quantize(dY, 0, nv.SR, 2, f, tensor_scale=g)
         torch.cuda.synchronize()

@@ -78,14 +78,15 @@ def test_quantize_argument_errors():
 
 def test_quantize_dual_argument_errors():
     def dual(x=FAKE, dt=nv.BF16, rows=64, cols=64, ld=64, rnd=nv.SR, fmt=nv.NVFP4, cr=FAKE, sr=FAKE, cc=FAKE,
-             sc=FAKE, ts=FAKE, flags=0, ws=FAKE, ws_bytes=1 << 20):
+             sc=FAKE, ts=FAKE, flags=0, ws=FAKE, ws_bytes=1 << 20, k2=nv.SR):
         f = fmt.c()
-        return nv.lib.nvfp4_quantize_dual(x, dt, rows, cols, ld, rnd, 1, 2, C.byref(f), cr, sr, cc, sc, ts, flags,
+        return nv.lib.nvfp4_quantize_dual(x, dt, rows, cols, ld, rnd, 1, k2, 2, C.byref(f), cr, sr, cc, sc, ts, flags,
                                           ws, ws_bytes, None)
     assert dual(x=None) == nv.EINVAL
     assert dual(cc=None) == nv.EINVAL
     assert dual(sr=None) == nv.EINVAL
     assert dual(rnd=2) == nv.EINVAL
+    assert dual(k2=5) == nv.EINVAL
     assert dual(flags=2) == nv.EINVAL
     assert dual(rows=72) == nv.ESHAPE                     # both axes are blocked
     assert dual(cols=72, ld=72) == nv.ESHAPE
@@ -110,17 +111,23 @@ def test_gemm_and_linear_argument_errors():
     assert g(f=nv.Format(64, nv.SCALE_E8M0, 0).c()) == nv.EUNSUPPORTED  # E8M0 GEMM exists for block 32 only
     assert g(M=0) == nv.OK           # empty product: nothing to do, nothing launched
     assert g(K=(1 << 23) + 32) == nv.ESHAPE  # contraction length beyond the kernels' 32-bit tile offsets
-    fw = lambda **k: nv.lib.nvfp4_linear_fwd(k.get("X", FAKE), FAKE, FAKE, 64, 64, k.get("K", 64), nv.BF16, nv.F32,
-                                             C.byref(f), k.get("ws", FAKE), k.get("wsb", 1 << 30), None, None)
+    fw = lambda **k: nv.lib.nvfp4_linear_fwd(k.get("X", FAKE), FAKE, FAKE, k.get("M", 64), 64, k.get("K", 64), nv.BF16,
+                                             nv.F32, C.byref(f), k.get("ws", FAKE), k.get("wsb", 1 << 30), None, None,
+                                             k.get("saved"), 0)
     assert fw(X=None) == nv.EINVAL
     assert fw(K=40) == nv.ESHAPE
     assert fw(ws=None) == nv.EWORKSPACE
     assert fw(wsb=16) == nv.EWORKSPACE
+    assert fw(M=48, saved=FAKE) == nv.ESHAPE     # X^T is blocked along M for the backward call
+    assert fw(saved=FAKE + 16) == nv.EALIGN
+    assert nv.linear_saved_bytes(4096, 11008, 4096) >= 4096 * (4096 + 11008) * 9 // 16
     bw = lambda **k: nv.lib.nvfp4_linear_bwd(k.get("dY", FAKE), FAKE, FAKE, FAKE, FAKE, k.get("M", 64), 64, 64,
-                                             nv.BF16, nv.F32, C.byref(f), 0, FAKE, k.get("wsb", 1 << 30), None, None)
+                                             nv.BF16, nv.F32, C.byref(f), 0, FAKE, k.get("wsb", 1 << 30), None, None,
+                                             k.get("saved"))
     assert bw(dY=None) == nv.EINVAL
     assert bw(M=48) == nv.ESHAPE     # the update GEMM contracts over M
     assert bw(wsb=16) == nv.EWORKSPACE
+    assert bw(saved=FAKE + 16) == nv.EALIGN
 
 
 # ---------------------------------------------------------------- scalar steps vs the oracle
