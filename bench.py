@@ -84,6 +84,9 @@ def main() -> int:
             for rnd in (nv.RTN, nv.SR):
                 for _ in range(2):
                     nv.quantize(xq, axis, rnd, 1, tensor_scale=g)
+        for rnd in (nv.RTN, nv.SR):
+            for _ in range(2):
+                nv.quantize_dual(xq, rnd, 1, rnd, 2, tensor_scale=g)
         torch.cuda.synchronize()
         print("probe done")
         return 0
