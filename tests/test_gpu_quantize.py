@@ -107,6 +107,29 @@ def test_software_rounding_path_equals_hardware_convert(monkeypatch):
     assert torch.equal(hw[0], sw[0]) and torch.equal(hw0[0], sw0[0])
 
 
+def test_software_sr_path_equals_hardware_sr_convert(monkeypatch):
+    # the integer formulation of the SR rule and the hardware SR convert fed with seed words built from the
+    # same draws: both against the oracle, rows and columns, aligned and unaligned widths, and the
+    # dual-orientation entry (one fused kernel vs its two-kernel fallback)
+    x = synth.student_t_outliers(288, 1024, seed=16, dtype=torch.bfloat16)
+    xu = synth.normal(64, 1004, 1.0, 17, torch.float32)   # its first 1001 columns: rows stay 16-byte aligned
+    res = {}
+    for mode in ("hw", "soft"):
+        if mode == "soft":
+            monkeypatch.setenv("NVFP4_SOFT_CONVERT", "1")
+        res[mode] = [run_both(x, 1, nv.SR, 3, nv.NVFP4, what=mode + "-rows"),
+                     run_both(x, 0, nv.SR, 4, nv.NVFP4, what=mode + "-cols"),
+                     run_both(x, 0, nv.SR, 4, nv.MXFP4, what=mode + "-cols-mx"),
+                     nv.quantize(xu.cuda()[:, :1001], 0, nv.SR, 5, nv.NVFP4)]
+        assert_quant_equal(res[mode][3], oracle.quantize(xu[:, :1001].contiguous(), 0, oracle.SR, 5), mode + "-cols-unaligned")
+        qr, qc = nv.quantize_dual(x.cuda(), nv.RTN, 0, nv.SR, 6, nv.NVFP4)
+        torch.cuda.synchronize()
+        assert_quant_equal(qr, oracle.quantize(x, 1, oracle.RTN, 0), mode + " dual rows")
+        assert_quant_equal(qc, oracle.quantize(x, 0, oracle.SR, 6), mode + " dual cols")
+    for a, b in zip(res["hw"], res["soft"]):
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
 def _blocks_with_leader(values, leader):
     """Rows of 1024 = 64 blocks, each block [leader, 15 values]."""
     n = (values.size + 14) // 15
