@@ -82,6 +82,18 @@ def test_random_codes_and_scales(shape):
     rng = np.random.default_rng(M * 7 + N)
     check(random_operand(rng, M, K, g=0.37), random_operand(rng, N, K, g=2.5e-3), nv.NVFP4, "random")
 
+@pytest.mark.parametrize("shape", [(2900, 3000, 256), (2560, 3330, 512), (4100, 8200, 256), (3000, 2900, 384)],
+                         ids=["144 ragged tiles, 2 K tiles", "140 tiles, 4 K tiles", "561 tiles", "3 K tiles"])
+def test_large_tile_kernel_ragged_edges(shape):
+    # >= 128 tiles of 256 x 256 select the 8-wave kernel: edge tiles (clamped rows, element-wise stores),
+    # even and odd numbers of K tiles, more tiles than CUs
+    M, N, K = shape
+    rng = np.random.default_rng(M + N + K)
+    A, B = random_operand(rng, M, K, lo=0x30, hi=0x48, g=0.5), random_operand(rng, N, K, lo=0x30, hi=0x48, g=0.25)
+    check(A, B, nv.NVFP4, "large-ragged")
+    if K == 256:
+        check(A, B, nv.NVFP4, "large-ragged-bf16", out_dtype=torch.bfloat16)
+
 
 def test_moderate_scales_tight():
     # scales within a few binades (what real tensors give): no cancellation of huge terms
