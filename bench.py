@@ -223,6 +223,15 @@ def main() -> int:
                            12, torch, warmup=NQ)
         gbs = nel * 2.5625 / (ms * 1e-3) / 1e9
         quant[label] = {"ms": round(ms, 4), "GB/s": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
+    # both orientations in one pass (what the fused forward / backward calls run): 2 + 2 x 0.5625 B/elt
+    for label, rr, rc in (("dual_rtn_rtn", nv.RTN, nv.RTN), ("dual_rtn_sr", nv.RTN, nv.SR), ("dual_sr_sr", nv.SR, nv.SR)):
+        douts = [nv.quantize_dual(xqs[i], rr, 1, rc, 2, tensor_scale=gs[i]) for i in range(NQ)]
+        douts = [(a[0], a[1], b[0], b[1], a[2]) for a, b in douts]
+        ms = event_time_ms(lambda i: nv.quantize_dual(xqs[i % NQ], rr, 1, rc, 2, tensor_scale=gs[i % NQ], out=douts[i % NQ]),
+                           12, torch, warmup=NQ)
+        gbs = nel * 3.125 / (ms * 1e-3) / 1e9
+        quant[label] = {"ms": round(ms, 4), "GB/s": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
+    del douts
     outs = [nv.quantize(xqs[i], 1, nv.RTN, 0) for i in range(NQ)]
     ms = event_time_ms(lambda i: nv.quantize(xqs[i % NQ], 1, nv.RTN, 0, out=outs[i % NQ]), 12, torch, warmup=NQ)
     gbs = nel * 4.5625 / (ms * 1e-3) / 1e9
@@ -235,7 +244,7 @@ def main() -> int:
         gbs = nel * 2.5625 / (ms * 1e-3) / 1e9
         quant[label] = {"ms": round(ms, 4), "GB/s": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
         del qs
-    quant["bytes_per_element"] = {"preset_scale": 2.5625, "with_amax_pass": 4.5625, "noise_stats": 2.5625}
+    quant["bytes_per_element"] = {"preset_scale": 2.5625, "with_amax_pass": 4.5625, "dual": 3.125, "noise_stats": 2.5625}
     del xqs, outs
 
     # ---- the oracle on the host cores, bounded sample of the same workload

@@ -94,13 +94,6 @@ SavedLayout saved_layout(void *saved, int64_t M, int64_t N, int64_t K, int64_t B
     return L;
 }
 
-__global__ void place_scales_kernel(float *ts, const float *g_xw)
-{
-    // {g_dY, gW, g_dY, gX}: the two pairs the backward GEMMs read
-    if (threadIdx.x == 0) ts[1] = g_xw[1];
-    if (threadIdx.x == 1) ts[3] = g_xw[0];
-}
-
 }  // namespace
 
 extern "C" {
@@ -307,7 +300,7 @@ nvfp4_status nvfp4_gemm(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
         return NVFP4_EALIGN;
     if (f->scale == NVFP4_SCALE_E8M0 && f->block != 32) return NVFP4_EUNSUPPORTED;  // E8M0 GEMM: MXFP4 only
     if (M == 0 || N == 0) return NVFP4_OK;
-    GemmArgs g{M, N, K, A_codes, A_scales, B_codes, B_scales, tensor_scales, out, ldc};
+    GemmArgs g{M, N, K, A_codes, A_scales, B_codes, B_scales, tensor_scales, tensor_scales + 1, out, ldc};
     return launch_gemm(g, f->block, f->scale, out_dt, reinterpret_cast<hipStream_t>(stream)) == hipSuccess
                ? NVFP4_OK
                : NVFP4_EHIP;
@@ -368,7 +361,7 @@ nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, 
         if (run_quantize(qx, f, st) != hipSuccess) return NVFP4_EHIP;
         if (run_quantize(qw, f, st) != hipSuccess) return NVFP4_EHIP;
     }
-    GemmArgs g{M, N, K, xc, xs, wc, wsc, ts, Y, N};
+    GemmArgs g{M, N, K, xc, xs, wc, wsc, ts, ts + 1, Y, N};
     return launch_gemm(g, f->block, f->scale, out_dt, st) == hipSuccess ? NVFP4_OK : NVFP4_EHIP;
 }
 
@@ -412,6 +405,7 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
     uint8_t *dyts = p; p += align_up((size_t)N * (M / B));
     uint8_t *xtc = p; p += align_up((size_t)K * M / 2);
     uint8_t *xts = p;
+    const float *g_w = ts + 1, *g_x = ts + 3;  // written by the W^T and X^T quantizers below, or saved by the forward call
     if (saved) {
         // Q_RtN(W^T) and Q_SR(X^T) as the forward call left them (its bwd_seed must equal seed)
         const SavedLayout L = saved_layout(const_cast<void *>(saved), M, N, K, B);
@@ -419,7 +413,8 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
         wts = L.wts;
         xtc = L.xtc;
         xts = L.xts;
-        hipLaunchKernelGGL(place_scales_kernel, dim3(1), dim3(64), 0, st, ts, L.g);
+        g_x = L.g + 0;
+        g_w = L.g + 1;
     }
 
     const int gm = f->tensor_scale ? G_FROM_AMAX : G_NONE;
@@ -458,7 +453,7 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
         QuantPlan qb{W, in_dt, N, K, K, 0, NVFP4_RTN, 0, wtc, wts, gsrc_w, ts + 1, gm_xw};
         if (!dual && run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
         if (!saved && run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
-        GemmArgs g{M, K, N, dyc, dys, wtc, wts, ts + 0, dX, K};
+        GemmArgs g{M, K, N, dyc, dys, wtc, wts, ts + 0, g_w, dX, K};
         if (launch_gemm(g, f->block, f->scale, out_dt, st) != hipSuccess) return NVFP4_EHIP;
     }
     if (dW) {
@@ -468,7 +463,7 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
         QuantPlan qb{X, in_dt, M, K, K, 0, NVFP4_SR, seed + 2, xtc, xts, gsrc_x, ts + 3, gm_xw};
         if (!dual && run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
         if (!saved && run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
-        GemmArgs g{N, K, M, dytc, dyts, xtc, xts, ts + 2, dW, K};
+        GemmArgs g{N, K, M, dytc, dyts, xtc, xts, ts + 2, g_x, dW, K};
         if (launch_gemm(g, f->block, f->scale, out_dt, st) != hipSuccess) return NVFP4_EHIP;
     }
     return NVFP4_OK;

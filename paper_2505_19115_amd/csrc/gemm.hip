@@ -373,7 +373,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
     // consecutive columns of one row = one packed convert pair and one 8-byte (bf16) or 16-byte
     // (fp32) store.  Full tiles with a suitably aligned output take that path; edge tiles store
     // element by element.
-    const float gg = P.tensor_scales[0] * P.tensor_scales[1];
+    const float gg = P.gA[0] * P.gB[0];
     constexpr int ESZ = OUT_DT == NVFP4_F32 ? 4 : 2;
     const int64_t row0 = m0 + wm * 32 * TA + r, col0 = n0 + wn * 32 * TB + 4 * h;
     const bool fast = m0 + BM <= P.M && n0 + BN <= P.N && (P.ldc & 3) == 0 && (reinterpret_cast<uintptr_t>(P.out) & 15) == 0;

@@ -46,7 +46,7 @@ __device__ __forceinline__ void mx_store_tile(const GemmArgs &P, float16v_t (&ac
     int lane_e = lane, wave_e = wave;
     asm volatile("" : "+v"(lane_e), "+v"(wave_e));
     const int re = lane_e & 31, ge = lane_e >> 5, wme = wave_e >> 1, wne = wave_e & 1;
-    const float gg = P.tensor_scales[0] * P.tensor_scales[1];
+    const float gg = P.gA[0] * P.gB[0];
     constexpr int ESZ = OUT_DT == NVFP4_F32 ? 4 : 2;
     const int64_t row0 = m0 + wme * 128 + re, col0 = n0 + wne * 128 + 4 * ge;
     uint8_t *const out = reinterpret_cast<uint8_t *>(P.out);

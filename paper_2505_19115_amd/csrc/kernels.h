@@ -33,7 +33,7 @@ struct DualArgs {
 struct GemmArgs {
     int64_t M, N, K;
     const uint8_t *A_codes, *A_scales, *B_codes, *B_scales;
-    const float *tensor_scales;  // {gA, gB}
+    const float *gA, *gB;  // per-tensor scales of the two operands (device)
     void *out;
     int64_t ldc;
 };
