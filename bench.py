@@ -45,6 +45,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--streams", type=int, default=2,
+                    help="2: gate and up run side by side on two streams as the MLP's dependency graph allows; "
+                         "1: every call on one stream")
     ap.add_argument("--probe", action="store_true",
                     help="run each kernel of interest a few times and exit (for rocprofv3 --pmc passes)")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
@@ -109,13 +112,48 @@ def main() -> int:
         data.append((name, N, K, X, W, dY, wf, wb, Y, dX, dW, saved))
     flop_per_step = sum(3 * 2 * M * N * K for _, N, K in layers)
 
-    def step(s):
-        for name, N, K, X, W, dY, wf, wb, Y, dX, dW, saved in data:
-            # the forward call's passes over X and W also leave Q_SR(X^T), Q_RtN(W^T) and the
-            # per-tensor scales for the backward call, which then reads only dY (once)
-            nv.linear_fwd(X, W, workspace=wf, out=Y, saved=saved, bwd_seed=1000 + 3 * s)
-            nv.linear_bwd(dY, None, None, seed=1000 + 3 * s, workspace=wb, out=(dX, dW), saved=saved, K=K)
+    def fwd(layer, s, fmt, base):
+        name, N, K, X, W, dY, wf, wb, Y, dX, dW, saved = layer
+        # the forward call's passes over X and W also leave Q_SR(X^T), Q_RtN(W^T) and the per-tensor
+        # scales for the backward call, which then reads only dY (once)
+        nv.linear_fwd(X, W, fmt, workspace=wf, out=Y, saved=saved, bwd_seed=base + 3 * s)
 
+    def bwd(layer, s, fmt, base):
+        name, N, K, X, W, dY, wf, wb, Y, dX, dW, saved = layer
+        nv.linear_bwd(dY, None, None, base + 3 * s, fmt, workspace=wb, out=(dX, dW), saved=saved, K=K)
+
+    def step_serial(s, fmt=nv.NVFP4, base=1000):
+        for layer in data:
+            fwd(layer, s, fmt, base)
+            bwd(layer, s, fmt, base)
+
+    # The MLP's own dependency graph: gate and up read the same input and do not depend on each
+    # other, down consumes both; backward runs the graph in reverse.  gate runs on the timing
+    # stream, up on a second stream of default priority, forked and joined with events.
+    side = torch.cuda.Stream()
+    ev = [torch.cuda.Event() for _ in range(4)]
+
+    def step_graph(s, fmt=nv.NVFP4, base=1000):
+        gate, up, down = data
+        main = torch.cuda.current_stream()
+        ev[0].record(main)
+        side.wait_event(ev[0])
+        fwd(gate, s, fmt, base)
+        with torch.cuda.stream(side):
+            fwd(up, s, fmt, base)
+            ev[1].record(side)
+        main.wait_event(ev[1])
+        fwd(down, s, fmt, base)
+        bwd(down, s, fmt, base)
+        ev[2].record(main)
+        side.wait_event(ev[2])
+        bwd(gate, s, fmt, base)
+        with torch.cuda.stream(side):
+            bwd(up, s, fmt, base)
+            ev[3].record(side)
+        main.wait_event(ev[3])
+
+    step = step_graph if args.streams >= 2 else step_serial
     for s in range(args.warmup):
         step(s)
     torch.cuda.synchronize()
@@ -126,12 +164,15 @@ def main() -> int:
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
     tflops = flop_per_step / (elapsed / args.steps) / 1e12
+    # the other schedule, for comparison
+    other = step_serial if args.streams >= 2 else step_graph
+    other_ms = event_time_ms(other, max(args.steps // 2, 3), torch)
+    schedules = {"timed": "mlp_graph_2_streams" if args.streams >= 2 else "one_stream",
+                 "one_stream_ms" if args.streams >= 2 else "mlp_graph_2_streams_ms": round(other_ms, 3)}
 
     # the same step in MXFP4 (block 32, E8M0; the GEMMs then run on the FP4 matrix instruction)
     def step_mx(s):
-        for name, N, K, X, W, dY, wf, wb, Y, dX, dW, saved in data:
-            nv.linear_fwd(X, W, nv.MXFP4, workspace=wf, out=Y, saved=saved, bwd_seed=2000 + 3 * s)
-            nv.linear_bwd(dY, None, None, 2000 + 3 * s, nv.MXFP4, workspace=wb, out=(dX, dW), saved=saved, K=K)
+        step(s, nv.MXFP4, 2000)
 
     mx_step_ms = event_time_ms(step_mx, max(args.steps // 2, 3), torch)
     mx_step = {"ms_per_step": round(mx_step_ms, 3), "TFLOP/s": round(flop_per_step / (mx_step_ms * 1e-3) / 1e12, 1),
@@ -273,7 +314,11 @@ def main() -> int:
         "config": {"workload": "Llama2-7B SwiGLU MLP linears fwd+bwd (gate, up, down), tokens=4096: "
                                "9 GEMMs + 9 dual-orientation quantize passes (X, W in the forward call, which saves Q_SR(X^T), Q_RtN(W^T) and the scales for the backward call; dY in the backward call) + 9 tensor-maximum passes per step, bf16 in",
                    "M": M, "layers": [[n, N, K] for n, N, K in layers], "format": "NVFP4 (block 16, E4M3, tensor scale)",
-                   "rounding": "fwd RtN; bwd/update SR (Philox4x32-10)"},
+                   "rounding": "fwd RtN; bwd/update SR (Philox4x32-10)",
+                   "schedule": ("all forward calls, then all backward calls, in the MLP's dependency order; gate and up side by side "
+                                "on two HIP streams (fork/join with events), down after both" if args.streams >= 2 else
+                                "fwd then bwd per layer, every call on one stream")},
+        "schedules": schedules,
         "frac_of_fp4_peak": round(tflops / PEAK_FP4_TFLOPS, 4),
         "roofline": roofline, "mfma_sustained": sustained, "mxfp4_gemm": mxfp4, "mxfp4_step": mx_step, "format_sweep": sweep,
         "quantize": quant, "cpu_baseline": cpu,
