@@ -45,9 +45,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
-    ap.add_argument("--streams", type=int, default=2,
-                    help="2: gate and up run side by side on two streams as the MLP's dependency graph allows; "
-                         "1: every call on one stream")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="1: every call on one stream (the timed default); 2: gate and up side by side on two "
+                         "streams as the MLP's dependency graph allows (timed next to it either way)")
     ap.add_argument("--probe", action="store_true",
                     help="run each kernel of interest a few times and exit (for rocprofv3 --pmc passes)")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
