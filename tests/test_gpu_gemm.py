@@ -356,3 +356,44 @@ def test_mxfp4_7b_shape_sampled():
     ref = oracle.gemm_nt_sample(A, B, ii, jj, oracle.MXFP4)
     ref_abs = oracle.gemm_nt_sample(A, B, ii, jj, oracle.MXFP4, take_abs=True)
     assert_gemm_close(to_np(Y)[ii, jj], ref, ref_abs, "mx-7b-gate")
+
+
+def test_fused_calls_replay_from_a_hip_graph():
+    # the fused entries launch only kernels on the given stream (no allocation, no memset, no host
+    # synchronisation), so a forward + backward pair can be captured once and replayed; every
+    # replay is checked against the eager result for the data then in the buffers
+    M, N, K = 256, 384, 512
+    f = nv.NVFP4.c()
+    import ctypes as C
+    X = synth.normal(M, K, 1.0, 91).cuda()
+    W = synth.normal(N, K, 0.02, 92).cuda()
+    dY = synth.gradient_like(M, N, 93).cuda()
+    wf = torch.empty(nv.lib.nvfp4_linear_fwd_workspace_bytes(M, N, K, C.byref(f)), dtype=torch.uint8, device="cuda")
+    wb = torch.empty(nv.lib.nvfp4_linear_bwd_workspace_bytes(M, N, K, C.byref(f)), dtype=torch.uint8, device="cuda")
+    saved = torch.empty(nv.linear_saved_bytes(M, N, K), dtype=torch.uint8, device="cuda")
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    dX = torch.empty((M, K), dtype=torch.bfloat16, device="cuda")
+    dW = torch.empty((N, K), dtype=torch.bfloat16, device="cuda")
+
+    def step():
+        nv.linear_fwd(X, W, workspace=wf, out=Y, saved=saved, bwd_seed=17)
+        nv.linear_bwd(dY, None, None, seed=17, workspace=wb, out=(dX, dW), saved=saved, K=K)
+
+    step()  # (first launches set kernel attributes: outside the capture)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for it in range(3):
+        print(f"[case] graph replay {it}", flush=True)
+        X.copy_(synth.normal(M, K, 1.0, 100 + it).cuda())
+        dY.copy_(synth.gradient_like(M, N, 200 + it).cuda())
+        step()
+        torch.cuda.synchronize()
+        want = (Y.clone(), dX.clone(), dW.clone())
+        for t in (Y, dX, dW):
+            t.fill_(-1.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y, want[0]) and torch.equal(dX, want[1]) and torch.equal(dW, want[2])
