@@ -397,3 +397,22 @@ def test_fused_calls_replay_from_a_hip_graph():
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(Y, want[0]) and torch.equal(dX, want[1]) and torch.equal(dW, want[2])
+
+
+def test_saved_operand_path_at_the_benchmark_shapes():
+    # the launch configuration bench.py times (bf16 in/out, saved operands, dual quantizers) against the
+    # plain calls, whose operands and GEMMs the other full-size tests check against the oracle
+    M = 4096
+    for N, K in ((11008, 4096), (4096, 11008)):
+        print(f"[case] saved operands full size N={N} K={K}", flush=True)
+        X = synth.normal(M, K, 1.0, 100).cuda()
+        W = synth.normal(N, K, 0.02, 200).cuda()
+        dY = synth.gradient_like(M, N, 300).cuda()
+        saved = torch.empty(nv.linear_saved_bytes(M, N, K), dtype=torch.uint8, device="cuda")
+        Y0 = nv.linear_fwd(X, W, out_dtype=torch.bfloat16)
+        Y1 = nv.linear_fwd(X, W, out_dtype=torch.bfloat16, saved=saved, bwd_seed=1000)
+        a = nv.linear_bwd(dY, X, W, 1000, out_dtype=torch.bfloat16)
+        b = nv.linear_bwd(dY, None, None, 1000, out_dtype=torch.bfloat16, saved=saved, K=K)
+        torch.cuda.synchronize()
+        assert torch.equal(Y0, Y1) and torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+        del X, W, dY, saved, Y0, Y1, a, b
