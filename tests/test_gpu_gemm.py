@@ -416,3 +416,26 @@ def test_saved_operand_path_at_the_benchmark_shapes():
         torch.cuda.synchronize()
         assert torch.equal(Y0, Y1) and torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
         del X, W, dY, saved, Y0, Y1, a, b
+
+
+@pytest.mark.parametrize("fmt_name", ["NVFP4", "MXFP4"])
+def test_full_size_outputs_follow_row_permutations(fmt_name):
+    # a property that holds at any size and checks EVERY output of the benchmark-shape GEMM: an output
+    # element depends on one row of A and one row of B and is accumulated in a fixed order along K, so
+    # permuting the rows of A (of B) permutes the rows (columns) of the result bit for bit -- whatever
+    # tile, wave and lane a row lands in.  (Sampled outputs of these shapes are checked against the
+    # oracle in the tests above.)
+    fmt = getattr(nv, fmt_name)
+    M, N, K = 4096, 11008, 4096
+    X = synth.normal(M, K, 1.0, 100).cuda()
+    W = synth.normal(N, K, 0.02, 200).cuda()
+    qa, qb = nv.quantize(X, 1, fmt=fmt), nv.quantize(W, 1, fmt=fmt)
+    Y = nv.gemm(qa, qb, fmt, torch.bfloat16)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    pm, pn = torch.randperm(M, device="cuda", generator=g), torch.randperm(N, device="cuda", generator=g)
+    qa2 = (qa[0][pm].contiguous(), qa[1][pm].contiguous(), qa[2])
+    qb2 = (qb[0][pn].contiguous(), qb[1][pn].contiguous(), qb[2])
+    Y2 = nv.gemm(qa2, qb2, fmt, torch.bfloat16)
+    torch.cuda.synchronize()
+    assert torch.equal(Y2, Y[pm][:, pn])
