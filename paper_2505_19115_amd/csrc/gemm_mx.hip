@@ -38,9 +38,13 @@ __device__ __forceinline__ uint16_t mx_bf16_rne(float f)
 // one packed convert pair and one 8-byte (bf16) or 16-byte (fp32) store per four outputs; edge
 // tiles store element by element.  The lane coordinates are re-derived from an opaque copy so
 // that none of the output addressing is computed before the K loop and kept in registers across it.
+// lds_lines: 32 KB of LDS that no wave reads and no load writes any more (the caller has waited and
+// synchronized), or nullptr.  With it, bf16 output goes out in complete lines: per accumulator row
+// of tiles a wave transposes its 32 rows x 128 columns through a private 8 KB piece (16-byte chunks
+// XOR-swizzled by row) and stores 4 rows of 256 contiguous bytes per instruction.
 template <int OUT_DT>
 __device__ __forceinline__ void mx_store_tile(const GemmArgs &P, float16v_t (&acc)[mx::TA][mx::TB], int64_t m0, int64_t n0,
-                                              int lane, int wave)
+                                              int lane, int wave, uint8_t *lds_lines = nullptr)
 {
     using namespace mx;
     int lane_e = lane, wave_e = wave;
@@ -51,7 +55,34 @@ __device__ __forceinline__ void mx_store_tile(const GemmArgs &P, float16v_t (&ac
     const int64_t row0 = m0 + wme * 128 + re, col0 = n0 + wne * 128 + 4 * ge;
     uint8_t *const out = reinterpret_cast<uint8_t *>(P.out);
     const bool fast = m0 + BM <= P.M && n0 + BN <= P.N && (P.ldc & 3) == 0 && (reinterpret_cast<uintptr_t>(P.out) & 15) == 0;
-    if (fast) {
+    if (OUT_DT == NVFP4_BF16 && lds_lines != nullptr && fast && (P.ldc & 7) == 0) {
+        uint8_t *const mine = lds_lines + __builtin_amdgcn_readfirstlane(wave_e) * 8192;
+#pragma unroll
+        for (int a = 0; a < TA; ++a) {
+#pragma unroll
+            for (int b = 0; b < TB; ++b)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float2v_t lo = {acc[a][b][4 * q] * gg, acc[a][b][4 * q + 1] * gg};
+                    const float2v_t hi = {acc[a][b][4 * q + 2] * gg, acc[a][b][4 * q + 3] * gg};
+                    const bf16x2_t blo = __builtin_convertvector(lo, bf16x2_t), bhi = __builtin_convertvector(hi, bf16x2_t);
+                    uint2 w;
+                    w.x = *reinterpret_cast<const uint32_t *>(&blo);
+                    w.y = *reinterpret_cast<const uint32_t *>(&bhi);
+                    const int chunk = 4 * b + q;  // columns 8 chunk .. 8 chunk + 7 of the wave's 128
+                    *reinterpret_cast<uint2 *>(mine + re * 256 + ((chunk ^ (re & 15)) << 4) + 8 * ge) = w;
+                }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int rowl = 4 * i + (lane_e >> 4), chunk = lane_e & 15;
+                const uint4 v = *reinterpret_cast<const uint4 *>(mine + rowl * 256 + ((chunk ^ (rowl & 15)) << 4));
+                const int64_t grow = m0 + wme * 128 + 32 * a + rowl, gcol = n0 + wne * 128 + 8 * chunk;
+                *reinterpret_cast<uint4 *>(out + (grow * P.ldc + gcol) * 2) = v;
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
+    } else if (fast) {
 #pragma unroll
         for (int a = 0; a < TA; ++a) {
             uint8_t *prow = out + ((row0 + 32 * a) * P.ldc + col0) * ESZ;
@@ -474,7 +505,11 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
 #undef NVFP4_MXD_WAIT
 #undef NVFP4_MXD_MMA
 
-    mx_store_tile<OUT_DT>(P, acc, m0, n0, lane, wave);
+    // every load of every wave has landed and every fragment has been read: stage 0 is free for
+    // the epilogue's line buffers
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    mx_store_tile<OUT_DT>(P, acc, m0, n0, lane, wave, lds);
 }
 
 static void launch_mx_dma(const GemmArgs &P, int out_dt, hipStream_t st)
