@@ -439,3 +439,24 @@ def test_full_size_outputs_follow_row_permutations(fmt_name):
     Y2 = nv.gemm(qa2, qb2, fmt, torch.bfloat16)
     torch.cuda.synchronize()
     assert torch.equal(Y2, Y[pm][:, pn])
+
+
+@pytest.mark.parametrize("pad", [0, 4, 8])
+def test_large_tile_bf16_output_with_padded_rows(pad):
+    # the 8-wave kernel's bf16 epilogue writes complete lines through LDS when the output rows are
+    # 16-byte aligned (pad 0, 8) and falls back to 8-byte stores otherwise (pad 4); both into a
+    # wider buffer whose padding must stay untouched
+    M, N, K = 2816, 3072, 256
+    rng = np.random.default_rng(77 + pad)
+    A, B = random_operand(rng, M, K, lo=0x30, hi=0x48, g=0.5), random_operand(rng, N, K, lo=0x30, hi=0x48, g=0.25)
+    for fmt, a, b in ((nv.NVFP4, A, B), (nv.MXFP4, mx_operand(rng, M, K), mx_operand(rng, N, K))):
+        print(f"[case] padded bf16 output pad={pad} fmt={fmt}", flush=True)
+        buf = torch.full((M, N + pad), -3.0, dtype=torch.bfloat16, device="cuda")
+        nv.gemm(dev(a), dev(b), fmt, out=buf[:, :N])
+        torch.cuda.synchronize()
+        ref = oracle.gemm_nt(a, b, ofmt(fmt))
+        ref_abs = oracle.gemm_nt(a, b, ofmt(fmt), take_abs=True)
+        got = to_np(buf[:, :N].float())
+        assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * ref_abs)
+        if pad:
+            assert torch.all(buf[:, N:] == -3.0)
