@@ -57,7 +57,24 @@ struct QuantPlan {
     const float *g_src;
     float *g_out;
     int g_mode;
+    int n_partials = 0;
 };
+
+// Where a quantizer finds the tensor maximum: one folded bit pattern (n == 0) or n partial maxima.
+struct GSource {
+    const float *src;
+    int n;
+};
+constexpr size_t PARTIAL_SLOT = 4 * (size_t)AMAX_DENSE_PARTIALS;  // bytes of one tensor's partial maxima
+
+// Maximum pass over a dense tensor into slot `slot` of the workspace's partials area; the
+// quantizers fold the partials themselves, so no fold kernel runs between the two.
+hipError_t amax_dense(const void *x, int dt, int64_t n_elements, uint32_t *partials, int slot, hipStream_t st, GSource *g)
+{
+    uint32_t *dst = partials + slot * AMAX_DENSE_PARTIALS;
+    g->src = reinterpret_cast<const float *>(dst);
+    return launch_tensor_amax_dense(x, dt, n_elements, dst, &g->n, st);
+}
 
 hipError_t run_quantize(const QuantPlan &q, const nvfp4_format *f, hipStream_t st)
 {
@@ -72,6 +89,7 @@ hipError_t run_quantize(const QuantPlan &q, const nvfp4_format *f, hipStream_t s
     a.g_out = q.g_out;
     a.g_mode = q.g_mode;
     a.seed = q.seed;
+    a.n_partials = q.n_partials;
     return launch_quantize(a, q.dt, q.axis, q.rounding, f->block, f->scale, use_hw_convert(), st);
 }
 
@@ -128,8 +146,9 @@ size_t nvfp4_scales_bytes(int64_t rows, int64_t cols, int axis, const nvfp4_form
 // needs at least as many as the dense one)
 static size_t partials_bytes(int64_t rows, int64_t cols)
 {
-    if (rows <= 0 || cols <= 0) return WS_ALIGN;
-    return align_up(4 * (size_t)tensor_amax_partials(rows, cols, cols + 8));
+    if (rows <= 0 || cols <= 0) return align_up(3 * PARTIAL_SLOT);
+    const size_t strided = align_up(4 * (size_t)tensor_amax_partials(rows, cols, cols + 8));
+    return strided > 3 * PARTIAL_SLOT ? strided : align_up(3 * PARTIAL_SLOT);  // up to three dense tensors side by side
 }
 
 size_t nvfp4_quantize_workspace_bytes(int64_t rows, int64_t cols) { return WS_HEADER + partials_bytes(rows, cols); }
@@ -213,11 +232,17 @@ nvfp4_status nvfp4_quantize(const void *x, nvfp4_dtype dt, int64_t rows, int64_t
         } else {
             uint32_t *bits = reinterpret_cast<uint32_t *>(workspace);
             uint32_t *partials = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(workspace) + WS_HEADER);
-            // an empty tensor gets its scale (1) written here; otherwise the quantizer writes it
-            if (launch_tensor_amax(x, dt, rows, cols, ld, bits, partials, empty ? tensor_scale : nullptr, st) != hipSuccess)
-                return NVFP4_EHIP;
             q.g_src = reinterpret_cast<const float *>(bits);
             q.g_mode = G_FROM_AMAX;
+            if (!empty && ld == cols) {
+                GSource g;
+                if (amax_dense(x, dt, rows * cols, partials, 0, st, &g) != hipSuccess) return NVFP4_EHIP;
+                q.g_src = g.src;
+                q.n_partials = g.n;
+            } else if (launch_tensor_amax(x, dt, rows, cols, ld, bits, partials, empty ? tensor_scale : nullptr, st) != hipSuccess) {
+                // (an empty tensor gets its scale (1) written there; otherwise the quantizer writes it)
+                return NVFP4_EHIP;
+            }
         }
     }
     if (empty) return NVFP4_OK;  // nothing to encode
@@ -272,10 +297,16 @@ nvfp4_status nvfp4_quantize_dual(const void *x, nvfp4_dtype dt, int64_t rows, in
         } else {
             uint32_t *bits = reinterpret_cast<uint32_t *>(workspace);
             uint32_t *partials = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(workspace) + WS_HEADER);
-            if (launch_tensor_amax(x, dt, rows, cols, ld, bits, partials, empty ? tensor_scale : nullptr, st) != hipSuccess)
-                return NVFP4_EHIP;
             d.c.g_src = reinterpret_cast<const float *>(bits);
             d.c.g_mode = G_FROM_AMAX;
+            if (!empty && ld == cols) {
+                GSource g;
+                if (amax_dense(x, dt, rows * cols, partials, 0, st, &g) != hipSuccess) return NVFP4_EHIP;
+                d.c.g_src = g.src;
+                d.c.n_partials = g.n;
+            } else if (launch_tensor_amax(x, dt, rows, cols, ld, bits, partials, empty ? tensor_scale : nullptr, st) != hipSuccess) {
+                return NVFP4_EHIP;
+            }
         }
     }
     if (empty) return NVFP4_OK;
@@ -341,23 +372,22 @@ nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, 
     uint8_t *wsc = p;
 
     const int gm = f->tensor_scale ? G_FROM_AMAX : G_NONE;
+    GSource gx{reinterpret_cast<const float *>(amax + 0), 0}, gw{reinterpret_cast<const float *>(amax + 1), 0};
     if (f->tensor_scale) {
-        if (launch_tensor_amax(X, in_dt, M, K, K, amax + 0, partials, nullptr, st) != hipSuccess) return NVFP4_EHIP;
-        if (launch_tensor_amax(W, in_dt, N, K, K, amax + 1, partials, nullptr, st) != hipSuccess) return NVFP4_EHIP;
+        if (amax_dense(X, in_dt, M * K, partials, 0, st, &gx) != hipSuccess) return NVFP4_EHIP;
+        if (amax_dense(W, in_dt, N * K, partials, 1, st, &gw) != hipSuccess) return NVFP4_EHIP;
     }
     if (saved) {
         // one pass over X and one over W also leave what Eqs. 5-6 need of them: Q_SR(X^T) with
         // the backward call's third stream, and Q_RtN(W^T)
         const SavedLayout L = saved_layout(saved, M, N, K, f->block);
-        DualArgs dx{{X, M, K, K, L.xtc, L.xts, reinterpret_cast<const float *>(amax + 0), ts + 0, gm, bwd_seed + 2},
-                    xc, xs, 0, L.g + 0};
-        DualArgs dw{{W, N, K, K, L.wtc, L.wts, reinterpret_cast<const float *>(amax + 1), ts + 1, gm, 0},
-                    wc, wsc, 0, L.g + 1};
+        DualArgs dx{{X, M, K, K, L.xtc, L.xts, gx.src, ts + 0, gm, bwd_seed + 2, gx.n}, xc, xs, 0, L.g + 0};
+        DualArgs dw{{W, N, K, K, L.wtc, L.wts, gw.src, ts + 1, gm, 0, gw.n}, wc, wsc, 0, L.g + 1};
         if (launch_quantize_dual(dx, in_dt, NVFP4_RTN, NVFP4_SR, f->block, f->scale, use_hw_convert(), st) != hipSuccess) return NVFP4_EHIP;
         if (launch_quantize_dual(dw, in_dt, NVFP4_RTN, NVFP4_RTN, f->block, f->scale, use_hw_convert(), st) != hipSuccess) return NVFP4_EHIP;
     } else {
-        QuantPlan qx{X, in_dt, M, K, K, 1, NVFP4_RTN, 0, xc, xs, reinterpret_cast<const float *>(amax + 0), ts + 0, gm};
-        QuantPlan qw{W, in_dt, N, K, K, 1, NVFP4_RTN, 0, wc, wsc, reinterpret_cast<const float *>(amax + 1), ts + 1, gm};
+        QuantPlan qx{X, in_dt, M, K, K, 1, NVFP4_RTN, 0, xc, xs, gx.src, ts + 0, gm, gx.n};
+        QuantPlan qw{W, in_dt, N, K, K, 1, NVFP4_RTN, 0, wc, wsc, gw.src, ts + 1, gm, gw.n};
         if (run_quantize(qx, f, st) != hipSuccess) return NVFP4_EHIP;
         if (run_quantize(qw, f, st) != hipSuccess) return NVFP4_EHIP;
     }
@@ -421,10 +451,11 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
     // X and W: scales handed over from the forward call (used as given), else from their maxima
     const bool known = f->tensor_scale && xw_scales != nullptr;
     const int gm_xw = known ? G_PRESET : gm;
-    const float *gsrc_w = known ? xw_scales + 1 : reinterpret_cast<const float *>(amax + 1);
-    const float *gsrc_x = known ? xw_scales + 0 : reinterpret_cast<const float *>(amax + 2);
+    GSource gdy{reinterpret_cast<const float *>(amax + 0), 0};
+    GSource gw{known ? xw_scales + 1 : reinterpret_cast<const float *>(amax + 1), 0};
+    GSource gx{known ? xw_scales + 0 : reinterpret_cast<const float *>(amax + 2), 0};
     if (f->tensor_scale) {
-        if (launch_tensor_amax(dY, in_dt, M, N, N, amax + 0, partials, nullptr, st) != hipSuccess) return NVFP4_EHIP;
+        if (amax_dense(dY, in_dt, M * N, partials, 0, st, &gdy) != hipSuccess) return NVFP4_EHIP;
     }
     // with both GEMMs wanted, dY is read once for its two orientations (streams seed, seed+1)
     const bool dual = dX && dW && quantize_dual_fused(in_dt, M, N, N, f->block, use_hw_convert());
@@ -436,7 +467,8 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
         d.c.ld = N;
         d.c.codes = dytc;
         d.c.scales = dyts;
-        d.c.g_src = reinterpret_cast<const float *>(amax + 0);
+        d.c.g_src = gdy.src;
+        d.c.n_partials = gdy.n;
         d.c.g_out = ts + 0;
         d.c.g_mode = gm;
         d.c.seed = seed + 1;
@@ -447,20 +479,20 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
         if (launch_quantize_dual(d, in_dt, NVFP4_SR, NVFP4_SR, f->block, f->scale, true, st) != hipSuccess) return NVFP4_EHIP;
     }
     if (dX) {
-        if (f->tensor_scale && !known && !saved && launch_tensor_amax(W, in_dt, N, K, K, amax + 1, partials, nullptr, st) != hipSuccess) return NVFP4_EHIP;
+        if (f->tensor_scale && !known && !saved && amax_dense(W, in_dt, N * K, partials, 1, st, &gw) != hipSuccess) return NVFP4_EHIP;
         // Eq. 5: dX[M, K] = Q_SR(dY)[M, N] * Q_RtN(W^T)[K, N]^T
-        QuantPlan qa{dY, in_dt, M, N, N, 1, NVFP4_SR, seed, dyc, dys, reinterpret_cast<const float *>(amax + 0), ts + 0, gm};
-        QuantPlan qb{W, in_dt, N, K, K, 0, NVFP4_RTN, 0, wtc, wts, gsrc_w, ts + 1, gm_xw};
+        QuantPlan qa{dY, in_dt, M, N, N, 1, NVFP4_SR, seed, dyc, dys, gdy.src, ts + 0, gm, gdy.n};
+        QuantPlan qb{W, in_dt, N, K, K, 0, NVFP4_RTN, 0, wtc, wts, gw.src, ts + 1, gm_xw, gw.n};
         if (!dual && run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
         if (!saved && run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
         GemmArgs g{M, K, N, dyc, dys, wtc, wts, ts + 0, g_w, dX, K};
         if (launch_gemm(g, f->block, f->scale, out_dt, st) != hipSuccess) return NVFP4_EHIP;
     }
     if (dW) {
-        if (f->tensor_scale && !known && !saved && launch_tensor_amax(X, in_dt, M, K, K, amax + 2, partials, nullptr, st) != hipSuccess) return NVFP4_EHIP;
+        if (f->tensor_scale && !known && !saved && amax_dense(X, in_dt, M * K, partials, 2, st, &gx) != hipSuccess) return NVFP4_EHIP;
         // Eq. 6: dW[N, K] = Q_SR(dY^T)[N, M] * Q_SR(X^T)[K, M]^T
-        QuantPlan qa{dY, in_dt, M, N, N, 0, NVFP4_SR, seed + 1, dytc, dyts, reinterpret_cast<const float *>(amax + 0), ts + 2, gm};
-        QuantPlan qb{X, in_dt, M, K, K, 0, NVFP4_SR, seed + 2, xtc, xts, gsrc_x, ts + 3, gm_xw};
+        QuantPlan qa{dY, in_dt, M, N, N, 0, NVFP4_SR, seed + 1, dytc, dyts, gdy.src, ts + 2, gm, gdy.n};
+        QuantPlan qb{X, in_dt, M, K, K, 0, NVFP4_SR, seed + 2, xtc, xts, gx.src, ts + 3, gm_xw, gx.n};
         if (!dual && run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
         if (!saved && run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
         GemmArgs g{N, K, M, dytc, dyts, xtc, xts, ts + 2, g_x, dW, K};

@@ -14,10 +14,12 @@ struct QuantArgs {
     int64_t rows, cols, ld;
     uint8_t *codes;       // axis 1: [rows, cols/2]; axis 0: [cols, rows/2]
     uint8_t *scales;      // axis 1: [rows, cols/B]; axis 0: [cols, rows/B]
-    const float *g_src;   // G_PRESET: the scale; G_FROM_AMAX: bit pattern of max|x|
+    const float *g_src;   // G_PRESET: the scale; G_FROM_AMAX: bit pattern of max|x| (n_partials == 0) or
+                          // n_partials per-workgroup maxima that every workgroup folds for itself
     float *g_out;         // receives the scale actually used
     int g_mode;
     uint64_t seed;
+    int n_partials = 0;
 };
 
 // Both orientations of one tensor: c describes the tensor and the column-blocked outputs
@@ -61,6 +63,10 @@ __device__ __forceinline__ void tile_coords(int wg, int ntx, int nty, int &ty, i
 
 hipError_t launch_tensor_amax(const void *x, int dt, int64_t rows, int64_t cols, int64_t ld,
                               uint32_t *amax_bits, uint32_t *partials, float *g_out, hipStream_t st);
+// Dense tensors only: at most AMAX_DENSE_PARTIALS partial maxima into `partials`, no fold kernel
+// (the consuming quantizer folds them: QuantArgs::n_partials).  Returns their number in *n.
+constexpr int AMAX_DENSE_PARTIALS = 512;
+hipError_t launch_tensor_amax_dense(const void *x, int dt, int64_t n_elements, uint32_t *partials, int *n, hipStream_t st);
 hipError_t launch_quantize(const QuantArgs &P, int dt, int axis, int rounding, int block, int sf,
                            bool hw_convert, hipStream_t st);
 // Row-blocked and column-blocked quantization of one tensor; one fused kernel when

@@ -138,6 +138,9 @@ __device__ __forceinline__ float chunk_amax(const Chunk<DT> &c)
 
 // Per-tensor scale as the kernels see it: none, preset in memory, or the bit pattern of the
 // tensor maximum left by the amax kernel.
+// With n_partials > 0 the tensor maximum arrives as that many per-workgroup maxima and every
+// workgroup (256 threads, all of them must call this) folds them for itself: 2 KB from the L2 per
+// workgroup instead of a separate one-workgroup kernel between the maximum pass and the quantizer.
 __device__ __forceinline__ float resolve_g(const QuantArgs &P)
 {
     if (P.g_mode == G_NONE) return 1.0f;
@@ -145,7 +148,17 @@ __device__ __forceinline__ float resolve_g(const QuantArgs &P)
         float g = *P.g_src;
         return g < tensor_scale_floor() ? tensor_scale_floor() : g;
     }
-    return tensor_scale_from_amax(u2f(*reinterpret_cast<const uint32_t *>(P.g_src)));
+    const uint32_t *bits = reinterpret_cast<const uint32_t *>(P.g_src);
+    if (P.n_partials == 0) return tensor_scale_from_amax(u2f(*bits));
+    __shared__ uint32_t fold[16];
+    uint32_t m = 0;
+    for (int i = threadIdx.x; i < P.n_partials; i += 256) m = umax(m, bits[i]);
+    m = f2u(group_max<16>(u2f(m)));
+    if ((threadIdx.x & 15) == 0) fold[threadIdx.x >> 4] = m;
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < 16; ++t) m = umax(m, fold[t]);
+    return tensor_scale_from_amax(u2f(m));
 }
 
 // Block scale byte and the multiplier q that maps the block onto the E2M1 range.
@@ -253,6 +266,44 @@ __global__ __launch_bounds__(256) void amax_kernel(const void *x, int64_t cols, 
     }
 }
 
+// Dense tensors: a fixed grid of large workgroups strides over the chunks, one partial each.
+constexpr int AMAX_DENSE_THREADS = 1024;
+template <int DT>
+__global__ __launch_bounds__(AMAX_DENSE_THREADS) void amax_dense_kernel(const void *x, int64_t n, uint32_t *part_out)
+{
+    const int64_t nchunk = n >> 3;
+    const int64_t stride = (int64_t)gridDim.x * (AMAX_DENSE_THREADS * AMAX_UNROLL);
+    float a = 0.0f;
+    for (int64_t base = (int64_t)blockIdx.x * (AMAX_DENSE_THREADS * AMAX_UNROLL) + threadIdx.x; base < nchunk; base += stride) {
+        Chunk<DT> v[AMAX_UNROLL];
+#pragma unroll
+        for (int u = 0; u < AMAX_UNROLL; ++u) {
+            const int64_t c = base + u * AMAX_DENSE_THREADS;
+            if (c < nchunk)
+                v[u].template load<false>(x, c * 8);
+            else
+                v[u].zero();
+        }
+#pragma unroll
+        for (int u = 0; u < AMAX_UNROLL; ++u) a = fmaxf(a, chunk_amax(v[u]));
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0 && (n & 7)) {
+        Chunk<DT> t;
+        t.load_partial(x, nchunk * 8, (int)(n & 7));
+        a = fmaxf(a, chunk_amax(t));
+    }
+    a = group_max<16>(a);
+    __shared__ uint32_t part[AMAX_DENSE_THREADS / 16];
+    if ((threadIdx.x & 15) == 0) part[threadIdx.x >> 4] = f2u(a);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t m = 0;
+#pragma unroll
+        for (int t = 0; t < AMAX_DENSE_THREADS / 16; ++t) m = umax(m, part[t]);
+        part_out[blockIdx.x] = m;
+    }
+}
+
 // Folds n partial maxima into amax_bits[0]; with g_out != nullptr also writes the tensor scale.
 __global__ __launch_bounds__(1024) void fold_amax_kernel(const uint32_t *partials, int64_t n,
                                                          uint32_t *amax_bits, float *g_out)
@@ -282,10 +333,6 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(QuantArgs P)
     constexpr int LPB = B / 8;  // lanes per block
     const int64_t cpr = P.cols >> 3;
     const int64_t total = P.rows * cpr;
-    const float g = resolve_g(P);
-    const float k = 1.0f / (6.0f * g);
-    if (blockIdx.x == 0 && threadIdx.x == 0) *P.g_out = g;
-
     const int64_t base = (int64_t)blockIdx.x * (256 * ROWS_UNROLL) + threadIdx.x;
     const bool dense = P.ld == P.cols;
     Chunk<DT> v[ROWS_UNROLL];
@@ -303,6 +350,10 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(QuantArgs P)
             v[u].zero();
         }
     }
+    // (after the loads are issued: folding the partial maxima then overlaps their latency)
+    const float g = resolve_g(P);
+    const float k = 1.0f / (6.0f * g);
+    if (blockIdx.x == 0 && threadIdx.x == 0) *P.g_out = g;
 #pragma unroll
     for (int u = 0; u < ROWS_UNROLL; ++u) {
         const int64_t id = base + u * 256;
@@ -418,10 +469,6 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(QuantArgs P)
     constexpr int NB = RPL / BL;                 // blocks (or block parts) per lane per column
     constexpr int LPB = B / BL;                  // lanes sharing one block
 
-    const float g = resolve_g(P);
-    const float k = 1.0f / (6.0f * g);
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *P.g_out = g;
-
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int lv = lane % G::LANES_V, lh = lane / G::LANES_V;
     const int64_t row0 = (int64_t)blockIdx.y * G::WG_ROWS + lv * RPL;
@@ -439,6 +486,9 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(QuantArgs P)
         else
             v[r].zero();
     }
+    const float g = resolve_g(P);
+    const float k = 1.0f / (6.0f * g);
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *P.g_out = g;
     cols_tile<DT, B, SF, RND, HW, ALIGNED, LV>(P, v, g, k, row0, col0, ncol, lv);
 }
 
@@ -577,12 +627,6 @@ __global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
     __shared__ __align__(16) uint8_t lds_scales[G::WG_ROWS * 16];
 
     const QuantArgs &P = D.c;
-    const float g = resolve_g(P);
-    const float k = 1.0f / (6.0f * g);
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
-        *P.g_out = g;
-        if (D.g_out2) *D.g_out2 = g;
-    }
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int lv = lane % G::LANES_V, lh = lane / G::LANES_V;
@@ -598,6 +642,13 @@ __global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
             v[r].template load<true>(P.x, (row0 + r) * P.ld + col0);
         else
             v[r].zero();
+    }
+
+    const float g = resolve_g(P);
+    const float k = 1.0f / (6.0f * g);
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+        *P.g_out = g;
+        if (D.g_out2) *D.g_out2 = g;
     }
 
     // row-blocked side: one block scale and 8 codes per row of the lane tile
@@ -716,6 +767,18 @@ hipError_t launch_tensor_amax(const void *x, int dt, int64_t rows, int64_t cols,
                                base, span_cols, ld, partials + r0 * gx);
     }
     hipLaunchKernelGGL(fold_amax_kernel, dim3(1), dim3(1024), 0, st, partials, gx * span_rows, amax_bits, g_out);
+    return launch_status();
+}
+
+hipError_t launch_tensor_amax_dense(const void *x, int dt, int64_t n_elements, uint32_t *partials, int *n, hipStream_t st)
+{
+    int64_t gx = ((n_elements >> 3) + AMAX_DENSE_THREADS * AMAX_UNROLL - 1) / (AMAX_DENSE_THREADS * AMAX_UNROLL);
+    gx = gx < 1 ? 1 : (gx > AMAX_DENSE_PARTIALS ? AMAX_DENSE_PARTIALS : gx);
+    if (dt == NVFP4_BF16)
+        hipLaunchKernelGGL(amax_dense_kernel<NVFP4_BF16>, dim3((unsigned)gx), dim3(AMAX_DENSE_THREADS), 0, st, x, n_elements, partials);
+    else
+        hipLaunchKernelGGL(amax_dense_kernel<NVFP4_F32>, dim3((unsigned)gx), dim3(AMAX_DENSE_THREADS), 0, st, x, n_elements, partials);
+    *n = (int)gx;
     return launch_status();
 }
 
