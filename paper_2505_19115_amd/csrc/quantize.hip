@@ -163,12 +163,24 @@ __device__ __forceinline__ float resolve_g(const QuantArgs &P)
 
 // Block scale byte and the multiplier q that maps the block onto the E2M1 range.
 // q = 0 for a block whose magnitudes are all zero.
-template <int SF>
+// HW: the E4M3 byte and its value come from the gfx950 FP8 converts (OCP E4M3, round to nearest
+// even; the input is clamped to 448 first, as in the software encode, so the convert never sees
+// an out-of-range value).  Checked against e4m3_encode / e4m3_decode on every non-negative fp32
+// up to 512: identical bytes and values.  The software formulation costs ~15 instructions per block.
+template <int SF, bool HW = false>
 __device__ __forceinline__ uint32_t block_scale(float a, float g, float k, float *q)
 {
     if (SF == NVFP4_SCALE_E4M3) {
         float s;
-        uint32_t byte = e4m3_encode(a * k, &s);
+        uint32_t byte;
+        if (HW) {
+            const float r = a * k;
+            const float rc = r < 448.0f ? r : 448.0f;
+            byte = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(rc, 0.0f, 0, false) & 0xFFu;
+            s = __builtin_amdgcn_cvt_f32_fp8((int)byte, 0);
+        } else {
+            byte = e4m3_encode(a * k, &s);
+        }
         float d = s * g;
         *q = byte == 0 ? 0.0f : 1.0f / d;
         return byte;
@@ -361,7 +373,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(QuantArgs P)
         // either all live or all holding zeros
         const float a = group_max<LPB>(chunk_amax(v[u]));
         float q;
-        const uint32_t sbyte = block_scale<SF>(a, g, k, &q);
+        const uint32_t sbyte = block_scale<SF, HW>(a, g, k, &q);
         uint32_t packed = 0;
         if (RND == NVFP4_RTN && HW) {
 #pragma unroll
@@ -517,7 +529,7 @@ __device__ __forceinline__ void cols_tile(const QuantArgs &P, Chunk<DT> (&v)[16]
 #pragma unroll
             for (int r = 0; r < BL; ++r) a = fmaxf(a, fabsf(v[nb * BL + r].get(c)));
             a = group_max<LPB>(a);
-            sbytes[c][nb] = block_scale<SF>(a, g, k, &q[c][nb]);
+            sbytes[c][nb] = block_scale<SF, HW>(a, g, k, &q[c][nb]);
         }
     }
 
@@ -661,7 +673,7 @@ __global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
             a = u2f(umax(f2u(a), o));
         }
         float q;
-        const uint32_t sbyte = block_scale<SF>(a, g, k, &q);
+        const uint32_t sbyte = block_scale<SF, true>(a, g, k, &q);
         uint32_t packed = 0;
         if (RND_R == NVFP4_RTN) {
 #pragma unroll
