@@ -379,8 +379,33 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
     constexpr int ESZ = OUT_DT == NVFP4_F32 ? 4 : 2;
     const int64_t row0 = m0 + wm * 32 * TA + r, col0 = n0 + wn * 32 * TB + 4 * h;
     const bool fast = m0 + BM <= P.M && n0 + BN <= P.N && (P.ldc & 3) == 0 && (reinterpret_cast<uintptr_t>(P.out) & 15) == 0;
-    constexpr bool LINES = OUT_DT == NVFP4_BF16 && TA == 4 && TB == 2 && !KTAIL;  // 128 x 64 per wave: 128-byte rows
-    if (LINES && fast && (P.ldc & 7) == 0) {
+    constexpr bool LINES = TA == 4 && TB == 2 && !KTAIL;  // 128 x 64 per wave: 128-byte (bf16) or 256-byte (fp32) rows
+    if (LINES && OUT_DT == NVFP4_F32 && fast) {
+        // fp32: 32 rows x 256 bytes at a time through the wave's 8 KB, four complete rows per store
+        __syncthreads();
+        uint8_t *const out = reinterpret_cast<uint8_t *>(P.out);
+        uint8_t *const mine = lds + wave * 8192;
+#pragma unroll
+        for (int a = 0; a < TA; ++a) {
+#pragma unroll
+            for (int b = 0; b < TB; ++b)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int chunk = 8 * b + 2 * q + h;  // columns 4 chunk .. 4 chunk + 3 of the wave's 64
+                    *reinterpret_cast<float4 *>(mine + r * 256 + ((chunk ^ (r & 15)) << 4)) =
+                        make_float4(acc[a][b][4 * q] * gg, acc[a][b][4 * q + 1] * gg, acc[a][b][4 * q + 2] * gg, acc[a][b][4 * q + 3] * gg);
+                }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int rowl = 4 * i + (lane >> 4), chunk = lane & 15;
+                const uint4 v = *reinterpret_cast<const uint4 *>(mine + rowl * 256 + ((chunk ^ (rowl & 15)) << 4));
+                const int64_t grow = m0 + wm * 128 + 32 * a + rowl, gcol = n0 + wn * 64 + 4 * chunk;
+                *reinterpret_cast<uint4 *>(out + (grow * P.ldc + gcol) * 4) = v;
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
+    } else if (LINES && OUT_DT == NVFP4_BF16 && fast && (P.ldc & 7) == 0) {
         // Full-line output: the wave transposes its accumulators through a private 8 KB piece of
         // LDS (64 rows x 128 bytes at a time, 16-byte chunks XOR-swizzled by row) so that a store
         // instruction writes 8 complete 128-byte rows instead of 32 pieces of 16 bytes.

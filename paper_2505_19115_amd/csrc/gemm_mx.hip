@@ -38,7 +38,7 @@ __device__ __forceinline__ uint16_t mx_bf16_rne(float f)
 // one packed convert pair and one 8-byte (bf16) or 16-byte (fp32) store per four outputs; edge
 // tiles store element by element.  The lane coordinates are re-derived from an opaque copy so
 // that none of the output addressing is computed before the K loop and kept in registers across it.
-// lds_lines: 32 KB of LDS that no wave reads and no load writes any more (the caller has waited and
+// lds_lines: 64 KB of LDS (32 KB suffice for bf16) that no wave reads and no load writes any more (the caller has waited and
 // synchronized), or nullptr.  With it, bf16 output goes out in complete lines: per accumulator row
 // of tiles a wave transposes its 32 rows x 128 columns through a private 8 KB piece (16-byte chunks
 // XOR-swizzled by row) and stores 4 rows of 256 contiguous bytes per instruction.
@@ -55,7 +55,30 @@ __device__ __forceinline__ void mx_store_tile(const GemmArgs &P, float16v_t (&ac
     const int64_t row0 = m0 + wme * 128 + re, col0 = n0 + wne * 128 + 4 * ge;
     uint8_t *const out = reinterpret_cast<uint8_t *>(P.out);
     const bool fast = m0 + BM <= P.M && n0 + BN <= P.N && (P.ldc & 3) == 0 && (reinterpret_cast<uintptr_t>(P.out) & 15) == 0;
-    if (OUT_DT == NVFP4_BF16 && lds_lines != nullptr && fast && (P.ldc & 7) == 0) {
+    if (OUT_DT == NVFP4_F32 && lds_lines != nullptr && fast) {
+        // fp32: 32 rows x 512 bytes at a time (16 KB per wave), two complete rows per store
+        uint8_t *const mine = lds_lines + __builtin_amdgcn_readfirstlane(wave_e) * 16384;
+#pragma unroll
+        for (int a = 0; a < TA; ++a) {
+#pragma unroll
+            for (int b = 0; b < TB; ++b)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int chunk = 8 * b + 2 * q + ge;  // columns 4 chunk .. 4 chunk + 3 of the wave's 128
+                    *reinterpret_cast<float4 *>(mine + re * 512 + ((chunk ^ (re & 15)) << 4)) =
+                        make_float4(acc[a][b][4 * q] * gg, acc[a][b][4 * q + 1] * gg, acc[a][b][4 * q + 2] * gg, acc[a][b][4 * q + 3] * gg);
+                }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int rowl = 2 * i + (lane_e >> 5), chunk = lane_e & 31;
+                const uint4 v = *reinterpret_cast<const uint4 *>(mine + rowl * 512 + ((chunk ^ (rowl & 15)) << 4));
+                const int64_t grow = m0 + wme * 128 + 32 * a + rowl, gcol = n0 + wne * 128 + 4 * chunk;
+                *reinterpret_cast<uint4 *>(out + (grow * P.ldc + gcol) * 4) = v;
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
+    } else if (OUT_DT == NVFP4_BF16 && lds_lines != nullptr && fast && (P.ldc & 7) == 0) {
         uint8_t *const mine = lds_lines + __builtin_amdgcn_readfirstlane(wave_e) * 8192;
 #pragma unroll
         for (int a = 0; a < TA; ++a) {
