@@ -107,7 +107,8 @@ nvfp4_status nvfp4_tensor_scale(const void *x, nvfp4_dtype dt, int64_t rows, int
  *
  * rounding (Sec. 3.2, Eqs. 4-6): NVFP4_RTN = nearest grid value, ties to the
  * even code; NVFP4_SR = round up with probability equal to the relative
- * distance from the lower neighbour, drawn from 16 bits of Philox4x32-10 with
+ * distance t from the lower neighbour (exactly: up iff u + 1/2 <= 65536 t for
+ * the element's 16-bit draw u), drawn from 16 bits of Philox4x32-10 with
  * key = seed and counter = (row-major index of the element in x) >> 3; the
  * draw does not depend on `axis`.  `seed` is ignored for RTN.
  *
