@@ -227,9 +227,12 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
             if (!srow_on[u]) continue;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const uint32_t b0 = (uint32_t)(gs[u] >> (8 * ((32 * j) / B))) & 0xFFu;
-                const uint32_t b1 = (uint32_t)(gs[u] >> (8 * ((32 * j + 16) / B))) & 0xFFu;
-                sS[j * (BM + BN) + tid + NT * u] = (b0 << 7) | (b1 << 23);
+                // bytes i0, i1 of the staged scale bytes -> (b0 << 7) | (b1 << 23): one byte permute
+                // (b0 into byte 0, b1 into byte 2, zeros between) and one shift
+                const int i0 = (32 * j) / B, i1 = (32 * j + 16) / B;  // (constants after unrolling)
+                const uint32_t lo = (uint32_t)gs[u], hi = (uint32_t)(gs[u] >> 32);
+                const uint32_t sel = 0x0C000C00u | (uint32_t)i0 | ((uint32_t)i1 << 16);
+                sS[j * (BM + BN) + tid + NT * u] = __builtin_amdgcn_perm(hi, lo, sel) << 7;
             }
         }
     };
