@@ -9,10 +9,11 @@
 // squares are summed in fp32 over those 8 and then accumulated in fp64, lanes / waves / workgroups
 // are combined in fp64 in a fixed order, so the result does not depend on timing.
 //   axis 1 (blocks along rows of x):  the 8 elements are 16 contiguous bytes of x (bf16);
-//   axis 0 (blocks down columns):     the operand row is a column of x; a wave covers 64
-//                                     consecutive columns, so each of its 8 element loads is one
-//                                     contiguous 128-byte (bf16) line and each lane reads 32
-//                                     contiguous code bytes (64 elements) of its column.
+//   axis 0 (blocks down columns):     the operand row is a column of x; a lane owns 4 adjacent
+//                                     columns (1 for shapes that do not allow vector loads) and a
+//                                     wave 256 consecutive ones, so each of its 8 row loads is 512
+//                                     contiguous bytes (bf16) and each lane reads 32 contiguous
+//                                     code bytes (64 elements) of each of its columns.
 #include "kernels.h"
 #include "nvfp4_math.h"
 
@@ -143,34 +144,65 @@ __global__ __launch_bounds__(NOISE_THREADS) void noise_rows_kernel(NoiseArgs P)
     reduce_and_store(sx, se, P.partials);
 }
 
-template <int DT>
+// CW = adjacent columns per lane: 4 (one 8-byte bf16 / 16-byte fp32 load per row; needs cols % 4 == 0 and
+// 16-byte aligned rows) or 1 (any shape).  A wave covers 64 CW consecutive columns.
+template <int DT, int CW>
 __global__ __launch_bounds__(NOISE_THREADS) void noise_cols_kernel(NoiseArgs P)
 {
     const float g = P.g ? *P.g : 1.0f;
-    // workgroup = 64 columns x (4 waves x 64 rows); operand row o = column of x, position n = row of x
-    const int64_t ctiles = (P.cols + 63) >> 6;
+    // workgroup = 64 CW columns x (4 waves x 64 rows); operand row o = column of x, position n = row of x
+    constexpr int ESZ = DT == NVFP4_F32 ? 4 : 2;
+    const int64_t ctiles = (P.cols + 64 * CW - 1) / (64 * CW);
     const int64_t tr = blockIdx.x / ctiles, tc = blockIdx.x - tr * ctiles;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t o = tc * 64 + lane, n0 = (tr * 4 + wave) * NOISE_COLS_SPAN;
+    const int64_t o = (tc * 64 + lane) * CW, n0 = (tr * 4 + wave) * NOISE_COLS_SPAN;
     double sx = 0.0, se = 0.0;
     if (o < P.cols && n0 < P.rows) {
         // rows is a multiple of the block, hence of 8: groups of 8 are all-or-nothing
         const int groups = (int)((P.rows - n0 < NOISE_COLS_SPAN ? P.rows - n0 : NOISE_COLS_SPAN) >> 3);
-        const uint8_t *px = reinterpret_cast<const uint8_t *>(P.x) + (n0 * P.ld + o) * (DT == NVFP4_F32 ? 4 : 2);
-        const uint32_t stride = (uint32_t)P.ld * (DT == NVFP4_F32 ? 4 : 2);  // bytes between rows (< 4 GB)
-        const uint8_t *pc = P.codes + o * (P.rows >> 1) + (n0 >> 1);
-        const uint8_t *ps = P.scales + o * (P.rows / P.block);
+        const uint8_t *px = reinterpret_cast<const uint8_t *>(P.x) + (n0 * P.ld + o) * ESZ;
+        const uint32_t stride = (uint32_t)P.ld * ESZ;  // bytes between rows (< 4 GB)
+        const int64_t crow = P.rows >> 1, srow = P.rows / P.block;  // bytes per operand row
+        const uint8_t *pc = P.codes + o * crow + (n0 >> 1);
+        const uint8_t *ps = P.scales + o * srow;
         const int bshift = P.block == 16 ? 4 : P.block == 32 ? 5 : P.block == 64 ? 6 : 7;
-        for (int k = 0; k < groups; ++k) {
-            float xs[8];
+        // the lane's codes (32 bytes per column) and scale bytes (one per 16 rows) first: a 4-byte read per
+        // group of 8 rows would fetch the same line of every column eight times, and the lines of a wave's
+        // columns do not all stay in the vector L1 in between
+        uint32_t cw[CW][8], sb[CW][4];
+#pragma unroll
+        for (int j = 0; j < CW; ++j) {
+            if (groups == 8) {
+                const uint4 lo = *reinterpret_cast<const uint4 *>(pc + j * crow), hi = *reinterpret_cast<const uint4 *>(pc + j * crow + 16);
+                cw[j][0] = lo.x; cw[j][1] = lo.y; cw[j][2] = lo.z; cw[j][3] = lo.w;
+                cw[j][4] = hi.x; cw[j][5] = hi.y; cw[j][6] = hi.z; cw[j][7] = hi.w;
+            } else {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) cw[j][k] = k < groups ? *reinterpret_cast<const uint32_t *>(pc + j * crow + k * 4) : 0u;
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) sb[j][i] = 2 * i < groups ? ps[j * srow + ((n0 + 16 * i) >> bshift)] : 0u;
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            if (k >= groups) break;
+            float xs[CW][8];
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
                 const uint8_t *p = px + (uint32_t)(k * 8 + t) * stride;
-                xs[t] = DT == NVFP4_F32 ? *reinterpret_cast<const float *>(p) : u2f((uint32_t)*reinterpret_cast<const uint16_t *>(p) << 16);
+                if (CW == 1) {
+                    xs[0][t] = DT == NVFP4_F32 ? *reinterpret_cast<const float *>(p) : u2f((uint32_t)*reinterpret_cast<const uint16_t *>(p) << 16);
+                } else if (DT == NVFP4_F32) {
+                    const float4 v = *reinterpret_cast<const float4 *>(p);
+                    xs[0][t] = v.x; xs[1 % CW][t] = v.y; xs[2 % CW][t] = v.z; xs[3 % CW][t] = v.w;
+                } else {
+                    const uint2 v = *reinterpret_cast<const uint2 *>(p);
+                    xs[0][t] = u2f(v.x << 16); xs[1 % CW][t] = u2f(v.x & 0xFFFF0000u);
+                    xs[2 % CW][t] = u2f(v.y << 16); xs[3 % CW][t] = u2f(v.y & 0xFFFF0000u);
+                }
             }
-            const uint32_t w = *reinterpret_cast<const uint32_t *>(pc + k * 4);
-            const float d = scale_of(ps[(n0 + k * 8) >> bshift], P.sf) * g;
-            accumulate8(w, d, xs, sx, se);
+#pragma unroll
+            for (int j = 0; j < CW; ++j) accumulate8(cw[j][k], scale_of(sb[j][k >> 1], P.sf) * g, xs[j], sx, se);
         }
     }
     reduce_and_store(sx, se, P.partials);
@@ -200,14 +232,20 @@ int64_t quant_noise_partials(int64_t rows, int64_t cols, int axis)
         const int64_t per_wg = (int64_t)NOISE_THREADS * NOISE_ROWS_CHUNKS;
         return (rows * (cols >> 3) + per_wg - 1) / per_wg;
     }
-    return ((cols + 63) >> 6) * ((rows + 4 * NOISE_COLS_SPAN - 1) / (4 * NOISE_COLS_SPAN));
+    return ((cols + 63) >> 6) * ((rows + 4 * NOISE_COLS_SPAN - 1) / (4 * NOISE_COLS_SPAN));  // (an upper bound when 4 columns per lane are used)
+}
+
+// workgroups of the axis-0 kernel with CW columns per lane
+static int64_t noise_cols_wgs(int64_t rows, int64_t cols, int cw)
+{
+    return ((cols + 64 * cw - 1) / (64 * cw)) * ((rows + 4 * NOISE_COLS_SPAN - 1) / (4 * NOISE_COLS_SPAN));
 }
 
 hipError_t launch_quant_noise(const void *x, int dt, int64_t rows, int64_t cols, int64_t ld, int axis, int block, int sf,
                               const uint8_t *codes, const uint8_t *scales, const float *g, double *partials, double *sums,
                               hipStream_t st)
 {
-    const int64_t nwg = quant_noise_partials(rows, cols, axis);
+    int64_t nwg = quant_noise_partials(rows, cols, axis);
     if (rows > 0 && cols > 0) {
         NoiseArgs P{x, rows, cols, ld, codes, scales, g, block, sf, partials};
         if (axis == 1) {
@@ -216,10 +254,17 @@ hipError_t launch_quant_noise(const void *x, int dt, int64_t rows, int64_t cols,
             else
                 hipLaunchKernelGGL(noise_rows_kernel<NVFP4_BF16>, dim3((unsigned)nwg), dim3(NOISE_THREADS), 0, st, P);
         } else {
-            if (dt == NVFP4_F32)
-                hipLaunchKernelGGL(noise_cols_kernel<NVFP4_F32>, dim3((unsigned)nwg), dim3(NOISE_THREADS), 0, st, P);
+            const int64_t esz = dt == NVFP4_F32 ? 4 : 2;
+            const bool wide = cols % 4 == 0 && (ld * esz) % 16 == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
+            nwg = noise_cols_wgs(rows, cols, wide ? 4 : 1);
+            if (wide && dt == NVFP4_F32)
+                hipLaunchKernelGGL((noise_cols_kernel<NVFP4_F32, 4>), dim3((unsigned)nwg), dim3(NOISE_THREADS), 0, st, P);
+            else if (wide)
+                hipLaunchKernelGGL((noise_cols_kernel<NVFP4_BF16, 4>), dim3((unsigned)nwg), dim3(NOISE_THREADS), 0, st, P);
+            else if (dt == NVFP4_F32)
+                hipLaunchKernelGGL((noise_cols_kernel<NVFP4_F32, 1>), dim3((unsigned)nwg), dim3(NOISE_THREADS), 0, st, P);
             else
-                hipLaunchKernelGGL(noise_cols_kernel<NVFP4_BF16>, dim3((unsigned)nwg), dim3(NOISE_THREADS), 0, st, P);
+                hipLaunchKernelGGL((noise_cols_kernel<NVFP4_BF16, 1>), dim3((unsigned)nwg), dim3(NOISE_THREADS), 0, st, P);
         }
         hipLaunchKernelGGL(noise_fold_kernel, dim3(1), dim3(NOISE_THREADS), 0, st, partials, nwg, sums);
     } else {

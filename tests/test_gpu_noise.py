@@ -17,9 +17,13 @@ def ofmt(fmt):
     return oracle.Format(fmt.block, fmt.scale, fmt.tensor_scale)
 
 
-def run(x, axis, rounding, seed, fmt, what):
-    print(f"[case] quant_noise {what} shape={tuple(x.shape)} {x.dtype} axis={axis} rounding={rounding} fmt={fmt}", flush=True)
-    xg = x.cuda()
+def run(x, axis, rounding, seed, fmt, what, ld=None):
+    print(f"[case] quant_noise {what} shape={tuple(x.shape)} {x.dtype} axis={axis} rounding={rounding} fmt={fmt} ld={ld}", flush=True)
+    if ld is None:
+        xg = x.cuda()
+    else:  # rows padded to ld elements on the device
+        xg = torch.zeros((x.shape[0], ld), dtype=x.dtype, device="cuda")[:, : x.shape[1]]
+        xg.copy_(x)
     q = nv.quantize(xg, axis, rounding, seed, fmt)
     got = nv.quant_noise(xg, q, axis, fmt).cpu().numpy()
     oq = oracle.quantize(x, axis, rounding, seed, ofmt(fmt))
@@ -42,6 +46,18 @@ def test_ragged_shapes_all_formats(fmt, axis, dtype):
     x = synth.student_t_outliers(rows, cols, seed=7 + axis, dtype=dtype)
     run(x, axis, nv.SR, 5, fmt, "ragged")
     run(x, axis, nv.RTN, 0, fmt, "ragged")
+
+
+@pytest.mark.parametrize("fmt", FORMATS[:2], ids=["nvfp4", "mxfp4"])
+@pytest.mark.parametrize("cols", [328, 330], ids=["4-columns-per-lane", "1-column-per-lane"])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_column_kernel_variants_with_a_short_last_span(fmt, cols, dtype):
+    # 416 rows = one full 256-row tile, two full 64-row spans and one of 32 rows (four groups of 8);
+    # 330 columns (rows padded to 336 elements for the 16-byte row alignment every entry point asks for)
+    # rule out four columns per lane, so the one-column-per-lane kernel runs
+    x = synth.student_t_outliers(416, cols, seed=11, dtype=dtype)
+    run(x, 0, nv.SR, 3, fmt, "short span", ld=336)
+    run(x, 0, nv.RTN, 0, fmt, "short span", ld=336)
 
 
 def test_tiny_and_empty():
