@@ -112,6 +112,15 @@ struct u32x4 {
     uint32_t x, y, z, w;
 };
 
+NVFP4_HD uint32_t xor3(uint32_t a, uint32_t b, uint32_t c)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);  // one three-input bit operation (truth table of a ^ b ^ c)
+#else
+    return a ^ b ^ c;
+#endif
+}
+
 NVFP4_HD u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
                              uint32_t k1)
 {
@@ -119,8 +128,8 @@ NVFP4_HD u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
     for (int r = 0; r < 10; ++r) {
         uint64_t p0 = (uint64_t)0xD2511F53u * c0;
         uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
-        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n0 = xor3((uint32_t)(p1 >> 32), c1, k0);
+        uint32_t n2 = xor3((uint32_t)(p0 >> 32), c3, k1);
         c1 = (uint32_t)p1;
         c3 = (uint32_t)p0;
         c0 = n0;
@@ -131,11 +140,34 @@ NVFP4_HD u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
     return u32x4{c0, c1, c2, c3};
 }
 
+// Philox4x32-10 of the counter (c0, c1, 0, 0): the first round written out, since with the upper counter
+// words zero one of its two products is zero and two of its xor operands vanish.
+NVFP4_HD u32x4 philox4x32_10_low(uint32_t c0, uint32_t c1, uint32_t k0, uint32_t k1)
+{
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+    uint32_t a0 = c1 ^ k0, a1 = 0u, a2 = (uint32_t)(p0 >> 32) ^ k1, a3 = (uint32_t)p0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+#pragma unroll
+    for (int r = 1; r < 10; ++r) {
+        uint64_t q0 = (uint64_t)0xD2511F53u * a0;
+        uint64_t q1 = (uint64_t)0xCD9E8D57u * a2;
+        uint32_t n0 = xor3((uint32_t)(q1 >> 32), a1, k0);
+        uint32_t n2 = xor3((uint32_t)(q0 >> 32), a3, k1);
+        a1 = (uint32_t)q1;
+        a3 = (uint32_t)q0;
+        a0 = n0;
+        a2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return u32x4{a0, a1, a2, a3};
+}
+
 // The 128 random bits shared by the 8 elements whose row-major indices are 8c .. 8c+7.
 NVFP4_HD u32x4 sr_draw(uint64_t seed, uint64_t c)
 {
-    return philox4x32_10((uint32_t)c, (uint32_t)(c >> 32), 0u, 0u, (uint32_t)seed,
-                         (uint32_t)(seed >> 32));
+    return philox4x32_10_low((uint32_t)c, (uint32_t)(c >> 32), (uint32_t)seed, (uint32_t)(seed >> 32));
 }
 
 // 16 bits of element e & 7 out of its group's draw.
