@@ -460,3 +460,64 @@ def test_large_tile_bf16_output_with_padded_rows(pad):
         assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * ref_abs)
         if pad:
             assert torch.all(buf[:, N:] == -3.0)
+
+
+def test_swiglu_mlp_fwd_bwd_stage_by_stage():
+    # The SwiGLU MLP graph of the 7B benchmark configuration at reduced width (tokens 256, d 256, ffn 704):
+    # gate and up share X, h = silu(G) * U feeds down, and the backward pass walks the graph in reverse with
+    # every operand of Eqs. 5-6 stochastically rounded.  bf16 tensors between the calls and saved operands, as
+    # in the timed step.  The elementwise SwiGLU belongs to the caller (plain torch ops on the device here);
+    # every library call is checked against the oracle ON THE INPUTS IT ACTUALLY RECEIVED, so a one-ulp bf16
+    # difference upstream cannot be mistaken for, or hide, an error downstream.
+    T, D, F = 256, 256, 704
+    X = synth.normal(T, D, 1.0, 901).cuda()
+    Wg, Wu = synth.normal(F, D, 0.02, 902).cuda(), synth.normal(F, D, 0.02, 903).cuda()
+    Wd = synth.normal(D, F, 0.02, 904).cuda()
+    dY = synth.gradient_like(T, D, 905).cuda()
+    bf = torch.bfloat16
+
+    def close_bf16(got, qa, qb, what):
+        ref, ref_abs = oracle.gemm_nt(qa, qb), oracle.gemm_nt(qa, qb, take_abs=True)
+        assert np.all(np.abs(to_np(got.float()) - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * ref_abs), what
+
+    def fwd(x, w, seed, what):
+        print(f"[case] mlp chain fwd {what}", flush=True)
+        saved = torch.empty(nv.linear_saved_bytes(x.shape[0], w.shape[0], x.shape[1]), dtype=torch.uint8, device="cuda")
+        y = nv.linear_fwd(x, w, out_dtype=bf, saved=saved, bwd_seed=seed)
+        torch.cuda.synchronize()
+        close_bf16(y, oracle.quantize(x.cpu(), 1), oracle.quantize(w.cpu(), 1), what)
+        return y, saved
+
+    def bwd(dy, x, w, seed, saved, what):
+        print(f"[case] mlp chain bwd {what}", flush=True)
+        dx, dw = nv.linear_bwd(dy, None, None, seed, out_dtype=bf, saved=saved, K=x.shape[1])
+        torch.cuda.synchronize()
+        dyc, xc, wc = dy.cpu(), x.cpu(), w.cpu()
+        close_bf16(dx, oracle.quantize(dyc, 1, oracle.SR, seed), oracle.quantize(wc, 0), what + " dX")
+        close_bf16(dw, oracle.quantize(dyc, 0, oracle.SR, seed + 1), oracle.quantize(xc, 0, oracle.SR, seed + 2), what + " dW")
+        return dx, dw
+
+    G, sg = fwd(X, Wg, 10, "gate")
+    U, su = fwd(X, Wu, 20, "up")
+    sig = torch.sigmoid(G.float())
+    H = (G.float() * sig * U.float()).to(bf)
+    Y, sd = fwd(H, Wd, 30, "down")
+    assert Y.shape == (T, D)
+    dH, dWd = bwd(dY, H, Wd, 30, sd, "down")
+    dG = (dH.float() * U.float() * sig * (1.0 + G.float() * (1.0 - sig))).to(bf)
+    dU = (dH.float() * G.float() * sig).to(bf)
+    dXg, dWg = bwd(dG, X, Wg, 10, sg, "gate")
+    dXu, dWu = bwd(dU, X, Wu, 20, su, "up")
+    dX = dXg.float() + dXu.float()
+    # sanity of the whole graph against the unquantized fp64 MLP: same direction, moderate relative error
+    Xd, Wgd, Wud, Wdd = (t.double().cpu().numpy() for t in (X, Wg, Wu, Wd))
+    g, u = Xd @ Wgd.T, Xd @ Wud.T
+    s = 1.0 / (1.0 + np.exp(-g))
+    dh = dY.double().cpu().numpy() @ Wdd
+    dx_ref = (dh * u * s * (1.0 + g * (1.0 - s))) @ Wgd + (dh * g * s) @ Wud
+    got = dX.double().cpu().numpy()
+    cos = (got * dx_ref).sum() / (np.linalg.norm(got) * np.linalg.norm(dx_ref))
+    print(f"[info] mlp chain: cosine of dX with the unquantized fp64 MLP {cos:.4f}", flush=True)
+    assert cos > 0.9
+    for t in (dWd, dWg, dWu):
+        assert torch.isfinite(t.float()).all()
