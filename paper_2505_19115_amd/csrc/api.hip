@@ -15,6 +15,10 @@ constexpr size_t WS_HEADER = 256;  // tensor scales and maxima live at the front
 constexpr int64_t MAX_CONTRACTION = (int64_t)1 << 23;  // the GEMM kernels keep 32-bit byte offsets inside a 256-row tile
 
 inline size_t align_up(size_t n) { return (n + WS_ALIGN - 1) / WS_ALIGN * WS_ALIGN; }
+// Bytes of an internal packed operand of `rows` rows and contraction length K: rows padded to whole slabs, so
+// that the buffer can hold either the plain or the slab layout.
+inline size_t op_codes(int64_t rows, int64_t K) { return align_up((size_t)slab_rows_padded(rows) * K / 2); }
+inline size_t op_scales(int64_t rows, int64_t K, int64_t block) { return align_up((size_t)slab_rows_padded(rows) * (K / block)); }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t elem_size(int dt) { return dt == NVFP4_BF16 ? 2 : 4; }
 inline bool valid_dtype(int dt) { return dt == NVFP4_F32 || dt == NVFP4_BF16; }
@@ -35,6 +39,23 @@ bool use_hw_convert()
 {
     const char *e = getenv("NVFP4_SOFT_CONVERT");
     return !(e && e[0] == '1');
+}
+
+// The fused linear entries keep their packed operands in the slab layout (kernels.h) wherever the dual-orientation
+// quantizer produces them and the 256 x 256 GEMM kernel consumes them; NVFP4_PLAIN_OPERANDS=1 keeps the plain
+// row-major layout everywhere (same results bit for bit: a cross-check and a timing reference).
+bool use_slabs()
+{
+    const char *e = getenv("NVFP4_PLAIN_OPERANDS");
+    return !(e && e[0] == '1');
+}
+
+// A dense [rows, cols] tensor goes through the one-pass dual quantizer (the only writer of slabs) with these
+// roundings; its answer does not depend on the element type for shapes the linear entries accept.
+bool dual_writes_slabs(const nvfp4_format *f, int dt, int64_t rows, int64_t cols, int rnd_r, int rnd_c)
+{
+    return use_slabs() && f->block == 16 && f->scale == NVFP4_SCALE_E4M3 &&
+           quantize_dual_fused(dt, rows, cols, cols, f->block, use_hw_convert()) && !(rnd_r == NVFP4_SR && rnd_c == NVFP4_RTN);
 }
 
 // An empty tensor (rows or cols 0) may come with a null data pointer.
@@ -105,9 +126,9 @@ SavedLayout saved_layout(void *saved, int64_t M, int64_t N, int64_t K, int64_t B
     SavedLayout L;
     L.g = reinterpret_cast<float *>(p);
     p += WS_HEADER;
-    L.xtc = p; p += align_up((size_t)K * M / 2);
-    L.xts = p; p += align_up((size_t)K * (M / B));
-    L.wtc = p; p += align_up((size_t)K * N / 2);
+    L.xtc = p; p += op_codes(K, M);
+    L.xts = p; p += op_scales(K, M, B);
+    L.wtc = p; p += op_codes(K, N);
     L.wts = p;
     return L;
 }
@@ -157,16 +178,16 @@ size_t nvfp4_linear_fwd_workspace_bytes(int64_t M, int64_t N, int64_t K, const n
 {
     if (M <= 0 || N <= 0 || K <= 0 || check_format(f) != NVFP4_OK) return 0;
     const size_t part = partials_bytes(M, K) > partials_bytes(N, K) ? partials_bytes(M, K) : partials_bytes(N, K);
-    return WS_HEADER + part + align_up((size_t)M * K / 2) + align_up((size_t)M * (K / f->block)) +
-           align_up((size_t)N * K / 2) + align_up((size_t)N * (K / f->block));
+    return WS_HEADER + part + op_codes(M, K) + op_scales(M, K, f->block) +
+           op_codes(N, K) + op_scales(N, K, f->block);
 }
 
 size_t nvfp4_linear_saved_bytes(int64_t M, int64_t N, int64_t K, const nvfp4_format *f)
 {
     if (M <= 0 || N <= 0 || K <= 0 || check_format(f) != NVFP4_OK) return 0;
     const size_t B = (size_t)f->block;
-    return WS_HEADER + align_up((size_t)K * M / 2) + align_up((size_t)K * (M / B)) +  // X^T blocked along M
-           align_up((size_t)K * N / 2) + align_up((size_t)K * (N / B));               // W^T blocked along N
+    return WS_HEADER + op_codes(K, M) + op_scales(K, M, B) +  // X^T blocked along M
+           op_codes(K, N) + op_scales(K, N, B);               // W^T blocked along N
 }
 
 size_t nvfp4_linear_bwd_workspace_bytes(int64_t M, int64_t N, int64_t K, const nvfp4_format *f)
@@ -177,10 +198,10 @@ size_t nvfp4_linear_bwd_workspace_bytes(int64_t M, int64_t N, int64_t K, const n
     if (partials_bytes(N, K) > part) part = partials_bytes(N, K);
     if (partials_bytes(M, K) > part) part = partials_bytes(M, K);
     return WS_HEADER + part +
-           align_up((size_t)M * N / 2) + align_up((size_t)M * (N / B)) +  // dY blocked along N
-           align_up((size_t)K * N / 2) + align_up((size_t)K * (N / B)) +  // W^T blocked along N
-           align_up((size_t)N * M / 2) + align_up((size_t)N * (M / B)) +  // dY^T blocked along M
-           align_up((size_t)K * M / 2) + align_up((size_t)K * (M / B));   // X^T blocked along M
+           op_codes(M, N) + op_scales(M, N, B) +  // dY blocked along N
+           op_codes(K, N) + op_scales(K, N, B) +  // W^T blocked along N
+           op_codes(N, M) + op_scales(N, M, B) +  // dY^T blocked along M
+           op_codes(K, M) + op_scales(K, M, B);   // X^T blocked along M
 }
 
 nvfp4_status nvfp4_tensor_scale(const void *x, nvfp4_dtype dt, int64_t rows, int64_t cols,
@@ -366,9 +387,9 @@ nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, 
     uint32_t *amax = reinterpret_cast<uint32_t *>(ws + 64);    // two maxima
     uint32_t *partials = reinterpret_cast<uint32_t *>(ws + WS_HEADER);
     uint8_t *p = ws + WS_HEADER + (partials_bytes(M, K) > partials_bytes(N, K) ? partials_bytes(M, K) : partials_bytes(N, K));
-    uint8_t *xc = p; p += align_up((size_t)M * K / 2);
-    uint8_t *xs = p; p += align_up((size_t)M * (K / f->block));
-    uint8_t *wc = p; p += align_up((size_t)N * K / 2);
+    uint8_t *xc = p; p += op_codes(M, K);
+    uint8_t *xs = p; p += op_scales(M, K, f->block);
+    uint8_t *wc = p; p += op_codes(N, K);
     uint8_t *wsc = p;
 
     const int gm = f->tensor_scale ? G_FROM_AMAX : G_NONE;
@@ -377,12 +398,20 @@ nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, 
         if (amax_dense(X, in_dt, M * K, partials, 0, st, &gx) != hipSuccess) return NVFP4_EHIP;
         if (amax_dense(W, in_dt, N * K, partials, 1, st, &gw) != hipSuccess) return NVFP4_EHIP;
     }
+    int a_slab = 0, b_slab = 0;
     if (saved) {
         // one pass over X and one over W also leave what Eqs. 5-6 need of them: Q_SR(X^T) with
         // the backward call's third stream, and Q_RtN(W^T)
         const SavedLayout L = saved_layout(saved, M, N, K, f->block);
         DualArgs dx{{X, M, K, K, L.xtc, L.xts, gx.src, ts + 0, gm, bwd_seed + 2, gx.n}, xc, xs, 0, L.g + 0};
         DualArgs dw{{W, N, K, K, L.wtc, L.wts, gw.src, ts + 1, gm, 0, gw.n}, wc, wsc, 0, L.g + 1};
+        // row-blocked sides feed this call's GEMM, Q(X^T) the update GEMM (Eq. 6), Q(W^T) the input-gradient GEMM (Eq. 5)
+        const bool sx = dual_writes_slabs(f, in_dt, M, K, NVFP4_RTN, NVFP4_SR), sw = dual_writes_slabs(f, in_dt, N, K, NVFP4_RTN, NVFP4_RTN);
+        const bool t_fwd = gemm_takes_slabs(M, N, K, f->block, f->scale);
+        dx.slab_r = a_slab = sx && t_fwd;
+        dx.slab_c = sx && gemm_takes_slabs(N, K, M, f->block, f->scale);
+        dw.slab_r = b_slab = sw && t_fwd;
+        dw.slab_c = sw && gemm_takes_slabs(M, K, N, f->block, f->scale);
         if (launch_quantize_dual(dx, in_dt, NVFP4_RTN, NVFP4_SR, f->block, f->scale, use_hw_convert(), st) != hipSuccess) return NVFP4_EHIP;
         if (launch_quantize_dual(dw, in_dt, NVFP4_RTN, NVFP4_RTN, f->block, f->scale, use_hw_convert(), st) != hipSuccess) return NVFP4_EHIP;
     } else {
@@ -391,7 +420,7 @@ nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, 
         if (run_quantize(qx, f, st) != hipSuccess) return NVFP4_EHIP;
         if (run_quantize(qw, f, st) != hipSuccess) return NVFP4_EHIP;
     }
-    GemmArgs g{M, N, K, xc, xs, wc, wsc, ts, ts + 1, Y, N};
+    GemmArgs g{M, N, K, xc, xs, wc, wsc, ts, ts + 1, Y, N, a_slab, b_slab};
     return launch_gemm(g, f->block, f->scale, out_dt, st) == hipSuccess ? NVFP4_OK : NVFP4_EHIP;
 }
 
@@ -427,13 +456,13 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
     if (partials_bytes(N, K) > part) part = partials_bytes(N, K);
     if (partials_bytes(M, K) > part) part = partials_bytes(M, K);
     uint8_t *p = ws + WS_HEADER + part;
-    uint8_t *dyc = p; p += align_up((size_t)M * N / 2);
-    uint8_t *dys = p; p += align_up((size_t)M * (N / B));
-    uint8_t *wtc = p; p += align_up((size_t)K * N / 2);
-    uint8_t *wts = p; p += align_up((size_t)K * (N / B));
-    uint8_t *dytc = p; p += align_up((size_t)N * M / 2);
-    uint8_t *dyts = p; p += align_up((size_t)N * (M / B));
-    uint8_t *xtc = p; p += align_up((size_t)K * M / 2);
+    uint8_t *dyc = p; p += op_codes(M, N);
+    uint8_t *dys = p; p += op_scales(M, N, B);
+    uint8_t *wtc = p; p += op_codes(K, N);
+    uint8_t *wts = p; p += op_scales(K, N, B);
+    uint8_t *dytc = p; p += op_codes(N, M);
+    uint8_t *dyts = p; p += op_scales(N, M, B);
+    uint8_t *xtc = p; p += op_codes(K, M);
     uint8_t *xts = p;
     const float *g_w = ts + 1, *g_x = ts + 3;  // written by the W^T and X^T quantizers below, or saved by the forward call
     if (saved) {
@@ -459,6 +488,12 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
     }
     // with both GEMMs wanted, dY is read once for its two orientations (streams seed, seed+1)
     const bool dual = dX && dW && quantize_dual_fused(in_dt, M, N, N, f->block, use_hw_convert());
+    // layouts: dY's two sides as this call's dual pass writes them, W^T and X^T as the forward call wrote them
+    const bool t_dx = gemm_takes_slabs(M, K, N, f->block, f->scale), t_dw = gemm_takes_slabs(N, K, M, f->block, f->scale);
+    const bool sdy = dual && dual_writes_slabs(f, in_dt, M, N, NVFP4_SR, NVFP4_SR);
+    const int dy_slab_r = sdy && t_dx, dy_slab_c = sdy && t_dw;
+    const int wt_slab = saved && t_dx && dual_writes_slabs(f, in_dt, N, K, NVFP4_RTN, NVFP4_RTN);
+    const int xt_slab = saved && t_dw && dual_writes_slabs(f, in_dt, M, K, NVFP4_RTN, NVFP4_SR);
     if (dual) {
         DualArgs d;
         d.c.x = dY;
@@ -476,6 +511,8 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
         d.scales_r = dys;
         d.seed_r = seed;
         d.g_out2 = ts + 2;
+        d.slab_r = dy_slab_r;
+        d.slab_c = dy_slab_c;
         if (launch_quantize_dual(d, in_dt, NVFP4_SR, NVFP4_SR, f->block, f->scale, true, st) != hipSuccess) return NVFP4_EHIP;
     }
     if (dX) {
@@ -485,7 +522,7 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
         QuantPlan qb{W, in_dt, N, K, K, 0, NVFP4_RTN, 0, wtc, wts, gw.src, ts + 1, gm_xw, gw.n};
         if (!dual && run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
         if (!saved && run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
-        GemmArgs g{M, K, N, dyc, dys, wtc, wts, ts + 0, g_w, dX, K};
+        GemmArgs g{M, K, N, dyc, dys, wtc, wts, ts + 0, g_w, dX, K, dy_slab_r, wt_slab};
         if (launch_gemm(g, f->block, f->scale, out_dt, st) != hipSuccess) return NVFP4_EHIP;
     }
     if (dW) {
@@ -495,7 +532,7 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
         QuantPlan qb{X, in_dt, M, K, K, 0, NVFP4_SR, seed + 2, xtc, xts, gx.src, ts + 3, gm_xw, gx.n};
         if (!dual && run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
         if (!saved && run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
-        GemmArgs g{N, K, M, dytc, dyts, xtc, xts, ts + 2, g_x, dW, K};
+        GemmArgs g{N, K, M, dytc, dyts, xtc, xts, ts + 2, g_x, dW, K, dy_slab_c, xt_slab};
         if (launch_gemm(g, f->block, f->scale, out_dt, st) != hipSuccess) return NVFP4_EHIP;
     }
     return NVFP4_OK;

@@ -122,7 +122,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
         const int row = DMA ? (wave * CA + u) * 16 + (lane >> 2) : qd >> 2;
         const int ch = DMA ? (lane & 3) ^ ((lane >> 4) & 3) : qd & 3;
         const int64_t lr = m0 + row < P.M ? row : P.M - 1 - m0;  // row inside the tile, clamped
-        offA[u] = (uint32_t)(lr * Kb + ch * 16);                  // (relative to the tile's first row: 32 bits suffice)
+        offA[u] = P.a_slab ? (uint32_t)(slab_row(row) * 64 + ch * 16)  // (a slab holds all 256 rows: nothing to clamp)
+                           : (uint32_t)(lr * Kb + ch * 16);       // (relative to the tile's first row: 32 bits suffice)
         ldsA[u] = DMA ? __builtin_amdgcn_readfirstlane((wave * CA + u) * 1024) : swz(row, ch);
     }
 #pragma unroll
@@ -131,7 +132,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
         const int row = DMA ? (wave * CB + u) * 16 + (lane >> 2) : qd >> 2;
         const int ch = DMA ? (lane & 3) ^ ((lane >> 4) & 3) : qd & 3;
         const int64_t lr = n0 + row < P.N ? row : P.N - 1 - n0;
-        offB[u] = (uint32_t)(lr * Kb + ch * 16);
+        offB[u] = P.b_slab ? (uint32_t)(slab_row(row) * 64 + ch * 16) : (uint32_t)(lr * Kb + ch * 16);
         ldsB[u] = DMA ? __builtin_amdgcn_readfirstlane(A_BYTES + (wave * CB + u) * 1024) : A_BYTES + swz(row, ch);
     }
     typedef __attribute__((address_space(3))) void *lds_ptr_t;
@@ -150,6 +151,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(voff), "s"(base) : "memory");
     };
     const uint8_t *srow_ptr[NSR];
+    int srow_step[NSR];  // bytes from one K tile's scales of the row to the next
     bool srow_on[NSR];
 #pragma unroll
     for (int u = 0; u < NSR; ++u) {
@@ -160,12 +162,23 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
         gr = gr < nrows ? gr : nrows - 1;
         srow_on[u] = srow < BM + BN;
         srow_ptr[u] = (isA ? P.A_scales : P.B_scales) + gr * Ks;
+        srow_step[u] = SPT;
+        if (DMA && (isA ? P.a_slab : P.b_slab) && srow_on[u]) {
+            const int64_t tile = isA ? ty : tx;
+            const int lrow = isA ? srow : srow - BM;
+            srow_ptr[u] = (isA ? P.A_scales : P.B_scales) + tile * nkt * SLAB_SCALE_BYTES + slab_row(lrow) * 8;
+            srow_step[u] = (int)SLAB_SCALE_BYTES;
+        }
     }
+    // codes of K tile kt: base + kt * step (+ the lane offsets above)
+    const uint8_t *baseA = P.a_slab ? P.A_codes + (int64_t)ty * nkt * SLAB_CODE_BYTES : P.A_codes + m0 * Kb;
+    const uint8_t *baseB = P.b_slab ? P.B_codes + (int64_t)tx * nkt * SLAB_CODE_BYTES : P.B_codes + n0 * Kb;
+    const int64_t stepA = P.a_slab ? SLAB_CODE_BYTES : KTB, stepB = P.b_slab ? SLAB_CODE_BYTES : KTB;
     const int64_t last_chunk = Kb - 16;
     // tile kt: codes -> LDS stage `stage` (direct) or staging registers; scale bytes -> registers
     auto fetch = [&](int kt, int stage) {
         const int64_t kb = (int64_t)kt * KTB;
-        const uint8_t *pa = P.A_codes + m0 * Kb + kb, *pb = P.B_codes + n0 * Kb + kb;
+        const uint8_t *pa = baseA + kt * stepA, *pb = baseB + kt * stepB;
         if (!KTAIL) {
             const uint8_t *ua = uniform_ptr(pa), *ub = uniform_ptr(pb);
             const uint32_t dst = __builtin_amdgcn_readfirstlane(lds0 + stage * STAGE);
@@ -176,7 +189,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_f16_kernel(GemmArgs P)
 #pragma unroll
             for (int u = 0; u < NSR; ++u) {
                 if (!srow_on[u]) continue;
-                const uint8_t *sp = srow_ptr[u] + (int64_t)kt * SPT;
+                const uint8_t *sp = srow_ptr[u] + (int64_t)kt * srow_step[u];
                 if (SPT == 8) gs[u] = *reinterpret_cast<const uint64_t *>(sp);
                 else if (SPT == 4) gs[u] = *reinterpret_cast<const uint32_t *>(sp);
                 else if (SPT == 2) gs[u] = *reinterpret_cast<const uint16_t *>(sp);
@@ -510,11 +523,22 @@ static void launch_f16(const GemmArgs &P, int out_dt, hipStream_t st)
 
 // Tile choice: 256 x 256 (8 waves) when the output has enough such tiles to occupy the 256
 // CUs, else 128 x 128 (4 waves, several workgroups per CU).
+static bool large_tile(int64_t M, int64_t N, int64_t K)
+{
+    const int64_t big = ((M + 255) / 256) * ((N + 255) / 256);
+    return big >= 128 && K % KT == 0;  // the large tile is built for K % 128 == 0 only
+}
+
+bool gemm_takes_slabs(int64_t M, int64_t N, int64_t K, int block, int sf)
+{
+    return sf == NVFP4_SCALE_E4M3 && block == 16 && large_tile(M, N, K);
+}
+
 template <int B>
 static void launch_f16_auto(const GemmArgs &P, int out_dt, hipStream_t st)
 {
     const int64_t big = ((P.M + 255) / 256) * ((P.N + 255) / 256);
-    const bool ktail = (P.K % KT) != 0;  // the large tile is built for K % 128 == 0 only
+    const bool ktail = (P.K % KT) != 0;
     if (big >= 128 && !ktail)
         launch_f16<B, 2, 4, 4, 2, false>(P, out_dt, st);
     else if (!ktail)
@@ -527,6 +551,7 @@ hipError_t launch_gemm(const GemmArgs &P, int block, int sf, int out_dt, hipStre
 {
     // lane offsets inside a 256-row tile are 32-bit
     if ((P.K >> 1) * 256 >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
+    if ((P.a_slab || P.b_slab) && !gemm_takes_slabs(P.M, P.N, P.K, block, sf)) return hipErrorInvalidValue;
     if (sf == NVFP4_SCALE_E8M0) return block == 32 ? launch_gemm_mxfp4(P, out_dt, st) : hipErrorNotSupported;
     switch (block) {
     case 16: launch_f16_auto<16>(P, out_dt, st); break;

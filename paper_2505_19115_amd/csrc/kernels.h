@@ -30,7 +30,20 @@ struct DualArgs {
     uint8_t *scales_r;  // [rows, cols/B]
     uint64_t seed_r;
     float *g_out2;      // optional second destination of the tensor scale
+    int slab_r = 0;     // write the row-blocked / column-blocked output in the slab layout (below) instead
+    int slab_c = 0;
 };
+
+// Slab layout of a packed operand (library-internal: workspaces and the saved buffer of the fused linear
+// entries; never crosses the C ABI as a documented format).  For an operand of R rows and contraction length K
+// (block 16, K a multiple of 128) the codes are stored as [ceil(R / 256)][K / 128] slabs of 16 KB: one slab is
+// what one GEMM workgroup fetches per K tile, 256 rows x 64 bytes, contiguous.  Inside a slab row r (0..255) sits
+// at position slab_row(r), which swaps the two 3-bit fields of r below bit 6: the column-blocked quantizer holds
+// rows 8 cx + j (lane group cx, column j of the lane) and with this order each of its store instructions writes
+// 512 contiguous bytes.  The scales follow the same scheme with 8 bytes per row (slabs of 2 KB).
+constexpr int64_t SLAB_ROWS = 256, SLAB_K = 128, SLAB_CODE_BYTES = 16384, SLAB_SCALE_BYTES = 2048;
+__host__ __device__ inline int slab_row(int r) { return (r & ~63) | ((r & 7) << 3) | ((r >> 3) & 7); }
+inline int64_t slab_rows_padded(int64_t rows) { return (rows + SLAB_ROWS - 1) / SLAB_ROWS * SLAB_ROWS; }
 
 struct GemmArgs {
     int64_t M, N, K;
@@ -38,7 +51,11 @@ struct GemmArgs {
     const float *gA, *gB;  // per-tensor scales of the two operands (device)
     void *out;
     int64_t ldc;
+    int a_slab = 0, b_slab = 0;  // operand stored in the slab layout (only where gemm_takes_slabs() holds)
 };
+// True when launch_gemm() runs the 256 x 256 direct-to-LDS kernel for this problem, the one that can read operands
+// in the slab layout.
+bool gemm_takes_slabs(int64_t M, int64_t N, int64_t K, int block, int sf);
 
 // Tensor maximum: one partial per workgroup into `partials` (tensor_amax_partials() entries),
 // then folded into amax_bits[0] (bit pattern of max|x|) and, if g_out is given, into the scale.

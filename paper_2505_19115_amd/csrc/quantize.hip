@@ -467,9 +467,15 @@ __device__ __forceinline__ void col_sr_hw(const QuantArgs &P, Chunk<DT> (&v)[16]
     }
 }
 
+// Where a lane's column-blocked outputs go in the slab layout: column c of the lane stores its 8 code bytes at
+// codes + 512 c and its scale byte at scales + 64 c (the lane index is folded into the two pointers).
+struct ColSlab {
+    uint8_t *codes, *scales;
+};
+
 template <int DT, int B, int SF, int RND, bool HW, bool ALIGNED, int LV>
 __device__ __forceinline__ void cols_tile(const QuantArgs &P, Chunk<DT> (&v)[16], float g, float k, int64_t row0,
-                                          int64_t col0, int ncol, int lv);
+                                          int64_t col0, int ncol, int lv, const ColSlab *slab = nullptr);
 
 // ALIGNED: cols is a multiple of 8, so the 8 columns of a lane share one random draw per row.
 template <int DT, int B, int SF, int RND, bool HW, bool ALIGNED, int LV = 8>
@@ -508,7 +514,7 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(QuantArgs P)
 // scale bytes, codes, and the stores into the transposed outputs.
 template <int DT, int B, int SF, int RND, bool HW, bool ALIGNED, int LV>
 __device__ __forceinline__ void cols_tile(const QuantArgs &P, Chunk<DT> (&v)[16], float g, float k, int64_t row0,
-                                          int64_t col0, int ncol, int lv)
+                                          int64_t col0, int ncol, int lv, const ColSlab *slab)
 {
     using G = ColGeom<DT, LV>;
     constexpr int RPL = G::RPL;
@@ -593,6 +599,18 @@ __device__ __forceinline__ void cols_tile(const QuantArgs &P, Chunk<DT> (&v)[16]
         }
     }
 
+    if (B == 16 && RPL == 16 && slab != nullptr) {
+        // slab layout (the caller guarantees a lane tile entirely inside the tensor or entirely outside): a store
+        // instruction of the wave writes 512 contiguous code bytes, 64 contiguous scale bytes
+        if (ncol == 8) {
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                store8_stream(slab->codes + 512 * c, words[c][0], words[c][1]);
+                slab->scales[64 * c] = (uint8_t)sbytes[c][0];
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
         if (c < ncol) {
@@ -702,10 +720,43 @@ __global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
 #pragma unroll
     for (int r = 0; r < 16; ++r) v[r].launder();
 
-    // column-blocked side: exactly the columns kernel's tile
-    cols_tile<DT, B, SF, RND_C, true, true, 8>(P, v, g, k, row0, col0, inside ? 8 : 0, lv);
+    // column-blocked side: exactly the columns kernel's tile.  In the slab layout the workgroup's 256 columns are
+    // one tile of operand rows and its 128 rows one K tile: it fills exactly one slab.
+    ColSlab cs;
+    if (B == 16 && D.slab_c) {
+        const int64_t slab = (int64_t)blockIdx.x * (P.rows / SLAB_K) + blockIdx.y;
+        cs.codes = P.codes + slab * SLAB_CODE_BYTES + wave * 4096 + lane * 8;
+        cs.scales = P.scales + slab * SLAB_SCALE_BYTES + wave * 512 + lane;
+    }
+    cols_tile<DT, B, SF, RND_C, true, true, 8>(P, v, g, k, row0, col0, inside ? 8 : 0, lv, B == 16 && D.slab_c ? &cs : nullptr);
 
     __syncthreads();
+    if (B == 16 && D.slab_r) {
+        // slab layout: the tile is rows (wrow0 % 256) .. + 127 of two slabs (K tiles 2 blockIdx.x and + 1 of row
+        // tile wrow0 / 256).  Threads walk the slab positions q; position q holds tile row slab_row(q).
+        const int64_t nkt = P.cols / SLAB_K;
+        const int64_t slab0 = (wrow0 / SLAB_ROWS) * nkt + 2 * (int64_t)blockIdx.x;
+        const int half = (int)(wrow0 & 128);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int id = threadIdx.x + 256 * i, q = id >> 3, c = id & 7, R = slab_row(q);
+            if (wrow0 + R < P.rows && wcol0 + c * 32 < P.cols) {
+                const uint4 w = *reinterpret_cast<const uint4 *>(&lds_codes[R * (ROW_BYTES / 4) + ((c ^ (R >> 4)) << 2)]);
+                const u32x4_t o = {w.x, w.y, w.z, w.w};
+                __builtin_nontemporal_store(o, reinterpret_cast<u32x4_t *>(D.codes_r + (slab0 + (c >> 2)) * SLAB_CODE_BYTES + (half + q) * 64 + (c & 3) * 16));
+            }
+        }
+        if (threadIdx.x < G::WG_ROWS) {
+            const int q = threadIdx.x, R = slab_row(q);
+            if (wrow0 + R < P.rows) {
+                const uint32_t *src = reinterpret_cast<const uint32_t *>(&lds_scales[R * 16]);
+                uint8_t *dst = D.scales_r + slab0 * SLAB_SCALE_BYTES + (half + q) * 8;
+                store8_stream(dst, src[0], src[1]);
+                if (wcol0 + 128 < P.cols) store8_stream(dst + SLAB_SCALE_BYTES, src[2], src[3]);
+            }
+        }
+        return;
+    }
     const int64_t cpr = P.cols >> 1;
     const bool wide = (cpr & 15) == 0;  // rows of the code matrix are 16-byte aligned
 #pragma unroll
@@ -897,7 +948,8 @@ hipError_t launch_quantize_dual(const DualArgs &D, int dt, int rnd_r, int rnd_c,
             launch_dual_fmt<NVFP4_F32>(D, rnd_r, rnd_c, block, sf, st);
         return launch_status();
     }
-    // other block sizes and ragged shapes: the two single-orientation kernels
+    // other block sizes and ragged shapes: the two single-orientation kernels (they write the plain layout only)
+    if (D.slab_r || D.slab_c) return hipErrorInvalidValue;
     QuantArgs r = D.c;
     r.codes = D.codes_r;
     r.scales = D.scales_r;

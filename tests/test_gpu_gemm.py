@@ -521,3 +521,43 @@ def test_swiglu_mlp_fwd_bwd_stage_by_stage():
     assert cos > 0.9
     for t in (dWd, dWg, dWu):
         assert torch.isfinite(t.float()).all()
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_slab_operand_layout_is_invisible(dtype, monkeypatch):
+    # Between the quantizers and the large-tile GEMM the fused entries keep their packed operands as per-K-tile
+    # slabs; NVFP4_PLAIN_OPERANDS=1 keeps them row-major.  Both must give the same bits.  Shape: all three GEMMs
+    # of the layer large enough for the slab path, two of the three dimensions not multiples of the 256-row slab.
+    M, N, K = 2944, 3200, 2816
+    print(f"[case] slab layout vs plain M={M} N={N} K={K} {dtype}", flush=True)
+    X = synth.normal(M, K, 1.0, 611, dtype).cuda()
+    W = synth.normal(N, K, 0.02, 612, dtype).cuda()
+    dY = synth.gradient_like(M, N, 613, dtype=dtype).cuda()
+    outs = []
+    for plain in ("0", "1"):
+        monkeypatch.setenv("NVFP4_PLAIN_OPERANDS", plain)
+        saved = torch.empty(nv.linear_saved_bytes(M, N, K), dtype=torch.uint8, device="cuda")
+        Y = nv.linear_fwd(X, W, out_dtype=torch.bfloat16, saved=saved, bwd_seed=77)
+        dX, dW = nv.linear_bwd(dY, None, None, 77, out_dtype=torch.bfloat16, saved=saved, K=K)
+        torch.cuda.synchronize()
+        outs.append((Y, dX, dW))
+    for a, b, what in zip(outs[0], outs[1], ("Y", "dX", "dW")):
+        assert torch.equal(a, b), what
+    # and against the oracle on sampled outputs (rows from the ragged last slabs included)
+    rng = np.random.default_rng(5)
+    Xc, Wc, dYc = X.cpu(), W.cpu(), dY.cpu()
+    ii = np.concatenate([rng.integers(0, M, 24), [M - 1, M - 100, 2816]])
+    jj = np.concatenate([rng.integers(0, N, 24), [N - 1, N - 60, 3072]])
+    qx, qw = oracle.quantize(Xc, 1), oracle.quantize(Wc, 1)
+    ref, ref_abs = oracle.gemm_nt_sample(qx, qw, ii, jj), oracle.gemm_nt_sample(qx, qw, ii, jj, take_abs=True)
+    got = to_np(outs[0][0].float())[ii, jj]
+    assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * ref_abs)
+    kk = rng.integers(0, K, 27)
+    qdy, qwt = oracle.quantize(dYc, 1, oracle.SR, 77), oracle.quantize(Wc, 0)
+    ref, ref_abs = oracle.gemm_nt_sample(qdy, qwt, ii, kk), oracle.gemm_nt_sample(qdy, qwt, ii, kk, take_abs=True)
+    got = to_np(outs[0][1].float())[ii, kk]
+    assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * ref_abs)
+    qdyt, qxt = oracle.quantize(dYc, 0, oracle.SR, 78), oracle.quantize(Xc, 0, oracle.SR, 79)
+    ref, ref_abs = oracle.gemm_nt_sample(qdyt, qxt, jj, kk), oracle.gemm_nt_sample(qdyt, qxt, jj, kk, take_abs=True)
+    got = to_np(outs[0][2].float())[jj, kk]
+    assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * ref_abs)
