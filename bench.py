@@ -74,10 +74,11 @@ def main() -> int:
         for _ in range(3):
             dst.copy_(src)
         Xp, Wp = synth.normal(4096, 4096, 1.0, 100).to(dev), synth.normal(11008, 4096, 0.02, 200).to(dev)
-        qa, qb = nv.quantize(Xp, 1), nv.quantize(Wp, 1)
+        # operands in the slab layout, as the fused calls of the step hand them to the GEMM
+        qa, qb = nv.quantize_dual(Xp, slab_rows=True)[0], nv.quantize_dual(Wp, slab_rows=True)[0]
         Yp = torch.empty((4096, 11008), dtype=torch.bfloat16, device=dev)
         for _ in range(10):
-            nv.gemm(qa, qb, out=Yp)
+            nv.gemm(qa, qb, out=Yp, slabs=(True, True), shape=(4096, 11008, 4096))
         qam, qbm = nv.quantize(Xp, 1, fmt=nv.MXFP4), nv.quantize(Wp, 1, fmt=nv.MXFP4)
         for _ in range(10):
             nv.gemm(qam, qbm, nv.MXFP4, out=Yp)
@@ -89,7 +90,7 @@ def main() -> int:
                     nv.quantize(xq, axis, rnd, 1, tensor_scale=g)
         for rnd in (nv.RTN, nv.SR):
             for _ in range(2):
-                nv.quantize_dual(xq, rnd, 1, rnd, 2, tensor_scale=g)
+                nv.quantize_dual(xq, rnd, 1, rnd, 2, tensor_scale=g, slab_rows=True, slab_cols=True)
         torch.cuda.synchronize()
         print("probe done")
         return 0
@@ -180,9 +181,18 @@ def main() -> int:
 
     # ---- dominant kernel: the block-scaled GEMM at the gate/up shape (same launch as in step)
     name, N, K, X, W, dY, wf, wb, Y, dX, dW, _ = data[0]
-    qa, qb = nv.quantize(X, 1), nv.quantize(W, 1)
-    gemm_ms = event_time_ms(lambda i: nv.gemm(qa, qb, out=Y), max(args.steps, 5), torch)
+    # operands in the slab layout, which is how the fused calls of the step hand them to this kernel; the same
+    # launch on row-major operands (what nvfp4_gemm takes) is timed beside it
+    # (the two are timed in alternating batches: the clock under a run of GEMMs depends on what ran just before)
+    qa, qb = nv.quantize_dual(X, slab_rows=True)[0], nv.quantize_dual(W, slab_rows=True)[0]
+    pa, pb = nv.quantize(X, 1), nv.quantize(W, 1)
+    batches = [], []
+    for _ in range(3):
+        batches[0].append(event_time_ms(lambda i: nv.gemm(qa, qb, out=Y, slabs=(True, True), shape=(M, N, K)), max(args.steps, 5), torch))
+        batches[1].append(event_time_ms(lambda i: nv.gemm(pa, pb, out=Y), max(args.steps, 5), torch))
+    gemm_ms, gemm_plain_ms = sum(batches[0]) / 3, sum(batches[1]) / 3
     gemm_tflops = 2.0 * M * N * K / (gemm_ms * 1e-3) / 1e12
+    del pa, pb
     traffic = mx_traffic = None
     if os.path.exists(args.traffic_json):
         try:
@@ -204,7 +214,8 @@ def main() -> int:
                 "frac": round(gemm_tflops / PEAK_F16_TFLOPS, 4),
                 "frac_of_fp4_peak": round(gemm_tflops / PEAK_FP4_TFLOPS, 4),
                 "frac_of_sustained_f16": round(gemm_tflops / max(sustained["f16_random_operands"], 1e-9), 4),
-                "avg_launch_ms": round(gemm_ms, 4), "traffic": traffic}
+                "avg_launch_ms": round(gemm_ms, 4), "traffic": traffic,
+                "operands": "slab layout (as in the timed step)", "avg_launch_ms_row_major_operands": round(gemm_plain_ms, 4)}
 
     # ---- MXFP4 (block 32, E8M0): the same GEMM on the FP4 matrix instruction, and the format sweep
     # of the paper's Table 1 / Fig. 1 axes on the down-projection shape (forward linear, bf16 in/out)
@@ -265,11 +276,14 @@ def main() -> int:
         gbs = nel * 2.5625 / (ms * 1e-3) / 1e9
         quant[label] = {"ms": round(ms, 4), "GB/s": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
     # both orientations in one pass (what the fused forward / backward calls run): 2 + 2 x 0.5625 B/elt
-    for label, rr, rc in (("dual_rtn_rtn", nv.RTN, nv.RTN), ("dual_rtn_sr", nv.RTN, nv.SR), ("dual_sr_sr", nv.SR, nv.SR)):
-        douts = [nv.quantize_dual(xqs[i], rr, 1, rc, 2, tensor_scale=gs[i]) for i in range(NQ)]
+    # (row-major outputs, and the slab layout the fused calls use between quantizer and GEMM)
+    for label, rr, rc, slab in (("dual_rtn_rtn", nv.RTN, nv.RTN, False), ("dual_rtn_sr", nv.RTN, nv.SR, False),
+                                ("dual_sr_sr", nv.SR, nv.SR, False), ("dual_rtn_rtn_slabs", nv.RTN, nv.RTN, True),
+                                ("dual_rtn_sr_slabs", nv.RTN, nv.SR, True), ("dual_sr_sr_slabs", nv.SR, nv.SR, True)):
+        douts = [nv.quantize_dual(xqs[i], rr, 1, rc, 2, tensor_scale=gs[i], slab_rows=slab, slab_cols=slab) for i in range(NQ)]
         douts = [(a[0], a[1], b[0], b[1], a[2]) for a, b in douts]
-        ms = event_time_ms(lambda i: nv.quantize_dual(xqs[i % NQ], rr, 1, rc, 2, tensor_scale=gs[i % NQ], out=douts[i % NQ]),
-                           12, torch, warmup=NQ)
+        ms = event_time_ms(lambda i: nv.quantize_dual(xqs[i % NQ], rr, 1, rc, 2, tensor_scale=gs[i % NQ], out=douts[i % NQ],
+                                                      slab_rows=slab, slab_cols=slab), 12, torch, warmup=NQ)
         gbs = nel * 3.125 / (ms * 1e-3) / 1e9
         quant[label] = {"ms": round(ms, 4), "GB/s": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
     del douts

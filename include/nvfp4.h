@@ -61,6 +61,9 @@ typedef struct {
 
 /* nvfp4_quantize flags */
 #define NVFP4_PRESET_TSCALE 1u /* read g from *tensor_scale instead of computing it */
+/* nvfp4_quantize_dual only: write the row-blocked / the column-blocked output in the slab layout (below) */
+#define NVFP4_SLAB_ROWS 2u
+#define NVFP4_SLAB_COLS 4u
 
 const char *nvfp4_status_string(nvfp4_status s);
 
@@ -161,6 +164,36 @@ nvfp4_status nvfp4_gemm(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
                         const uint8_t *A_codes, const uint8_t *A_scales, const uint8_t *B_codes,
                         const uint8_t *B_scales, const float *tensor_scales, void *out,
                         nvfp4_dtype out_dt, int64_t ldc, void *stream);
+
+/*
+ * Slab layout of an NVFP4 operand (block 16, E4M3 scales), an alternative to the
+ * row-major [rows, K/2] codes and [rows, K/16] scales above.  It holds the same
+ * bytes (same quantization, Sec. 3), arranged the way the large GEMM kernel
+ * fetches them: K must be a multiple of 128; the rows are padded to a multiple
+ * of 256; codes are [rows/256][K/128] slabs of 16 KB, scales the same grid of
+ * 2 KB slabs.  Inside a slab, row r (0..255) of the tile sits at position
+ * p(r) = (r & ~63) | ((r & 7) << 3) | ((r >> 3) & 7) and owns 64 code bytes
+ * (its 128 elements of that K tile, even element in the low nibble) or 8 scale
+ * bytes.  Padding rows are never written and never reach a stored output.
+ * nvfp4_quantize_dual writes it on request (NVFP4_SLAB_ROWS / NVFP4_SLAB_COLS:
+ * the one-pass kernel must apply, i.e. 16-byte aligned rows of x and not SR rows
+ * with RtN columns, else NVFP4_EUNSUPPORTED; cols resp. rows a multiple of 128,
+ * else NVFP4_ESHAPE); the output buffers then need nvfp4_slab_codes_bytes /
+ * nvfp4_slab_scales_bytes (rows = rows of the OPERAND: cols of x for the
+ * column-blocked side).  nvfp4_gemm_slab is nvfp4_gemm with either operand in
+ * this layout (a_slab, b_slab non-zero); it applies where
+ * nvfp4_gemm_takes_slabs returns 1 (NVFP4, K a multiple of 128, at least 128
+ * output tiles of 256 x 256), otherwise NVFP4_EUNSUPPORTED.  The fused linear
+ * entries below use the layout internally wherever it applies; results are
+ * bit-identical either way.
+ */
+size_t nvfp4_slab_codes_bytes(int64_t rows, int64_t K);
+size_t nvfp4_slab_scales_bytes(int64_t rows, int64_t K);
+int nvfp4_gemm_takes_slabs(int64_t M, int64_t N, int64_t K, const nvfp4_format *f);
+nvfp4_status nvfp4_gemm_slab(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
+                             const uint8_t *A_codes, const uint8_t *A_scales, const uint8_t *B_codes,
+                             const uint8_t *B_scales, const float *tensor_scales, void *out,
+                             nvfp4_dtype out_dt, int64_t ldc, int a_slab, int b_slab, void *stream);
 
 /*
  * Forward GEMM, Eq. 4:  Y[M, N] = Q_RtN(X[M, K]) * Q_RtN(W[N, K])^T, blocks along K.

@@ -21,6 +21,8 @@ RTN, SR = 0, 1
 F32, BF16 = 0, 1
 SCALE_E4M3, SCALE_E8M0 = 0, 1
 PRESET_TSCALE = 1
+SLAB_ROWS = 2
+SLAB_COLS = 4
 
 OK, EINVAL, ESHAPE, EALIGN, EUNSUPPORTED, EWORKSPACE, EHIP = range(7)
 
@@ -75,6 +77,14 @@ def _load() -> C.CDLL:
     L.nvfp4_quantize_dual.argtypes = [vp, ci, i64, i64, i64, ci, u64, ci, u64, fp, vp, vp, vp, vp, vp, u32, vp, sz, vp]
     L.nvfp4_gemm.restype = ci
     L.nvfp4_gemm.argtypes = [i64, i64, i64, fp, vp, vp, vp, vp, vp, vp, ci, i64, vp]
+    L.nvfp4_gemm_slab.restype = ci
+    L.nvfp4_gemm_slab.argtypes = [i64, i64, i64, fp, vp, vp, vp, vp, vp, vp, ci, i64, ci, ci, vp]
+    L.nvfp4_gemm_takes_slabs.restype = ci
+    L.nvfp4_gemm_takes_slabs.argtypes = [i64, i64, i64, fp]
+    L.nvfp4_slab_codes_bytes.restype = sz
+    L.nvfp4_slab_codes_bytes.argtypes = [i64, i64]
+    L.nvfp4_slab_scales_bytes.restype = sz
+    L.nvfp4_slab_scales_bytes.argtypes = [i64, i64]
     L.nvfp4_linear_fwd.restype = ci
     L.nvfp4_linear_fwd.argtypes = [vp, vp, vp, i64, i64, i64, ci, ci, fp, vp, sz, vp, vp, vp, u64]
     L.nvfp4_linear_bwd.restype = ci
@@ -118,6 +128,7 @@ EXPORTS = (
     "nvfp4_status_string", "nvfp4_codes_bytes", "nvfp4_scales_bytes",
     "nvfp4_quantize_workspace_bytes", "nvfp4_linear_fwd_workspace_bytes",
     "nvfp4_linear_bwd_workspace_bytes", "nvfp4_linear_saved_bytes", "nvfp4_tensor_scale", "nvfp4_quantize", "nvfp4_quantize_dual", "nvfp4_gemm",
+    "nvfp4_gemm_slab", "nvfp4_gemm_takes_slabs", "nvfp4_slab_codes_bytes", "nvfp4_slab_scales_bytes",
     "nvfp4_linear_fwd", "nvfp4_linear_bwd", "nvfp4_host_e4m3_encode", "nvfp4_host_e4m3_decode",
     "nvfp4_host_round_rtn", "nvfp4_host_round_sr", "nvfp4_host_philox4x32_10",
     "nvfp4_host_sr_bits", "nvfp4_host_e8m0_encode", "nvfp4_host_e4m3_encode_n",
@@ -194,11 +205,14 @@ def quantize(x: torch.Tensor, axis: int = 1, rounding: int = RTN, seed: int = 0,
 
 
 def quantize_dual(x: torch.Tensor, rounding_rows: int = RTN, seed_rows: int = 0, rounding_cols: int = RTN,
-                  seed_cols: int = 0, fmt: Format = NVFP4, tensor_scale: torch.Tensor | None = None, out=None):
+                  seed_cols: int = 0, fmt: Format = NVFP4, tensor_scale: torch.Tensor | None = None, out=None,
+                  slab_rows: bool = False, slab_cols: bool = False):
     """nvfp4_quantize_dual -> ((codes [rows, cols/2], scales [rows, cols/block], g),
     (codes [cols, rows/2], scales [cols, rows/block], g)): both orientations, one shared g.
 
     `out` = (codes_rows, scales_rows, codes_cols, scales_cols, g) reuses caller-provided tensors.
+    slab_rows / slab_cols: that side comes back in the slab layout instead (flat byte tensors of
+    nvfp4_slab_codes_bytes / nvfp4_slab_scales_bytes), for gemm(..., slabs=...).
     """
     _require_gpu(x, tensor_scale)
     assert x.dim() == 2 and (x.stride(1) == 1 or x.shape[1] <= 1)
@@ -210,12 +224,18 @@ def quantize_dual(x: torch.Tensor, rounding_rows: int = RTN, seed_rows: int = 0,
         sr = torch.empty((rows, cols // fmt.block), dtype=torch.uint8, device=x.device)
         cc = torch.empty((cols, rows // 2), dtype=torch.uint8, device=x.device)
         sc = torch.empty((cols, rows // fmt.block), dtype=torch.uint8, device=x.device)
+        if slab_rows:
+            cr = torch.empty(lib.nvfp4_slab_codes_bytes(rows, cols), dtype=torch.uint8, device=x.device)
+            sr = torch.empty(lib.nvfp4_slab_scales_bytes(rows, cols), dtype=torch.uint8, device=x.device)
+        if slab_cols:
+            cc = torch.empty(lib.nvfp4_slab_codes_bytes(cols, rows), dtype=torch.uint8, device=x.device)
+            sc = torch.empty(lib.nvfp4_slab_scales_bytes(cols, rows), dtype=torch.uint8, device=x.device)
         g = torch.empty(1, dtype=torch.float32, device=x.device) if tensor_scale is None else tensor_scale
     else:
         cr, sr, cc, sc, g = out
         if tensor_scale is not None:
             g = tensor_scale
-    flags = PRESET_TSCALE if tensor_scale is not None else 0
+    flags = (PRESET_TSCALE if tensor_scale is not None else 0) | (SLAB_ROWS if slab_rows else 0) | (SLAB_COLS if slab_cols else 0)
     ws = torch.empty(lib.nvfp4_quantize_workspace_bytes(rows, cols), dtype=torch.uint8, device=x.device)
     _check(lib.nvfp4_quantize_dual(x.data_ptr(), _dtype_tag(x), rows, cols, ld, rounding_rows, seed_rows, rounding_cols, seed_cols,
                                    C.byref(f), cr.data_ptr(), sr.data_ptr(), cc.data_ptr(), sc.data_ptr(),
@@ -223,18 +243,25 @@ def quantize_dual(x: torch.Tensor, rounding_rows: int = RTN, seed_rows: int = 0,
     return (cr, sr, g), (cc, sc, g)
 
 
-def gemm(A, B, fmt: Format = NVFP4, out_dtype: torch.dtype = torch.float32, out=None) -> torch.Tensor:
-    """nvfp4_gemm: A = (codes [M,K/2], scales, g[1]), B = (codes [N,K/2], scales, g[1]) -> [M, N]."""
+def gemm(A, B, fmt: Format = NVFP4, out_dtype: torch.dtype = torch.float32, out=None, slabs=(False, False),
+         shape=None) -> torch.Tensor:
+    """nvfp4_gemm: A = (codes [M,K/2], scales, g[1]), B = (codes [N,K/2], scales, g[1]) -> [M, N].
+    slabs = (a, b): that operand is in the slab layout (nvfp4_gemm_slab); then shape = (M, N, K) is required,
+    since a flat slab buffer does not carry it."""
     (ac, asc, ga), (bc, bsc, gb) = A, B
     _require_gpu(ac, asc, ga, bc, bsc, gb)
-    M, N, K = ac.shape[0], bc.shape[0], ac.shape[1] * 2
+    if shape is None:
+        assert not (slabs[0] or slabs[1]), "slab operands: pass shape=(M, N, K)"
+        M, N, K = ac.shape[0], bc.shape[0], ac.shape[1] * 2
+    else:
+        M, N, K = shape
     ts = torch.cat([ga.reshape(1), gb.reshape(1)])
     if out is None:
         out = torch.empty((M, N), dtype=out_dtype, device=ac.device)
     f = fmt.c()
-    _check(lib.nvfp4_gemm(M, N, K, C.byref(f), ac.data_ptr(), asc.data_ptr(), bc.data_ptr(),
-                          bsc.data_ptr(), ts.data_ptr(), out.data_ptr(), _dtype_tag(out),
-                          out.stride(0), _stream()), "nvfp4_gemm")
+    _check(lib.nvfp4_gemm_slab(M, N, K, C.byref(f), ac.data_ptr(), asc.data_ptr(), bc.data_ptr(),
+                               bsc.data_ptr(), ts.data_ptr(), out.data_ptr(), _dtype_tag(out),
+                               out.stride(0), int(bool(slabs[0])), int(bool(slabs[1])), _stream()), "nvfp4_gemm")
     return out
 
 

@@ -285,10 +285,18 @@ nvfp4_status nvfp4_quantize_dual(const void *x, nvfp4_dtype dt, int64_t rows, in
     if (!tensor_scale || (!empty && (!codes_rows || !scales_rows || !codes_cols || !scales_cols))) return NVFP4_EINVAL;
     if (rounding_rows != NVFP4_RTN && rounding_rows != NVFP4_SR) return NVFP4_EINVAL;
     if (rounding_cols != NVFP4_RTN && rounding_cols != NVFP4_SR) return NVFP4_EINVAL;
-    if (flags & ~NVFP4_PRESET_TSCALE) return NVFP4_EINVAL;
+    if (flags & ~(NVFP4_PRESET_TSCALE | NVFP4_SLAB_ROWS | NVFP4_SLAB_COLS)) return NVFP4_EINVAL;
     if (rows % f->block != 0 || cols % f->block != 0) return NVFP4_ESHAPE;
     if (!aligned16(codes_rows) || !aligned16(scales_rows) || !aligned16(codes_cols) || !aligned16(scales_cols))
         return NVFP4_EALIGN;
+    const bool slab_r = (flags & NVFP4_SLAB_ROWS) != 0, slab_c = (flags & NVFP4_SLAB_COLS) != 0;
+    if (slab_r || slab_c) {
+        // only the one-pass kernel writes slabs, and only NVFP4 operands are read back from them
+        if (f->block != 16 || f->scale != NVFP4_SCALE_E4M3 || !use_hw_convert() ||
+            !quantize_dual_fused(dt, rows, cols, ld, f->block, true) || (rounding_rows == NVFP4_SR && rounding_cols == NVFP4_RTN))
+            return NVFP4_EUNSUPPORTED;
+        if ((slab_r && cols % SLAB_K != 0) || (slab_c && rows % SLAB_K != 0)) return NVFP4_ESHAPE;
+    }
     const bool preset = (flags & NVFP4_PRESET_TSCALE) != 0;
     const bool need_amax = f->tensor_scale && !preset;
     if (need_amax) {
@@ -312,6 +320,8 @@ nvfp4_status nvfp4_quantize_dual(const void *x, nvfp4_dtype dt, int64_t rows, in
     d.scales_r = scales_rows;
     d.seed_r = seed_rows;
     d.g_out2 = nullptr;
+    d.slab_r = slab_r;
+    d.slab_c = slab_c;
     if (f->tensor_scale) {
         if (preset) {
             d.c.g_mode = G_PRESET;
@@ -341,6 +351,29 @@ nvfp4_status nvfp4_gemm(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
                         const uint8_t *B_scales, const float *tensor_scales, void *out,
                         nvfp4_dtype out_dt, int64_t ldc, void *stream)
 {
+    return nvfp4_gemm_slab(M, N, K, f, A_codes, A_scales, B_codes, B_scales, tensor_scales, out, out_dt, ldc, 0, 0, stream);
+}
+
+int nvfp4_gemm_takes_slabs(int64_t M, int64_t N, int64_t K, const nvfp4_format *f)
+{
+    return check_format(f) == NVFP4_OK && M > 0 && N > 0 && K > 0 && gemm_takes_slabs(M, N, K, f->block, f->scale) ? 1 : 0;
+}
+
+size_t nvfp4_slab_codes_bytes(int64_t rows, int64_t K)
+{
+    return rows <= 0 || K <= 0 ? 0 : (size_t)slab_rows_padded(rows) * (size_t)K / 2;
+}
+
+size_t nvfp4_slab_scales_bytes(int64_t rows, int64_t K)
+{
+    return rows <= 0 || K <= 0 ? 0 : (size_t)slab_rows_padded(rows) * (size_t)K / 16;
+}
+
+nvfp4_status nvfp4_gemm_slab(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
+                             const uint8_t *A_codes, const uint8_t *A_scales, const uint8_t *B_codes,
+                             const uint8_t *B_scales, const float *tensor_scales, void *out,
+                             nvfp4_dtype out_dt, int64_t ldc, int a_slab, int b_slab, void *stream)
+{
     nvfp4_status s = check_format(f);
     if (s != NVFP4_OK) return s;
     if (!A_codes || !A_scales || !B_codes || !B_scales || !tensor_scales || !out) return NVFP4_EINVAL;
@@ -351,8 +384,9 @@ nvfp4_status nvfp4_gemm(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
         !aligned16(out))
         return NVFP4_EALIGN;
     if (f->scale == NVFP4_SCALE_E8M0 && f->block != 32) return NVFP4_EUNSUPPORTED;  // E8M0 GEMM: MXFP4 only
+    if ((a_slab || b_slab) && !gemm_takes_slabs(M, N, K, f->block, f->scale)) return NVFP4_EUNSUPPORTED;
     if (M == 0 || N == 0) return NVFP4_OK;
-    GemmArgs g{M, N, K, A_codes, A_scales, B_codes, B_scales, tensor_scales, tensor_scales + 1, out, ldc};
+    GemmArgs g{M, N, K, A_codes, A_scales, B_codes, B_scales, tensor_scales, tensor_scales + 1, out, ldc, a_slab != 0, b_slab != 0};
     return launch_gemm(g, f->block, f->scale, out_dt, reinterpret_cast<hipStream_t>(stream)) == hipSuccess
                ? NVFP4_OK
                : NVFP4_EHIP;

@@ -561,3 +561,48 @@ def test_slab_operand_layout_is_invisible(dtype, monkeypatch):
     ref, ref_abs = oracle.gemm_nt_sample(qdyt, qxt, jj, kk), oracle.gemm_nt_sample(qdyt, qxt, jj, kk, take_abs=True)
     got = to_np(outs[0][2].float())[jj, kk]
     assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * ref_abs)
+
+
+def _slab_to_plain(buf, rows, K, per_row):
+    """Undo the documented slab layout: [rows/256][K/128] slabs of 256 positions x per_row bytes, tile row r at
+    position (r & ~63) | ((r & 7) << 3) | ((r >> 3) & 7)."""
+    rt, nkt = (rows + 255) // 256, K // 128
+    a = buf.reshape(rt, nkt, 256, per_row)
+    r = np.arange(256)
+    pos = (r & ~63) | ((r & 7) << 3) | ((r >> 3) & 7)
+    a = a[:, :, pos, :]                                  # [rt, kt, r, bytes]
+    return a.transpose(0, 2, 1, 3).reshape(rt * 256, nkt * per_row)[:rows]
+
+
+@pytest.mark.parametrize("rounding", [(0, 0), (0, 1), (1, 1)], ids=["rtn-rtn", "rtn-sr", "sr-sr"])
+def test_slab_outputs_of_the_dual_quantizer_and_slab_gemm(rounding):
+    # the slab layout as the header documents it: un-permuted on the host it must be the oracle's quantization,
+    # and the GEMM must give the same bits from slab operands as from row-major ones
+    rows, cols = 2944, 3200   # 11.5 and 12.5 slabs of rows; 23 and 25 K tiles
+    rr, rc = rounding
+    x = synth.gradient_like(rows, cols, 71).cuda()
+    print(f"[case] slab outputs rows={rows} cols={cols} rounding={rounding}", flush=True)
+    (cr, sr, g), (cc, sc, _) = nv.quantize_dual(x, rr, 11, rc, 12, slab_rows=True, slab_cols=True)
+    (pr, psr, pg), (pc, psc, _) = nv.quantize_dual(x, rr, 11, rc, 12)
+    torch.cuda.synchronize()
+    assert cr.numel() == 12 * 25 * 16384 and cc.numel() == 13 * 23 * 16384
+    assert np.array_equal(_slab_to_plain(to_np(cr), rows, cols, 64), to_np(pr))
+    assert np.array_equal(_slab_to_plain(to_np(sr), rows, cols, 8), to_np(psr))
+    assert np.array_equal(_slab_to_plain(to_np(cc), cols, rows, 64), to_np(pc))
+    assert np.array_equal(_slab_to_plain(to_np(sc), cols, rows, 8), to_np(psc))
+    assert float(g) == float(pg)
+    xc = x.cpu()
+    assert_quant_equal((pr, psr, pg), oracle.quantize(xc, 1, rr, 11), "rows side")
+    assert_quant_equal((pc, psc, pg), oracle.quantize(xc, 0, rc, 12), "cols side")
+    # GEMM: out[rows, rows'] with K = cols from the row-blocked side against itself, and the column-blocked side
+    # (operand rows = cols of x, K = rows of x) against itself; mixed slab / plain operands too
+    assert nv.lib.nvfp4_gemm_takes_slabs(rows, rows, cols, nv.NVFP4.c()) == 1
+    ref = nv.gemm((pr, psr, pg), (pr, psr, pg), out_dtype=torch.bfloat16)
+    for slabs in ((True, True), (True, False), (False, True)):
+        A = (cr, sr, g) if slabs[0] else (pr, psr, pg)
+        B = (cr, sr, g) if slabs[1] else (pr, psr, pg)
+        got = nv.gemm(A, B, out_dtype=torch.bfloat16, slabs=slabs, shape=(rows, rows, cols))
+        assert torch.equal(got, ref), slabs
+    ref = nv.gemm((pc, psc, pg), (pc, psc, pg))
+    got = nv.gemm((cc, sc, g), (cc, sc, g), slabs=(True, True), shape=(cols, cols, rows))
+    assert torch.equal(got, ref)

@@ -87,7 +87,12 @@ def test_quantize_dual_argument_errors():
     assert dual(sr=None) == nv.EINVAL
     assert dual(rnd=2) == nv.EINVAL
     assert dual(k2=5) == nv.EINVAL
-    assert dual(flags=2) == nv.EINVAL
+    assert dual(flags=8) == nv.EINVAL
+    # slab outputs: NVFP4 only, through the one-pass kernel only, whole K tiles of 128 only
+    assert dual(flags=nv.SLAB_ROWS) == nv.ESHAPE                      # cols = 64
+    assert dual(flags=nv.SLAB_COLS, cols=128, ld=128) == nv.ESHAPE    # rows = 64
+    assert dual(flags=nv.SLAB_ROWS, fmt=nv.MXFP4, rows=128, cols=128, ld=128) == nv.EUNSUPPORTED
+    assert dual(flags=nv.SLAB_ROWS, rows=128, cols=128, ld=128, rnd=nv.SR, k2=nv.RTN) == nv.EUNSUPPORTED
     assert dual(rows=72) == nv.ESHAPE                     # both axes are blocked
     assert dual(cols=72, ld=72) == nv.ESHAPE
     assert dual(rows=96, cols=96, ld=96, fmt=nv.Format(64, 0, 1)) == nv.ESHAPE
@@ -111,6 +116,20 @@ def test_gemm_and_linear_argument_errors():
     assert g(f=nv.Format(64, nv.SCALE_E8M0, 0).c()) == nv.EUNSUPPORTED  # E8M0 GEMM exists for block 32 only
     assert g(M=0) == nv.OK           # empty product: nothing to do, nothing launched
     assert g(K=(1 << 23) + 32) == nv.ESHAPE  # contraction length beyond the kernels' 32-bit tile offsets
+    # slab operands: only where the large-tile kernel runs (NVFP4, K % 128 == 0, >= 128 tiles of 256 x 256)
+    gs = lambda M, N, K, fmt=nv.NVFP4, a=1, b=0: nv.lib.nvfp4_gemm_slab(M, N, K, C.byref(fmt.c()), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
+                                                                        nv.F32, N, a, b, None)
+    assert gs(64, 64, 128) == nv.EUNSUPPORTED
+    assert gs(4096, 4096, 192) == nv.EUNSUPPORTED
+    assert gs(4096, 4096, 4096, nv.MXFP4) == nv.EUNSUPPORTED
+    assert gs(4096, 4096, 4096, nv.Format(32, nv.SCALE_E4M3, 1)) == nv.EUNSUPPORTED
+    takes = lambda M, N, K, fmt=nv.NVFP4: nv.lib.nvfp4_gemm_takes_slabs(M, N, K, C.byref(fmt.c()))
+    assert takes(4096, 11008, 4096) == 1 and takes(2944, 3200, 2816) == 1
+    assert takes(2048, 2048, 4096) == 0 and takes(4096, 4096, 4096 + 64) == 0 and takes(4096, 4096, 4096, nv.MXFP4) == 0
+    # slab buffers: rows padded to whole slabs of 256
+    assert nv.lib.nvfp4_slab_codes_bytes(256, 128) == 16384 and nv.lib.nvfp4_slab_scales_bytes(256, 128) == 2048
+    assert nv.lib.nvfp4_slab_codes_bytes(257, 256) == 2 * 2 * 16384 and nv.lib.nvfp4_slab_scales_bytes(1, 128) == 2048
+    assert nv.lib.nvfp4_slab_codes_bytes(0, 128) == 0
     fw = lambda **k: nv.lib.nvfp4_linear_fwd(k.get("X", FAKE), FAKE, FAKE, k.get("M", 64), 64, k.get("K", 64), nv.BF16,
                                              nv.F32, C.byref(f), k.get("ws", FAKE), k.get("wsb", 1 << 30), None, None,
                                              k.get("saved"), 0)
