@@ -209,6 +209,9 @@ nvfp4_status nvfp4_gemm_slab(int64_t M, int64_t N, int64_t K, const nvfp4_format
  * `saved` and seed == bwd_seed, reads neither X nor W.  Requires M and N to be
  * multiples of the block size and of 32 (NVFP4_ESHAPE otherwise).  Y is the
  * same with and without `saved`.  bwd_seed is ignored when saved is NULL.
+ * The buffer's contents are private to the library (row-major or slab layout
+ * per operand, whichever the consuming GEMM of the backward call will read):
+ * pass it to nvfp4_linear_bwd in the same process and leave it alone.
  */
 nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, int64_t N,
                               int64_t K, nvfp4_dtype in_dt, nvfp4_dtype out_dt,
