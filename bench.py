@@ -79,9 +79,9 @@ def main() -> int:
         Yp = torch.empty((4096, 11008), dtype=torch.bfloat16, device=dev)
         for _ in range(10):
             nv.gemm(qa, qb, out=Yp, slabs=(True, True), shape=(4096, 11008, 4096))
-        qam, qbm = nv.quantize(Xp, 1, fmt=nv.MXFP4), nv.quantize(Wp, 1, fmt=nv.MXFP4)
+        qam, qbm = nv.quantize_dual(Xp, fmt=nv.MXFP4, slab_rows=True)[0], nv.quantize_dual(Wp, fmt=nv.MXFP4, slab_rows=True)[0]
         for _ in range(10):
-            nv.gemm(qam, qbm, nv.MXFP4, out=Yp)
+            nv.gemm(qam, qbm, nv.MXFP4, out=Yp, slabs=(True, True), shape=(4096, 11008, 4096))
         xq = synth.student_t_outliers(8192, 8192, seed=100).to(dev)
         g = nv.tensor_scale(xq)
         for axis in (1, 0):
@@ -219,8 +219,8 @@ def main() -> int:
 
     # ---- MXFP4 (block 32, E8M0): the same GEMM on the FP4 matrix instruction, and the format sweep
     # of the paper's Table 1 / Fig. 1 axes on the down-projection shape (forward linear, bf16 in/out)
-    qam, qbm = nv.quantize(X, 1, fmt=nv.MXFP4), nv.quantize(W, 1, fmt=nv.MXFP4)
-    mx_ms = event_time_ms(lambda i: nv.gemm(qam, qbm, nv.MXFP4, out=Y), max(args.steps, 5), torch)
+    qam, qbm = nv.quantize_dual(X, fmt=nv.MXFP4, slab_rows=True)[0], nv.quantize_dual(W, fmt=nv.MXFP4, slab_rows=True)[0]
+    mx_ms = event_time_ms(lambda i: nv.gemm(qam, qbm, nv.MXFP4, out=Y, slabs=(True, True), shape=(M, N, K)), max(args.steps, 5), torch)
     mx_tflops = 2.0 * M * N * K / (mx_ms * 1e-3) / 1e12
     mxfp4 = {"kernel": "gemm_nt_mxfp4_dma_kernel (gate: 4096x11008x4096)", "bound": "mfma",
              "achieved": round(mx_tflops, 2), "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s",

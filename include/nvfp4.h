@@ -167,7 +167,10 @@ nvfp4_status nvfp4_gemm(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
 
 /*
  * Slab layout of an NVFP4 operand (block 16, E4M3 scales), an alternative to the
- * row-major [rows, K/2] codes and [rows, K/16] scales above.  It holds the same
+ * row-major [rows, K/2] codes and [rows, K/16] scales above.  (MXFP4 operands,
+ * block 32 with E8M0 scales, can use it for their CODES only: same flags, same
+ * nvfp4_slab_codes_bytes, while their scales stay row-major [rows, K/32];
+ * nvfp4_gemm_takes_slabs then asks for K a multiple of 128 and at least 512.)  It holds the same
  * bytes (same quantization, Sec. 3), arranged the way the large GEMM kernel
  * fetches them: K must be a multiple of 128; the rows are padded to a multiple
  * of 256; codes are [rows/256][K/128] slabs of 16 KB, scales the same grid of
@@ -182,7 +185,7 @@ nvfp4_status nvfp4_gemm(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
  * nvfp4_slab_scales_bytes (rows = rows of the OPERAND: cols of x for the
  * column-blocked side).  nvfp4_gemm_slab is nvfp4_gemm with either operand in
  * this layout (a_slab, b_slab non-zero); it applies where
- * nvfp4_gemm_takes_slabs returns 1 (NVFP4, K a multiple of 128, at least 128
+ * nvfp4_gemm_takes_slabs returns 1 (NVFP4: K a multiple of 128 and at least 128
  * output tiles of 256 x 256), otherwise NVFP4_EUNSUPPORTED.  The fused linear
  * entries below use the layout internally wherever it applies; results are
  * bit-identical either way.

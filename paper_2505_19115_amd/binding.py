@@ -226,10 +226,12 @@ def quantize_dual(x: torch.Tensor, rounding_rows: int = RTN, seed_rows: int = 0,
         sc = torch.empty((cols, rows // fmt.block), dtype=torch.uint8, device=x.device)
         if slab_rows:
             cr = torch.empty(lib.nvfp4_slab_codes_bytes(rows, cols), dtype=torch.uint8, device=x.device)
-            sr = torch.empty(lib.nvfp4_slab_scales_bytes(rows, cols), dtype=torch.uint8, device=x.device)
+            if fmt.block == 16:  # (MXFP4 keeps its scales row-major)
+                sr = torch.empty(lib.nvfp4_slab_scales_bytes(rows, cols), dtype=torch.uint8, device=x.device)
         if slab_cols:
             cc = torch.empty(lib.nvfp4_slab_codes_bytes(cols, rows), dtype=torch.uint8, device=x.device)
-            sc = torch.empty(lib.nvfp4_slab_scales_bytes(cols, rows), dtype=torch.uint8, device=x.device)
+            if fmt.block == 16:
+                sc = torch.empty(lib.nvfp4_slab_scales_bytes(cols, rows), dtype=torch.uint8, device=x.device)
         g = torch.empty(1, dtype=torch.float32, device=x.device) if tensor_scale is None else tensor_scale
     else:
         cr, sr, cc, sc, g = out

@@ -54,7 +54,8 @@ bool use_slabs()
 // roundings; its answer does not depend on the element type for shapes the linear entries accept.
 bool dual_writes_slabs(const nvfp4_format *f, int dt, int64_t rows, int64_t cols, int rnd_r, int rnd_c)
 {
-    return use_slabs() && f->block == 16 && f->scale == NVFP4_SCALE_E4M3 &&
+    const bool slab_format = (f->block == 16 && f->scale == NVFP4_SCALE_E4M3) || (f->block == 32 && f->scale == NVFP4_SCALE_E8M0);
+    return use_slabs() && slab_format &&
            quantize_dual_fused(dt, rows, cols, cols, f->block, use_hw_convert()) && !(rnd_r == NVFP4_SR && rnd_c == NVFP4_RTN);
 }
 
@@ -292,7 +293,8 @@ nvfp4_status nvfp4_quantize_dual(const void *x, nvfp4_dtype dt, int64_t rows, in
     const bool slab_r = (flags & NVFP4_SLAB_ROWS) != 0, slab_c = (flags & NVFP4_SLAB_COLS) != 0;
     if (slab_r || slab_c) {
         // only the one-pass kernel writes slabs, and only NVFP4 operands are read back from them
-        if (f->block != 16 || f->scale != NVFP4_SCALE_E4M3 || !use_hw_convert() ||
+        const bool slab_format = (f->block == 16 && f->scale == NVFP4_SCALE_E4M3) || (f->block == 32 && f->scale == NVFP4_SCALE_E8M0);
+        if (!slab_format || !use_hw_convert() ||
             !quantize_dual_fused(dt, rows, cols, ld, f->block, true) || (rounding_rows == NVFP4_SR && rounding_cols == NVFP4_RTN))
             return NVFP4_EUNSUPPORTED;
         if ((slab_r && cols % SLAB_K != 0) || (slab_c && rows % SLAB_K != 0)) return NVFP4_ESHAPE;

@@ -531,15 +531,15 @@ static bool large_tile(int64_t M, int64_t N, int64_t K)
 
 bool gemm_takes_slabs(int64_t M, int64_t N, int64_t K, int block, int sf)
 {
+    if (sf == NVFP4_SCALE_E8M0) return block == 32 && mxfp4_gemm_takes_slabs(K);
     return sf == NVFP4_SCALE_E4M3 && block == 16 && large_tile(M, N, K);
 }
 
 template <int B>
 static void launch_f16_auto(const GemmArgs &P, int out_dt, hipStream_t st)
 {
-    const int64_t big = ((P.M + 255) / 256) * ((P.N + 255) / 256);
     const bool ktail = (P.K % KT) != 0;
-    if (big >= 128 && !ktail)
+    if (large_tile(P.M, P.N, P.K))
         launch_f16<B, 2, 4, 4, 2, false>(P, out_dt, st);
     else if (!ktail)
         launch_f16<B, 2, 2, 2, 2, false>(P, out_dt, st);

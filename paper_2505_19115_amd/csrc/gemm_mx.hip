@@ -348,8 +348,9 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
     for (int u = 0; u < 4; ++u) {
         const int row = (wave * 4 + u) * 16 + (lane >> 2);
         const int c = (lane & 3) ^ ((lane >> 4) & 3);
-        offA[u] = (uint32_t)((row < mrows ? row : mrows - 1) * Kb + c * 16);
-        offB[u] = (uint32_t)((row < nrows ? row : nrows - 1) * Kb + c * 16);
+        // (an operand in the slab layout has all 256 rows of the tile, 64 bytes apart, in slab order)
+        offA[u] = P.a_slab ? (uint32_t)(slab_row(row) * 64 + c * 16) : (uint32_t)((row < mrows ? row : mrows - 1) * Kb + c * 16);
+        offB[u] = P.b_slab ? (uint32_t)(slab_row(row) * 64 + c * 16) : (uint32_t)((row < nrows ? row : nrows - 1) * Kb + c * 16);
     }
     const int srow = wave * 64 + lane;
     const uint32_t offSA = (uint32_t)((srow < mrows ? srow : mrows - 1) * Ks);
@@ -371,11 +372,14 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
     auto dma16 = [&](uint32_t lds_addr, uint32_t voff, const uint8_t *base) {
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(voff), "s"(base) : "memory");
     };
-    const uint8_t *tileA = P.A_codes + m0 * Kb, *tileB = P.B_codes + n0 * Kb;
+    // codes of K tile kt: tile + kt * step (row-major: 64 bytes further along every row; slabs: the next 16 KB slab)
+    const uint8_t *tileA = P.a_slab ? P.A_codes + (int64_t)ty * nkt * SLAB_CODE_BYTES : P.A_codes + m0 * Kb;
+    const uint8_t *tileB = P.b_slab ? P.B_codes + (int64_t)tx * nkt * SLAB_CODE_BYTES : P.B_codes + n0 * Kb;
+    const int64_t stepA = P.a_slab ? SLAB_CODE_BYTES : ROWB, stepB = P.b_slab ? SLAB_CODE_BYTES : ROWB;
     const uint8_t *tileSA = P.A_scales + m0 * Ks, *tileSB = P.B_scales + n0 * Ks;
     auto dma_codes = [&](int kt) {
         const uint32_t st = (uint32_t)(kt & (NS - 1)) * STAGE;
-        const uint8_t *pa = uniform_ptr(tileA + (int64_t)kt * ROWB), *pb = uniform_ptr(tileB + (int64_t)kt * ROWB);
+        const uint8_t *pa = uniform_ptr(tileA + kt * stepA), *pb = uniform_ptr(tileB + kt * stepB);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             dma16(code_dst + st + u * 1024, offA[u], pa);
@@ -472,8 +476,8 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
         const bool more = kt + 3 < nkt;
         const uint32_t lanes = more ? ~0u : 0u;
         const uint32_t dst3 = code_dst + (uint32_t)((kt + 3) & (NS - 1)) * STAGE;
-        const uint8_t *pa = uniform_ptr(more ? tileA + (int64_t)(kt + 3) * ROWB : tileSA);
-        const uint8_t *pb = uniform_ptr(more ? tileB + (int64_t)(kt + 3) * ROWB : tileSA);
+        const uint8_t *pa = uniform_ptr(more ? tileA + (kt + 3) * stepA : tileSA);
+        const uint8_t *pb = uniform_ptr(more ? tileB + (kt + 3) * stepB : tileSA);
         shift_scales(R, S);
         NVFP4_MXD_FENCE
         // step 0: MFMAs 0-7 each shadow one fragment read of step 1 (B fragments first: every row of
@@ -567,14 +571,23 @@ static void launch_mx_fallback(const GemmArgs &P, int out_dt, hipStream_t st)
     }
 }
 
+// The shapes the direct-to-LDS kernel serves (given 16-byte aligned codes and 4-byte aligned scales); it is also the
+// kernel that can read the codes of an operand from slabs.
+bool mxfp4_gemm_takes_slabs(int64_t K)
+{
+    // lane offsets of the direct-to-LDS loads are 32-bit and relative to the tile's first row
+    const bool offsets_fit = (K >> 1) * 256 < ((int64_t)1 << 31);
+    return K % 128 == 0 && K >= 512 && offsets_fit;
+}
+
 hipError_t launch_gemm_mxfp4(const GemmArgs &P, int out_dt, hipStream_t st)
 {
     const uintptr_t codes = reinterpret_cast<uintptr_t>(P.A_codes) | reinterpret_cast<uintptr_t>(P.B_codes);
     const uintptr_t scales = reinterpret_cast<uintptr_t>(P.A_scales) | reinterpret_cast<uintptr_t>(P.B_scales);
-    // lane offsets of the direct-to-LDS loads are 32-bit and relative to the tile's first row
-    const bool offsets_fit = (P.K >> 1) * 256 < ((int64_t)1 << 31);
-    if (P.K % 128 == 0 && P.K >= 512 && (codes & 15) == 0 && (scales & 3) == 0 && offsets_fit)
+    if (mxfp4_gemm_takes_slabs(P.K) && (codes & 15) == 0 && (scales & 3) == 0)
         launch_mx_dma(P, out_dt, st);
+    else if (P.a_slab || P.b_slab)
+        return hipErrorInvalidValue;  // (the fallback kernel reads row-major operands only)
     else
         launch_mx_fallback(P, out_dt, st);
     return hipGetLastError();

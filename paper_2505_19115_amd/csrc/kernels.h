@@ -36,11 +36,13 @@ struct DualArgs {
 
 // Slab layout of a packed operand (library-internal: workspaces and the saved buffer of the fused linear
 // entries; never crosses the C ABI as a documented format).  For an operand of R rows and contraction length K
-// (block 16, K a multiple of 128) the codes are stored as [ceil(R / 256)][K / 128] slabs of 16 KB: one slab is
+// (K a multiple of 128) the codes are stored as [ceil(R / 256)][K / 128] slabs of 16 KB: one slab is
 // what one GEMM workgroup fetches per K tile, 256 rows x 64 bytes, contiguous.  Inside a slab row r (0..255) sits
 // at position slab_row(r), which swaps the two 3-bit fields of r below bit 6: the column-blocked quantizer holds
 // rows 8 cx + j (lane group cx, column j of the lane) and with this order each of its store instructions writes
 // 512 contiguous bytes.  The scales follow the same scheme with 8 bytes per row (slabs of 2 KB).
+// MXFP4 operands (block 32, E8M0) use the same slabs for their codes and keep their scales row-major: the FP4 GEMM
+// fetches 16 scale bytes = four K tiles of a row at a time.
 constexpr int64_t SLAB_ROWS = 256, SLAB_K = 128, SLAB_CODE_BYTES = 16384, SLAB_SCALE_BYTES = 2048;
 __host__ __device__ inline int slab_row(int r) { return (r & ~63) | ((r & 7) << 3) | ((r >> 3) & 7); }
 inline int64_t slab_rows_padded(int64_t rows) { return (rows + SLAB_ROWS - 1) / SLAB_ROWS * SLAB_ROWS; }
@@ -93,6 +95,7 @@ hipError_t launch_quantize_dual(const DualArgs &D, int dt, int rnd_rows, int rnd
                                 bool hw_convert, hipStream_t st);
 hipError_t launch_gemm(const GemmArgs &P, int block, int sf, int out_dt, hipStream_t st);
 hipError_t launch_gemm_mxfp4(const GemmArgs &P, int out_dt, hipStream_t st);  // block 32, E8M0
+bool mxfp4_gemm_takes_slabs(int64_t K);  // MXFP4: the codes of an operand may come as slabs (its scales stay row-major)
 // Noise statistics: per-workgroup partial pairs (quant_noise_partials() of them), folded into sums[2].
 int64_t quant_noise_partials(int64_t rows, int64_t cols, int axis);
 hipError_t launch_quant_noise(const void *x, int dt, int64_t rows, int64_t cols, int64_t ld, int axis, int block, int sf,

@@ -599,14 +599,18 @@ __device__ __forceinline__ void cols_tile(const QuantArgs &P, Chunk<DT> (&v)[16]
         }
     }
 
-    if (B == 16 && RPL == 16 && slab != nullptr) {
+    if (RPL == 16 && slab != nullptr) {
         // slab layout (the caller guarantees a lane tile entirely inside the tensor or entirely outside): a store
-        // instruction of the wave writes 512 contiguous code bytes, 64 contiguous scale bytes
+        // instruction of the wave writes 512 contiguous code bytes and, for blocks of 16, 64 contiguous scale
+        // bytes; wider blocks keep their scales row-major
         if (ncol == 8) {
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
                 store8_stream(slab->codes + 512 * c, words[c][0], words[c][1]);
-                slab->scales[64 * c] = (uint8_t)sbytes[c][0];
+                if (B == 16)
+                    slab->scales[64 * c] = (uint8_t)sbytes[c][0];
+                else if (lv % LPB == 0)
+                    P.scales[(col0 + c) * nblk + row0 / B] = (uint8_t)sbytes[c][0];
             }
         }
         return;
@@ -723,15 +727,15 @@ __global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
     // column-blocked side: exactly the columns kernel's tile.  In the slab layout the workgroup's 256 columns are
     // one tile of operand rows and its 128 rows one K tile: it fills exactly one slab.
     ColSlab cs;
-    if (B == 16 && D.slab_c) {
+    if (D.slab_c) {
         const int64_t slab = (int64_t)blockIdx.x * (P.rows / SLAB_K) + blockIdx.y;
         cs.codes = P.codes + slab * SLAB_CODE_BYTES + wave * 4096 + lane * 8;
-        cs.scales = P.scales + slab * SLAB_SCALE_BYTES + wave * 512 + lane;
+        cs.scales = P.scales + slab * SLAB_SCALE_BYTES + wave * 512 + lane;  // (used for blocks of 16 only)
     }
-    cols_tile<DT, B, SF, RND_C, true, true, 8>(P, v, g, k, row0, col0, inside ? 8 : 0, lv, B == 16 && D.slab_c ? &cs : nullptr);
+    cols_tile<DT, B, SF, RND_C, true, true, 8>(P, v, g, k, row0, col0, inside ? 8 : 0, lv, D.slab_c ? &cs : nullptr);
 
     __syncthreads();
-    if (B == 16 && D.slab_r) {
+    if (D.slab_r) {
         // slab layout: the tile is rows (wrow0 % 256) .. + 127 of two slabs (K tiles 2 blockIdx.x and + 1 of row
         // tile wrow0 / 256).  Threads walk the slab positions q; position q holds tile row slab_row(q).
         const int64_t nkt = P.cols / SLAB_K;
@@ -746,7 +750,7 @@ __global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
                 __builtin_nontemporal_store(o, reinterpret_cast<u32x4_t *>(D.codes_r + (slab0 + (c >> 2)) * SLAB_CODE_BYTES + (half + q) * 64 + (c & 3) * 16));
             }
         }
-        if (threadIdx.x < G::WG_ROWS) {
+        if (B == 16 && threadIdx.x < G::WG_ROWS) {
             const int q = threadIdx.x, R = slab_row(q);
             if (wrow0 + R < P.rows) {
                 const uint32_t *src = reinterpret_cast<const uint32_t *>(&lds_scales[R * 16]);
@@ -755,23 +759,25 @@ __global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
                 if (wcol0 + 128 < P.cols) store8_stream(dst + SLAB_SCALE_BYTES, src[2], src[3]);
             }
         }
-        return;
+        if (B == 16) return;
     }
     const int64_t cpr = P.cols >> 1;
     const bool wide = (cpr & 15) == 0;  // rows of the code matrix are 16-byte aligned
+    if (!D.slab_r) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int id = threadIdx.x + 256 * i, R = id >> 3, c = id & 7;
-        const int64_t row = wrow0 + R, col = wcol0 + c * 32;
-        if (row < P.rows && col < P.cols) {
-            const uint4 w = *reinterpret_cast<const uint4 *>(&lds_codes[R * (ROW_BYTES / 4) + ((c ^ (R >> 4)) << 2)]);
-            uint8_t *dst = D.codes_r + row * cpr + (col >> 1);
-            if (col + 32 <= P.cols && wide) {
-                const u32x4_t o = {w.x, w.y, w.z, w.w};
-                __builtin_nontemporal_store(o, reinterpret_cast<u32x4_t *>(dst));
-            } else {
-                store8_stream(dst, w.x, w.y);
-                if (col + 32 <= P.cols) store8_stream(dst + 8, w.z, w.w);
+        for (int i = 0; i < 4; ++i) {
+            const int id = threadIdx.x + 256 * i, R = id >> 3, c = id & 7;
+            const int64_t row = wrow0 + R, col = wcol0 + c * 32;
+            if (row < P.rows && col < P.cols) {
+                const uint4 w = *reinterpret_cast<const uint4 *>(&lds_codes[R * (ROW_BYTES / 4) + ((c ^ (R >> 4)) << 2)]);
+                uint8_t *dst = D.codes_r + row * cpr + (col >> 1);
+                if (col + 32 <= P.cols && wide) {
+                    const u32x4_t o = {w.x, w.y, w.z, w.w};
+                    __builtin_nontemporal_store(o, reinterpret_cast<u32x4_t *>(dst));
+                } else {
+                    store8_stream(dst, w.x, w.y);
+                    if (col + 32 <= P.cols) store8_stream(dst + 8, w.z, w.w);
+                }
             }
         }
     }

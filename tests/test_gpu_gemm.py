@@ -523,22 +523,25 @@ def test_swiglu_mlp_fwd_bwd_stage_by_stage():
         assert torch.isfinite(t.float()).all()
 
 
+@pytest.mark.parametrize("fmt_name", ["NVFP4", "MXFP4"])
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
-def test_slab_operand_layout_is_invisible(dtype, monkeypatch):
+def test_slab_operand_layout_is_invisible(dtype, fmt_name, monkeypatch):
     # Between the quantizers and the large-tile GEMM the fused entries keep their packed operands as per-K-tile
     # slabs; NVFP4_PLAIN_OPERANDS=1 keeps them row-major.  Both must give the same bits.  Shape: all three GEMMs
     # of the layer large enough for the slab path, two of the three dimensions not multiples of the 256-row slab.
     M, N, K = 2944, 3200, 2816
-    print(f"[case] slab layout vs plain M={M} N={N} K={K} {dtype}", flush=True)
+    fmt = getattr(nv, fmt_name)
+    of = ofmt(fmt)
+    print(f"[case] slab layout vs plain M={M} N={N} K={K} {dtype} {fmt_name}", flush=True)
     X = synth.normal(M, K, 1.0, 611, dtype).cuda()
     W = synth.normal(N, K, 0.02, 612, dtype).cuda()
     dY = synth.gradient_like(M, N, 613, dtype=dtype).cuda()
     outs = []
     for plain in ("0", "1"):
         monkeypatch.setenv("NVFP4_PLAIN_OPERANDS", plain)
-        saved = torch.empty(nv.linear_saved_bytes(M, N, K), dtype=torch.uint8, device="cuda")
-        Y = nv.linear_fwd(X, W, out_dtype=torch.bfloat16, saved=saved, bwd_seed=77)
-        dX, dW = nv.linear_bwd(dY, None, None, 77, out_dtype=torch.bfloat16, saved=saved, K=K)
+        saved = torch.empty(nv.linear_saved_bytes(M, N, K, fmt), dtype=torch.uint8, device="cuda")
+        Y = nv.linear_fwd(X, W, fmt, out_dtype=torch.bfloat16, saved=saved, bwd_seed=77)
+        dX, dW = nv.linear_bwd(dY, None, None, 77, fmt, out_dtype=torch.bfloat16, saved=saved, K=K)
         torch.cuda.synchronize()
         outs.append((Y, dX, dW))
     for a, b, what in zip(outs[0], outs[1], ("Y", "dX", "dW")):
@@ -548,17 +551,17 @@ def test_slab_operand_layout_is_invisible(dtype, monkeypatch):
     Xc, Wc, dYc = X.cpu(), W.cpu(), dY.cpu()
     ii = np.concatenate([rng.integers(0, M, 24), [M - 1, M - 100, 2816]])
     jj = np.concatenate([rng.integers(0, N, 24), [N - 1, N - 60, 3072]])
-    qx, qw = oracle.quantize(Xc, 1), oracle.quantize(Wc, 1)
-    ref, ref_abs = oracle.gemm_nt_sample(qx, qw, ii, jj), oracle.gemm_nt_sample(qx, qw, ii, jj, take_abs=True)
+    qx, qw = oracle.quantize(Xc, 1, oracle.RTN, 0, of), oracle.quantize(Wc, 1, oracle.RTN, 0, of)
+    ref, ref_abs = oracle.gemm_nt_sample(qx, qw, ii, jj, of), oracle.gemm_nt_sample(qx, qw, ii, jj, of, take_abs=True)
     got = to_np(outs[0][0].float())[ii, jj]
     assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * ref_abs)
     kk = rng.integers(0, K, 27)
-    qdy, qwt = oracle.quantize(dYc, 1, oracle.SR, 77), oracle.quantize(Wc, 0)
-    ref, ref_abs = oracle.gemm_nt_sample(qdy, qwt, ii, kk), oracle.gemm_nt_sample(qdy, qwt, ii, kk, take_abs=True)
+    qdy, qwt = oracle.quantize(dYc, 1, oracle.SR, 77, of), oracle.quantize(Wc, 0, oracle.RTN, 0, of)
+    ref, ref_abs = oracle.gemm_nt_sample(qdy, qwt, ii, kk, of), oracle.gemm_nt_sample(qdy, qwt, ii, kk, of, take_abs=True)
     got = to_np(outs[0][1].float())[ii, kk]
     assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * ref_abs)
-    qdyt, qxt = oracle.quantize(dYc, 0, oracle.SR, 78), oracle.quantize(Xc, 0, oracle.SR, 79)
-    ref, ref_abs = oracle.gemm_nt_sample(qdyt, qxt, jj, kk), oracle.gemm_nt_sample(qdyt, qxt, jj, kk, take_abs=True)
+    qdyt, qxt = oracle.quantize(dYc, 0, oracle.SR, 78, of), oracle.quantize(Xc, 0, oracle.SR, 79, of)
+    ref, ref_abs = oracle.gemm_nt_sample(qdyt, qxt, jj, kk, of), oracle.gemm_nt_sample(qdyt, qxt, jj, kk, of, take_abs=True)
     got = to_np(outs[0][2].float())[jj, kk]
     assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * ref_abs)
 
@@ -574,35 +577,40 @@ def _slab_to_plain(buf, rows, K, per_row):
     return a.transpose(0, 2, 1, 3).reshape(rt * 256, nkt * per_row)[:rows]
 
 
+@pytest.mark.parametrize("fmt_name", ["NVFP4", "MXFP4"])
 @pytest.mark.parametrize("rounding", [(0, 0), (0, 1), (1, 1)], ids=["rtn-rtn", "rtn-sr", "sr-sr"])
-def test_slab_outputs_of_the_dual_quantizer_and_slab_gemm(rounding):
+def test_slab_outputs_of_the_dual_quantizer_and_slab_gemm(rounding, fmt_name):
     # the slab layout as the header documents it: un-permuted on the host it must be the oracle's quantization,
     # and the GEMM must give the same bits from slab operands as from row-major ones
     rows, cols = 2944, 3200   # 11.5 and 12.5 slabs of rows; 23 and 25 K tiles
     rr, rc = rounding
+    fmt = getattr(nv, fmt_name)
     x = synth.gradient_like(rows, cols, 71).cuda()
-    print(f"[case] slab outputs rows={rows} cols={cols} rounding={rounding}", flush=True)
-    (cr, sr, g), (cc, sc, _) = nv.quantize_dual(x, rr, 11, rc, 12, slab_rows=True, slab_cols=True)
-    (pr, psr, pg), (pc, psc, _) = nv.quantize_dual(x, rr, 11, rc, 12)
+    print(f"[case] slab outputs rows={rows} cols={cols} rounding={rounding} {fmt_name}", flush=True)
+    (cr, sr, g), (cc, sc, _) = nv.quantize_dual(x, rr, 11, rc, 12, fmt, slab_rows=True, slab_cols=True)
+    (pr, psr, pg), (pc, psc, _) = nv.quantize_dual(x, rr, 11, rc, 12, fmt)
     torch.cuda.synchronize()
     assert cr.numel() == 12 * 25 * 16384 and cc.numel() == 13 * 23 * 16384
     assert np.array_equal(_slab_to_plain(to_np(cr), rows, cols, 64), to_np(pr))
-    assert np.array_equal(_slab_to_plain(to_np(sr), rows, cols, 8), to_np(psr))
     assert np.array_equal(_slab_to_plain(to_np(cc), cols, rows, 64), to_np(pc))
-    assert np.array_equal(_slab_to_plain(to_np(sc), cols, rows, 8), to_np(psc))
+    if fmt.block == 16:
+        assert np.array_equal(_slab_to_plain(to_np(sr), rows, cols, 8), to_np(psr))
+        assert np.array_equal(_slab_to_plain(to_np(sc), cols, rows, 8), to_np(psc))
+    else:  # MXFP4: only the codes move; the scales stay row-major
+        assert torch.equal(sr, psr) and torch.equal(sc, psc)
     assert float(g) == float(pg)
     xc = x.cpu()
-    assert_quant_equal((pr, psr, pg), oracle.quantize(xc, 1, rr, 11), "rows side")
-    assert_quant_equal((pc, psc, pg), oracle.quantize(xc, 0, rc, 12), "cols side")
+    assert_quant_equal((pr, psr, pg), oracle.quantize(xc, 1, rr, 11, ofmt(fmt)), "rows side")
+    assert_quant_equal((pc, psc, pg), oracle.quantize(xc, 0, rc, 12, ofmt(fmt)), "cols side")
     # GEMM: out[rows, rows'] with K = cols from the row-blocked side against itself, and the column-blocked side
     # (operand rows = cols of x, K = rows of x) against itself; mixed slab / plain operands too
-    assert nv.lib.nvfp4_gemm_takes_slabs(rows, rows, cols, nv.NVFP4.c()) == 1
-    ref = nv.gemm((pr, psr, pg), (pr, psr, pg), out_dtype=torch.bfloat16)
+    assert nv.lib.nvfp4_gemm_takes_slabs(rows, rows, cols, fmt.c()) == 1
+    ref = nv.gemm((pr, psr, pg), (pr, psr, pg), fmt, out_dtype=torch.bfloat16)
     for slabs in ((True, True), (True, False), (False, True)):
         A = (cr, sr, g) if slabs[0] else (pr, psr, pg)
         B = (cr, sr, g) if slabs[1] else (pr, psr, pg)
-        got = nv.gemm(A, B, out_dtype=torch.bfloat16, slabs=slabs, shape=(rows, rows, cols))
+        got = nv.gemm(A, B, fmt, out_dtype=torch.bfloat16, slabs=slabs, shape=(rows, rows, cols))
         assert torch.equal(got, ref), slabs
-    ref = nv.gemm((pc, psc, pg), (pc, psc, pg))
-    got = nv.gemm((cc, sc, g), (cc, sc, g), slabs=(True, True), shape=(cols, cols, rows))
+    ref = nv.gemm((pc, psc, pg), (pc, psc, pg), fmt)
+    got = nv.gemm((cc, sc, g), (cc, sc, g), fmt, slabs=(True, True), shape=(cols, cols, rows))
     assert torch.equal(got, ref)

@@ -91,7 +91,7 @@ def test_quantize_dual_argument_errors():
     # slab outputs: NVFP4 only, through the one-pass kernel only, whole K tiles of 128 only
     assert dual(flags=nv.SLAB_ROWS) == nv.ESHAPE                      # cols = 64
     assert dual(flags=nv.SLAB_COLS, cols=128, ld=128) == nv.ESHAPE    # rows = 64
-    assert dual(flags=nv.SLAB_ROWS, fmt=nv.MXFP4, rows=128, cols=128, ld=128) == nv.EUNSUPPORTED
+    assert dual(flags=nv.SLAB_ROWS, fmt=nv.Format(32, nv.SCALE_E4M3, 1), rows=128, cols=128, ld=128) == nv.EUNSUPPORTED
     assert dual(flags=nv.SLAB_ROWS, rows=128, cols=128, ld=128, rnd=nv.SR, k2=nv.RTN) == nv.EUNSUPPORTED
     assert dual(rows=72) == nv.ESHAPE                     # both axes are blocked
     assert dual(cols=72, ld=72) == nv.ESHAPE
@@ -121,11 +121,12 @@ def test_gemm_and_linear_argument_errors():
                                                                         nv.F32, N, a, b, None)
     assert gs(64, 64, 128) == nv.EUNSUPPORTED
     assert gs(4096, 4096, 192) == nv.EUNSUPPORTED
-    assert gs(4096, 4096, 4096, nv.MXFP4) == nv.EUNSUPPORTED
+    assert gs(4096, 4096, 256, nv.MXFP4) == nv.EUNSUPPORTED      # MXFP4: the direct-to-LDS kernel needs K >= 512
     assert gs(4096, 4096, 4096, nv.Format(32, nv.SCALE_E4M3, 1)) == nv.EUNSUPPORTED
     takes = lambda M, N, K, fmt=nv.NVFP4: nv.lib.nvfp4_gemm_takes_slabs(M, N, K, C.byref(fmt.c()))
     assert takes(4096, 11008, 4096) == 1 and takes(2944, 3200, 2816) == 1
-    assert takes(2048, 2048, 4096) == 0 and takes(4096, 4096, 4096 + 64) == 0 and takes(4096, 4096, 4096, nv.MXFP4) == 0
+    assert takes(2048, 2048, 4096) == 0 and takes(4096, 4096, 4096 + 64) == 0
+    assert takes(4096, 4096, 4096, nv.MXFP4) == 1 and takes(64, 64, 512, nv.MXFP4) == 1 and takes(64, 64, 384, nv.MXFP4) == 0
     # slab buffers: rows padded to whole slabs of 256
     assert nv.lib.nvfp4_slab_codes_bytes(256, 128) == 16384 and nv.lib.nvfp4_slab_scales_bytes(256, 128) == 2048
     assert nv.lib.nvfp4_slab_codes_bytes(257, 256) == 2 * 2 * 16384 and nv.lib.nvfp4_slab_scales_bytes(1, 128) == 2048
