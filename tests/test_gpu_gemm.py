@@ -614,3 +614,28 @@ def test_slab_outputs_of_the_dual_quantizer_and_slab_gemm(rounding, fmt_name):
     ref = nv.gemm((pc, psc, pg), (pc, psc, pg), fmt)
     got = nv.gemm((cc, sc, g), (cc, sc, g), fmt, slabs=(True, True), shape=(cols, cols, rows))
     assert torch.equal(got, ref)
+
+
+@pytest.mark.parametrize("fmt_name", ["NVFP4", "MXFP4"])
+@pytest.mark.parametrize("shape", [(4096, 4096, 256), (8192, 256, 8192), (2048, 2048, 2048), (4096, 640, 4096)],
+                         ids=["fwd-only", "dX-only", "none-for-nvfp4", "mixed"])
+def test_slab_layout_chosen_per_operand(shape, fmt_name, monkeypatch):
+    # shapes where only some of the three GEMMs take slab operands (few output tiles, short K): each operand's
+    # layout is decided by its own consumer, and every combination must equal the all-row-major run bit for bit
+    M, N, K = shape
+    fmt = getattr(nv, fmt_name)
+    print(f"[case] per-operand slab choice M={M} N={N} K={K} {fmt_name}", flush=True)
+    X = synth.normal(M, K, 1.0, 701).cuda()
+    W = synth.normal(N, K, 0.02, 702).cuda()
+    dY = synth.gradient_like(M, N, 703).cuda()
+    outs = []
+    for plain in ("0", "1"):
+        monkeypatch.setenv("NVFP4_PLAIN_OPERANDS", plain)
+        saved = torch.empty(nv.linear_saved_bytes(M, N, K, fmt), dtype=torch.uint8, device="cuda")
+        Y = nv.linear_fwd(X, W, fmt, out_dtype=torch.bfloat16, saved=saved, bwd_seed=5)
+        dX, dW = nv.linear_bwd(dY, None, None, 5, fmt, out_dtype=torch.bfloat16, saved=saved, K=K)
+        torch.cuda.synchronize()
+        outs.append((Y, dX, dW))
+    for a, b, what in zip(outs[0], outs[1], ("Y", "dX", "dW")):
+        assert torch.equal(a, b), what
+    assert torch.isfinite(outs[0][0].float()).all() and torch.isfinite(outs[0][1].float()).all() and torch.isfinite(outs[0][2].float()).all()
