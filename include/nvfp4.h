@@ -59,6 +59,12 @@ typedef struct {
     int32_t tensor_scale; /* 1: per-tensor fp32 scale g; 0: g = 1 */
 } nvfp4_format;
 
+/*
+ * Two environment switches exist for cross-checking, read at every call; neither changes a result bit:
+ *   NVFP4_SOFT_CONVERT=1    round elements and block scales with integer/fp32 arithmetic instead of the gfx950
+ *                           convert instructions (then nvfp4_quantize_dual runs as two kernels, no slabs);
+ *   NVFP4_PLAIN_OPERANDS=1  the fused linear entries keep their internal operands row-major (no slabs).
+ */
 /* nvfp4_quantize flags */
 #define NVFP4_PRESET_TSCALE 1u /* read g from *tensor_scale instead of computing it */
 /* nvfp4_quantize_dual only: write the row-blocked / the column-blocked output in the slab layout (below) */
