@@ -326,7 +326,7 @@ def main() -> int:
         "dtype": "e2m1 codes x e4m3 scales, expanded exactly to f16 for MFMA, f32 accumulate",
         "data": "synthetic",
         "config": {"workload": "Llama2-7B SwiGLU MLP linears fwd+bwd (gate, up, down), tokens=4096: "
-                               "9 GEMMs + 9 dual-orientation quantize passes (X, W in the forward call, which saves Q_SR(X^T), Q_RtN(W^T) and the scales for the backward call; dY in the backward call) + 9 tensor-maximum passes per step, bf16 in",
+                               "9 GEMMs + 9 dual-orientation quantize passes (X, W in the forward call, which saves Q_SR(X^T), Q_RtN(W^T) and the scales for the backward call; dY in the backward call) + 9 tensor-maximum passes per step, bf16 in and out; packed operands pass from the quantizers to the GEMMs in the library's slab layout",
                    "M": M, "layers": [[n, N, K] for n, N, K in layers], "format": "NVFP4 (block 16, E4M3, tensor scale)",
                    "rounding": "fwd RtN; bwd/update SR (Philox4x32-10)",
                    "schedule": ("all forward calls, then all backward calls, in the MLP's dependency order; gate and up side by side "
