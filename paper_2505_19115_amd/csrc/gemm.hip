@@ -12,6 +12,11 @@
 // which is exact for every E4M3 byte, including its subnormals; the MFMA operands themselves
 // are always normal fp16 numbers or zero.  The contraction runs on v_mfma_f32_32x32x16_f16 with
 // fp32 accumulation; the tensor scales multiply once in the epilogue.
+//
+// Operand storage: row-major ([rows, K/2] codes, [rows, K/B] scale bytes), or, for blocks of 16 in the 256 x 256
+// kernel, the slab layout of kernels.h, in which the 256 rows x 64 code bytes (and 256 x 8 scale bytes) that a
+// workgroup fetches per K tile are one contiguous piece.  Only addresses differ: per-lane offsets, two base
+// pointers and their step per K tile.
 #include "kernels.h"
 #include "nvfp4_math.h"
 
