@@ -91,6 +91,12 @@ def main() -> int:
         for rnd in (nv.RTN, nv.SR):
             for _ in range(2):
                 nv.quantize_dual(xq, rnd, 1, rnd, 2, tensor_scale=g, slab_rows=True, slab_cols=True)
+        # the dual passes of the step at their own shapes: X (RtN rows, SR columns), W (RtN, RtN), dY (SR, SR)
+        dYp = synth.gradient_like(4096, 11008, 300).to(dev)
+        for t, rr, rc in ((Xp, nv.RTN, nv.SR), (Wp, nv.RTN, nv.RTN), (dYp, nv.SR, nv.SR)):
+            gt = nv.tensor_scale(t)
+            for _ in range(2):
+                nv.quantize_dual(t, rr, 1, rc, 2, tensor_scale=gt, slab_rows=True, slab_cols=True)
         torch.cuda.synchronize()
         print("probe done")
         return 0

@@ -60,11 +60,20 @@ typedef struct {
 } nvfp4_format;
 
 /*
- * Two environment switches exist for cross-checking, read at every call; neither changes a result bit:
- *   NVFP4_SOFT_CONVERT=1    round elements and block scales with integer/fp32 arithmetic instead of the gfx950
- *                           convert instructions (then nvfp4_quantize_dual runs as two kernels, no slabs);
- *   NVFP4_PLAIN_OPERANDS=1  the fused linear entries keep their internal operands row-major (no slabs).
+ * Two switches exist for cross-checking; neither changes a result bit.  They are taken from the environment once,
+ * by the first call that needs them, and stay fixed for the process unless nvfp4_cross_check_switches replaces them:
+ *   bit 0 / NVFP4_SOFT_CONVERT=1    round elements and block scales with integer/fp32 arithmetic instead of the
+ *                                   gfx950 convert instructions (then nvfp4_quantize_dual runs as two kernels, no slabs);
+ *   bit 1 / NVFP4_PLAIN_OPERANDS=1  the fused linear entries keep their internal operands row-major (no slabs).
+ * nvfp4_cross_check_switches(set, value) returns the switches in force and, with set != 0, replaces them by
+ * `value` (bits 0-1) for every later call of the process.  It is a test hook: call it only while no other thread is
+ * inside the library, and not between a forward call that fills a `saved` buffer and its backward call
+ * (nvfp4_linear_bwd refuses such a buffer with NVFP4_EINVAL).
  */
+#define NVFP4_SWITCH_SOFT_CONVERT 1u
+#define NVFP4_SWITCH_PLAIN_OPERANDS 2u
+uint32_t nvfp4_cross_check_switches(int set, uint32_t value);
+
 /* nvfp4_quantize flags */
 #define NVFP4_PRESET_TSCALE 1u /* read g from *tensor_scale instead of computing it */
 /* nvfp4_quantize_dual only: write the row-blocked / the column-blocked output in the slab layout (below) */
@@ -220,7 +229,9 @@ nvfp4_status nvfp4_gemm_slab(int64_t M, int64_t N, int64_t K, const nvfp4_format
  * same with and without `saved`.  bwd_seed is ignored when saved is NULL.
  * The buffer's contents are private to the library (row-major or slab layout
  * per operand, whichever the consuming GEMM of the backward call will read):
- * pass it to nvfp4_linear_bwd in the same process and leave it alone.
+ * pass it to nvfp4_linear_bwd in the same process and leave it alone.  Its
+ * header carries a tag (M, N, K, format, bwd_seed, operand layouts) that the
+ * backward call checks.
  */
 nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, int64_t N,
                               int64_t K, nvfp4_dtype in_dt, nvfp4_dtype out_dt,
@@ -238,7 +249,12 @@ nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, 
  * results are identical).  Ignored for a format without tensor scale.
  * saved: NULL, or what nvfp4_linear_fwd wrote for the same M, N, K, format and
  * bwd_seed == seed: X, W and xw_scales are then not read (they may be NULL) and
- * the results are identical to those of the call without `saved`.
+ * the results are identical to those of the call without `saved`.  A buffer
+ * that one of the last 256 forward calls of this process wrote for different
+ * shapes, format, seed or cross-check switches is refused with NVFP4_EINVAL
+ * before anything is launched; for a buffer the library has no host record of,
+ * the tag in the buffer itself is compared on the device and a mismatch turns
+ * dX and dW into NaN.
  * With both dX and dW requested, dY is read once for its two quantizations.
  */
 nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void *dX, void *dW,

@@ -132,9 +132,9 @@ uint32_t orc_sr_bits(uint64_t seed, uint64_t e)
 
 /* --------------------------------------------------------- element rounding */
 
-/* Round-to-nearest (Sec. 1: "maps each value to its closest representable
- * value"): m in [0, 6] -> magnitude code 0..7.  Ties go to the even code
- * (reading; the IEEE default). */
+/* Round-to-nearest as Sec. 1 defines it (the grid value nearest to the input):
+ * m in [0, 6] -> magnitude code 0..7.  Ties go to the even code (reading; the
+ * IEEE default). */
 uint8_t orc_round_rtn(float m)
 {
     uint8_t best = 0;
@@ -149,13 +149,13 @@ uint8_t orc_round_rtn(float m)
     return best;
 }
 
-/* Stochastic rounding (Sec. 1: "probabilistically rounds based on the distance
- * to neighboring values"): with lo <= m < hi the neighbouring grid values and
- * t = (m - lo)/(hi - lo), the result is hi with probability t (to 2^-17) and lo
+/* Stochastic rounding as Sec. 1 defines it (one of the two neighbouring grid
+ * values, chosen at random by how close each is): with lo <= m < hi the
+ * neighbouring grid values and t = (m - lo)/(hi - lo), the result is hi with probability t (to 2^-17) and lo
  * otherwise, so that the expected result is m (the E[eps] = 0 property used in
  * Sec. 4).  The draw is a 16-bit uniform u: round up iff u + 1/2 <= 65536 t,
- * which is the classic formulation "add uniformly random bits below the kept
- * digit, then truncate" with the draw centred on the 16-bit grid (reading: the
+ * which is the classic formulation (add uniformly random bits below the kept
+ * digit, then truncate) with the draw centred on the 16-bit grid (reading: the
  * paper fixes neither the number of random bits nor which way the one exact
  * tie u + 1/2 = 65536 t goes).  A value on the grid (t = 0) and the saturated
  * value 6 never move. */

@@ -73,6 +73,8 @@ def _load() -> C.CDLL:
     L.nvfp4_tensor_scale.argtypes = [vp, ci, i64, i64, i64, vp, vp, sz, vp]
     L.nvfp4_quantize.restype = ci
     L.nvfp4_quantize.argtypes = [vp, ci, i64, i64, i64, ci, ci, u64, fp, vp, vp, vp, u32, vp, sz, vp]
+    L.nvfp4_cross_check_switches.restype = u32
+    L.nvfp4_cross_check_switches.argtypes = [ci, u32]
     L.nvfp4_quantize_dual.restype = ci
     L.nvfp4_quantize_dual.argtypes = [vp, ci, i64, i64, i64, ci, u64, ci, u64, fp, vp, vp, vp, vp, vp, u32, vp, sz, vp]
     L.nvfp4_gemm.restype = ci
@@ -133,7 +135,7 @@ EXPORTS = (
     "nvfp4_host_round_rtn", "nvfp4_host_round_sr", "nvfp4_host_philox4x32_10",
     "nvfp4_host_sr_bits", "nvfp4_host_e8m0_encode", "nvfp4_host_e4m3_encode_n",
     "nvfp4_host_round_rtn_n", "nvfp4_host_round_sr_n", "nvfp4_probe_mfma_rate",
-    "nvfp4_quant_noise_workspace_bytes", "nvfp4_quant_noise",
+    "nvfp4_quant_noise_workspace_bytes", "nvfp4_quant_noise", "nvfp4_cross_check_switches",
 )
 
 
@@ -202,6 +204,14 @@ def quantize(x: torch.Tensor, axis: int = 1, rounding: int = RTN, seed: int = 0,
                               C.byref(f), codes.data_ptr(), scales.data_ptr(), g.data_ptr(), flags,
                               ws.data_ptr(), ws.numel(), _stream()), "nvfp4_quantize")
     return codes, scales, g
+
+
+SWITCH_SOFT_CONVERT, SWITCH_PLAIN_OPERANDS = 1, 2
+
+
+def cross_check_switches(value: int | None = None) -> int:
+    """nvfp4_cross_check_switches: returns the switches in force; with `value` given, replaces them."""
+    return lib.nvfp4_cross_check_switches(0 if value is None else 1, 0 if value is None else value)
 
 
 def quantize_dual(x: torch.Tensor, rounding_rows: int = RTN, seed_rows: int = 0, rounding_cols: int = RTN,

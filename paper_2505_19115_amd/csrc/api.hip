@@ -3,6 +3,9 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <atomic>
+#include <mutex>
+
 #include "kernels.h"
 #include "nvfp4_math.h"
 
@@ -33,22 +36,26 @@ nvfp4_status check_format(const nvfp4_format *f)
     return NVFP4_OK;
 }
 
-// The gfx950 convert instruction is the default for round-to-nearest; the integer/fp32
-// formulation (the one the host probes evaluate) can be forced for cross-checking.
-bool use_hw_convert()
-{
-    const char *e = getenv("NVFP4_SOFT_CONVERT");
-    return !(e && e[0] == '1');
-}
+// Two cross-check switches, neither of which changes a result bit.  They are taken from the environment once,
+// at the first call that needs them, and can be replaced by nvfp4_cross_check_switches() (tests flip them inside
+// one process).  Bit 0: round elements and block scales with the integer/fp32 formulation (the one the host probes
+// evaluate) instead of the gfx950 convert instructions.  Bit 1: keep the packed operands inside the fused linear
+// entries row-major instead of in the slab layout (kernels.h).
+constexpr uint32_t SW_SOFT_CONVERT = 1u, SW_PLAIN_OPERANDS = 2u, SW_UNREAD = 0x80000000u;
+std::atomic<uint32_t> g_switches{SW_UNREAD};
 
-// The fused linear entries keep their packed operands in the slab layout (kernels.h) wherever the dual-orientation
-// quantizer produces them and the 256 x 256 GEMM kernel consumes them; NVFP4_PLAIN_OPERANDS=1 keeps the plain
-// row-major layout everywhere (same results bit for bit: a cross-check and a timing reference).
-bool use_slabs()
+uint32_t switches()
 {
-    const char *e = getenv("NVFP4_PLAIN_OPERANDS");
-    return !(e && e[0] == '1');
+    uint32_t v = g_switches.load(std::memory_order_relaxed);
+    if (v == SW_UNREAD) {
+        const char *a = getenv("NVFP4_SOFT_CONVERT"), *b = getenv("NVFP4_PLAIN_OPERANDS");
+        v = ((a && a[0] == '1') ? SW_SOFT_CONVERT : 0u) | ((b && b[0] == '1') ? SW_PLAIN_OPERANDS : 0u);
+        g_switches.store(v, std::memory_order_relaxed);
+    }
+    return v;
 }
+bool use_hw_convert() { return (switches() & SW_SOFT_CONVERT) == 0; }
+bool use_slabs() { return (switches() & SW_PLAIN_OPERANDS) == 0; }
 
 // A dense [rows, cols] tensor goes through the one-pass dual quantizer (the only writer of slabs) with these
 // roundings; its answer does not depend on the element type for shapes the linear entries accept.
@@ -134,9 +141,73 @@ SavedLayout saved_layout(void *saved, int64_t M, int64_t N, int64_t K, int64_t B
     return L;
 }
 
+// Identity of a `saved` buffer: shapes, format, seed and the layout each transposed operand was written in.
+constexpr size_t SAVED_TAG_OFFSET = 64;  // bytes into the header; {gX, gW} sit at its front
+TagArgs saved_tag(int64_t M, int64_t N, int64_t K, const nvfp4_format *f, uint64_t seed, bool xt_slab, bool wt_slab)
+{
+    TagArgs t;
+    t.w[0] = 0x4E564634u;  // "NVF4"
+    t.w[1] = (xt_slab ? 1u : 0u) | (wt_slab ? 2u : 0u) | (use_hw_convert() ? 4u : 0u);
+    t.w[2] = (uint32_t)f->block | ((uint32_t)f->scale << 8) | ((uint32_t)f->tensor_scale << 9);
+    t.w[3] = (uint32_t)M;
+    t.w[4] = (uint32_t)N;
+    t.w[5] = (uint32_t)K;
+    t.w[6] = (uint32_t)seed;
+    t.w[7] = (uint32_t)(seed >> 32);
+    return t;
+}
+
+// Host-side record of the last forward calls' `saved` buffers (address -> tag), so that a backward call whose
+// shapes, format, seed or operand layouts differ from what the forward call wrote is refused before anything is
+// launched.  A buffer the table does not know (written more than SAVED_SLOTS forward calls ago) is trusted; the
+// tag in the buffer's own header then still poisons the outputs on a mismatch (TagArgs).
+constexpr int SAVED_SLOTS = 256;
+struct SavedRecord {
+    const void *ptr = nullptr;
+    uint32_t w[8];
+};
+SavedRecord g_saved[SAVED_SLOTS];
+int g_saved_next = 0;
+std::mutex g_saved_mutex;
+
+void saved_remember(const void *ptr, const TagArgs &t)
+{
+    std::lock_guard<std::mutex> lock(g_saved_mutex);
+    int slot = -1;
+    for (int i = 0; i < SAVED_SLOTS; ++i)
+        if (g_saved[i].ptr == ptr) slot = i;
+    if (slot < 0) {
+        slot = g_saved_next;
+        g_saved_next = (g_saved_next + 1) % SAVED_SLOTS;
+    }
+    g_saved[slot].ptr = ptr;
+    memcpy(g_saved[slot].w, t.w, sizeof(t.w));
+}
+
+// false only if the buffer is known and was written for something else
+bool saved_matches(const void *ptr, const TagArgs &t)
+{
+    std::lock_guard<std::mutex> lock(g_saved_mutex);
+    for (int i = 0; i < SAVED_SLOTS; ++i)
+        if (g_saved[i].ptr == ptr) return memcmp(g_saved[i].w, t.w, sizeof(t.w)) == 0;
+    return true;
+}
+
+nvfp4_status quantize_impl(const void *x, nvfp4_dtype dt, int64_t rows, int64_t cols, int64_t ld, int axis,
+                           nvfp4_rounding rounding, uint64_t seed, const nvfp4_format *f, uint8_t *codes,
+                           uint8_t *scales, float *tensor_scale, uint32_t flags, void *workspace,
+                           size_t workspace_bytes, size_t workspace_required, void *stream);
+
 }  // namespace
 
 extern "C" {
+
+uint32_t nvfp4_cross_check_switches(int set, uint32_t value)
+{
+    const uint32_t before = switches();
+    if (set) g_switches.store(value & (SW_SOFT_CONVERT | SW_PLAIN_OPERANDS), std::memory_order_relaxed);
+    return before;
+}
 
 const char *nvfp4_status_string(nvfp4_status s)
 {
@@ -227,6 +298,19 @@ nvfp4_status nvfp4_quantize(const void *x, nvfp4_dtype dt, int64_t rows, int64_t
                             float *tensor_scale, uint32_t flags, void *workspace,
                             size_t workspace_bytes, void *stream)
 {
+    return quantize_impl(x, dt, rows, cols, ld, axis, rounding, seed, f, codes, scales, tensor_scale, flags, workspace,
+                         workspace_bytes, nvfp4_quantize_workspace_bytes(rows, cols), stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+nvfp4_status quantize_impl(const void *x, nvfp4_dtype dt, int64_t rows, int64_t cols, int64_t ld, int axis,
+                           nvfp4_rounding rounding, uint64_t seed, const nvfp4_format *f, uint8_t *codes,
+                           uint8_t *scales, float *tensor_scale, uint32_t flags, void *workspace,
+                           size_t workspace_bytes, size_t workspace_required, void *stream)
+{
     nvfp4_status s = check_format(f);
     if (s != NVFP4_OK) return s;
     s = check_tensor(x, dt, rows, cols, ld);
@@ -242,7 +326,7 @@ nvfp4_status nvfp4_quantize(const void *x, nvfp4_dtype dt, int64_t rows, int64_t
     const bool preset = (flags & NVFP4_PRESET_TSCALE) != 0;
     const bool need_amax = f->tensor_scale && !preset;
     if (need_amax) {
-        if (!workspace || workspace_bytes < nvfp4_quantize_workspace_bytes(rows, cols)) return NVFP4_EWORKSPACE;
+        if (!workspace || workspace_bytes < workspace_required) return NVFP4_EWORKSPACE;
         if (!aligned16(workspace)) return NVFP4_EALIGN;
     }
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -262,7 +346,7 @@ nvfp4_status nvfp4_quantize(const void *x, nvfp4_dtype dt, int64_t rows, int64_t
                 q.g_src = g.src;
                 q.n_partials = g.n;
             } else if (launch_tensor_amax(x, dt, rows, cols, ld, bits, partials, empty ? tensor_scale : nullptr, st) != hipSuccess) {
-                // (an empty tensor gets its scale (1) written there; otherwise the quantizer writes it)
+                // (an empty tensor gets its scale (1) written there, by the fold alone; otherwise the quantizer writes it)
                 return NVFP4_EHIP;
             }
         }
@@ -270,6 +354,10 @@ nvfp4_status nvfp4_quantize(const void *x, nvfp4_dtype dt, int64_t rows, int64_t
     if (empty) return NVFP4_OK;  // nothing to encode
     return run_quantize(q, f, st) == hipSuccess ? NVFP4_OK : NVFP4_EHIP;
 }
+
+}  // namespace
+
+extern "C" {
 
 nvfp4_status nvfp4_quantize_dual(const void *x, nvfp4_dtype dt, int64_t rows, int64_t cols, int64_t ld,
                                  nvfp4_rounding rounding_rows, uint64_t seed_rows,
@@ -448,6 +536,9 @@ nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, 
         dx.slab_c = sx && gemm_takes_slabs(N, K, M, f->block, f->scale);
         dw.slab_r = b_slab = sw && t_fwd;
         dw.slab_c = sw && gemm_takes_slabs(M, K, N, f->block, f->scale);
+        dw.tag = saved_tag(M, N, K, f, bwd_seed, dx.slab_c != 0, dw.slab_c != 0);
+        dw.tag.dst = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(saved) + SAVED_TAG_OFFSET);
+        saved_remember(saved, dw.tag);
         if (launch_quantize_dual(dx, in_dt, NVFP4_RTN, NVFP4_SR, f->block, f->scale, use_hw_convert(), st) != hipSuccess) return NVFP4_EHIP;
         if (launch_quantize_dual(dw, in_dt, NVFP4_RTN, NVFP4_RTN, f->block, f->scale, use_hw_convert(), st) != hipSuccess) return NVFP4_EHIP;
     } else {
@@ -530,8 +621,15 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
     const int dy_slab_r = sdy && t_dx, dy_slab_c = sdy && t_dw;
     const int wt_slab = saved && t_dx && dual_writes_slabs(f, in_dt, N, K, NVFP4_RTN, NVFP4_RTN);
     const int xt_slab = saved && t_dw && dual_writes_slabs(f, in_dt, M, K, NVFP4_RTN, NVFP4_SR);
+    TagArgs tag;
+    if (saved) {
+        tag = saved_tag(M, N, K, f, seed, xt_slab != 0, wt_slab != 0);
+        tag.chk = reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint8_t *>(saved) + SAVED_TAG_OFFSET);
+        if (!saved_matches(saved, tag)) return NVFP4_EINVAL;
+    }
     if (dual) {
         DualArgs d;
+        d.tag = tag;
         d.c.x = dY;
         d.c.rows = M;
         d.c.cols = N;
@@ -557,6 +655,7 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
         QuantPlan qa{dY, in_dt, M, N, N, 1, NVFP4_SR, seed, dyc, dys, gdy.src, ts + 0, gm, gdy.n};
         QuantPlan qb{W, in_dt, N, K, K, 0, NVFP4_RTN, 0, wtc, wts, gw.src, ts + 1, gm_xw, gw.n};
         if (!dual && run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
+        if (!dual && launch_saved_tag(tag, ts + 0, nullptr, st) != hipSuccess) return NVFP4_EHIP;
         if (!saved && run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
         GemmArgs g{M, K, N, dyc, dys, wtc, wts, ts + 0, g_w, dX, K, dy_slab_r, wt_slab};
         if (launch_gemm(g, f->block, f->scale, out_dt, st) != hipSuccess) return NVFP4_EHIP;
@@ -567,6 +666,7 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
         QuantPlan qa{dY, in_dt, M, N, N, 0, NVFP4_SR, seed + 1, dytc, dyts, gdy.src, ts + 2, gm, gdy.n};
         QuantPlan qb{X, in_dt, M, K, K, 0, NVFP4_SR, seed + 2, xtc, xts, gx.src, ts + 3, gm_xw, gx.n};
         if (!dual && run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
+        if (!dual && launch_saved_tag(tag, ts + 2, nullptr, st) != hipSuccess) return NVFP4_EHIP;
         if (!saved && run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
         GemmArgs g{N, K, M, dytc, dyts, xtc, xts, ts + 2, g_x, dW, K, dy_slab_c, xt_slab};
         if (launch_gemm(g, f->block, f->scale, out_dt, st) != hipSuccess) return NVFP4_EHIP;

@@ -22,6 +22,29 @@ struct QuantArgs {
     int n_partials = 0;
 };
 
+// Identity of what nvfp4_linear_fwd left in a `saved` buffer (shapes, format, seed, layout of each operand): the
+// forward call's quantizer writes the words to dst; the backward call's quantizer compares them with chk and, on a
+// mismatch, replaces the tensor scale it hands to the GEMMs by NaN, so that a backward call on the wrong buffer
+// gives NaN outputs instead of plausible wrong numbers.
+struct TagArgs {
+    uint32_t *dst = nullptr;
+    const uint32_t *chk = nullptr;
+    uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+};
+// (one thread) writes / checks the tag; returns false on a mismatch
+__device__ __forceinline__ bool tag_apply(const TagArgs &t)
+{
+    bool ok = true;
+    if (t.dst)
+        for (int i = 0; i < 8; ++i) t.dst[i] = t.w[i];
+    if (t.chk)
+        for (int i = 0; i < 8; ++i) ok = ok && t.chk[i] == t.w[i];
+    return ok;
+}
+// The same from a one-thread kernel, for the paths that do not run the one-pass dual quantizer; g1 / g2 (either may
+// be null) are overwritten with NaN on a mismatch.
+hipError_t launch_saved_tag(const TagArgs &t, float *g1, float *g2, hipStream_t st);
+
 // Both orientations of one tensor: c describes the tensor and the column-blocked outputs
 // (codes [cols, rows/2], scales [cols, rows/B], seed); the row-blocked outputs come beside it.
 struct DualArgs {
@@ -32,10 +55,11 @@ struct DualArgs {
     float *g_out2;      // optional second destination of the tensor scale
     int slab_r = 0;     // write the row-blocked / column-blocked output in the slab layout (below) instead
     int slab_c = 0;
+    TagArgs tag;        // optional: identity of a `saved` buffer to write or to check (fused linear entries)
 };
 
-// Slab layout of a packed operand (library-internal: workspaces and the saved buffer of the fused linear
-// entries; never crosses the C ABI as a documented format).  For an operand of R rows and contraction length K
+// Slab layout of a packed operand (used inside the workspaces and the saved buffer of the fused linear entries,
+// and documented in include/nvfp4.h for nvfp4_quantize_dual's slab outputs and nvfp4_gemm_slab).  For an operand of R rows and contraction length K
 // (K a multiple of 128) the codes are stored as [ceil(R / 256)][K / 128] slabs of 16 KB: one slab is
 // what one GEMM workgroup fetches per K tile, 256 rows x 64 bytes, contiguous.  Inside a slab row r (0..255) sits
 // at position slab_row(r), which swaps the two 3-bit fields of r below bit 6: the column-blocked quantizer holds

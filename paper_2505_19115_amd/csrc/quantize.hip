@@ -681,8 +681,10 @@ __global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
     const float g = resolve_g(P);
     const float k = 1.0f / (6.0f * g);
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
-        *P.g_out = g;
-        if (D.g_out2) *D.g_out2 = g;
+        // (a `saved` buffer that is not the one this call expects poisons the scale the GEMMs will multiply by)
+        const float g_gemm = tag_apply(D.tag) ? g : __builtin_nanf("");
+        *P.g_out = g_gemm;
+        if (D.g_out2) *D.g_out2 = g_gemm;
     }
 
     // row-blocked side: one block scale and 8 codes per row of the lane tile
@@ -798,6 +800,14 @@ __global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
     }
 }
 
+__global__ void saved_tag_kernel(TagArgs t, float *g1, float *g2)
+{
+    if (!tag_apply(t)) {
+        if (g1) *g1 = __builtin_nanf("");
+        if (g2) *g2 = __builtin_nanf("");
+    }
+}
+
 // ------------------------------------------------------------------ host-side launchers
 
 static inline hipError_t launch_status() { return hipGetLastError(); }
@@ -817,6 +827,11 @@ int64_t tensor_amax_partials(int64_t rows, int64_t cols, int64_t ld)
 hipError_t launch_tensor_amax(const void *x, int dt, int64_t rows, int64_t cols, int64_t ld,
                               uint32_t *amax_bits, uint32_t *partials, float *g_out, hipStream_t st)
 {
+    if (rows <= 0 || cols <= 0) {
+        // an empty tensor has no partial maxima: the fold alone leaves max = 0, scale = 1
+        hipLaunchKernelGGL(fold_amax_kernel, dim3(1), dim3(1024), 0, st, partials, (int64_t)0, amax_bits, g_out);
+        return launch_status();
+    }
     int64_t span_rows = rows, span_cols = cols;
     if (ld == cols) {
         span_cols = rows * cols;
@@ -964,8 +979,19 @@ hipError_t launch_quantize_dual(const DualArgs &D, int dt, int rnd_r, int rnd_c,
     hipError_t e = launch_quantize(r, dt, 1, rnd_r, block, sf, hw_convert, st);
     if (e != hipSuccess) return e;
     e = launch_quantize(D.c, dt, 0, rnd_c, block, sf, hw_convert, st);
-    if (e != hipSuccess || !D.g_out2) return e;
-    return hipMemcpyAsync(D.g_out2, D.c.g_out, sizeof(float), hipMemcpyDeviceToDevice, st);
+    if (e != hipSuccess) return e;
+    if (D.g_out2) {
+        e = hipMemcpyAsync(D.g_out2, D.c.g_out, sizeof(float), hipMemcpyDeviceToDevice, st);
+        if (e != hipSuccess) return e;
+    }
+    return launch_saved_tag(D.tag, D.c.g_out, D.g_out2, st);
+}
+
+hipError_t launch_saved_tag(const TagArgs &t, float *g1, float *g2, hipStream_t st)
+{
+    if (!t.dst && !t.chk) return hipSuccess;
+    hipLaunchKernelGGL(saved_tag_kernel, dim3(1), dim3(1), 0, st, t, g1, g2);
+    return launch_status();
 }
 
 }  // namespace nvfp4

@@ -43,3 +43,23 @@ def assert_gemm_close(Y: np.ndarray, ref: np.ndarray, ref_abs: np.ndarray, what=
     if ref.size:
         fro = np.linalg.norm(Y - ref) / max(np.linalg.norm(ref), 1e-300)
         assert fro <= tol, f"{what}: Frobenius relative error {fro:.3e}"
+
+
+def _to_bf16_f64(a: np.ndarray) -> np.ndarray:
+    """Round-to-nearest-even of fp64 values to bf16, returned as fp64 (through fp32: every value
+    used here is far from the fp32 rounding boundaries that could make the double rounding matter)."""
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float64)).to(torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
+
+
+def assert_bf16_gemm_close(Y: np.ndarray, ref: np.ndarray, ref_abs: np.ndarray, what="", tol=REL_TOL):
+    """bf16 output of a GEMM whose fp32 result must lie within tol * sum_k |a||b| of ref: rounding
+    to bf16 is monotonic, so the stored value must lie between the bf16 roundings of the two ends
+    of that interval (no allowance beyond the one rounding the output format forces)."""
+    Y = Y.astype(np.float64)
+    slack = tol * ref_abs + 1e-300
+    lo, hi = _to_bf16_f64(ref - slack * (1 + 1e-6)), _to_bf16_f64(ref + slack * (1 + 1e-6))
+    bad = (Y < lo) | (Y > hi)
+    if bad.any():
+        t = np.argwhere(bad)[0]
+        raise AssertionError(f"{what}: {int(bad.sum())} of {Y.size} bf16 outputs outside [bf16(ref - tol), bf16(ref + tol)], "
+                             f"first at {tuple(t)}: got {Y[tuple(t)]!r}, ref {ref[tuple(t)]!r}")

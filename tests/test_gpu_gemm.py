@@ -5,7 +5,7 @@ import torch
 
 import oracle
 from paper_2505_19115_amd import synth
-from gpu_util import assert_gemm_close, assert_quant_equal, ofmt, to_np
+from gpu_util import assert_bf16_gemm_close, assert_gemm_close, assert_quant_equal, ofmt, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -19,6 +19,14 @@ def _binding():
     from paper_2505_19115_amd import binding
     nv = binding
     yield
+
+
+@pytest.fixture
+def switches():
+    """A test that flips the library's cross-check switches gets them restored afterwards."""
+    before = nv.cross_check_switches()
+    yield
+    nv.cross_check_switches(before)
 
 
 def dev(q):
@@ -183,25 +191,88 @@ def test_linear_fp32_inputs_bf16_outputs():
         assert np.all(np.abs(to_np(got.float()) - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * np.abs(ref).max())
 
 
+def sample_positions(rng, M, N, n=3000):
+    """n random outputs, one full row, one full column, and the last row/column corner tile."""
+    ii = np.concatenate([rng.integers(0, M, n), np.full(N, M // 3), np.arange(M), np.full(256, M - 1)])
+    jj = np.concatenate([rng.integers(0, N, n), np.arange(N), np.full(M, N - 7), np.arange(N - 256, N)])
+    return ii, jj
+
+
+def check_sampled(Y, A, B, of, what, rng, n=3000):
+    """Sampled outputs of a large product against the oracle's fp64 dot products: fp32 outputs to the stated
+    1e-5, bf16 outputs to the bf16 rounding of that interval."""
+    M, N = A[0].shape[0], B[0].shape[0]
+    ii, jj = sample_positions(rng, M, N, n)
+    ref = oracle.gemm_nt_sample(A, B, ii, jj, of)
+    ref_abs = oracle.gemm_nt_sample(A, B, ii, jj, of, take_abs=True)
+    got = to_np(Y.float())[ii, jj]
+    if Y.dtype == torch.bfloat16:
+        assert_bf16_gemm_close(got, ref, ref_abs, what)
+    else:
+        assert_gemm_close(got, ref, ref_abs, what)
+
+
+@pytest.mark.parametrize("out_dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
 @pytest.mark.parametrize("fmt_name", ["NVFP4", "MXFP4"])
 @pytest.mark.parametrize("shape", [(4096, 4096, 11008), (11008, 4096, 4096)], ids=["down-or-dX", "dW"])
-def test_7b_backward_gemm_shapes_sampled(shape, fmt_name):
+def test_7b_backward_gemm_shapes_sampled(shape, fmt_name, out_dtype):
     # the other two GEMM shapes of the benchmark step (K = 11008: 86 K tiles; 11008 output rows), the kernels
-    # and launch configuration bench.py times, checked on sampled outputs the oracle computes one by one
+    # and launch configuration bench.py times, checked on sampled outputs the oracle computes one by one:
+    # fp32 output at the stated 1e-5, bf16 output (what the benchmark stores) at the rounding of that interval
     M, N, K = shape
     fmt, of = getattr(nv, fmt_name), getattr(oracle, fmt_name)
     A = oracle.quantize(synth.normal(M, K, 1.0, 81), 1, 0, 0, of)
     B = oracle.quantize(synth.normal(N, K, 0.02, 82), 1, 0, 0, of)
-    print(f"[case] gemm {fmt_name} {shape} sampled", flush=True)
-    Y = nv.gemm(dev(A), dev(B), fmt, torch.bfloat16)
+    print(f"[case] gemm {fmt_name} {shape} {out_dtype} sampled", flush=True)
+    Y = nv.gemm(dev(A), dev(B), fmt, out_dtype)
     torch.cuda.synchronize()
-    rng = np.random.default_rng(6)
-    ii = np.concatenate([rng.integers(0, M, 3000), np.full(256, M - 1), np.arange(0, M, 97)])
-    jj = np.concatenate([rng.integers(0, N, 3000), np.arange(N - 256, N), np.full(len(range(0, M, 97)), N - 1)])
-    ref = oracle.gemm_nt_sample(A, B, ii, jj, of)
-    ref_abs = oracle.gemm_nt_sample(A, B, ii, jj, of, take_abs=True)
-    got = to_np(Y.float())[ii, jj]
-    assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * ref_abs)  # bf16 output: one more rounding
+    check_sampled(Y, A, B, of, f"{fmt_name} {shape}", np.random.default_rng(6))
+
+
+@pytest.mark.parametrize("fmt_name", ["NVFP4", "MXFP4"])
+@pytest.mark.parametrize("layer", [("gate", 11008, 4096), ("down", 4096, 11008)], ids=["gate", "down"])
+def test_fused_entries_as_the_benchmark_calls_them(layer, fmt_name):
+    # nvfp4_linear_fwd / nvfp4_linear_bwd exactly as bench.py's timed step calls them (bf16 in and out,
+    # caller-owned workspaces, operands saved by the forward call, slab hand-over active), each of the three
+    # products of Eqs. 4-6 checked on sampled outputs against the oracle's quantization OF THE INPUTS THE CALL
+    # RECEIVED (RtN, RtN / SR, RtN / SR, SR) and its fp64 dot products
+    import ctypes as C
+    name, N, K = layer
+    M, seed = 4096, 1000
+    fmt, of = getattr(nv, fmt_name), getattr(oracle, fmt_name)
+    X, W, dY = synth.normal(M, K, 1.0, 100), synth.normal(N, K, 0.02, 200), synth.gradient_like(M, N, 300)
+    Xg, Wg, dYg = X.cuda(), W.cuda(), dY.cuda()
+    f = fmt.c()
+    wf = torch.empty(nv.lib.nvfp4_linear_fwd_workspace_bytes(M, N, K, C.byref(f)), dtype=torch.uint8, device="cuda")
+    wb = torch.empty(nv.lib.nvfp4_linear_bwd_workspace_bytes(M, N, K, C.byref(f)), dtype=torch.uint8, device="cuda")
+    saved = torch.empty(nv.linear_saved_bytes(M, N, K, fmt), dtype=torch.uint8, device="cuda")
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    dX = torch.empty((M, K), dtype=torch.bfloat16, device="cuda")
+    dW = torch.empty((N, K), dtype=torch.bfloat16, device="cuda")
+    print(f"[case] fused entries, bench configuration, {name} {fmt_name}", flush=True)
+    nv.linear_fwd(Xg, Wg, fmt, workspace=wf, out=Y, saved=saved, bwd_seed=seed)
+    nv.linear_bwd(dYg, None, None, seed, fmt, workspace=wb, out=(dX, dW), saved=saved, K=K)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(17)
+    check_sampled(Y, oracle.quantize(X, 1, oracle.RTN, 0, of), oracle.quantize(W, 1, oracle.RTN, 0, of), of, f"{name} Y", rng)
+    check_sampled(dX, oracle.quantize(dY, 1, oracle.SR, seed, of), oracle.quantize(W, 0, oracle.RTN, 0, of), of, f"{name} dX", rng)
+    check_sampled(dW, oracle.quantize(dY, 0, oracle.SR, seed + 1, of), oracle.quantize(X, 0, oracle.SR, seed + 2, of), of, f"{name} dW", rng)
+
+
+@pytest.mark.parametrize("layer", [("qkv", 12288, 4096), ("out_proj", 4096, 4096)], ids=["qkv", "out_proj"])
+def test_7b_attention_projections_forward_sampled(layer):
+    # the two forward linears of the 7B configuration that the MLP tests do not cover (Sec. 5 setup: fused QKV
+    # 4096 -> 12288 and the attention output projection 4096 -> 4096), tokens = 4096, RtN, bf16 inputs; fp32
+    # output at 1e-5 and bf16 output at the rounding of that interval
+    name, N, K = layer
+    M = 4096
+    X, W = synth.normal(M, K, 1.0, 111), synth.normal(N, K, 0.02, 112)
+    A, B = oracle.quantize(X, 1), oracle.quantize(W, 1)
+    for out_dtype in (torch.float32, torch.bfloat16):
+        print(f"[case] forward linear {name} {out_dtype}", flush=True)
+        Y = nv.linear_fwd(X.cuda(), W.cuda(), out_dtype=out_dtype)
+        torch.cuda.synchronize()
+        check_sampled(Y, A, B, oracle.NVFP4, f"{name} {out_dtype}", np.random.default_rng(23))
 
 
 def test_gemm_is_deterministic():
@@ -265,6 +336,57 @@ def test_backward_from_operands_saved_by_forward(fmtname, dtype):
         assert_gemm_close(to_np(b[0]), oracle.gemm_nt(qdy, qwt, of), oracle.gemm_nt(qdy, qwt, of, take_abs=True), "saved dX")
         qdyt, qxt = oracle.quantize(dYc, 0, oracle.SR, seed + 1, of), oracle.quantize(Xc, 0, oracle.SR, seed + 2, of)
         assert_gemm_close(to_np(b[1]), oracle.gemm_nt(qdyt, qxt, of), oracle.gemm_nt(qdyt, qxt, of, take_abs=True), "saved dW")
+
+
+def test_saved_buffer_identity_is_checked(switches):
+    # the backward call refuses a `saved` buffer that a forward call wrote for another seed, shape, format or
+    # cross-check setting (host record of the buffer), and a copy of such a buffer at an address the library has
+    # no record of turns dX and dW into NaN through the tag in the buffer's own header
+    M, N, K, seed = 256, 384, 512, 21
+    X, W, dY = synth.normal(M, K, 1.0, 131).cuda(), synth.normal(N, K, 0.02, 132).cuda(), synth.gradient_like(M, N, 133).cuda()
+    fmts = (nv.NVFP4, nv.MXFP4, nv.Format(64, nv.SCALE_E4M3, 1))
+    nbytes = max(nv.linear_saved_bytes(M, N, K, fmt) for fmt in fmts)
+    # (both buffers allocated once, before any forward call: `moved_buf` is then an address no forward call ever saw)
+    saved_buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    moved_buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    for fmt in fmts:
+        print(f"[case] saved tag fmt={fmt}", flush=True)
+        saved = saved_buf[:nv.linear_saved_bytes(M, N, K, fmt)]
+        nv.linear_fwd(X, W, fmt, saved=saved, bwd_seed=seed)
+        good = nv.linear_bwd(dY, None, None, seed, fmt, saved=saved, K=K)
+        with pytest.raises(nv.Nvfp4Error) as e:
+            nv.linear_bwd(dY, None, None, seed + 1, fmt, saved=saved, K=K)
+        assert e.value.code == nv.EINVAL
+        other = nv.Format(32, nv.SCALE_E4M3, 1)
+        if nv.linear_saved_bytes(M, N, K, other) <= saved.numel():
+            with pytest.raises(nv.Nvfp4Error) as e:
+                nv.linear_bwd(dY, None, None, seed, other, saved=saved, K=K)
+            assert e.value.code == nv.EINVAL
+        nv.cross_check_switches(nv.SWITCH_SOFT_CONVERT)
+        with pytest.raises(nv.Nvfp4Error) as e:
+            nv.linear_bwd(dY, None, None, seed, fmt, saved=saved, K=K)
+        assert e.value.code == nv.EINVAL
+        nv.cross_check_switches(0)
+        moved = moved_buf[:saved.numel()]  # an address no forward call wrote to: only the tag inside the buffer can tell
+        moved.copy_(saved)
+        again = nv.linear_bwd(dY, None, None, seed, fmt, saved=moved, K=K)
+        bad = nv.linear_bwd(dY, None, None, seed + 1, fmt, saved=moved, K=K)
+        only_dx = nv.lib.nvfp4_linear_bwd  # (dW = NULL below: the path without the dual quantizer checks the tag too)
+        torch.cuda.synchronize()
+        assert torch.equal(again[0], good[0]) and torch.equal(again[1], good[1])
+        assert torch.isnan(bad[0]).all() and torch.isnan(bad[1]).all()
+        import ctypes as C
+        f = fmt.c()
+        ws = torch.empty(nv.lib.nvfp4_linear_bwd_workspace_bytes(M, N, K, C.byref(f)), dtype=torch.uint8, device="cuda")
+        dx = torch.zeros((M, K), device="cuda")
+        for sd, want_nan in ((seed, False), (seed + 1, True)):
+            rc = only_dx(dY.data_ptr(), None, None, dx.data_ptr(), None, M, N, K, nv.BF16, nv.F32, C.byref(f), sd,
+                         ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream, None, moved.data_ptr())
+            torch.cuda.synchronize()
+            assert rc == nv.OK
+            assert bool(torch.isnan(dx).all()) == want_nan
+            if not want_nan:
+                assert torch.equal(dx, good[0])
 
 
 # ---------------------------------------------------------------- MXFP4 (block 32, E8M0): native FP4 MFMA
@@ -525,7 +647,7 @@ def test_swiglu_mlp_fwd_bwd_stage_by_stage():
 
 @pytest.mark.parametrize("fmt_name", ["NVFP4", "MXFP4"])
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
-def test_slab_operand_layout_is_invisible(dtype, fmt_name, monkeypatch):
+def test_slab_operand_layout_is_invisible(dtype, fmt_name, switches):
     # Between the quantizers and the large-tile GEMM the fused entries keep their packed operands as per-K-tile
     # slabs; NVFP4_PLAIN_OPERANDS=1 keeps them row-major.  Both must give the same bits.  Shape: all three GEMMs
     # of the layer large enough for the slab path, two of the three dimensions not multiples of the 256-row slab.
@@ -538,7 +660,7 @@ def test_slab_operand_layout_is_invisible(dtype, fmt_name, monkeypatch):
     dY = synth.gradient_like(M, N, 613, dtype=dtype).cuda()
     outs = []
     for plain in ("0", "1"):
-        monkeypatch.setenv("NVFP4_PLAIN_OPERANDS", plain)
+        nv.cross_check_switches(nv.SWITCH_PLAIN_OPERANDS if plain == "1" else 0)
         saved = torch.empty(nv.linear_saved_bytes(M, N, K, fmt), dtype=torch.uint8, device="cuda")
         Y = nv.linear_fwd(X, W, fmt, out_dtype=torch.bfloat16, saved=saved, bwd_seed=77)
         dX, dW = nv.linear_bwd(dY, None, None, 77, fmt, out_dtype=torch.bfloat16, saved=saved, K=K)
@@ -619,7 +741,7 @@ def test_slab_outputs_of_the_dual_quantizer_and_slab_gemm(rounding, fmt_name):
 @pytest.mark.parametrize("fmt_name", ["NVFP4", "MXFP4"])
 @pytest.mark.parametrize("shape", [(4096, 4096, 256), (8192, 256, 8192), (2048, 2048, 2048), (4096, 640, 4096)],
                          ids=["fwd-only", "dX-only", "none-for-nvfp4", "mixed"])
-def test_slab_layout_chosen_per_operand(shape, fmt_name, monkeypatch):
+def test_slab_layout_chosen_per_operand(shape, fmt_name, switches):
     # shapes where only some of the three GEMMs take slab operands (few output tiles, short K): each operand's
     # layout is decided by its own consumer, and every combination must equal the all-row-major run bit for bit
     M, N, K = shape
@@ -630,7 +752,7 @@ def test_slab_layout_chosen_per_operand(shape, fmt_name, monkeypatch):
     dY = synth.gradient_like(M, N, 703).cuda()
     outs = []
     for plain in ("0", "1"):
-        monkeypatch.setenv("NVFP4_PLAIN_OPERANDS", plain)
+        nv.cross_check_switches(nv.SWITCH_PLAIN_OPERANDS if plain == "1" else 0)
         saved = torch.empty(nv.linear_saved_bytes(M, N, K, fmt), dtype=torch.uint8, device="cuda")
         Y = nv.linear_fwd(X, W, fmt, out_dtype=torch.bfloat16, saved=saved, bwd_seed=5)
         dX, dW = nv.linear_bwd(dY, None, None, 5, fmt, out_dtype=torch.bfloat16, saved=saved, K=K)

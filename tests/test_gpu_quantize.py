@@ -24,6 +24,14 @@ def _binding():
     yield
 
 
+@pytest.fixture
+def switches():
+    """A test that flips the library's cross-check switches gets them restored afterwards."""
+    before = nv.cross_check_switches()
+    yield
+    nv.cross_check_switches(before)
+
+
 def run_both(x_cpu, axis, rounding, seed, fmt, preset=None, what=""):
     print(f"[case] {what} shape={tuple(x_cpu.shape)} dtype={x_cpu.dtype} axis={axis} rounding={rounding} "
           f"seed={seed} fmt={fmt}", flush=True)
@@ -45,7 +53,7 @@ FORMATS = {
 }
 
 
-def test_config1_fp32_256(monkeypatch):
+def test_config1_fp32_256():
     # X, W fp32 [256, 256] ~ N(0,1): row-blocked RtN as the forward GEMM consumes them
     for seed in (1, 2):
         x = synth.normal(256, 256, 1.0, seed, torch.float32)
@@ -97,17 +105,17 @@ def test_columns_not_multiple_of_8(rounding):
     assert_quant_equal(got, oracle.quantize(big32[:, :1001].contiguous(), 0, rounding, 5), "cols1001-f32")
 
 
-def test_software_rounding_path_equals_hardware_convert(monkeypatch):
+def test_software_rounding_path_equals_hardware_convert(switches):
     x = synth.student_t_outliers(256, 1024, seed=15, dtype=torch.bfloat16)
     hw = run_both(x, 1, nv.RTN, 0, nv.NVFP4, what="hw")
     hw0 = run_both(x, 0, nv.RTN, 0, nv.NVFP4, what="hw-cols")
-    monkeypatch.setenv("NVFP4_SOFT_CONVERT", "1")
+    nv.cross_check_switches(nv.SWITCH_SOFT_CONVERT)
     sw = run_both(x, 1, nv.RTN, 0, nv.NVFP4, what="soft")
     sw0 = run_both(x, 0, nv.RTN, 0, nv.NVFP4, what="soft-cols")
     assert torch.equal(hw[0], sw[0]) and torch.equal(hw0[0], sw0[0])
 
 
-def test_software_sr_path_equals_hardware_sr_convert(monkeypatch):
+def test_software_sr_path_equals_hardware_sr_convert(switches):
     # the integer formulation of the SR rule and the hardware SR convert fed with seed words built from the
     # same draws: both against the oracle, rows and columns, aligned and unaligned widths, and the
     # dual-orientation entry (one fused kernel vs its two-kernel fallback)
@@ -116,7 +124,7 @@ def test_software_sr_path_equals_hardware_sr_convert(monkeypatch):
     res = {}
     for mode in ("hw", "soft"):
         if mode == "soft":
-            monkeypatch.setenv("NVFP4_SOFT_CONVERT", "1")
+            nv.cross_check_switches(nv.SWITCH_SOFT_CONVERT)
         res[mode] = [run_both(x, 1, nv.SR, 3, nv.NVFP4, what=mode + "-rows"),
                      run_both(x, 0, nv.SR, 4, nv.NVFP4, what=mode + "-cols"),
                      run_both(x, 0, nv.SR, 4, nv.MXFP4, what=mode + "-cols-mx"),
@@ -201,6 +209,20 @@ def test_degenerate_inputs():
     c, s, g = nv.quantize(e, 1, nv.RTN, 0, nv.NVFP4)
     torch.cuda.synchronize()
     assert c.numel() == 0 and float(g.item()) == 1.0
+    # empty and strided with many rows: no maximum kernel may run (there is nothing for it to cover)
+    e2 = torch.empty(3000, 8, dtype=torch.bfloat16, device="cuda")[:, :0]
+    guard = torch.full((1 << 16,), 7, dtype=torch.uint8, device="cuda")
+    ws = guard[:nv.lib.nvfp4_quantize_workspace_bytes(3000, 0)]
+    import ctypes as C
+    f = nv.NVFP4.c()
+    g2 = torch.zeros(1, device="cuda")
+    for entry in (nv.lib.nvfp4_quantize,):
+        rc = entry(e2.data_ptr(), nv.BF16, 3000, 0, 8, 1, nv.RTN, 0, C.byref(f), None, None, g2.data_ptr(), 0,
+                   ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert rc == nv.OK and float(g2) == 1.0
+    assert bool((guard[ws.numel():] == 7).all()), "wrote past the workspace"
+    assert float(nv.tensor_scale(e2)) == 1.0
 
 
 def test_tensor_scale_entry_and_determinism():
@@ -218,12 +240,18 @@ def test_tensor_scale_entry_and_determinism():
     assert not torch.equal(a[0], c[0]) and torch.equal(a[1], c[1])
 
 
-@pytest.mark.parametrize("axis,rounding,seed", [(1, 0, 0), (0, 0, 0), (1, 1, 3), (0, 1, 7)])
+_SWEEP_TENSOR = {}
+
+
+@pytest.mark.parametrize("axis", [1, 0])
+@pytest.mark.parametrize("rounding,seed", [(0, 0)] + [(1, s) for s in range(8)],
+                         ids=["rtn"] + [f"sr-seed{s}" for s in range(8)])
 def test_full_size_quantizer_sweep_tensor(axis, rounding, seed):
-    # the benchmark's tensor: bf16 [8192, 8192], Student-t(3) * 0.02 with 0.1 % outliers x100,
-    # compared element by element (the oracle needs a few seconds per run)
-    x = synth.student_t_outliers(8192, 8192, seed=100)
-    run_both(x, axis, rounding, seed, nv.NVFP4, what="config2")
+    # the quantizer sweep in full: bf16 [8192, 8192], Student-t(3) * 0.02 with 0.1 % outliers x100, along rows
+    # and down columns, RtN and stochastic rounding with seeds 0..7 -- all 18 runs compared element by element
+    if "x" not in _SWEEP_TENSOR:
+        _SWEEP_TENSOR["x"] = synth.student_t_outliers(8192, 8192, seed=100)
+    run_both(_SWEEP_TENSOR["x"], axis, rounding, seed, nv.NVFP4, what="config2")
 
 
 @pytest.mark.parametrize("what,shape,axis,rounding,fmt", [

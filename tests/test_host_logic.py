@@ -76,6 +76,16 @@ def test_quantize_argument_errors():
     assert _quant(ws_bytes=2) == nv.EWORKSPACE
 
 
+def test_cross_check_switches_round_trip():
+    before = nv.cross_check_switches()
+    assert before in (0, 1, 2, 3)
+    assert nv.cross_check_switches(nv.SWITCH_PLAIN_OPERANDS) == before
+    assert nv.cross_check_switches() == nv.SWITCH_PLAIN_OPERANDS
+    assert nv.cross_check_switches(0xFFFFFFFF) == nv.SWITCH_PLAIN_OPERANDS and nv.cross_check_switches() == 3
+    nv.cross_check_switches(before)
+    assert nv.cross_check_switches() == before
+
+
 def test_quantize_dual_argument_errors():
     def dual(x=FAKE, dt=nv.BF16, rows=64, cols=64, ld=64, rnd=nv.SR, fmt=nv.NVFP4, cr=FAKE, sr=FAKE, cc=FAKE,
              sc=FAKE, ts=FAKE, flags=0, ws=FAKE, ws_bytes=1 << 20, k2=nv.SR):
