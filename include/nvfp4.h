@@ -143,6 +143,24 @@ nvfp4_status nvfp4_quantize(const void *x, nvfp4_dtype dt, int64_t rows, int64_t
                             size_t workspace_bytes, void *stream);
 
 /*
+ * nvfp4_quantize for callers that cannot allocate device memory or carry a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and errors as
+ * nvfp4_quantize without `workspace`: the scratch (header + per-workgroup partial maxima of the tensor-maximum
+ * pass) is a 65792-byte array inside the library's device image, one per GPU, held until the process ends.  The
+ * call allocates nothing.  Limit: any dense tensor (ld == cols) fits; a strided one needs one partial maximum per
+ * 8192-element span of a row and at most 16384 of them (e.g. 16384 rows of up to 8192 columns) -- beyond that the
+ * call returns NVFP4_EWORKSPACE and enqueues nothing.  With NVFP4_PRESET_TSCALE or a format without tensor scale
+ * the array is not touched.  Every call on a GPU shares that GPU's array: calls whose kernels may overlap on one
+ * GPU (different streams, or threads) race on it and must be ordered by the caller; calls on one stream are safe.
+ * Nothing in the array has to start at zero (every partial maximum is written before it is read).
+ * NVFP4_EHIP if the runtime cannot report the array's address on the current device.
+ */
+nvfp4_status nvfp4_quantize_static(const void *x, nvfp4_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                                   int axis, nvfp4_rounding rounding, uint64_t seed,
+                                   const nvfp4_format *f, uint8_t *codes, uint8_t *scales,
+                                   float *tensor_scale, uint32_t flags, void *stream);
+
+/*
  * Both orientations of one tensor in one pass over it: Eqs. 5-6 use the output
  * gradient blocked along N (for dX) and along M (for dW), Eqs. 4-5 use W blocked
  * along K and along N.  The results are exactly those of

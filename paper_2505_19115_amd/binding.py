@@ -73,6 +73,8 @@ def _load() -> C.CDLL:
     L.nvfp4_tensor_scale.argtypes = [vp, ci, i64, i64, i64, vp, vp, sz, vp]
     L.nvfp4_quantize.restype = ci
     L.nvfp4_quantize.argtypes = [vp, ci, i64, i64, i64, ci, ci, u64, fp, vp, vp, vp, u32, vp, sz, vp]
+    L.nvfp4_quantize_static.restype = ci
+    L.nvfp4_quantize_static.argtypes = [vp, ci, i64, i64, i64, ci, ci, u64, fp, vp, vp, vp, u32, vp]
     L.nvfp4_cross_check_switches.restype = u32
     L.nvfp4_cross_check_switches.argtypes = [ci, u32]
     L.nvfp4_quantize_dual.restype = ci
@@ -135,7 +137,7 @@ EXPORTS = (
     "nvfp4_host_round_rtn", "nvfp4_host_round_sr", "nvfp4_host_philox4x32_10",
     "nvfp4_host_sr_bits", "nvfp4_host_e8m0_encode", "nvfp4_host_e4m3_encode_n",
     "nvfp4_host_round_rtn_n", "nvfp4_host_round_sr_n", "nvfp4_probe_mfma_rate",
-    "nvfp4_quant_noise_workspace_bytes", "nvfp4_quant_noise", "nvfp4_cross_check_switches",
+    "nvfp4_quant_noise_workspace_bytes", "nvfp4_quant_noise", "nvfp4_quantize_static", "nvfp4_cross_check_switches",
 )
 
 
@@ -203,6 +205,31 @@ def quantize(x: torch.Tensor, axis: int = 1, rounding: int = RTN, seed: int = 0,
     _check(lib.nvfp4_quantize(x.data_ptr(), _dtype_tag(x), rows, cols, ld, axis, rounding, seed,
                               C.byref(f), codes.data_ptr(), scales.data_ptr(), g.data_ptr(), flags,
                               ws.data_ptr(), ws.numel(), _stream()), "nvfp4_quantize")
+    return codes, scales, g
+
+
+def quantize_static(x: torch.Tensor, axis: int = 1, rounding: int = RTN, seed: int = 0, fmt: Format = NVFP4,
+                    tensor_scale: torch.Tensor | None = None, out=None):
+    """nvfp4_quantize_static: nvfp4_quantize on the library's own static scratch (no workspace argument).
+    `out` = (codes, scales, g) must be given by a caller that may not allocate; otherwise torch allocates them."""
+    _require_gpu(x, tensor_scale)
+    assert x.dim() == 2 and (x.stride(1) == 1 or x.shape[1] <= 1)
+    rows, cols = x.shape
+    ld = x.stride(0) if rows > 1 else cols
+    outer, inner = (rows, cols) if axis == 1 else (cols, rows)
+    f = fmt.c()
+    if out is None:
+        codes = torch.empty((outer, inner // 2), dtype=torch.uint8, device=x.device)
+        scales = torch.empty((outer, inner // fmt.block), dtype=torch.uint8, device=x.device)
+        g = torch.empty(1, dtype=torch.float32, device=x.device) if tensor_scale is None else tensor_scale
+    else:
+        codes, scales, g = out
+        if tensor_scale is not None:
+            g = tensor_scale
+    flags = PRESET_TSCALE if tensor_scale is not None else 0
+    _check(lib.nvfp4_quantize_static(x.data_ptr(), _dtype_tag(x), rows, cols, ld, axis, rounding, seed,
+                                     C.byref(f), codes.data_ptr(), scales.data_ptr(), g.data_ptr(), flags,
+                                     _stream()), "nvfp4_quantize_static")
     return codes, scales, g
 
 

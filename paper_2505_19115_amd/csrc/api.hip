@@ -11,6 +11,13 @@
 
 using namespace nvfp4;
 
+// Scratch of nvfp4_quantize_static (the entry point for callers that cannot allocate): the workspace that
+// nvfp4_quantize takes as an argument -- header plus per-workgroup partial maxima -- as one array per GPU in the
+// library's own image.  Host code never uses this name as an address: static_scratch() asks the runtime for the
+// array's device address once per device and everything else goes through that pointer.
+constexpr size_t STATIC_SCRATCH_BYTES = 256 + 4 * 16384;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
 namespace {
 
 constexpr size_t WS_ALIGN = 256;
@@ -193,6 +200,33 @@ bool saved_matches(const void *ptr, const TagArgs &t)
     return true;
 }
 
+// Device address of `scratch` on the current device (each GPU holds its own copy at its own address).
+constexpr int MAX_DEVICES = 64;
+void *g_scratch_ptr[MAX_DEVICES];
+std::mutex g_scratch_mutex;
+
+nvfp4_status static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return NVFP4_EHIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return NVFP4_EHIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return NVFP4_OK;
+}
+
+// Scratch bytes nvfp4_quantize really touches for this tensor: a dense tensor leaves at most AMAX_DENSE_PARTIALS
+// partial maxima, a strided one one per 8192-element span of a row.
+size_t quantize_scratch_need(int64_t rows, int64_t cols, int64_t ld)
+{
+    if (rows <= 0 || cols <= 0 || ld == cols) return WS_HEADER + PARTIAL_SLOT;
+    return WS_HEADER + 4 * (size_t)tensor_amax_partials(rows, cols, ld);
+}
+
 nvfp4_status quantize_impl(const void *x, nvfp4_dtype dt, int64_t rows, int64_t cols, int64_t ld, int axis,
                            nvfp4_rounding rounding, uint64_t seed, const nvfp4_format *f, uint8_t *codes,
                            uint8_t *scales, float *tensor_scale, uint32_t flags, void *workspace,
@@ -300,6 +334,20 @@ nvfp4_status nvfp4_quantize(const void *x, nvfp4_dtype dt, int64_t rows, int64_t
 {
     return quantize_impl(x, dt, rows, cols, ld, axis, rounding, seed, f, codes, scales, tensor_scale, flags, workspace,
                          workspace_bytes, nvfp4_quantize_workspace_bytes(rows, cols), stream);
+}
+
+nvfp4_status nvfp4_quantize_static(const void *x, nvfp4_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                                   int axis, nvfp4_rounding rounding, uint64_t seed,
+                                   const nvfp4_format *f, uint8_t *codes, uint8_t *scales,
+                                   float *tensor_scale, uint32_t flags, void *stream)
+{
+    // (a shape whose partial maxima do not fit the array is refused here, before the device is touched)
+    if (rows > 0 && cols > 0 && ld >= cols && quantize_scratch_need(rows, cols, ld) > STATIC_SCRATCH_BYTES) return NVFP4_EWORKSPACE;
+    void *ws = nullptr;
+    const nvfp4_status s = static_scratch(&ws);
+    if (s != NVFP4_OK) return s;
+    return quantize_impl(x, dt, rows, cols, ld, axis, rounding, seed, f, codes, scales, tensor_scale, flags, ws,
+                         STATIC_SCRATCH_BYTES, quantize_scratch_need(rows, cols, ld), stream);
 }
 
 }  // extern "C"

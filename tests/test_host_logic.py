@@ -76,6 +76,17 @@ def test_quantize_argument_errors():
     assert _quant(ws_bytes=2) == nv.EWORKSPACE
 
 
+def test_quantize_static_argument_errors():
+    # the entry that allocates nothing validates like nvfp4_quantize, and refuses a tensor whose partial maxima
+    # do not fit its static scratch before it touches any device
+    def qs(x=FAKE, rows=64, cols=64, ld=64, axis=1, rnd=nv.RTN, fmt=nv.NVFP4, codes=FAKE, ts=FAKE, flags=0):
+        f = fmt.c()
+        return nv.lib.nvfp4_quantize_static(x, nv.BF16, rows, cols, ld, axis, rnd, 0, C.byref(f), codes, FAKE, ts, flags, None)
+    assert qs(rows=16385, cols=16, ld=24) == nv.EWORKSPACE          # 16385 row spans > 16384 partial maxima
+    assert qs(rows=4096, cols=5 * 8192, ld=5 * 8192 + 8) == nv.EWORKSPACE
+    assert qs(rows=16385, cols=16, ld=24, flags=nv.PRESET_TSCALE) == nv.EWORKSPACE  # the limit does not depend on flags
+
+
 def test_cross_check_switches_round_trip():
     before = nv.cross_check_switches()
     assert before in (0, 1, 2, 3)
