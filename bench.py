@@ -177,6 +177,74 @@ def main() -> int:
     schedules = {"timed": "mlp_graph_2_streams" if args.streams >= 2 else "one_stream",
                  "one_stream_ms" if args.streams >= 2 else "mlp_graph_2_streams_ms": round(other_ms, 3)}
 
+    # ---- the same step composed from the single entry points (tensor-maximum pass + dual quantizer through
+    # nvfp4_quantize_dual with slab outputs, GEMMs through nvfp4_gemm_slab): exactly the kernels of the fused
+    # calls, in their order, with an event pair around every GEMM, so that the three GEMM shapes are timed
+    # INSIDE the step (the clock a GEMM sees depends on what ran just before it) and the parts can be added up
+    def composed(fmt):
+        parts = []
+        for name, N, K, X, W, dY, wf, wb, Y, dX, dW, saved in data:
+            takes = lambda m, n, k: bool(nv.lib.nvfp4_gemm_takes_slabs(m, n, k, C.byref(fmt.c())))
+            s_fwd, s_dx, s_dw = takes(M, N, K), takes(M, K, N), takes(N, K, M)
+            qx = nv.quantize_dual(X, nv.RTN, 0, nv.SR, 1002, fmt, slab_rows=s_fwd, slab_cols=s_dw)
+            qw = nv.quantize_dual(W, nv.RTN, 0, nv.RTN, 0, fmt, slab_rows=s_fwd, slab_cols=s_dx)
+            qd = nv.quantize_dual(dY, nv.SR, 1000, nv.SR, 1001, fmt, slab_rows=s_dx, slab_cols=s_dw)
+            ts = [torch.cat([a[2], b[2]]) for a, b in ((qx[0], qw[0]), (qd[0], qw[1]), (qd[1], qx[1]))]
+            flat = lambda q: (q[0][0], q[0][1], q[1][0], q[1][1], torch.empty(1, dtype=torch.float32, device=dev))
+            parts.append(dict(N=N, K=K, X=X, W=W, dY=dY, Y=Y, dX=dX, dW=dW, qx=qx, qw=qw, qd=qd, ts=ts,
+                              ox=flat(qx), ow=flat(qw), od=flat(qd), s=(s_fwd, s_dx, s_dw)))
+        return parts
+
+    def step_composed(parts, fmt, events=None):
+        def gemm(mnk, *a, **k):
+            if events is not None:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+            nv.gemm(*a, shape=mnk, **k)
+            if events is not None:
+                e1.record()
+                events.append((mnk, e0, e1))
+        for p in parts:
+            N, K, (s_fwd, s_dx, s_dw) = p["N"], p["K"], p["s"]
+            nv.quantize_dual(p["X"], nv.RTN, 0, nv.SR, 1002, fmt, out=p["ox"], slab_rows=s_fwd, slab_cols=s_dw)
+            nv.quantize_dual(p["W"], nv.RTN, 0, nv.RTN, 0, fmt, out=p["ow"], slab_rows=s_fwd, slab_cols=s_dx)
+            gemm((M, N, K), p["qx"][0], p["qw"][0], fmt, out=p["Y"], slabs=(s_fwd, s_fwd), tensor_scales=p["ts"][0])
+            nv.quantize_dual(p["dY"], nv.SR, 1000, nv.SR, 1001, fmt, out=p["od"], slab_rows=s_dx, slab_cols=s_dw)
+            gemm((M, K, N), p["qd"][0], p["qw"][1], fmt, out=p["dX"], slabs=(s_dx, s_dx), tensor_scales=p["ts"][1])
+            gemm((N, K, M), p["qd"][1], p["qx"][1], fmt, out=p["dW"], slabs=(s_dw, s_dw), tensor_scales=p["ts"][2])
+
+    def in_step_gemm_times(fmt, peak):
+        parts = composed(fmt)
+        n_it = max(args.steps // 2, 3)
+        plain_ms = event_time_ms(lambda i: step_composed(parts, fmt), n_it, torch)
+        events = []
+        for i in range(2):
+            step_composed(parts, fmt)
+        torch.cuda.synchronize()
+        for i in range(n_it):
+            step_composed(parts, fmt, events)
+        torch.cuda.synchronize()
+        per = {}
+        for shape, e0, e1 in events:
+            per.setdefault(shape, []).append(e0.elapsed_time(e1))
+        out, total = {}, 0.0
+        for shape, v in per.items():
+            ms = sum(v) / len(v)
+            calls = len(v) // n_it
+            total += ms * calls
+            fl = 2.0 * shape[0] * shape[1] * shape[2]
+            out["x".join(map(str, shape))] = {"calls_per_step": calls, "avg_ms": round(ms, 4), "min_ms": round(min(v), 4),
+                                              "TFLOP/s": round(fl / (ms * 1e-3) / 1e12, 1), "frac_of_peak": round(fl / (ms * 1e-3) / 1e12 / peak, 4)}
+        out["gemm_ms_per_step"] = round(total, 3)
+        out["composed_step_ms"] = round(plain_ms, 3)
+        out["other_kernels_ms_per_step"] = round(plain_ms - total, 3)
+        out["how"] = ("the step composed from nvfp4_quantize_dual (maximum pass + dual quantizer, slab outputs) and nvfp4_gemm_slab: the same "
+                      "kernels in the same order as the fused calls; event pair around each GEMM; M x N x K of the GEMM (contraction last)")
+        return out
+
+    in_step = in_step_gemm_times(nv.NVFP4, PEAK_F16_TFLOPS)
+    in_step_mx = in_step_gemm_times(nv.MXFP4, PEAK_FP4_TFLOPS)
+
     # the same step in MXFP4 (block 32, E8M0; the GEMMs then run on the FP4 matrix instruction)
     def step_mx(s):
         step(s, nv.MXFP4, 2000)
@@ -184,6 +252,27 @@ def main() -> int:
     mx_step_ms = event_time_ms(step_mx, max(args.steps // 2, 3), torch)
     mx_step = {"ms_per_step": round(mx_step_ms, 3), "TFLOP/s": round(flop_per_step / (mx_step_ms * 1e-3) / 1e12, 1),
                "frac_of_fp4_peak": round(flop_per_step / (mx_step_ms * 1e-3) / 1e12 / PEAK_FP4_TFLOPS, 4)}
+
+    # ---- the step of a later micro-batch of the same optimizer step: W's operands (Eqs. 4-5) were quantized once
+    # by nvfp4_quantize_weight and are reused, so no pass over W is made (reported beside the headline, which
+    # quantizes W in every step)
+    def weights_reused(fmt, base):
+        wqs = [nv.quantize_weight(layer[4], M, fmt) for layer in data]
+        t_q = event_time_ms(lambda i: [nv.quantize_weight(layer[4], M, fmt, out=wq) for layer, wq in zip(data, wqs)], 5, torch)
+
+        def step_wq(s):
+            for (name, N, K, X, W, dY, wf, wb, Y, dX, dW, saved), wq in zip(data, wqs):
+                nv.linear_fwd(X, None, fmt, workspace=wf, out=Y, saved=saved, bwd_seed=base + 3 * s, w_operands=wq, N=N)
+                nv.linear_bwd(dY, None, None, base + 3 * s, fmt, workspace=wb, out=(dX, dW), saved=saved, K=K, w_operands=wq)
+
+        ms = event_time_ms(step_wq, max(args.steps // 2, 3), torch)
+        return {"ms_per_step": round(ms, 3), "TFLOP/s": round(flop_per_step / (ms * 1e-3) / 1e12, 1),
+                "frac_of_fp4_peak": round(flop_per_step / (ms * 1e-3) / 1e12 / PEAK_FP4_TFLOPS, 4),
+                "quantize_weights_once_ms": round(t_q, 3)}
+
+    reuse = {"nvfp4": weights_reused(nv.NVFP4, 3000), "mxfp4": weights_reused(nv.MXFP4, 4000),
+             "what": "nvfp4_linear_fwd_wq / nvfp4_linear_bwd_wq on operands of W written once by nvfp4_quantize_weight (3 tensor-maximum "
+                     "passes and 3 dual passes over W, timed separately): per step 9 GEMMs + 6 dual passes + 6 maximum passes"}
 
     # ---- dominant kernel: the block-scaled GEMM at the gate/up shape (same launch as in step)
     name, N, K, X, W, dY, wf, wb, Y, dX, dW, _ = data[0]
@@ -267,6 +356,35 @@ def main() -> int:
                          "rel_mse = sum (Q(x)-x)^2 / sum x^2; ratio = ||dY|| / (sigma_q sqrt(d)), threshold sqrt(3)")
     del sX, sW, sdY, sY, sdX, sdW
 
+    # ---- the five forward linears of the 7B block at 4096 tokens (RtN, bf16 in and out), and the single small
+    # fp32 forward linear: secondary rows, same entry point (nvfp4_linear_fwd), nothing saved for a backward pass
+    fwd_layers = []
+    for idx, (lname, N, K) in enumerate(synth.LLAMA2_7B_LINEARS):
+        Xl, Wl = synth.normal(M, K, 1.0, 600 + idx).to(dev), synth.normal(N, K, 0.02, 700 + idx).to(dev)
+        f = nv.NVFP4.c()
+        wsl = torch.empty(nv.lib.nvfp4_linear_fwd_workspace_bytes(M, N, K, C.byref(f)), dtype=torch.uint8, device=dev)
+        fwd_layers.append((lname, N, K, Xl, Wl, wsl, torch.empty((M, N), dtype=torch.bfloat16, device=dev)))
+    fwd_flop = sum(2.0 * M * N * K for _, N, K, *_ in fwd_layers)
+    forward_linears = {}
+    for label, fmt in (("nvfp4", nv.NVFP4), ("mxfp4", nv.MXFP4)):
+        def fwd_all(i):
+            for lname, N, K, Xl, Wl, wsl, Yl in fwd_layers:
+                nv.linear_fwd(Xl, Wl, fmt, workspace=wsl, out=Yl)
+        ms = event_time_ms(fwd_all, max(args.steps, 5), torch)
+        tf = fwd_flop / (ms * 1e-3) / 1e12
+        forward_linears[label] = {"ms": round(ms, 4), "TFLOP/s": round(tf, 1), "frac_of_fp4_peak": round(tf / PEAK_FP4_TFLOPS, 4),
+                                  "frac_of_f16_peak": round(tf / PEAK_F16_TFLOPS, 4)}
+    forward_linears["workload"] = (f"QKV 4096->12288, out-proj 4096->4096, gate and up 4096->11008, down 11008->4096 at {M} tokens: "
+                                   f"{fwd_flop / 1e9:.1f} GFLOP; per linear two tensor-maximum passes, two row quantizers (RtN), one GEMM")
+    del fwd_layers
+    X1, W1 = synth.normal(256, 256, 1.0, 1, torch.float32).to(dev), synth.normal(256, 256, 1.0, 2, torch.float32).to(dev)
+    f = nv.NVFP4.c()
+    ws1 = torch.empty(nv.lib.nvfp4_linear_fwd_workspace_bytes(256, 256, 256, C.byref(f)), dtype=torch.uint8, device=dev)
+    Y1 = torch.empty((256, 256), dtype=torch.float32, device=dev)
+    ms1 = event_time_ms(lambda i: nv.linear_fwd(X1, W1, workspace=ws1, out=Y1), 200, torch, warmup=10)
+    small_forward = {"workload": "single NVFP4 linear forward, X and W fp32 [256 x 256], fp32 out: 5 kernel launches", "us_per_call": round(ms1 * 1e3, 2),
+                     "GFLOP/s": round(2.0 * 256 ** 3 / (ms1 * 1e-3) / 1e9, 1)}
+
     # ---- quantizer sweep tensor (second half of the metric): bf16 [8192, 8192].
     # Four different tensors are cycled (512 MiB in total) so that the 256 MB last-level cache
     # cannot serve the reads of the next call: the rate is an HBM rate.
@@ -312,7 +430,7 @@ def main() -> int:
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        Ms, Ns, Ks = 4096, 4096, 8192  # about 15 s of host work
+        Ms, Ns, Ks = 4096, 11008, 4096  # the gate layer of the timed step, whole: about 20 s of host work
         Xs, Ws, dYs = synth.normal(Ms, Ks, 1.0, 1), synth.normal(Ns, Ks, 0.02, 2), synth.gradient_like(Ms, Ns, 3)
         t0 = time.perf_counter()
         oracle.linear_fwd(Xs, Ws)
@@ -335,12 +453,14 @@ def main() -> int:
                                "9 GEMMs + 9 dual-orientation quantize passes (X, W in the forward call, which saves Q_SR(X^T), Q_RtN(W^T) and the scales for the backward call; dY in the backward call) + 9 tensor-maximum passes per step, bf16 in and out; packed operands pass from the quantizers to the GEMMs in the library's slab layout",
                    "M": M, "layers": [[n, N, K] for n, N, K in layers], "format": "NVFP4 (block 16, E4M3, tensor scale)",
                    "rounding": "fwd RtN; bwd/update SR (Philox4x32-10)",
+                   "not_included": "the elementwise SwiGLU between the linears (three independent linear layers with synthetic inputs each)",
                    "schedule": ("all forward calls, then all backward calls, in the MLP's dependency order; gate and up side by side "
                                 "on two HIP streams (fork/join with events), down after both" if args.streams >= 2 else
                                 "fwd then bwd per layer, every call on one stream")},
         "schedules": schedules,
         "frac_of_fp4_peak": round(tflops / PEAK_FP4_TFLOPS, 4),
-        "roofline": roofline, "mfma_sustained": sustained, "mxfp4_gemm": mxfp4, "mxfp4_step": mx_step, "format_sweep": sweep,
+        "roofline": roofline, "in_step_gemms": in_step, "mfma_sustained": sustained, "mxfp4_gemm": mxfp4, "mxfp4_step": mx_step,
+        "mxfp4_in_step_gemms": in_step_mx, "weights_reused_step": reuse, "forward_linears_7b": forward_linears, "small_forward": small_forward, "format_sweep": sweep,
         "quantize": quant, "cpu_baseline": cpu,
     }
     print(json.dumps(line))

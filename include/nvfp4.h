@@ -282,6 +282,44 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
                               const float *xw_scales, const void *saved);
 
 /*
+ * The weight operand of Eqs. 4-5 quantized once for every micro-batch of an
+ * optimizer step: with a global batch of several micro-batches per device
+ * (Sec. 5 trains with 4M tokens per step on 256 devices) W does not change
+ * between them, and Eqs. 4 and 5 use the same Q_RtN(W) / Q_RtN(W^T) each time.
+ * nvfp4_quantize_weight runs the tensor-maximum pass and one dual-orientation
+ * pass over W[N, K] (dense row-major of dt) and leaves, in the caller-owned
+ * device buffer w_operands (>= nvfp4_weight_operands_bytes(N, K, f) bytes,
+ * 256-byte aligned): gW, Q_RtN(W) blocked along K and Q_RtN(W^T) blocked along
+ * N, each in the layout (row-major or slabs) that the GEMMs of micro-batches of
+ * M tokens will read -- so M here must be the M of the later calls.  N and K
+ * must be multiples of the block size and of 32.  workspace: >=
+ * nvfp4_quantize_workspace_bytes(N, K) (not needed without tensor scale).
+ * The buffer's contents are private to the library; it carries a tag (M, N, K,
+ * format, layouts) that the calls below check (NVFP4_EINVAL on a mismatch).
+ *
+ * nvfp4_linear_fwd_wq / nvfp4_linear_bwd_wq are nvfp4_linear_fwd /
+ * nvfp4_linear_bwd with w_operands in place of W: no pass over W is made (no
+ * maximum, no quantizer), everything else -- arguments, `saved` hand-over of
+ * Q_SR(X^T), results bit for bit -- is the same.  A `saved` buffer filled by
+ * nvfp4_linear_fwd_wq holds only the X part and must go to nvfp4_linear_bwd_wq.
+ * Since W's operands depend on nothing but W, nvfp4_quantize_weight can run on
+ * another stream, under the GEMMs of another layer.
+ */
+size_t nvfp4_weight_operands_bytes(int64_t N, int64_t K, const nvfp4_format *f);
+nvfp4_status nvfp4_quantize_weight(const void *W, nvfp4_dtype dt, int64_t M, int64_t N, int64_t K,
+                                   const nvfp4_format *f, void *w_operands, void *workspace,
+                                   size_t workspace_bytes, void *stream);
+nvfp4_status nvfp4_linear_fwd_wq(const void *X, const void *w_operands, void *Y, int64_t M, int64_t N,
+                                 int64_t K, nvfp4_dtype in_dt, nvfp4_dtype out_dt,
+                                 const nvfp4_format *f, void *workspace, size_t workspace_bytes,
+                                 void *stream, float *xw_scales_out, void *saved, uint64_t bwd_seed);
+nvfp4_status nvfp4_linear_bwd_wq(const void *dY, const void *X, const void *w_operands, void *dX, void *dW,
+                                 int64_t M, int64_t N, int64_t K, nvfp4_dtype in_dt,
+                                 nvfp4_dtype out_dt, const nvfp4_format *f, uint64_t seed,
+                                 void *workspace, size_t workspace_bytes, void *stream,
+                                 const float *xw_scales, const void *saved);
+
+/*
  * Quantization-noise statistics of a quantized tensor against its source
  * (noise-threshold section, Sec. 4: with eps = Q(x) - x the quantization error
  * of a d-element gradient and sigma_q^2 its mean square, the paper monitors

@@ -93,6 +93,14 @@ def _load() -> C.CDLL:
     L.nvfp4_linear_fwd.argtypes = [vp, vp, vp, i64, i64, i64, ci, ci, fp, vp, sz, vp, vp, vp, u64]
     L.nvfp4_linear_bwd.restype = ci
     L.nvfp4_linear_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, fp, u64, vp, sz, vp, vp, vp]
+    L.nvfp4_linear_fwd_wq.restype = ci
+    L.nvfp4_linear_fwd_wq.argtypes = L.nvfp4_linear_fwd.argtypes
+    L.nvfp4_linear_bwd_wq.restype = ci
+    L.nvfp4_linear_bwd_wq.argtypes = L.nvfp4_linear_bwd.argtypes
+    L.nvfp4_weight_operands_bytes.restype = sz
+    L.nvfp4_weight_operands_bytes.argtypes = [i64, i64, fp]
+    L.nvfp4_quantize_weight.restype = ci
+    L.nvfp4_quantize_weight.argtypes = [vp, ci, i64, i64, i64, fp, vp, vp, sz, vp]
     L.nvfp4_linear_saved_bytes.restype = sz
     L.nvfp4_linear_saved_bytes.argtypes = [i64, i64, i64, fp]
     # host probes
@@ -138,6 +146,7 @@ EXPORTS = (
     "nvfp4_host_sr_bits", "nvfp4_host_e8m0_encode", "nvfp4_host_e4m3_encode_n",
     "nvfp4_host_round_rtn_n", "nvfp4_host_round_sr_n", "nvfp4_probe_mfma_rate",
     "nvfp4_quant_noise_workspace_bytes", "nvfp4_quant_noise", "nvfp4_quantize_static", "nvfp4_cross_check_switches",
+    "nvfp4_weight_operands_bytes", "nvfp4_quantize_weight", "nvfp4_linear_fwd_wq", "nvfp4_linear_bwd_wq",
 )
 
 
@@ -283,7 +292,7 @@ def quantize_dual(x: torch.Tensor, rounding_rows: int = RTN, seed_rows: int = 0,
 
 
 def gemm(A, B, fmt: Format = NVFP4, out_dtype: torch.dtype = torch.float32, out=None, slabs=(False, False),
-         shape=None) -> torch.Tensor:
+         shape=None, tensor_scales: torch.Tensor | None = None) -> torch.Tensor:
     """nvfp4_gemm: A = (codes [M,K/2], scales, g[1]), B = (codes [N,K/2], scales, g[1]) -> [M, N].
     slabs = (a, b): that operand is in the slab layout (nvfp4_gemm_slab); then shape = (M, N, K) is required,
     since a flat slab buffer does not carry it."""
@@ -294,7 +303,8 @@ def gemm(A, B, fmt: Format = NVFP4, out_dtype: torch.dtype = torch.float32, out=
         M, N, K = ac.shape[0], bc.shape[0], ac.shape[1] * 2
     else:
         M, N, K = shape
-    ts = torch.cat([ga.reshape(1), gb.reshape(1)])
+    # {gA, gB} side by side: as given (a caller that keeps them so), else gathered here
+    ts = torch.cat([ga.reshape(1), gb.reshape(1)]) if tensor_scales is None else tensor_scales
     if out is None:
         out = torch.empty((M, N), dtype=out_dtype, device=ac.device)
     f = fmt.c()
@@ -307,24 +317,28 @@ def gemm(A, B, fmt: Format = NVFP4, out_dtype: torch.dtype = torch.float32, out=
 def linear_fwd(X: torch.Tensor, W: torch.Tensor, fmt: Format = NVFP4,
                out_dtype: torch.dtype = torch.float32, workspace: torch.Tensor | None = None,
                out: torch.Tensor | None = None, scales_out: torch.Tensor | None = None,
-               saved: torch.Tensor | None = None, bwd_seed: int = 0) -> torch.Tensor:
+               saved: torch.Tensor | None = None, bwd_seed: int = 0, w_operands: torch.Tensor | None = None,
+               N: int | None = None) -> torch.Tensor:
     """nvfp4_linear_fwd (Eq. 4): Y[M,N] = Q_RtN(X[M,K]) Q_RtN(W[N,K])^T.
+    w_operands: what quantize_weight wrote for W (then W may be None, pass N): nvfp4_linear_fwd_wq.
     scales_out: device fp32[2] that receives {gX, gW} for linear_bwd(..., xw_scales=...).
     saved: device u8 buffer of linear_saved_bytes(M, N, K, fmt) that receives Q_SR(X^T), Q_RtN(W^T) and the
     scales for linear_bwd(..., seed=bwd_seed, saved=saved)."""
-    _require_gpu(X, W)
-    assert X.is_contiguous() and W.is_contiguous() and X.dtype == W.dtype
+    _require_gpu(X, *([W] if W is not None else []))
+    assert X.is_contiguous() and (W is None or (W.is_contiguous() and X.dtype == W.dtype))
+    assert (W is None) != (w_operands is None), "give W or w_operands"
     M, K = X.shape
-    N = W.shape[0]
+    N = W.shape[0] if W is not None else N
     f = fmt.c()
     if workspace is None:
         workspace = torch.empty(lib.nvfp4_linear_fwd_workspace_bytes(M, N, K, C.byref(f)),
                                 dtype=torch.uint8, device=X.device)
     Y = torch.empty((M, N), dtype=out_dtype, device=X.device) if out is None else out
-    _check(lib.nvfp4_linear_fwd(X.data_ptr(), W.data_ptr(), Y.data_ptr(), M, N, K, _dtype_tag(X),
-                                _dtype_tag(Y), C.byref(f), workspace.data_ptr(), workspace.numel(),
-                                _stream(), None if scales_out is None else scales_out.data_ptr(),
-                                None if saved is None else saved.data_ptr(), bwd_seed),
+    entry = lib.nvfp4_linear_fwd if w_operands is None else lib.nvfp4_linear_fwd_wq
+    _check(entry(X.data_ptr(), (W if w_operands is None else w_operands).data_ptr(), Y.data_ptr(), M, N, K, _dtype_tag(X),
+                 _dtype_tag(Y), C.byref(f), workspace.data_ptr(), workspace.numel(),
+                 _stream(), None if scales_out is None else scales_out.data_ptr(),
+                 None if saved is None else saved.data_ptr(), bwd_seed),
            "nvfp4_linear_fwd")
     return Y
 
@@ -332,13 +346,14 @@ def linear_fwd(X: torch.Tensor, W: torch.Tensor, fmt: Format = NVFP4,
 def linear_bwd(dY: torch.Tensor, X: torch.Tensor, W: torch.Tensor, seed: int, fmt: Format = NVFP4,
                out_dtype: torch.dtype = torch.float32, workspace: torch.Tensor | None = None,
                out=None, xw_scales: torch.Tensor | None = None, saved: torch.Tensor | None = None,
-               K: int | None = None):
+               K: int | None = None, w_operands: torch.Tensor | None = None):
     """nvfp4_linear_bwd (Eqs. 5-6) -> (dX [M,K], dW [N,K]).
+    w_operands: what quantize_weight wrote for W (then W is not read): nvfp4_linear_bwd_wq.
     xw_scales: device fp32[2] = {gX, gW} from linear_fwd(..., scales_out=...) for the same X and W.
     saved: what linear_fwd(..., saved=..., bwd_seed=seed) wrote; X and W may then be None (pass K)."""
     _require_gpu(dY, *[t for t in (X, W) if t is not None])
     assert dY.is_contiguous() and (X is None or X.is_contiguous()) and (W is None or W.is_contiguous())
-    assert saved is not None or (X is not None and W is not None)
+    assert saved is not None or (X is not None and (W is not None or w_operands is not None))
     M, N = dY.shape
     K = K if K is not None else (X.shape[1] if X is not None else W.shape[1])
     f = fmt.c()
@@ -350,14 +365,30 @@ def linear_bwd(dY: torch.Tensor, X: torch.Tensor, W: torch.Tensor, seed: int, fm
         dW = torch.empty((N, K), dtype=out_dtype, device=dY.device)
     else:
         dX, dW = out
-    _check(lib.nvfp4_linear_bwd(dY.data_ptr(), None if X is None else X.data_ptr(),
-                                None if W is None else W.data_ptr(), dX.data_ptr(),
+    entry = lib.nvfp4_linear_bwd if w_operands is None else lib.nvfp4_linear_bwd_wq
+    third = w_operands if w_operands is not None else W
+    _check(entry(dY.data_ptr(), None if X is None else X.data_ptr(),
+                                None if third is None else third.data_ptr(), dX.data_ptr(),
                                 dW.data_ptr(), M, N, K, _dtype_tag(dY), _dtype_tag(dX), C.byref(f),
                                 seed, workspace.data_ptr(), workspace.numel(), _stream(),
                                 None if xw_scales is None else xw_scales.data_ptr(),
                                 None if saved is None else saved.data_ptr()),
            "nvfp4_linear_bwd")
     return dX, dW
+
+
+def quantize_weight(W: torch.Tensor, M: int, fmt: Format = NVFP4, out: torch.Tensor | None = None) -> torch.Tensor:
+    """nvfp4_quantize_weight: W [N, K] -> the library's weight-operand buffer (u8) for micro-batches of M tokens."""
+    _require_gpu(W)
+    assert W.dim() == 2 and W.is_contiguous()
+    N, K = W.shape
+    f = fmt.c()
+    if out is None:
+        out = torch.empty(lib.nvfp4_weight_operands_bytes(N, K, C.byref(f)), dtype=torch.uint8, device=W.device)
+    ws = torch.empty(lib.nvfp4_quantize_workspace_bytes(N, K), dtype=torch.uint8, device=W.device)
+    _check(lib.nvfp4_quantize_weight(W.data_ptr(), _dtype_tag(W), M, N, K, C.byref(f), out.data_ptr(), ws.data_ptr(),
+                                     ws.numel(), _stream()), "nvfp4_quantize_weight")
+    return out
 
 
 def linear_saved_bytes(M: int, N: int, K: int, fmt: Format = NVFP4) -> int:

@@ -150,17 +150,55 @@ SavedLayout saved_layout(void *saved, int64_t M, int64_t N, int64_t K, int64_t B
 
 // Identity of a `saved` buffer: shapes, format, seed and the layout each transposed operand was written in.
 constexpr size_t SAVED_TAG_OFFSET = 64;  // bytes into the header; {gX, gW} sit at its front
-TagArgs saved_tag(int64_t M, int64_t N, int64_t K, const nvfp4_format *f, uint64_t seed, bool xt_slab, bool wt_slab)
+TagArgs saved_tag(int64_t M, int64_t N, int64_t K, const nvfp4_format *f, uint64_t seed, bool xt_slab, bool wt_slab,
+                  bool x_only = false)
 {
     TagArgs t;
     t.w[0] = 0x4E564634u;  // "NVF4"
-    t.w[1] = (xt_slab ? 1u : 0u) | (wt_slab ? 2u : 0u) | (use_hw_convert() ? 4u : 0u);
+    t.w[1] = (xt_slab ? 1u : 0u) | (wt_slab ? 2u : 0u) | (use_hw_convert() ? 4u : 0u) | (x_only ? 8u : 0u);
     t.w[2] = (uint32_t)f->block | ((uint32_t)f->scale << 8) | ((uint32_t)f->tensor_scale << 9);
     t.w[3] = (uint32_t)M;
     t.w[4] = (uint32_t)N;
     t.w[5] = (uint32_t)K;
     t.w[6] = (uint32_t)seed;
     t.w[7] = (uint32_t)(seed >> 32);
+    return t;
+}
+
+// What nvfp4_quantize_weight leaves for the forward and backward calls of every micro-batch: gW, then W blocked
+// along K (operand of Eq. 4) and W^T blocked along N (operand of Eq. 5).
+struct WeightLayout {
+    float *g;
+    uint8_t *wc, *wsc, *wtc, *wts;
+};
+
+WeightLayout weight_layout(const void *w_operands, int64_t N, int64_t K, int64_t B)
+{
+    uint8_t *p = reinterpret_cast<uint8_t *>(const_cast<void *>(w_operands));
+    WeightLayout L;
+    L.g = reinterpret_cast<float *>(p);
+    p += WS_HEADER;
+    L.wc = p; p += op_codes(N, K);
+    L.wsc = p; p += op_scales(N, K, B);
+    L.wtc = p; p += op_codes(K, N);
+    L.wts = p;
+    return L;
+}
+
+// Layout of the two weight operands for micro-batches of M tokens: slabs where the GEMM that consumes them takes them.
+void weight_slabs(const nvfp4_format *f, int64_t M, int64_t N, int64_t K, bool *w_slab, bool *wt_slab)
+{
+    const bool sw = dual_writes_slabs(f, NVFP4_BF16, N, K, NVFP4_RTN, NVFP4_RTN);  // (does not depend on the element type)
+    *w_slab = sw && gemm_takes_slabs(M, N, K, f->block, f->scale);
+    *wt_slab = sw && gemm_takes_slabs(M, K, N, f->block, f->scale);
+}
+
+TagArgs weight_tag(int64_t M, int64_t N, int64_t K, const nvfp4_format *f)
+{
+    bool w_slab, wt_slab;
+    weight_slabs(f, M, N, K, &w_slab, &wt_slab);
+    TagArgs t = saved_tag(M, N, K, f, 0, w_slab, wt_slab);
+    t.w[0] = 0x4E565734u;  // "NVW4"
     return t;
 }
 
@@ -530,14 +568,19 @@ nvfp4_status nvfp4_gemm_slab(int64_t M, int64_t N, int64_t K, const nvfp4_format
                : NVFP4_EHIP;
 }
 
-nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, int64_t N,
-                              int64_t K, nvfp4_dtype in_dt, nvfp4_dtype out_dt,
-                              const nvfp4_format *f, void *workspace, size_t workspace_bytes,
-                              void *stream, float *xw_scales_out, void *saved, uint64_t bwd_seed)
+}  // extern "C"
+
+namespace {
+
+// nvfp4_linear_fwd, with W either as a tensor (w_ops == nullptr) or as the operands nvfp4_quantize_weight wrote.
+nvfp4_status linear_fwd_impl(const void *X, const void *W, const void *w_ops, void *Y, int64_t M, int64_t N,
+                             int64_t K, nvfp4_dtype in_dt, nvfp4_dtype out_dt,
+                             const nvfp4_format *f, void *workspace, size_t workspace_bytes,
+                             void *stream, float *xw_scales_out, void *saved, uint64_t bwd_seed)
 {
     nvfp4_status s = check_format(f);
     if (s != NVFP4_OK) return s;
-    if (!X || !W || !Y) return NVFP4_EINVAL;
+    if (!X || (!W && !w_ops) || !Y) return NVFP4_EINVAL;
     if (!valid_dtype(in_dt) || !valid_dtype(out_dt)) return NVFP4_EINVAL;
     if (M <= 0 || N <= 0 || K <= 0 || K > MAX_CONTRACTION) return NVFP4_ESHAPE;
     if (K % f->block != 0 || K % 32 != 0) return NVFP4_ESHAPE;
@@ -545,12 +588,15 @@ nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, 
     if (!aligned16(X) || !aligned16(W) || !aligned16(Y)) return NVFP4_EALIGN;
     if (!workspace || workspace_bytes < nvfp4_linear_fwd_workspace_bytes(M, N, K, f)) return NVFP4_EWORKSPACE;
     if ((reinterpret_cast<uintptr_t>(workspace) & (WS_ALIGN - 1)) != 0) return NVFP4_EALIGN;
-    if (saved) {
+    if (saved || w_ops) {
         // X^T is blocked along M and W^T along N, and those are the backward GEMMs' contractions
-        if (M % f->block != 0 || M % 32 != 0 || N % f->block != 0 || N % 32 != 0) return NVFP4_ESHAPE;
+        if (saved && (M % f->block != 0 || M % 32 != 0)) return NVFP4_ESHAPE;
+        if (N % f->block != 0 || N % 32 != 0) return NVFP4_ESHAPE;
         if (M > MAX_CONTRACTION || N > MAX_CONTRACTION) return NVFP4_ESHAPE;
         if ((reinterpret_cast<uintptr_t>(saved) & (WS_ALIGN - 1)) != 0) return NVFP4_EALIGN;
+        if ((reinterpret_cast<uintptr_t>(w_ops) & (WS_ALIGN - 1)) != 0) return NVFP4_EALIGN;
     }
+    if (w_ops && !saved_matches(w_ops, weight_tag(M, N, K, f))) return NVFP4_EINVAL;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
 
     uint8_t *ws = reinterpret_cast<uint8_t *>(workspace);
@@ -561,66 +607,84 @@ nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, 
     uint8_t *p = ws + WS_HEADER + (partials_bytes(M, K) > partials_bytes(N, K) ? partials_bytes(M, K) : partials_bytes(N, K));
     uint8_t *xc = p; p += op_codes(M, K);
     uint8_t *xs = p; p += op_scales(M, K, f->block);
-    uint8_t *wc = p; p += op_codes(N, K);
-    uint8_t *wsc = p;
+    const uint8_t *wc = p; p += op_codes(N, K);
+    const uint8_t *wsc = p;
+    const float *g_w = ts + 1;
 
     const int gm = f->tensor_scale ? G_FROM_AMAX : G_NONE;
     GSource gx{reinterpret_cast<const float *>(amax + 0), 0}, gw{reinterpret_cast<const float *>(amax + 1), 0};
     if (f->tensor_scale) {
         if (amax_dense(X, in_dt, M * K, partials, 0, st, &gx) != hipSuccess) return NVFP4_EHIP;
-        if (amax_dense(W, in_dt, N * K, partials, 1, st, &gw) != hipSuccess) return NVFP4_EHIP;
+        if (!w_ops && amax_dense(W, in_dt, N * K, partials, 1, st, &gw) != hipSuccess) return NVFP4_EHIP;
     }
     int a_slab = 0, b_slab = 0;
+    const bool t_fwd = gemm_takes_slabs(M, N, K, f->block, f->scale);
+    if (w_ops) {
+        // W as quantized once for all micro-batches of the optimizer step: no pass over W here
+        const WeightLayout WL = weight_layout(w_ops, N, K, f->block);
+        bool w_slab, wt_slab;
+        weight_slabs(f, M, N, K, &w_slab, &wt_slab);
+        wc = WL.wc;
+        wsc = WL.wsc;
+        g_w = WL.g;
+        b_slab = w_slab;
+        if (xw_scales_out && hipMemcpyAsync(xw_scales_out + 1, WL.g, sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess) return NVFP4_EHIP;
+    }
     if (saved) {
         // one pass over X and one over W also leave what Eqs. 5-6 need of them: Q_SR(X^T) with
         // the backward call's third stream, and Q_RtN(W^T)
         const SavedLayout L = saved_layout(saved, M, N, K, f->block);
         DualArgs dx{{X, M, K, K, L.xtc, L.xts, gx.src, ts + 0, gm, bwd_seed + 2, gx.n}, xc, xs, 0, L.g + 0};
-        DualArgs dw{{W, N, K, K, L.wtc, L.wts, gw.src, ts + 1, gm, 0, gw.n}, wc, wsc, 0, L.g + 1};
+        DualArgs dw{{W, N, K, K, L.wtc, L.wts, gw.src, ts + 1, gm, 0, gw.n}, const_cast<uint8_t *>(wc), const_cast<uint8_t *>(wsc), 0, L.g + 1};
         // row-blocked sides feed this call's GEMM, Q(X^T) the update GEMM (Eq. 6), Q(W^T) the input-gradient GEMM (Eq. 5)
         const bool sx = dual_writes_slabs(f, in_dt, M, K, NVFP4_RTN, NVFP4_SR), sw = dual_writes_slabs(f, in_dt, N, K, NVFP4_RTN, NVFP4_RTN);
-        const bool t_fwd = gemm_takes_slabs(M, N, K, f->block, f->scale);
         dx.slab_r = a_slab = sx && t_fwd;
         dx.slab_c = sx && gemm_takes_slabs(N, K, M, f->block, f->scale);
-        dw.slab_r = b_slab = sw && t_fwd;
         dw.slab_c = sw && gemm_takes_slabs(M, K, N, f->block, f->scale);
-        dw.tag = saved_tag(M, N, K, f, bwd_seed, dx.slab_c != 0, dw.slab_c != 0);
-        dw.tag.dst = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(saved) + SAVED_TAG_OFFSET);
-        saved_remember(saved, dw.tag);
+        // the buffer's identity is written by the last quantizer that fills it
+        DualArgs &last = w_ops ? dx : dw;
+        last.tag = saved_tag(M, N, K, f, bwd_seed, dx.slab_c != 0, w_ops ? false : dw.slab_c != 0, w_ops != nullptr);
+        last.tag.dst = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(saved) + SAVED_TAG_OFFSET);
+        saved_remember(saved, last.tag);
         if (launch_quantize_dual(dx, in_dt, NVFP4_RTN, NVFP4_SR, f->block, f->scale, use_hw_convert(), st) != hipSuccess) return NVFP4_EHIP;
-        if (launch_quantize_dual(dw, in_dt, NVFP4_RTN, NVFP4_RTN, f->block, f->scale, use_hw_convert(), st) != hipSuccess) return NVFP4_EHIP;
+        if (!w_ops) {
+            dw.slab_r = b_slab = sw && t_fwd;
+            if (launch_quantize_dual(dw, in_dt, NVFP4_RTN, NVFP4_RTN, f->block, f->scale, use_hw_convert(), st) != hipSuccess) return NVFP4_EHIP;
+        }
     } else {
         QuantPlan qx{X, in_dt, M, K, K, 1, NVFP4_RTN, 0, xc, xs, gx.src, ts + 0, gm, gx.n};
-        QuantPlan qw{W, in_dt, N, K, K, 1, NVFP4_RTN, 0, wc, wsc, gw.src, ts + 1, gm, gw.n};
+        QuantPlan qw{W, in_dt, N, K, K, 1, NVFP4_RTN, 0, const_cast<uint8_t *>(wc), const_cast<uint8_t *>(wsc), gw.src, ts + 1, gm, gw.n};
         if (run_quantize(qx, f, st) != hipSuccess) return NVFP4_EHIP;
-        if (run_quantize(qw, f, st) != hipSuccess) return NVFP4_EHIP;
+        if (!w_ops && run_quantize(qw, f, st) != hipSuccess) return NVFP4_EHIP;
     }
-    GemmArgs g{M, N, K, xc, xs, wc, wsc, ts, ts + 1, Y, N, a_slab, b_slab};
+    GemmArgs g{M, N, K, xc, xs, wc, wsc, ts, g_w, Y, N, a_slab, b_slab};
     return launch_gemm(g, f->block, f->scale, out_dt, st) == hipSuccess ? NVFP4_OK : NVFP4_EHIP;
 }
 
-nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void *dX, void *dW,
-                              int64_t M, int64_t N, int64_t K, nvfp4_dtype in_dt,
-                              nvfp4_dtype out_dt, const nvfp4_format *f, uint64_t seed,
-                              void *workspace, size_t workspace_bytes, void *stream, const float *xw_scales,
-                              const void *saved)
+nvfp4_status linear_bwd_impl(const void *dY, const void *X, const void *W, const void *w_ops, void *dX, void *dW,
+                             int64_t M, int64_t N, int64_t K, nvfp4_dtype in_dt,
+                             nvfp4_dtype out_dt, const nvfp4_format *f, uint64_t seed,
+                             void *workspace, size_t workspace_bytes, void *stream, const float *xw_scales,
+                             const void *saved)
 {
     nvfp4_status s = check_format(f);
     if (s != NVFP4_OK) return s;
-    if (!dY || (!saved && ((dX && !W) || (dW && !X)))) return NVFP4_EINVAL;
+    if (!dY || (dX && !W && !saved && !w_ops) || (dW && !X && !saved)) return NVFP4_EINVAL;
     if (saved && (reinterpret_cast<uintptr_t>(saved) & (WS_ALIGN - 1)) != 0) return NVFP4_EALIGN;
+    if (w_ops && (reinterpret_cast<uintptr_t>(w_ops) & (WS_ALIGN - 1)) != 0) return NVFP4_EALIGN;
     if (!valid_dtype(in_dt) || !valid_dtype(out_dt)) return NVFP4_EINVAL;
     if (M <= 0 || N <= 0 || K <= 0) return NVFP4_ESHAPE;
     const int64_t B = f->block;
     // dX contracts over N, dW over M; K is a leading dimension of X and W read down columns
     if (dX && (N % B != 0 || N % 32 != 0 || N > MAX_CONTRACTION)) return NVFP4_ESHAPE;
     if (dW && (M % B != 0 || M % 32 != 0 || M > MAX_CONTRACTION)) return NVFP4_ESHAPE;
-    if (saved && (M % B != 0 || N % B != 0)) return NVFP4_ESHAPE;  // the shapes nvfp4_linear_fwd accepted
+    if ((saved || w_ops) && (M % B != 0 || N % B != 0)) return NVFP4_ESHAPE;  // the shapes the forward call accepted
     if ((K * (int64_t)elem_size(in_dt)) % 16 != 0 || (N * (int64_t)elem_size(in_dt)) % 16 != 0) return NVFP4_EALIGN;
     if (f->scale == NVFP4_SCALE_E8M0 && f->block != 32) return NVFP4_EUNSUPPORTED;  // E8M0 GEMM: MXFP4 only
     if (!aligned16(dY) || !aligned16(X) || !aligned16(W) || !aligned16(dX) || !aligned16(dW)) return NVFP4_EALIGN;
     if (!workspace || workspace_bytes < nvfp4_linear_bwd_workspace_bytes(M, N, K, f)) return NVFP4_EWORKSPACE;
     if ((reinterpret_cast<uintptr_t>(workspace) & (WS_ALIGN - 1)) != 0) return NVFP4_EALIGN;
+    if (w_ops && !saved_matches(w_ops, weight_tag(M, N, K, f))) return NVFP4_EINVAL;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
 
     uint8_t *ws = reinterpret_cast<uint8_t *>(workspace);
@@ -640,6 +704,7 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
     uint8_t *xtc = p; p += op_codes(K, M);
     uint8_t *xts = p;
     const float *g_w = ts + 1, *g_x = ts + 3;  // written by the W^T and X^T quantizers below, or saved by the forward call
+    const bool have_xt = saved != nullptr, have_wt = saved != nullptr || w_ops != nullptr;
     if (saved) {
         // Q_RtN(W^T) and Q_SR(X^T) as the forward call left them (its bwd_seed must equal seed)
         const SavedLayout L = saved_layout(const_cast<void *>(saved), M, N, K, B);
@@ -649,6 +714,15 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
         xts = L.xts;
         g_x = L.g + 0;
         g_w = L.g + 1;
+    }
+    bool w_slab = false, wq_wt_slab = false;
+    if (w_ops) {
+        // Q_RtN(W^T) as nvfp4_quantize_weight left it
+        const WeightLayout WL = weight_layout(w_ops, N, K, B);
+        weight_slabs(f, M, N, K, &w_slab, &wq_wt_slab);
+        wtc = WL.wtc;
+        wts = WL.wts;
+        g_w = WL.g;
     }
 
     const int gm = f->tensor_scale ? G_FROM_AMAX : G_NONE;
@@ -667,11 +741,11 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
     const bool t_dx = gemm_takes_slabs(M, K, N, f->block, f->scale), t_dw = gemm_takes_slabs(N, K, M, f->block, f->scale);
     const bool sdy = dual && dual_writes_slabs(f, in_dt, M, N, NVFP4_SR, NVFP4_SR);
     const int dy_slab_r = sdy && t_dx, dy_slab_c = sdy && t_dw;
-    const int wt_slab = saved && t_dx && dual_writes_slabs(f, in_dt, N, K, NVFP4_RTN, NVFP4_RTN);
+    const int wt_slab = w_ops ? (int)wq_wt_slab : (int)(saved && t_dx && dual_writes_slabs(f, in_dt, N, K, NVFP4_RTN, NVFP4_RTN));
     const int xt_slab = saved && t_dw && dual_writes_slabs(f, in_dt, M, K, NVFP4_RTN, NVFP4_SR);
     TagArgs tag;
     if (saved) {
-        tag = saved_tag(M, N, K, f, seed, xt_slab != 0, wt_slab != 0);
+        tag = saved_tag(M, N, K, f, seed, xt_slab != 0, w_ops ? false : wt_slab != 0, w_ops != nullptr);
         tag.chk = reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint8_t *>(saved) + SAVED_TAG_OFFSET);
         if (!saved_matches(saved, tag)) return NVFP4_EINVAL;
     }
@@ -698,28 +772,108 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
         if (launch_quantize_dual(d, in_dt, NVFP4_SR, NVFP4_SR, f->block, f->scale, true, st) != hipSuccess) return NVFP4_EHIP;
     }
     if (dX) {
-        if (f->tensor_scale && !known && !saved && amax_dense(W, in_dt, N * K, partials, 1, st, &gw) != hipSuccess) return NVFP4_EHIP;
+        if (f->tensor_scale && !known && !have_wt && amax_dense(W, in_dt, N * K, partials, 1, st, &gw) != hipSuccess) return NVFP4_EHIP;
         // Eq. 5: dX[M, K] = Q_SR(dY)[M, N] * Q_RtN(W^T)[K, N]^T
         QuantPlan qa{dY, in_dt, M, N, N, 1, NVFP4_SR, seed, dyc, dys, gdy.src, ts + 0, gm, gdy.n};
         QuantPlan qb{W, in_dt, N, K, K, 0, NVFP4_RTN, 0, wtc, wts, gw.src, ts + 1, gm_xw, gw.n};
         if (!dual && run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
         if (!dual && launch_saved_tag(tag, ts + 0, nullptr, st) != hipSuccess) return NVFP4_EHIP;
-        if (!saved && run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
+        if (!have_wt && run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
         GemmArgs g{M, K, N, dyc, dys, wtc, wts, ts + 0, g_w, dX, K, dy_slab_r, wt_slab};
         if (launch_gemm(g, f->block, f->scale, out_dt, st) != hipSuccess) return NVFP4_EHIP;
     }
     if (dW) {
-        if (f->tensor_scale && !known && !saved && amax_dense(X, in_dt, M * K, partials, 2, st, &gx) != hipSuccess) return NVFP4_EHIP;
+        if (f->tensor_scale && !known && !have_xt && amax_dense(X, in_dt, M * K, partials, 2, st, &gx) != hipSuccess) return NVFP4_EHIP;
         // Eq. 6: dW[N, K] = Q_SR(dY^T)[N, M] * Q_SR(X^T)[K, M]^T
         QuantPlan qa{dY, in_dt, M, N, N, 0, NVFP4_SR, seed + 1, dytc, dyts, gdy.src, ts + 2, gm, gdy.n};
         QuantPlan qb{X, in_dt, M, K, K, 0, NVFP4_SR, seed + 2, xtc, xts, gx.src, ts + 3, gm_xw, gx.n};
         if (!dual && run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
         if (!dual && launch_saved_tag(tag, ts + 2, nullptr, st) != hipSuccess) return NVFP4_EHIP;
-        if (!saved && run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
+        if (!have_xt && run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
         GemmArgs g{N, K, M, dytc, dyts, xtc, xts, ts + 2, g_x, dW, K, dy_slab_c, xt_slab};
         if (launch_gemm(g, f->block, f->scale, out_dt, st) != hipSuccess) return NVFP4_EHIP;
     }
     return NVFP4_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, int64_t N,
+                              int64_t K, nvfp4_dtype in_dt, nvfp4_dtype out_dt,
+                              const nvfp4_format *f, void *workspace, size_t workspace_bytes,
+                              void *stream, float *xw_scales_out, void *saved, uint64_t bwd_seed)
+{
+    if (!W) return NVFP4_EINVAL;
+    return linear_fwd_impl(X, W, nullptr, Y, M, N, K, in_dt, out_dt, f, workspace, workspace_bytes, stream, xw_scales_out, saved, bwd_seed);
+}
+
+nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void *dX, void *dW,
+                              int64_t M, int64_t N, int64_t K, nvfp4_dtype in_dt,
+                              nvfp4_dtype out_dt, const nvfp4_format *f, uint64_t seed,
+                              void *workspace, size_t workspace_bytes, void *stream, const float *xw_scales,
+                              const void *saved)
+{
+    return linear_bwd_impl(dY, X, W, nullptr, dX, dW, M, N, K, in_dt, out_dt, f, seed, workspace, workspace_bytes, stream, xw_scales, saved);
+}
+
+size_t nvfp4_weight_operands_bytes(int64_t N, int64_t K, const nvfp4_format *f)
+{
+    if (N <= 0 || K <= 0 || check_format(f) != NVFP4_OK) return 0;
+    return WS_HEADER + op_codes(N, K) + op_scales(N, K, f->block) + op_codes(K, N) + op_scales(K, N, f->block);
+}
+
+nvfp4_status nvfp4_quantize_weight(const void *W, nvfp4_dtype dt, int64_t M, int64_t N, int64_t K,
+                                   const nvfp4_format *f, void *w_operands, void *workspace,
+                                   size_t workspace_bytes, void *stream)
+{
+    nvfp4_status s = check_format(f);
+    if (s != NVFP4_OK) return s;
+    if (!W || !w_operands || !valid_dtype(dt)) return NVFP4_EINVAL;
+    if (M <= 0 || N <= 0 || K <= 0 || K > MAX_CONTRACTION || N > MAX_CONTRACTION || M > MAX_CONTRACTION) return NVFP4_ESHAPE;
+    if (K % f->block != 0 || K % 32 != 0 || N % f->block != 0 || N % 32 != 0) return NVFP4_ESHAPE;
+    if (f->scale == NVFP4_SCALE_E8M0 && f->block != 32) return NVFP4_EUNSUPPORTED;  // E8M0 GEMM: MXFP4 only
+    if (!aligned16(W) || (reinterpret_cast<uintptr_t>(w_operands) & (WS_ALIGN - 1)) != 0) return NVFP4_EALIGN;
+    if (f->tensor_scale) {
+        if (!workspace || workspace_bytes < nvfp4_quantize_workspace_bytes(N, K)) return NVFP4_EWORKSPACE;
+        if (!aligned16(workspace)) return NVFP4_EALIGN;
+    }
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const WeightLayout WL = weight_layout(w_operands, N, K, f->block);
+    GSource gw{WL.g, 0};
+    if (f->tensor_scale) {
+        uint32_t *partials = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(workspace) + WS_HEADER);
+        if (amax_dense(W, dt, N * K, partials, 0, st, &gw) != hipSuccess) return NVFP4_EHIP;
+    }
+    bool w_slab, wt_slab;
+    weight_slabs(f, M, N, K, &w_slab, &wt_slab);
+    DualArgs dw{{W, N, K, K, WL.wtc, WL.wts, gw.src, WL.g, f->tensor_scale ? G_FROM_AMAX : G_NONE, 0, gw.n}, WL.wc, WL.wsc, 0, nullptr};
+    dw.slab_r = w_slab;
+    dw.slab_c = wt_slab;
+    dw.tag = weight_tag(M, N, K, f);
+    dw.tag.dst = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(w_operands) + SAVED_TAG_OFFSET);
+    saved_remember(w_operands, dw.tag);
+    return launch_quantize_dual(dw, dt, NVFP4_RTN, NVFP4_RTN, f->block, f->scale, use_hw_convert(), st) == hipSuccess ? NVFP4_OK : NVFP4_EHIP;
+}
+
+nvfp4_status nvfp4_linear_fwd_wq(const void *X, const void *w_operands, void *Y, int64_t M, int64_t N,
+                                 int64_t K, nvfp4_dtype in_dt, nvfp4_dtype out_dt,
+                                 const nvfp4_format *f, void *workspace, size_t workspace_bytes,
+                                 void *stream, float *xw_scales_out, void *saved, uint64_t bwd_seed)
+{
+    if (!w_operands) return NVFP4_EINVAL;
+    return linear_fwd_impl(X, nullptr, w_operands, Y, M, N, K, in_dt, out_dt, f, workspace, workspace_bytes, stream, xw_scales_out, saved, bwd_seed);
+}
+
+nvfp4_status nvfp4_linear_bwd_wq(const void *dY, const void *X, const void *w_operands, void *dX, void *dW,
+                                 int64_t M, int64_t N, int64_t K, nvfp4_dtype in_dt,
+                                 nvfp4_dtype out_dt, const nvfp4_format *f, uint64_t seed,
+                                 void *workspace, size_t workspace_bytes, void *stream, const float *xw_scales,
+                                 const void *saved)
+{
+    if (!w_operands) return NVFP4_EINVAL;
+    return linear_bwd_impl(dY, X, nullptr, w_operands, dX, dW, M, N, K, in_dt, out_dt, f, seed, workspace, workspace_bytes, stream, xw_scales, saved);
 }
 
 size_t nvfp4_quant_noise_workspace_bytes(int64_t rows, int64_t cols, int axis)

@@ -338,6 +338,52 @@ def test_backward_from_operands_saved_by_forward(fmtname, dtype):
         assert_gemm_close(to_np(b[1]), oracle.gemm_nt(qdyt, qxt, of), oracle.gemm_nt(qdyt, qxt, of, take_abs=True), "saved dW")
 
 
+@pytest.mark.parametrize("fmtname", ["nvfp4", "mxfp4", "e4m3_b64"])
+def test_weight_operands_reused_across_micro_batches(fmtname):
+    # W quantized once (nvfp4_quantize_weight) and reused by the forward and backward calls of several micro-batches:
+    # Y, dX, dW must equal, bit for bit, what the calls that quantize W themselves give (and those are checked
+    # against the oracle here for the small shape); with and without the saved-operand hand-over of X; small shape
+    # (row-major operands) and a shape whose three GEMMs all take slab operands
+    fmt = {"nvfp4": nv.NVFP4, "mxfp4": nv.MXFP4, "e4m3_b64": nv.Format(64, nv.SCALE_E4M3, 1)}[fmtname]
+    of = ofmt(fmt)
+    shapes = [(256, 192, 320)] + ([(2944, 3200, 2816)] if fmtname != "e4m3_b64" else [])
+    for M, N, K in shapes:
+        W = synth.normal(N, K, 0.02, 142).cuda()
+        wq = nv.quantize_weight(W, M, fmt)
+        for mb in range(2):
+            print(f"[case] weight operands reused fmt={fmtname} M={M} N={N} K={K} micro-batch {mb}", flush=True)
+            seed = 50 + 3 * mb
+            X, dY = synth.normal(M, K, 1.0, 140 + 10 * mb).cuda(), synth.gradient_like(M, N, 141 + 10 * mb).cuda()
+            Y0 = nv.linear_fwd(X, W, fmt, out_dtype=torch.bfloat16)
+            Y1 = nv.linear_fwd(X, None, fmt, out_dtype=torch.bfloat16, w_operands=wq, N=N)
+            a = nv.linear_bwd(dY, X, W, seed, fmt, out_dtype=torch.bfloat16)
+            b = nv.linear_bwd(dY, X, None, seed, fmt, out_dtype=torch.bfloat16, w_operands=wq)
+            saved = torch.empty(nv.linear_saved_bytes(M, N, K, fmt), dtype=torch.uint8, device="cuda")
+            Y2 = nv.linear_fwd(X, None, fmt, out_dtype=torch.bfloat16, w_operands=wq, N=N, saved=saved, bwd_seed=seed)
+            c = nv.linear_bwd(dY, None, None, seed, fmt, out_dtype=torch.bfloat16, saved=saved, K=K, w_operands=wq)
+            torch.cuda.synchronize()
+            assert torch.equal(Y0, Y1) and torch.equal(Y0, Y2)
+            assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+            assert torch.equal(a[0], c[0]) and torch.equal(a[1], c[1])
+            # a saved buffer filled by the _wq forward holds no W^T: the plain backward must refuse it
+            with pytest.raises(nv.Nvfp4Error) as e:
+                nv.linear_bwd(dY, None, None, seed, fmt, saved=saved, K=K)
+            assert e.value.code == nv.EINVAL
+            if M == 256:
+                Xc, Wc, dYc = X.cpu(), W.cpu(), dY.cpu()
+                qx, qw = oracle.quantize(Xc, 1, oracle.RTN, 0, of), oracle.quantize(Wc, 1, oracle.RTN, 0, of)
+                assert_bf16_gemm_close(to_np(Y1.float()), oracle.gemm_nt(qx, qw, of), oracle.gemm_nt(qx, qw, of, take_abs=True), "wq Y")
+                qdy, qwt = oracle.quantize(dYc, 1, oracle.SR, seed, of), oracle.quantize(Wc, 0, oracle.RTN, 0, of)
+                assert_bf16_gemm_close(to_np(c[0].float()), oracle.gemm_nt(qdy, qwt, of), oracle.gemm_nt(qdy, qwt, of, take_abs=True), "wq dX")
+                qdyt, qxt = oracle.quantize(dYc, 0, oracle.SR, seed + 1, of), oracle.quantize(Xc, 0, oracle.SR, seed + 2, of)
+                assert_bf16_gemm_close(to_np(c[1].float()), oracle.gemm_nt(qdyt, qxt, of), oracle.gemm_nt(qdyt, qxt, of, take_abs=True), "wq dW")
+        # operands prepared for another micro-batch size are refused
+        X = synth.normal(M + 32, K, 1.0, 1).cuda()
+        with pytest.raises(nv.Nvfp4Error) as e:
+            nv.linear_fwd(X, None, fmt, w_operands=wq, N=N)
+        assert e.value.code == nv.EINVAL
+
+
 def test_saved_buffer_identity_is_checked(switches):
     # the backward call refuses a `saved` buffer that a forward call wrote for another seed, shape, format or
     # cross-check setting (host record of the buffer), and a copy of such a buffer at an address the library has

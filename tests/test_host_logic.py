@@ -87,6 +87,31 @@ def test_quantize_static_argument_errors():
     assert qs(rows=16385, cols=16, ld=24, flags=nv.PRESET_TSCALE) == nv.EWORKSPACE  # the limit does not depend on flags
 
 
+def test_weight_operand_argument_errors():
+    f = nv.NVFP4.c()
+    n = nv.lib.nvfp4_weight_operands_bytes(11008, 4096, C.byref(f))
+    assert n >= 2 * 11008 * 4096 * 9 // 16 and n < 2 * 11008 * 4096 * 9 // 16 + (1 << 21)
+    assert nv.lib.nvfp4_weight_operands_bytes(0, 4096, C.byref(f)) == 0
+    qw = lambda **k: nv.lib.nvfp4_quantize_weight(k.get("W", FAKE), k.get("dt", nv.BF16), k.get("M", 256), k.get("N", 128), k.get("K", 128),
+                                                  C.byref(k.get("f", f)), k.get("out", FAKE + 256 - FAKE % 256 if FAKE % 256 else FAKE), k.get("ws", FAKE), k.get("wsb", 1 << 20), None)
+    assert qw(W=None) == nv.EINVAL
+    assert qw(out=None) == nv.EINVAL
+    assert qw(dt=5) == nv.EINVAL
+    assert qw(N=72) == nv.ESHAPE          # W^T is blocked along N
+    assert qw(K=48) == nv.ESHAPE
+    assert qw(M=0) == nv.ESHAPE
+    assert qw(out=FAKE + 16) == nv.EALIGN
+    assert qw(ws=None) == nv.EWORKSPACE
+    assert qw(f=nv.Format(64, nv.SCALE_E8M0, 0).c()) == nv.EUNSUPPORTED
+    fw = lambda **k: nv.lib.nvfp4_linear_fwd_wq(FAKE, k.get("wq", FAKE), FAKE, k.get("M", 64), k.get("N", 64), 64, nv.BF16, nv.BF16, C.byref(f),
+                                                FAKE, 1 << 30, None, None, None, 0)
+    assert fw(wq=None) == nv.EINVAL
+    assert fw(N=72) == nv.ESHAPE
+    assert fw(wq=FAKE + 16) == nv.EALIGN
+    bw = nv.lib.nvfp4_linear_bwd_wq(FAKE, FAKE, None, FAKE, FAKE, 64, 64, 64, nv.BF16, nv.BF16, C.byref(f), 0, FAKE, 1 << 30, None, None, None)
+    assert bw == nv.EINVAL
+
+
 def test_cross_check_switches_round_trip():
     before = nv.cross_check_switches()
     assert before in (0, 1, 2, 3)
