@@ -167,7 +167,28 @@ __device__ __forceinline__ float resolve_g(const QuantArgs &P)
 // even; the input is clamped to 448 first, as in the software encode, so the convert never sees
 // an out-of-range value).  Checked against e4m3_encode / e4m3_decode on every non-negative fp32
 // up to 512: identical bytes and values.  The software formulation costs ~15 instructions per block.
-template <int SF, bool HW = false>
+// With E4M3 scales and a per-tensor g the multiplier q = 1 / (s * g) is a function of the scale byte alone: a
+// workgroup evaluates it once for each of the 127 finite bytes (the same multiply and correctly rounded division
+// every block would do) and the blocks then look it up, which takes ~12 instructions out of every block's path.
+// All 256 threads of the workgroup must call this (it ends in a barrier).  Returns false where no table applies.
+__shared__ float qtab[128];
+template <int SF, bool HW>
+__device__ __forceinline__ bool build_qtab(float g)
+{
+    if (SF != NVFP4_SCALE_E4M3 || !HW) return false;
+    if (threadIdx.x < 128) {
+        const uint32_t byte = threadIdx.x;
+        const float s = __builtin_amdgcn_cvt_f32_fp8((int)byte, 0);
+        const float d = byte == 0 ? 1.0f : s * g;
+        const float r = 1.0f / d;
+        qtab[byte] = byte == 0 ? 0.0f : r;
+    }
+    __syncthreads();
+    return true;
+}
+
+// TAB: look q up in the workgroup's table (build_qtab() must have run) instead of dividing.
+template <int SF, bool HW = false, bool TAB = false>
 __device__ __forceinline__ uint32_t block_scale(float a, float g, float k, float *q)
 {
     if (SF == NVFP4_SCALE_E4M3) {
@@ -177,12 +198,19 @@ __device__ __forceinline__ uint32_t block_scale(float a, float g, float k, float
             const float r = a * k;
             const float rc = r < 448.0f ? r : 448.0f;
             byte = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(rc, 0.0f, 0, false) & 0xFFu;
+            if (TAB) {
+                *q = qtab[byte];
+                return byte;
+            }
             s = __builtin_amdgcn_cvt_f32_fp8((int)byte, 0);
         } else {
             byte = e4m3_encode(a * k, &s);
         }
-        float d = s * g;
-        *q = byte == 0 ? 0.0f : 1.0f / d;
+        // (no branch around the division: a zero scale byte divides by 1 and is then replaced)
+        const bool zero = byte == 0;
+        const float d = zero ? 1.0f : s * g;
+        const float r = 1.0f / d;
+        *q = zero ? 0.0f : r;
         return byte;
     } else {
         if (a == 0.0f) {
@@ -204,10 +232,11 @@ __device__ __forceinline__ uint32_t quant_elem(float x, float q, uint32_t u16)
 }
 
 // Two adjacent elements -> one byte via the gfx950 convert (RNE, saturating at +-6, sign
-// kept on zero), low nibble = first element.
-__device__ __forceinline__ uint32_t quant_pair_hw(float x0, float x1, float q)
+// kept on zero), low nibble = first element; the byte replaces byte BYTE of acc, the others stay.
+template <int BYTE>
+__device__ __forceinline__ uint32_t quant_pair_hw(uint32_t acc, float x0, float x1, float q)
 {
-    return __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, x0 * q, x1 * q, 1.0f, 0) & 0xFFu;
+    return __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(acc, x0 * q, x1 * q, 1.0f, BYTE);
 }
 
 // Stochastic rounding of one element through the gfx950 convert, which takes a pair: the
@@ -228,6 +257,43 @@ __device__ __forceinline__ uint32_t sr_elem_hw(uint32_t acc, float y, uint32_t u
     if (BYTE == 2) asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, 1.0 op_sel:[0,0,0,1]" : "+v"(acc) : "v"(v), "v"(seed));
     if (BYTE == 3) asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, 1.0 op_sel:[0,0,1,1]" : "+v"(acc) : "v"(v), "v"(seed));
     return acc;
+}
+
+// The same through slot 0 only, with the seed word taken straight from a draw word: nw is the COMPLEMENT of the
+// Philox word that holds the element's 16 bits in its low (HALF 0) or high (HALF 1) half, and
+// sr_seed_first(u16) = ((~u16 & 0xFFFF) << 16) | 0x8000 becomes one shift-or or one and-or.  An element that
+// belongs in the high nibble of its byte is converted into the low nibble of a second accumulator, which the
+// caller shifts by 4 once per word.
+__device__ __forceinline__ uint32_t sr_seed0(uint32_t nw, int half)
+{
+    return half ? ((nw & 0xFFFF0000u) | 0x8000u) : ((nw << 16) | 0x8000u);
+}
+template <int BYTE>
+__device__ __forceinline__ uint32_t sr_elem0(uint32_t acc, float y, uint32_t seed)
+{
+    typedef float float2_t __attribute__((ext_vector_type(2)));
+    const float2_t v = float2_t{y, 0.0f};
+    if (BYTE == 0) asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, 1.0" : "+v"(acc) : "v"(v), "v"(seed));
+    if (BYTE == 1) asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, 1.0 op_sel:[0,0,1,0]" : "+v"(acc) : "v"(v), "v"(seed));
+    if (BYTE == 2) asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, 1.0 op_sel:[0,0,0,1]" : "+v"(acc) : "v"(v), "v"(seed));
+    if (BYTE == 3) asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, 1.0 op_sel:[0,0,1,1]" : "+v"(acc) : "v"(v), "v"(seed));
+    return acc;
+}
+// 8 consecutive elements of a row (chunk v, multiplier q, their draw d) -> 8 codes in one word
+template <int DT>
+__device__ __forceinline__ uint32_t sr_chunk_hw(const Chunk<DT> &v, float q, const u32x4 &d)
+{
+    const uint32_t n0 = ~d.x, n1 = ~d.y, n2 = ~d.z, n3 = ~d.w;
+    uint32_t lo = 0, hi = 0;
+    lo = sr_elem0<0>(lo, v.get(0) * q, sr_seed0(n0, 0));
+    hi = sr_elem0<0>(hi, v.get(1) * q, sr_seed0(n0, 1));
+    lo = sr_elem0<1>(lo, v.get(2) * q, sr_seed0(n1, 0));
+    hi = sr_elem0<1>(hi, v.get(3) * q, sr_seed0(n1, 1));
+    lo = sr_elem0<2>(lo, v.get(4) * q, sr_seed0(n2, 0));
+    hi = sr_elem0<2>(hi, v.get(5) * q, sr_seed0(n2, 1));
+    lo = sr_elem0<3>(lo, v.get(6) * q, sr_seed0(n3, 0));
+    hi = sr_elem0<3>(hi, v.get(7) * q, sr_seed0(n3, 1));
+    return lo | (hi << 4);
 }
 
 // ------------------------------------------------------------------ tensor maximum (Q0)
@@ -365,6 +431,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(QuantArgs P)
     // (after the loads are issued: folding the partial maxima then overlaps their latency)
     const float g = resolve_g(P);
     const float k = 1.0f / (6.0f * g);
+    build_qtab<SF, HW>(g);
     if (blockIdx.x == 0 && threadIdx.x == 0) *P.g_out = g;
 #pragma unroll
     for (int u = 0; u < ROWS_UNROLL; ++u) {
@@ -373,21 +440,15 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(QuantArgs P)
         // either all live or all holding zeros
         const float a = group_max<LPB>(chunk_amax(v[u]));
         float q;
-        const uint32_t sbyte = block_scale<SF, HW>(a, g, k, &q);
+        const uint32_t sbyte = block_scale<SF, HW, HW && SF == NVFP4_SCALE_E4M3>(a, g, k, &q);
         uint32_t packed = 0;
         if (RND == NVFP4_RTN && HW) {
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-                packed |= quant_pair_hw(v[u].get(2 * t), v[u].get(2 * t + 1), q) << (8 * t);
+            packed = quant_pair_hw<0>(packed, v[u].get(0), v[u].get(1), q);
+            packed = quant_pair_hw<1>(packed, v[u].get(2), v[u].get(3), q);
+            packed = quant_pair_hw<2>(packed, v[u].get(4), v[u].get(5), q);
+            packed = quant_pair_hw<3>(packed, v[u].get(6), v[u].get(7), q);
         } else if (RND == NVFP4_SR && HW) {
-            const u32x4 d = sr_draw(P.seed, (uint64_t)id);  // element index = 8*id + t
-            uint32_t lo = 0, hi = 0;
-#define NVFP4_SR_PAIR(t)                                                                    \
-    lo = sr_elem_hw<0, t>(lo, v[u].get(2 * t) * q, sr_bits_of(d, 2 * t));                   \
-    hi = sr_elem_hw<1, t>(hi, v[u].get(2 * t + 1) * q, sr_bits_of(d, 2 * t + 1));
-            NVFP4_SR_PAIR(0) NVFP4_SR_PAIR(1) NVFP4_SR_PAIR(2) NVFP4_SR_PAIR(3)
-#undef NVFP4_SR_PAIR
-            packed = lo | hi;
+            packed = sr_chunk_hw(v[u], q, sr_draw(P.seed, (uint64_t)id));  // element index = 8*id + t
         } else {
             u32x4 d = {0, 0, 0, 0};
             if (RND == NVFP4_SR) d = sr_draw(P.seed, (uint64_t)id);  // element index = 8*id + t
@@ -443,27 +504,53 @@ __device__ __forceinline__ uint32_t col_bits(const u32x4 &d0, const u32x4 &d1, u
 
 // Stochastic rounding of a lane's 16 x 8 tile through the hardware convert, two rows at a time
 // (the byte select of the convert must be a constant, hence the recursion over row pairs).
+// ALIGNED (every row holds a whole number of draws and the lane's 8 columns are one of them): ctr is the draw
+// counter of row row0 + R at the lane's columns and cstep = cols / 8 the distance to the next row's, both carried
+// along instead of being recomputed from 64-bit element indices for every row.
 template <int DT, int RND, bool ALIGNED, int BL, int R>
 __device__ __forceinline__ void col_sr_hw(const QuantArgs &P, Chunk<DT> (&v)[16], float (&q)[8][16 / BL],
                                           int64_t row0, int64_t col0, uint32_t (&weven)[8][2],
-                                          uint32_t (&wodd)[8][2])
+                                          uint32_t (&wodd)[8][2], uint64_t ctr, uint64_t cstep)
 {
     if constexpr (R < 16) {
         const uint64_t e0 = (uint64_t)(row0 + R) * (uint64_t)P.cols + (uint64_t)col0;
         const uint64_t e1 = e0 + (uint64_t)P.cols;
         const u32x4 z = {0, 0, 0, 0};
-        const u32x4 a0 = sr_draw(P.seed, e0 >> 3), b0 = sr_draw(P.seed, e1 >> 3);
+        const u32x4 a0 = sr_draw(P.seed, ALIGNED ? ctr : e0 >> 3), b0 = sr_draw(P.seed, ALIGNED ? ctr + cstep : e1 >> 3);
         const u32x4 a1 = ALIGNED ? z : sr_draw(P.seed, (e0 >> 3) + 1);
         const u32x4 b1 = ALIGNED ? z : sr_draw(P.seed, (e1 >> 3) + 1);
         const uint32_t sa = (uint32_t)e0 & 7u, sb = (uint32_t)e1 & 7u;
+        if constexpr (ALIGNED) {
+            // (odd rows are converted into the low nibbles of wodd; the caller shifts them up)
+            const uint32_t na[4] = {~a0.x, ~a0.y, ~a0.z, ~a0.w}, nb[4] = {~b0.x, ~b0.y, ~b0.z, ~b0.w};
 #pragma unroll
-        for (int c = 0; c < 8; ++c) {
-            weven[c][R / 8] = sr_elem_hw<0, (R % 8) / 2>(weven[c][R / 8], v[R].get(c) * q[c][R / BL],
-                                                         col_bits<ALIGNED>(a0, a1, sa, c));
-            wodd[c][R / 8] = sr_elem_hw<1, (R % 8) / 2>(wodd[c][R / 8], v[R + 1].get(c) * q[c][(R + 1) / BL],
-                                                        col_bits<ALIGNED>(b0, b1, sb, c));
+            for (int c = 0; c < 8; ++c) {
+                weven[c][R / 8] = sr_elem0<(R % 8) / 2>(weven[c][R / 8], v[R].get(c) * q[c][R / BL], sr_seed0(na[c / 2], c & 1));
+                wodd[c][R / 8] = sr_elem0<(R % 8) / 2>(wodd[c][R / 8], v[R + 1].get(c) * q[c][(R + 1) / BL], sr_seed0(nb[c / 2], c & 1));
+            }
+        } else {
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                weven[c][R / 8] = sr_elem_hw<0, (R % 8) / 2>(weven[c][R / 8], v[R].get(c) * q[c][R / BL],
+                                                             col_bits<ALIGNED>(a0, a1, sa, c));
+                wodd[c][R / 8] = sr_elem_hw<1, (R % 8) / 2>(wodd[c][R / 8], v[R + 1].get(c) * q[c][(R + 1) / BL],
+                                                            col_bits<ALIGNED>(b0, b1, sb, c));
+            }
         }
-        col_sr_hw<DT, RND, ALIGNED, BL, R + 2>(P, v, q, row0, col0, weven, wodd);
+        col_sr_hw<DT, RND, ALIGNED, BL, R + 2>(P, v, q, row0, col0, weven, wodd, ctr + 2 * cstep, cstep);
+    }
+}
+
+// Round-to-nearest of a lane's 16 x 8 tile through the hardware convert: rows R and R + 1 of a column share a
+// byte, which the convert writes in place (its byte select must be a constant, hence the recursion over row pairs).
+template <int DT, int BL, int R>
+__device__ __forceinline__ void col_rtn_hw(Chunk<DT> (&v)[16], float (&q)[8][16 / BL], uint32_t (&words)[8][2])
+{
+    if constexpr (R < 16) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+            words[c][R / 8] = quant_pair_hw<(R % 8) / 2>(words[c][R / 8], v[R].get(c), v[R + 1].get(c), q[c][R / BL]);
+        col_rtn_hw<DT, BL, R + 2>(v, q, words);
     }
 }
 
@@ -506,6 +593,7 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(QuantArgs P)
     }
     const float g = resolve_g(P);
     const float k = 1.0f / (6.0f * g);
+    build_qtab<SF, HW>(g);
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *P.g_out = g;
     cols_tile<DT, B, SF, RND, HW, ALIGNED, LV>(P, v, g, k, row0, col0, ncol, lv);
 }
@@ -535,7 +623,7 @@ __device__ __forceinline__ void cols_tile(const QuantArgs &P, Chunk<DT> (&v)[16]
 #pragma unroll
             for (int r = 0; r < BL; ++r) a = fmaxf(a, fabsf(v[nb * BL + r].get(c)));
             a = group_max<LPB>(a);
-            sbytes[c][nb] = block_scale<SF, HW>(a, g, k, &q[c][nb]);
+            sbytes[c][nb] = block_scale<SF, HW, HW && SF == NVFP4_SCALE_E4M3>(a, g, k, &q[c][nb]);
         }
     }
 
@@ -552,11 +640,7 @@ __device__ __forceinline__ void cols_tile(const QuantArgs &P, Chunk<DT> (&v)[16]
         for (int w = 0; w < RPL / 8; ++w) words[c][w] = 0;
 
     if (RND == NVFP4_RTN && HW) {
-#pragma unroll
-        for (int r = 0; r < RPL; r += 2)
-#pragma unroll
-            for (int c = 0; c < 8; ++c)
-                words[c][r / 8] |= quant_pair_hw(v[r].get(c), v[r + 1].get(c), q[c][r / BL]) << (4 * (r % 8));
+        col_rtn_hw<DT, BL, 0>(v, q, words);
     } else if (RND == NVFP4_SR && HW) {
         // rows 2p and 2p+1 of a column share a byte: even rows go through slot 0, odd rows
         // through slot 1 of the convert, into two sets of words that are OR-ed at the end
@@ -565,11 +649,12 @@ __device__ __forceinline__ void cols_tile(const QuantArgs &P, Chunk<DT> (&v)[16]
         for (int c = 0; c < 8; ++c)
 #pragma unroll
             for (int w = 0; w < RPL / 8; ++w) wodd[c][w] = 0;
-        col_sr_hw<DT, RND, ALIGNED, BL, 0>(P, v, q, row0, col0, words, wodd);
+        const uint64_t cstep = (uint64_t)P.cols >> 3;
+        col_sr_hw<DT, RND, ALIGNED, BL, 0>(P, v, q, row0, col0, words, wodd, (uint64_t)row0 * cstep + ((uint64_t)col0 >> 3), cstep);
 #pragma unroll
         for (int c = 0; c < 8; ++c)
 #pragma unroll
-            for (int w = 0; w < RPL / 8; ++w) words[c][w] |= wodd[c][w];
+            for (int w = 0; w < RPL / 8; ++w) words[c][w] |= ALIGNED ? wodd[c][w] << 4 : wodd[c][w];
     } else {
         // the 8 columns of a lane are 8 consecutive elements of a row; their random bits come
         // from one draw when that group is aligned in the row-major numbering, else from two
@@ -680,6 +765,7 @@ __global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
 
     const float g = resolve_g(P);
     const float k = 1.0f / (6.0f * g);
+    build_qtab<SF, true>(g);
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
         // (a `saved` buffer that is not the one this call expects poisons the scale the GEMMs will multiply by)
         const float g_gemm = tag_apply(D.tag) ? g : __builtin_nanf("");
@@ -688,6 +774,8 @@ __global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
     }
 
     // row-blocked side: one block scale and 8 codes per row of the lane tile
+    const uint64_t cstep_r = (uint64_t)P.cols >> 3;
+    uint64_t ctr_r = (uint64_t)row0 * cstep_r + ((uint64_t)col0 >> 3);
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         float a = chunk_amax(v[r]);
@@ -697,22 +785,17 @@ __global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
             a = u2f(umax(f2u(a), o));
         }
         float q;
-        const uint32_t sbyte = block_scale<SF, true>(a, g, k, &q);
+        const uint32_t sbyte = block_scale<SF, true, SF == NVFP4_SCALE_E4M3>(a, g, k, &q);
         uint32_t packed = 0;
         if (RND_R == NVFP4_RTN) {
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-                packed |= quant_pair_hw(v[r].get(2 * t), v[r].get(2 * t + 1), q) << (8 * t);
+            packed = quant_pair_hw<0>(packed, v[r].get(0), v[r].get(1), q);
+            packed = quant_pair_hw<1>(packed, v[r].get(2), v[r].get(3), q);
+            packed = quant_pair_hw<2>(packed, v[r].get(4), v[r].get(5), q);
+            packed = quant_pair_hw<3>(packed, v[r].get(6), v[r].get(7), q);
         } else {
-            const uint64_t e0 = (uint64_t)(row0 + r) * (uint64_t)P.cols + (uint64_t)col0;
-            const u32x4 d = sr_draw(D.seed_r, e0 >> 3);
-            uint32_t lo = 0, hi = 0;
-#define NVFP4_SR_PAIR(t)                                                                    \
-    lo = sr_elem_hw<0, t>(lo, v[r].get(2 * t) * q, sr_bits_of(d, 2 * t));                   \
-    hi = sr_elem_hw<1, t>(hi, v[r].get(2 * t + 1) * q, sr_bits_of(d, 2 * t + 1));
-            NVFP4_SR_PAIR(0) NVFP4_SR_PAIR(1) NVFP4_SR_PAIR(2) NVFP4_SR_PAIR(3)
-#undef NVFP4_SR_PAIR
-            packed = lo | hi;
+            // (cols is a multiple of the block, col0 of 8: the lane's 8 columns are one draw, cols / 8 draws per row)
+            packed = sr_chunk_hw(v[r], q, sr_draw(D.seed_r, ctr_r));
+            ctr_r += cstep_r;
         }
         // tile row R = 16 lv + r holds 32 dwords; dword w is stored at w ^ (4 lv): the 16-byte
         // chunk c of the row sits at chunk c ^ lv, which spreads the 8 rows a wave writes at a
