@@ -32,6 +32,16 @@ inline size_t op_scales(int64_t rows, int64_t K, int64_t block) { return align_u
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t elem_size(int dt) { return dt == NVFP4_BF16 ? 2 : 4; }
 inline bool valid_dtype(int dt) { return dt == NVFP4_F32 || dt == NVFP4_BF16; }
+// An enumeration argument of the C ABI as the integer the caller passed (C callers and foreign-function interfaces
+// pass plain ints, possibly outside the enumeration: the bytes are read, never an out-of-range enumeration value).
+template <class E>
+inline int raw(const E &e)
+{
+    static_assert(sizeof(E) == sizeof(int), "C enumerations of this ABI are int-sized");
+    int v;
+    memcpy(&v, &e, sizeof(v));
+    return v;
+}
 
 nvfp4_status check_format(const nvfp4_format *f)
 {
@@ -265,10 +275,10 @@ size_t quantize_scratch_need(int64_t rows, int64_t cols, int64_t ld)
     return WS_HEADER + 4 * (size_t)tensor_amax_partials(rows, cols, ld);
 }
 
-nvfp4_status quantize_impl(const void *x, nvfp4_dtype dt, int64_t rows, int64_t cols, int64_t ld, int axis,
-                           nvfp4_rounding rounding, uint64_t seed, const nvfp4_format *f, uint8_t *codes,
+nvfp4_status quantize_impl(const void *x, int dt, int64_t rows, int64_t cols, int64_t ld, int axis,
+                           int rounding, uint64_t seed, const nvfp4_format *f, uint8_t *codes,
                            uint8_t *scales, float *tensor_scale, uint32_t flags, void *workspace,
-                           size_t workspace_bytes, size_t workspace_required, void *stream);
+                           size_t workspace_bytes, size_t workspace_required, void *stream, bool validate_only = false);
 
 }  // namespace
 
@@ -283,7 +293,10 @@ uint32_t nvfp4_cross_check_switches(int set, uint32_t value)
 
 const char *nvfp4_status_string(nvfp4_status s)
 {
-    switch (s) {
+    // (a C caller may hand over any integer: read the argument's bytes, not an enumeration value)
+    int code;
+    memcpy(&code, &s, sizeof(code));
+    switch (code) {
     case NVFP4_OK: return "ok";
     case NVFP4_EINVAL: return "invalid argument";
     case NVFP4_ESHAPE: return "invalid shape";
@@ -348,10 +361,11 @@ size_t nvfp4_linear_bwd_workspace_bytes(int64_t M, int64_t N, int64_t K, const n
            op_codes(K, M) + op_scales(K, M, B);   // X^T blocked along M
 }
 
-nvfp4_status nvfp4_tensor_scale(const void *x, nvfp4_dtype dt, int64_t rows, int64_t cols,
+nvfp4_status nvfp4_tensor_scale(const void *x, nvfp4_dtype dt_, int64_t rows, int64_t cols,
                                 int64_t ld, float *tensor_scale, void *workspace,
                                 size_t workspace_bytes, void *stream)
 {
+    const int dt = raw(dt_);
     nvfp4_status s = check_tensor(x, dt, rows, cols, ld);
     if (s != NVFP4_OK) return s;
     if (!tensor_scale) return NVFP4_EINVAL;
@@ -370,7 +384,7 @@ nvfp4_status nvfp4_quantize(const void *x, nvfp4_dtype dt, int64_t rows, int64_t
                             float *tensor_scale, uint32_t flags, void *workspace,
                             size_t workspace_bytes, void *stream)
 {
-    return quantize_impl(x, dt, rows, cols, ld, axis, rounding, seed, f, codes, scales, tensor_scale, flags, workspace,
+    return quantize_impl(x, raw(dt), rows, cols, ld, axis, raw(rounding), seed, f, codes, scales, tensor_scale, flags, workspace,
                          workspace_bytes, nvfp4_quantize_workspace_bytes(rows, cols), stream);
 }
 
@@ -381,10 +395,14 @@ nvfp4_status nvfp4_quantize_static(const void *x, nvfp4_dtype dt, int64_t rows, 
 {
     // (a shape whose partial maxima do not fit the array is refused here, before the device is touched)
     if (rows > 0 && cols > 0 && ld >= cols && quantize_scratch_need(rows, cols, ld) > STATIC_SCRATCH_BYTES) return NVFP4_EWORKSPACE;
-    void *ws = nullptr;
-    const nvfp4_status s = static_scratch(&ws);
+    // (arguments are checked before the device is asked for the array's address)
+    void *ws = reinterpret_cast<void *>(WS_ALIGN);
+    nvfp4_status s = quantize_impl(x, raw(dt), rows, cols, ld, axis, raw(rounding), seed, f, codes, scales, tensor_scale, flags, ws,
+                                   STATIC_SCRATCH_BYTES, quantize_scratch_need(rows, cols, ld), stream, true);
     if (s != NVFP4_OK) return s;
-    return quantize_impl(x, dt, rows, cols, ld, axis, rounding, seed, f, codes, scales, tensor_scale, flags, ws,
+    s = static_scratch(&ws);
+    if (s != NVFP4_OK) return s;
+    return quantize_impl(x, raw(dt), rows, cols, ld, axis, raw(rounding), seed, f, codes, scales, tensor_scale, flags, ws,
                          STATIC_SCRATCH_BYTES, quantize_scratch_need(rows, cols, ld), stream);
 }
 
@@ -392,10 +410,10 @@ nvfp4_status nvfp4_quantize_static(const void *x, nvfp4_dtype dt, int64_t rows, 
 
 namespace {
 
-nvfp4_status quantize_impl(const void *x, nvfp4_dtype dt, int64_t rows, int64_t cols, int64_t ld, int axis,
-                           nvfp4_rounding rounding, uint64_t seed, const nvfp4_format *f, uint8_t *codes,
+nvfp4_status quantize_impl(const void *x, int dt, int64_t rows, int64_t cols, int64_t ld, int axis,
+                           int rounding, uint64_t seed, const nvfp4_format *f, uint8_t *codes,
                            uint8_t *scales, float *tensor_scale, uint32_t flags, void *workspace,
-                           size_t workspace_bytes, size_t workspace_required, void *stream)
+                           size_t workspace_bytes, size_t workspace_required, void *stream, bool validate_only)
 {
     nvfp4_status s = check_format(f);
     if (s != NVFP4_OK) return s;
@@ -415,6 +433,7 @@ nvfp4_status quantize_impl(const void *x, nvfp4_dtype dt, int64_t rows, int64_t 
         if (!workspace || workspace_bytes < workspace_required) return NVFP4_EWORKSPACE;
         if (!aligned16(workspace)) return NVFP4_EALIGN;
     }
+    if (validate_only) return NVFP4_OK;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
 
     QuantPlan q{x, dt, rows, cols, ld, axis, rounding, seed, codes, scales, tensor_scale, tensor_scale, G_NONE};
@@ -445,13 +464,16 @@ nvfp4_status quantize_impl(const void *x, nvfp4_dtype dt, int64_t rows, int64_t 
 
 extern "C" {
 
-nvfp4_status nvfp4_quantize_dual(const void *x, nvfp4_dtype dt, int64_t rows, int64_t cols, int64_t ld,
-                                 nvfp4_rounding rounding_rows, uint64_t seed_rows,
-                                 nvfp4_rounding rounding_cols, uint64_t seed_cols,
+nvfp4_status nvfp4_quantize_dual(const void *x, nvfp4_dtype dt_, int64_t rows, int64_t cols, int64_t ld,
+                                 nvfp4_rounding rounding_rows_, uint64_t seed_rows,
+                                 nvfp4_rounding rounding_cols_, uint64_t seed_cols,
                                  const nvfp4_format *f, uint8_t *codes_rows, uint8_t *scales_rows,
                                  uint8_t *codes_cols, uint8_t *scales_cols, float *tensor_scale,
                                  uint32_t flags, void *workspace, size_t workspace_bytes, void *stream)
 {
+    const int dt = raw(dt_);
+    const int rounding_rows = raw(rounding_rows_);
+    const int rounding_cols = raw(rounding_cols_);
     nvfp4_status s = check_format(f);
     if (s != NVFP4_OK) return s;
     s = check_tensor(x, dt, rows, cols, ld);
@@ -522,12 +544,17 @@ nvfp4_status nvfp4_quantize_dual(const void *x, nvfp4_dtype dt, int64_t rows, in
                : NVFP4_EHIP;
 }
 
+static nvfp4_status gemm_impl(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
+                              const uint8_t *A_codes, const uint8_t *A_scales, const uint8_t *B_codes,
+                              const uint8_t *B_scales, const float *tensor_scales, void *out,
+                              int out_dt, int64_t ldc, int a_slab, int b_slab, void *stream);
+
 nvfp4_status nvfp4_gemm(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
                         const uint8_t *A_codes, const uint8_t *A_scales, const uint8_t *B_codes,
                         const uint8_t *B_scales, const float *tensor_scales, void *out,
                         nvfp4_dtype out_dt, int64_t ldc, void *stream)
 {
-    return nvfp4_gemm_slab(M, N, K, f, A_codes, A_scales, B_codes, B_scales, tensor_scales, out, out_dt, ldc, 0, 0, stream);
+    return gemm_impl(M, N, K, f, A_codes, A_scales, B_codes, B_scales, tensor_scales, out, raw(out_dt), ldc, 0, 0, stream);
 }
 
 int nvfp4_gemm_takes_slabs(int64_t M, int64_t N, int64_t K, const nvfp4_format *f)
@@ -545,10 +572,10 @@ size_t nvfp4_slab_scales_bytes(int64_t rows, int64_t K)
     return rows <= 0 || K <= 0 ? 0 : (size_t)slab_rows_padded(rows) * (size_t)K / 16;
 }
 
-nvfp4_status nvfp4_gemm_slab(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
-                             const uint8_t *A_codes, const uint8_t *A_scales, const uint8_t *B_codes,
-                             const uint8_t *B_scales, const float *tensor_scales, void *out,
-                             nvfp4_dtype out_dt, int64_t ldc, int a_slab, int b_slab, void *stream)
+static nvfp4_status gemm_impl(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
+                              const uint8_t *A_codes, const uint8_t *A_scales, const uint8_t *B_codes,
+                              const uint8_t *B_scales, const float *tensor_scales, void *out,
+                              int out_dt, int64_t ldc, int a_slab, int b_slab, void *stream)
 {
     nvfp4_status s = check_format(f);
     if (s != NVFP4_OK) return s;
@@ -568,13 +595,21 @@ nvfp4_status nvfp4_gemm_slab(int64_t M, int64_t N, int64_t K, const nvfp4_format
                : NVFP4_EHIP;
 }
 
+nvfp4_status nvfp4_gemm_slab(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
+                             const uint8_t *A_codes, const uint8_t *A_scales, const uint8_t *B_codes,
+                             const uint8_t *B_scales, const float *tensor_scales, void *out,
+                             nvfp4_dtype out_dt, int64_t ldc, int a_slab, int b_slab, void *stream)
+{
+    return gemm_impl(M, N, K, f, A_codes, A_scales, B_codes, B_scales, tensor_scales, out, raw(out_dt), ldc, a_slab, b_slab, stream);
+}
+
 }  // extern "C"
 
 namespace {
 
 // nvfp4_linear_fwd, with W either as a tensor (w_ops == nullptr) or as the operands nvfp4_quantize_weight wrote.
 nvfp4_status linear_fwd_impl(const void *X, const void *W, const void *w_ops, void *Y, int64_t M, int64_t N,
-                             int64_t K, nvfp4_dtype in_dt, nvfp4_dtype out_dt,
+                             int64_t K, int in_dt, int out_dt,
                              const nvfp4_format *f, void *workspace, size_t workspace_bytes,
                              void *stream, float *xw_scales_out, void *saved, uint64_t bwd_seed)
 {
@@ -662,8 +697,8 @@ nvfp4_status linear_fwd_impl(const void *X, const void *W, const void *w_ops, vo
 }
 
 nvfp4_status linear_bwd_impl(const void *dY, const void *X, const void *W, const void *w_ops, void *dX, void *dW,
-                             int64_t M, int64_t N, int64_t K, nvfp4_dtype in_dt,
-                             nvfp4_dtype out_dt, const nvfp4_format *f, uint64_t seed,
+                             int64_t M, int64_t N, int64_t K, int in_dt,
+                             int out_dt, const nvfp4_format *f, uint64_t seed,
                              void *workspace, size_t workspace_bytes, void *stream, const float *xw_scales,
                              const void *saved)
 {
@@ -806,7 +841,7 @@ nvfp4_status nvfp4_linear_fwd(const void *X, const void *W, void *Y, int64_t M, 
                               void *stream, float *xw_scales_out, void *saved, uint64_t bwd_seed)
 {
     if (!W) return NVFP4_EINVAL;
-    return linear_fwd_impl(X, W, nullptr, Y, M, N, K, in_dt, out_dt, f, workspace, workspace_bytes, stream, xw_scales_out, saved, bwd_seed);
+    return linear_fwd_impl(X, W, nullptr, Y, M, N, K, raw(in_dt), raw(out_dt), f, workspace, workspace_bytes, stream, xw_scales_out, saved, bwd_seed);
 }
 
 nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void *dX, void *dW,
@@ -815,7 +850,7 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
                               void *workspace, size_t workspace_bytes, void *stream, const float *xw_scales,
                               const void *saved)
 {
-    return linear_bwd_impl(dY, X, W, nullptr, dX, dW, M, N, K, in_dt, out_dt, f, seed, workspace, workspace_bytes, stream, xw_scales, saved);
+    return linear_bwd_impl(dY, X, W, nullptr, dX, dW, M, N, K, raw(in_dt), raw(out_dt), f, seed, workspace, workspace_bytes, stream, xw_scales, saved);
 }
 
 size_t nvfp4_weight_operands_bytes(int64_t N, int64_t K, const nvfp4_format *f)
@@ -824,10 +859,11 @@ size_t nvfp4_weight_operands_bytes(int64_t N, int64_t K, const nvfp4_format *f)
     return WS_HEADER + op_codes(N, K) + op_scales(N, K, f->block) + op_codes(K, N) + op_scales(K, N, f->block);
 }
 
-nvfp4_status nvfp4_quantize_weight(const void *W, nvfp4_dtype dt, int64_t M, int64_t N, int64_t K,
+nvfp4_status nvfp4_quantize_weight(const void *W, nvfp4_dtype dt_, int64_t M, int64_t N, int64_t K,
                                    const nvfp4_format *f, void *w_operands, void *workspace,
                                    size_t workspace_bytes, void *stream)
 {
+    const int dt = raw(dt_);
     nvfp4_status s = check_format(f);
     if (s != NVFP4_OK) return s;
     if (!W || !w_operands || !valid_dtype(dt)) return NVFP4_EINVAL;
@@ -863,7 +899,7 @@ nvfp4_status nvfp4_linear_fwd_wq(const void *X, const void *w_operands, void *Y,
                                  void *stream, float *xw_scales_out, void *saved, uint64_t bwd_seed)
 {
     if (!w_operands) return NVFP4_EINVAL;
-    return linear_fwd_impl(X, nullptr, w_operands, Y, M, N, K, in_dt, out_dt, f, workspace, workspace_bytes, stream, xw_scales_out, saved, bwd_seed);
+    return linear_fwd_impl(X, nullptr, w_operands, Y, M, N, K, raw(in_dt), raw(out_dt), f, workspace, workspace_bytes, stream, xw_scales_out, saved, bwd_seed);
 }
 
 nvfp4_status nvfp4_linear_bwd_wq(const void *dY, const void *X, const void *w_operands, void *dX, void *dW,
@@ -873,7 +909,7 @@ nvfp4_status nvfp4_linear_bwd_wq(const void *dY, const void *X, const void *w_op
                                  const void *saved)
 {
     if (!w_operands) return NVFP4_EINVAL;
-    return linear_bwd_impl(dY, X, nullptr, w_operands, dX, dW, M, N, K, in_dt, out_dt, f, seed, workspace, workspace_bytes, stream, xw_scales, saved);
+    return linear_bwd_impl(dY, X, nullptr, w_operands, dX, dW, M, N, K, raw(in_dt), raw(out_dt), f, seed, workspace, workspace_bytes, stream, xw_scales, saved);
 }
 
 size_t nvfp4_quant_noise_workspace_bytes(int64_t rows, int64_t cols, int axis)
@@ -882,11 +918,12 @@ size_t nvfp4_quant_noise_workspace_bytes(int64_t rows, int64_t cols, int axis)
     return align_up(16 * (size_t)quant_noise_partials(rows, cols, axis));
 }
 
-nvfp4_status nvfp4_quant_noise(const void *x, nvfp4_dtype dt, int64_t rows, int64_t cols, int64_t ld, int axis,
+nvfp4_status nvfp4_quant_noise(const void *x, nvfp4_dtype dt_, int64_t rows, int64_t cols, int64_t ld, int axis,
                                const nvfp4_format *f, const uint8_t *codes, const uint8_t *scales,
                                const float *tensor_scale, double *sums, void *workspace, size_t workspace_bytes,
                                void *stream)
 {
+    const int dt = raw(dt_);
     nvfp4_status s = check_format(f);
     if (s != NVFP4_OK) return s;
     s = check_tensor(x, dt, rows, cols, ld);
