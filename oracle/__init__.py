@@ -90,6 +90,10 @@ def lib():
         L.orc_gemm_nt.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.POINTER(_Format),
                                   C.c_void_p, C.c_void_p, C.c_float,
                                   C.c_void_p, C.c_void_p, C.c_float, C.c_int, C.c_void_p]
+        L.orc_exp_nonpos.restype = C.c_float
+        L.orc_exp_nonpos.argtypes = [C.c_float]
+        L.orc_swiglu_bwd.restype = None
+        L.orc_swiglu_bwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_void_p, C.c_void_p]
         L.orc_gemm_nt_sample.restype = None
         L.orc_gemm_nt_sample.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.POINTER(_Format),
                                          C.c_void_p, C.c_void_p, C.c_float,
@@ -272,6 +276,22 @@ def gemm_nt_sample(A, B, ii, jj, fmt: Format = NVFP4, take_abs: bool = False) ->
                              _p(np.ascontiguousarray(bsc)), gb, int(take_abs),
                              _p(ii), _p(jj), ii.size, _p(out))
     return out
+
+
+def exp_nonpos(t: float) -> float:
+    """The fixed binary32 evaluation of exp(t), t <= 0, that swiglu_bwd uses."""
+    return float(lib().orc_exp_nonpos(float(t)))
+
+
+def swiglu_bwd(dH, G, U):
+    """Elementwise backward of h = silu(g) * u in the fixed binary32 evaluation stated in nvfp4_oracle.c:
+    -> (dG, dU) in the element type of the inputs (bf16 as numpy uint16 bit patterns, fp32 as float32), the
+    tensors the quantizers of the gate and up layers' backward GEMMs (Eqs. 5-6) then see."""
+    (h, tag), (g, tg), (u, tu) = _as_input(dH), _as_input(G), _as_input(U)
+    assert tag == tg == tu and h.shape == g.shape == u.shape
+    dG, dU = np.empty_like(h), np.empty_like(h)
+    lib().orc_swiglu_bwd(_p(h), _p(g), _p(u), tag, h.size, _p(dG), _p(dU))
+    return dG, dU
 
 
 # ------------------------------------------------- the three GEMMs, Eqs. 4-6

@@ -8,7 +8,9 @@
  *     block scales; block 16 = NVFP4, block 32 + E8M0 = MXFP4),
  *   - the quantization operation Q of Eqs. 1-3 in its two rounding modes
  *     (round-to-nearest and stochastic rounding, Sec. 1 / Sec. 3.2),
- *   - the three GEMMs of Eqs. 4-6 on dequantized operands, accumulated in fp64.
+ *   - the three GEMMs of Eqs. 4-6 on dequantized operands, accumulated in fp64,
+ *   - the elementwise SwiGLU backward that produces the gate/up layers' upstream
+ *     gradients (Sec. 5 model), in a fixed binary32 evaluation.
  *
  * It shares no code with the HIP library.  Only tests, the smoke check and the
  * benchmark's cpu_baseline leg may call it.  Every lookup is a brute-force scan
@@ -28,7 +30,8 @@
  * library cast, Philox known-answer vectors, brute-force nearest value,
  * idempotence on representable tensors, power-of-two covariance, sign
  * symmetry, SR support and unbiasedness, hand-worked blocks, exact integer
- * GEMM.  No function in this file is "parity unpinned".
+ * GEMM; the SwiGLU backward against a library exponential, finite differences
+ * and the closed form in fp64.  No function in this file is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -432,6 +435,74 @@ void orc_gemm_nt_sample(int64_t M, int64_t N, int64_t K, const orc_format *f,
             acc += take_abs ? fabs(p) : p;
         }
         out[t] = acc;
+    }
+}
+
+/* ------------------------------------------------- SwiGLU backward (glue) */
+
+/*
+ * The gate/up layers of the 7B model (Sec. 5 setup: SwiGLU MLP) receive, as the
+ * upstream gradient of Eqs. 5-6, the elementwise backward of h = silu(g) * u:
+ *     dG = dH * u * sigma(g) * (1 + g * (1 - sigma(g))),    dU = dH * g * sigma(g),
+ * sigma(g) = 1 / (1 + exp(-g)).  The paper gives no arithmetic for it.  Because
+ * the results are quantized next (a floating-point value decides an integer
+ * code), the evaluation is FIXED here, in binary32 with one rounding per
+ * written operation, so that any implementation can reproduce it bit for bit:
+ *   e   = exp(-|g|) by orc_exp_nonpos (below);
+ *   sig = g >= 0 ? 1 / (1 + e) : e / (1 + e)            (one add, one division)
+ *   dG  = (dH * u) * (sig * (1 + g * (1 - sig)));   dU = dH * (g * sig)
+ * and the results are rounded to the element type of the inputs (bf16: round
+ * to nearest even), which is the value the quantizer then sees.
+ *
+ * orc_exp_nonpos(t), t <= 0 (clamped at -87 so that every intermediate is a
+ * normal number): k = rint(t * log2(e)); r = t - k ln2 in two fused steps with
+ * ln2 split into a 12-bit head and a tail; exp(r) by the degree-6 Taylor
+ * polynomial in Horner form with fused multiply-adds (|r| <= 0.347: truncation
+ * below 1.3e-7 relative); the factor 2^k is applied exactly.
+ */
+float orc_exp_nonpos(float t)
+{
+    if (t < -87.0f) t = -87.0f;
+    const float k = rintf(t * 1.44269504f);
+    float r = fmaf(-k, 0.693145751953125f, t);
+    r = fmaf(-k, 1.42860677e-6f, r);
+    float p = 1.0f / 720.0f;
+    p = fmaf(p, r, 1.0f / 120.0f);
+    p = fmaf(p, r, 1.0f / 24.0f);
+    p = fmaf(p, r, 1.0f / 6.0f);
+    p = fmaf(p, r, 0.5f);
+    p = fmaf(p, r, 1.0f);
+    p = fmaf(p, r, 1.0f);
+    return ldexpf(p, (int)k); /* exact: p in [0.70, 1.42], k >= -126, result normal */
+}
+
+static void store_elem(void *x, int dtype, int64_t idx, float v)
+{
+    if (dtype == ORC_F32) {
+        ((float *)x)[idx] = v;
+        return;
+    }
+    uint32_t bits;
+    memcpy(&bits, &v, 4);
+    bits += 0x7FFFu + ((bits >> 16) & 1u); /* round to nearest even on the 16 dropped bits (finite inputs) */
+    ((uint16_t *)x)[idx] = (uint16_t)(bits >> 16);
+}
+
+void orc_swiglu_bwd(const void *dH, const void *G, const void *U, int dtype, int64_t n, void *dG, void *dU)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        const float h = load_elem(dH, dtype, i), g = load_elem(G, dtype, i), u = load_elem(U, dtype, i);
+        const float e = orc_exp_nonpos(-fabsf(g));
+        const float den = 1.0f + e;
+        const float sig = g >= 0.0f ? 1.0f / den : e / den;
+        const float a = 1.0f - sig;
+        const float b = g * a;
+        const float c = 1.0f + b;
+        const float d = sig * c;
+        const float hu = h * u;
+        const float q = g * sig;
+        store_elem(dG, dtype, i, hu * d);
+        store_elem(dU, dtype, i, h * q);
     }
 }
 
