@@ -320,6 +320,54 @@ nvfp4_status nvfp4_linear_bwd_wq(const void *dY, const void *X, const void *w_op
                                  const float *xw_scales, const void *saved);
 
 /*
+ * A tensor quantized along both axes, as nvfp4_quantize_dual writes it: the operand pair a backward call needs of
+ * its upstream gradient (Eq. 5 uses it blocked along N, Eq. 6 along M).  All pointers are device memory owned by
+ * the caller; layout = NVFP4_SLAB_ROWS / NVFP4_SLAB_COLS bits for a side stored in the slab layout; g = device
+ * fp32[1], the per-tensor scale shared by both sides (written as 1 for a format without tensor scale).
+ */
+typedef struct {
+    uint8_t *codes_rows, *scales_rows; /* [rows, cols/2], [rows, cols/block] */
+    uint8_t *codes_cols, *scales_cols; /* [cols, rows/2], [cols, rows/block] */
+    float *g;
+    uint32_t layout;
+} nvfp4_dual_operands;
+
+/*
+ * SwiGLU backward fused with the quantizers of its results.  In the SwiGLU MLP of the Sec. 5 model the gate and
+ * up layers' upstream gradients are dG = dH u sigma(g) (1 + g (1 - sigma(g))) and dU = dH g sigma(g), g and u the
+ * two layers' forward outputs and dH the down layer's input gradient; Eqs. 5-6 then need Q_SR(dG), Q_SR(dU)
+ * blocked along both axes.  This call produces those four operands from dH, G, U [M, F] (dense row-major of dt)
+ * without dG or dU ever being stored: one pass leaves their maxima, one dual-orientation pass per result
+ * re-evaluates it while loading.  The paper gives no arithmetic for the elementwise step; it is fixed in binary32
+ * (one rounding per operation): e = exp(-|g|) by k = rint(t log2 e), r = t - k ln2 (two fused steps, ln2 = 0.693145751953125
+ * + 1.42860677e-6), degree-6 Taylor polynomial in Horner form with fused multiply-adds, exact scaling by 2^k, t clamped
+ * at -87; sigma = (g >= 0 ? 1 : e) / (1 + e); dG = (dH u)(sigma (1 + g (1 - sigma))); dU = dH (g sigma); each result
+ * rounded to dt (bf16: nearest even) before it is quantized -- i.e. the results equal nvfp4_quantize_dual of the
+ * tensors an elementwise kernel with this arithmetic would have stored.
+ *   seed_gate, seed_up   SR streams: rows side seed, columns side seed + 1 (what nvfp4_linear_bwd uses for dY)
+ *   dG, dU               outputs; layout bits choose row-major or slabs per side (slabs: F resp. M a multiple of 128)
+ *   workspace            >= nvfp4_swiglu_bwd_workspace_bytes(M, F), 16-byte aligned (not needed without tensor scale)
+ * Formats: NVFP4 {16, E4M3, 1} and MXFP4 {32, E8M0, 0}; M and F multiples of the block size; not with the
+ * software-convert cross-check switch (NVFP4_EUNSUPPORTED).  Other errors as nvfp4_quantize_dual.
+ * nvfp4_linear_bwd_dyq is nvfp4_linear_bwd for an upstream gradient that is already quantized (such a pair, with
+ * the streams `seed`, `seed + 1`): no pass over dY is made; X, W / xw_scales / saved as in nvfp4_linear_bwd, and
+ * w_operands (may be NULL) as in nvfp4_linear_bwd_wq.  A side given in the slab layout must be one the consuming
+ * GEMM takes (nvfp4_gemm_takes_slabs(M, K, N) for rows, (N, K, M) for columns), else NVFP4_EUNSUPPORTED.
+ */
+size_t nvfp4_swiglu_bwd_workspace_bytes(int64_t M, int64_t F);
+nvfp4_status nvfp4_swiglu_bwd_quantize(const void *dH, const void *G, const void *U, nvfp4_dtype dt, int64_t M,
+                                       int64_t F, uint64_t seed_gate, uint64_t seed_up, const nvfp4_format *f,
+                                       const nvfp4_dual_operands *dG, const nvfp4_dual_operands *dU,
+                                       void *workspace, size_t workspace_bytes, void *stream);
+nvfp4_status nvfp4_linear_bwd_dyq(const nvfp4_dual_operands *dY, const void *X, const void *W,
+                                  const void *w_operands, void *dX, void *dW, int64_t M, int64_t N, int64_t K,
+                                  nvfp4_dtype in_dt, nvfp4_dtype out_dt, const nvfp4_format *f, uint64_t seed,
+                                  void *workspace, size_t workspace_bytes, void *stream,
+                                  const float *xw_scales, const void *saved);
+/* host evaluation of the elementwise step (the kernels' own inline function), n elements, host pointers */
+void nvfp4_host_swiglu_bwd(const float *dH, const float *G, const float *U, int64_t n, float *dG, float *dU);
+
+/*
  * Quantization-noise statistics of a quantized tensor against its source
  * (noise-threshold section, Sec. 4: with eps = Q(x) - x the quantization error
  * of a d-element gradient and sigma_q^2 its mean square, the paper monitors

@@ -27,6 +27,11 @@ SLAB_COLS = 4
 OK, EINVAL, ESHAPE, EALIGN, EUNSUPPORTED, EWORKSPACE, EHIP = range(7)
 
 
+class _DualOperands(C.Structure):
+    _fields_ = [("codes_rows", C.c_void_p), ("scales_rows", C.c_void_p), ("codes_cols", C.c_void_p),
+                ("scales_cols", C.c_void_p), ("g", C.c_void_p), ("layout", C.c_uint32)]
+
+
 class _Format(C.Structure):
     _fields_ = [("block", C.c_int32), ("scale", C.c_int32), ("tensor_scale", C.c_int32)]
 
@@ -101,6 +106,15 @@ def _load() -> C.CDLL:
     L.nvfp4_weight_operands_bytes.argtypes = [i64, i64, fp]
     L.nvfp4_quantize_weight.restype = ci
     L.nvfp4_quantize_weight.argtypes = [vp, ci, i64, i64, i64, fp, vp, vp, sz, vp]
+    dp = C.POINTER(_DualOperands)
+    L.nvfp4_swiglu_bwd_workspace_bytes.restype = sz
+    L.nvfp4_swiglu_bwd_workspace_bytes.argtypes = [i64, i64]
+    L.nvfp4_swiglu_bwd_quantize.restype = ci
+    L.nvfp4_swiglu_bwd_quantize.argtypes = [vp, vp, vp, ci, i64, i64, u64, u64, fp, dp, dp, vp, sz, vp]
+    L.nvfp4_linear_bwd_dyq.restype = ci
+    L.nvfp4_linear_bwd_dyq.argtypes = [dp, vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, fp, u64, vp, sz, vp, vp, vp]
+    L.nvfp4_host_swiglu_bwd.restype = None
+    L.nvfp4_host_swiglu_bwd.argtypes = [vp, vp, vp, i64, vp, vp]
     L.nvfp4_linear_saved_bytes.restype = sz
     L.nvfp4_linear_saved_bytes.argtypes = [i64, i64, i64, fp]
     # host probes
@@ -147,6 +161,7 @@ EXPORTS = (
     "nvfp4_host_round_rtn_n", "nvfp4_host_round_sr_n", "nvfp4_probe_mfma_rate",
     "nvfp4_quant_noise_workspace_bytes", "nvfp4_quant_noise", "nvfp4_quantize_static", "nvfp4_cross_check_switches",
     "nvfp4_weight_operands_bytes", "nvfp4_quantize_weight", "nvfp4_linear_fwd_wq", "nvfp4_linear_bwd_wq",
+    "nvfp4_swiglu_bwd_workspace_bytes", "nvfp4_swiglu_bwd_quantize", "nvfp4_linear_bwd_dyq", "nvfp4_host_swiglu_bwd",
 )
 
 
@@ -374,6 +389,85 @@ def linear_bwd(dY: torch.Tensor, X: torch.Tensor, W: torch.Tensor, seed: int, fm
                                 None if xw_scales is None else xw_scales.data_ptr(),
                                 None if saved is None else saved.data_ptr()),
            "nvfp4_linear_bwd")
+    return dX, dW
+
+
+@dataclass
+class DualOperands:
+    """A tensor quantized along both axes (nvfp4_dual_operands): rows side, columns side, shared g, layout bits."""
+    codes_rows: torch.Tensor
+    scales_rows: torch.Tensor
+    codes_cols: torch.Tensor
+    scales_cols: torch.Tensor
+    g: torch.Tensor
+    layout: int = 0
+
+    def c(self) -> _DualOperands:
+        return _DualOperands(self.codes_rows.data_ptr(), self.scales_rows.data_ptr(), self.codes_cols.data_ptr(),
+                             self.scales_cols.data_ptr(), self.g.data_ptr(), self.layout)
+
+    @property
+    def rows(self):
+        return self.codes_rows, self.scales_rows, self.g
+
+    @property
+    def cols(self):
+        return self.codes_cols, self.scales_cols, self.g
+
+
+def empty_dual_operands(rows: int, cols: int, fmt: Format = NVFP4, slab_rows: bool = False, slab_cols: bool = False,
+                        device="cuda") -> DualOperands:
+    """Output buffers for a [rows, cols] tensor quantized along both axes (row-major, or slabs per side)."""
+    u8 = dict(dtype=torch.uint8, device=device)
+    cr = torch.empty(lib.nvfp4_slab_codes_bytes(rows, cols), **u8) if slab_rows else torch.empty((rows, cols // 2), **u8)
+    cc = torch.empty(lib.nvfp4_slab_codes_bytes(cols, rows), **u8) if slab_cols else torch.empty((cols, rows // 2), **u8)
+    sr = (torch.empty(lib.nvfp4_slab_scales_bytes(rows, cols), **u8) if slab_rows and fmt.block == 16
+          else torch.empty((rows, cols // fmt.block), **u8))
+    sc = (torch.empty(lib.nvfp4_slab_scales_bytes(cols, rows), **u8) if slab_cols and fmt.block == 16
+          else torch.empty((cols, rows // fmt.block), **u8))
+    return DualOperands(cr, sr, cc, sc, torch.empty(1, dtype=torch.float32, device=device),
+                        (SLAB_ROWS if slab_rows else 0) | (SLAB_COLS if slab_cols else 0))
+
+
+def swiglu_bwd_quantize(dH: torch.Tensor, G: torch.Tensor, U: torch.Tensor, seed_gate: int, seed_up: int,
+                        fmt: Format = NVFP4, slab_rows: bool = False, slab_cols: bool = False, out=None):
+    """nvfp4_swiglu_bwd_quantize -> (dG, dU) as DualOperands: Q_SR of the SwiGLU backward's two results, both
+    orientations each, without the results being stored.  `out` = (dG, dU) reuses caller-provided buffers."""
+    _require_gpu(dH, G, U)
+    assert dH.is_contiguous() and G.is_contiguous() and U.is_contiguous() and dH.shape == G.shape == U.shape
+    assert dH.dtype == G.dtype == U.dtype
+    M, F = dH.shape
+    f = fmt.c()
+    dG, dU = out if out is not None else (empty_dual_operands(M, F, fmt, slab_rows, slab_cols, dH.device),
+                                          empty_dual_operands(M, F, fmt, slab_rows, slab_cols, dH.device))
+    ws = torch.empty(lib.nvfp4_swiglu_bwd_workspace_bytes(M, F), dtype=torch.uint8, device=dH.device)
+    cg, cu = dG.c(), dU.c()
+    _check(lib.nvfp4_swiglu_bwd_quantize(dH.data_ptr(), G.data_ptr(), U.data_ptr(), _dtype_tag(dH), M, F, seed_gate, seed_up,
+                                         C.byref(f), C.byref(cg), C.byref(cu), ws.data_ptr(), ws.numel(), _stream()),
+           "nvfp4_swiglu_bwd_quantize")
+    return dG, dU
+
+
+def linear_bwd_dyq(dyq: DualOperands, X, W, seed: int, M: int, N: int, K: int, fmt: Format = NVFP4,
+                   in_dtype: torch.dtype = torch.bfloat16, out_dtype: torch.dtype = torch.float32,
+                   workspace: torch.Tensor | None = None, out=None, xw_scales: torch.Tensor | None = None,
+                   saved: torch.Tensor | None = None, w_operands: torch.Tensor | None = None):
+    """nvfp4_linear_bwd_dyq (Eqs. 5-6 on an upstream gradient that is already quantized) -> (dX [M,K], dW [N,K])."""
+    f = fmt.c()
+    dev = dyq.g.device
+    if workspace is None:
+        workspace = torch.empty(lib.nvfp4_linear_bwd_workspace_bytes(M, N, K, C.byref(f)), dtype=torch.uint8, device=dev)
+    if out is None:
+        dX = torch.empty((M, K), dtype=out_dtype, device=dev)
+        dW = torch.empty((N, K), dtype=out_dtype, device=dev)
+    else:
+        dX, dW = out
+    cd = dyq.c()
+    ptr = lambda t: None if t is None else t.data_ptr()
+    _check(lib.nvfp4_linear_bwd_dyq(C.byref(cd), ptr(X), ptr(W), ptr(w_operands), dX.data_ptr(), dW.data_ptr(), M, N, K,
+                                    BF16 if in_dtype == torch.bfloat16 else F32, _dtype_tag(dX), C.byref(f), seed,
+                                    workspace.data_ptr(), workspace.numel(), _stream(), ptr(xw_scales), ptr(saved)),
+           "nvfp4_linear_bwd_dyq")
     return dX, dW
 
 

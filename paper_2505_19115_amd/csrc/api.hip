@@ -4,6 +4,7 @@
 #include <string.h>
 
 #include <atomic>
+#include <initializer_list>
 #include <mutex>
 
 #include "kernels.h"
@@ -696,7 +697,7 @@ nvfp4_status linear_fwd_impl(const void *X, const void *W, const void *w_ops, vo
     return launch_gemm(g, f->block, f->scale, out_dt, st) == hipSuccess ? NVFP4_OK : NVFP4_EHIP;
 }
 
-nvfp4_status linear_bwd_impl(const void *dY, const void *X, const void *W, const void *w_ops, void *dX, void *dW,
+nvfp4_status linear_bwd_impl(const void *dY, const nvfp4_dual_operands *dyq, const void *X, const void *W, const void *w_ops, void *dX, void *dW,
                              int64_t M, int64_t N, int64_t K, int in_dt,
                              int out_dt, const nvfp4_format *f, uint64_t seed,
                              void *workspace, size_t workspace_bytes, void *stream, const float *xw_scales,
@@ -704,7 +705,13 @@ nvfp4_status linear_bwd_impl(const void *dY, const void *X, const void *W, const
 {
     nvfp4_status s = check_format(f);
     if (s != NVFP4_OK) return s;
-    if (!dY || (dX && !W && !saved && !w_ops) || (dW && !X && !saved)) return NVFP4_EINVAL;
+    if ((!dY && !dyq) || (dX && !W && !saved && !w_ops) || (dW && !X && !saved)) return NVFP4_EINVAL;
+    if (dyq) {
+        // the upstream gradient arrives quantized: each side that a requested GEMM consumes must be there
+        if (!dyq->g || (dX && (!dyq->codes_rows || !dyq->scales_rows)) || (dW && (!dyq->codes_cols || !dyq->scales_cols))) return NVFP4_EINVAL;
+        if (dyq->layout & ~(NVFP4_SLAB_ROWS | NVFP4_SLAB_COLS)) return NVFP4_EINVAL;
+        if (!aligned16(dyq->codes_rows) || !aligned16(dyq->scales_rows) || !aligned16(dyq->codes_cols) || !aligned16(dyq->scales_cols)) return NVFP4_EALIGN;
+    }
     if (saved && (reinterpret_cast<uintptr_t>(saved) & (WS_ALIGN - 1)) != 0) return NVFP4_EALIGN;
     if (w_ops && (reinterpret_cast<uintptr_t>(w_ops) & (WS_ALIGN - 1)) != 0) return NVFP4_EALIGN;
     if (!valid_dtype(in_dt) || !valid_dtype(out_dt)) return NVFP4_EINVAL;
@@ -767,15 +774,25 @@ nvfp4_status linear_bwd_impl(const void *dY, const void *X, const void *W, const
     GSource gdy{reinterpret_cast<const float *>(amax + 0), 0};
     GSource gw{known ? xw_scales + 1 : reinterpret_cast<const float *>(amax + 1), 0};
     GSource gx{known ? xw_scales + 0 : reinterpret_cast<const float *>(amax + 2), 0};
-    if (f->tensor_scale) {
-        if (amax_dense(dY, in_dt, M * N, partials, 0, st, &gdy) != hipSuccess) return NVFP4_EHIP;
-    }
     // with both GEMMs wanted, dY is read once for its two orientations (streams seed, seed+1)
-    const bool dual = dX && dW && quantize_dual_fused(in_dt, M, N, N, f->block, use_hw_convert());
+    const bool dual = !dyq && dX && dW && quantize_dual_fused(in_dt, M, N, N, f->block, use_hw_convert());
     // layouts: dY's two sides as this call's dual pass writes them, W^T and X^T as the forward call wrote them
     const bool t_dx = gemm_takes_slabs(M, K, N, f->block, f->scale), t_dw = gemm_takes_slabs(N, K, M, f->block, f->scale);
     const bool sdy = dual && dual_writes_slabs(f, in_dt, M, N, NVFP4_SR, NVFP4_SR);
-    const int dy_slab_r = sdy && t_dx, dy_slab_c = sdy && t_dw;
+    int dy_slab_r = sdy && t_dx, dy_slab_c = sdy && t_dw;
+    const float *g_dy_r = ts + 0, *g_dy_c = ts + 2;  // written by this call's quantizers of dY
+    if (dyq) {
+        dy_slab_r = (dyq->layout & NVFP4_SLAB_ROWS) != 0;
+        dy_slab_c = (dyq->layout & NVFP4_SLAB_COLS) != 0;
+        if ((dX && dy_slab_r && !t_dx) || (dW && dy_slab_c && !t_dw)) return NVFP4_EUNSUPPORTED;
+        dyc = dyq->codes_rows;
+        dys = dyq->scales_rows;
+        dytc = dyq->codes_cols;
+        dyts = dyq->scales_cols;
+        g_dy_r = g_dy_c = dyq->g;
+    } else if (f->tensor_scale) {
+        if (amax_dense(dY, in_dt, M * N, partials, 0, st, &gdy) != hipSuccess) return NVFP4_EHIP;
+    }
     const int wt_slab = w_ops ? (int)wq_wt_slab : (int)(saved && t_dx && dual_writes_slabs(f, in_dt, N, K, NVFP4_RTN, NVFP4_RTN));
     const int xt_slab = saved && t_dw && dual_writes_slabs(f, in_dt, M, K, NVFP4_RTN, NVFP4_SR);
     TagArgs tag;
@@ -811,10 +828,10 @@ nvfp4_status linear_bwd_impl(const void *dY, const void *X, const void *W, const
         // Eq. 5: dX[M, K] = Q_SR(dY)[M, N] * Q_RtN(W^T)[K, N]^T
         QuantPlan qa{dY, in_dt, M, N, N, 1, NVFP4_SR, seed, dyc, dys, gdy.src, ts + 0, gm, gdy.n};
         QuantPlan qb{W, in_dt, N, K, K, 0, NVFP4_RTN, 0, wtc, wts, gw.src, ts + 1, gm_xw, gw.n};
-        if (!dual && run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
-        if (!dual && launch_saved_tag(tag, ts + 0, nullptr, st) != hipSuccess) return NVFP4_EHIP;
+        if (!dual && !dyq && run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
+        if (!dual && !dyq && launch_saved_tag(tag, ts + 0, nullptr, st) != hipSuccess) return NVFP4_EHIP;
         if (!have_wt && run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
-        GemmArgs g{M, K, N, dyc, dys, wtc, wts, ts + 0, g_w, dX, K, dy_slab_r, wt_slab};
+        GemmArgs g{M, K, N, dyc, dys, wtc, wts, g_dy_r, g_w, dX, K, dy_slab_r, wt_slab};
         if (launch_gemm(g, f->block, f->scale, out_dt, st) != hipSuccess) return NVFP4_EHIP;
     }
     if (dW) {
@@ -822,10 +839,10 @@ nvfp4_status linear_bwd_impl(const void *dY, const void *X, const void *W, const
         // Eq. 6: dW[N, K] = Q_SR(dY^T)[N, M] * Q_SR(X^T)[K, M]^T
         QuantPlan qa{dY, in_dt, M, N, N, 0, NVFP4_SR, seed + 1, dytc, dyts, gdy.src, ts + 2, gm, gdy.n};
         QuantPlan qb{X, in_dt, M, K, K, 0, NVFP4_SR, seed + 2, xtc, xts, gx.src, ts + 3, gm_xw, gx.n};
-        if (!dual && run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
-        if (!dual && launch_saved_tag(tag, ts + 2, nullptr, st) != hipSuccess) return NVFP4_EHIP;
+        if (!dual && !dyq && run_quantize(qa, f, st) != hipSuccess) return NVFP4_EHIP;
+        if (!dual && !dyq && launch_saved_tag(tag, ts + 2, nullptr, st) != hipSuccess) return NVFP4_EHIP;
         if (!have_xt && run_quantize(qb, f, st) != hipSuccess) return NVFP4_EHIP;
-        GemmArgs g{N, K, M, dytc, dyts, xtc, xts, ts + 2, g_x, dW, K, dy_slab_c, xt_slab};
+        GemmArgs g{N, K, M, dytc, dyts, xtc, xts, g_dy_c, g_x, dW, K, dy_slab_c, xt_slab};
         if (launch_gemm(g, f->block, f->scale, out_dt, st) != hipSuccess) return NVFP4_EHIP;
     }
     return NVFP4_OK;
@@ -850,7 +867,81 @@ nvfp4_status nvfp4_linear_bwd(const void *dY, const void *X, const void *W, void
                               void *workspace, size_t workspace_bytes, void *stream, const float *xw_scales,
                               const void *saved)
 {
-    return linear_bwd_impl(dY, X, W, nullptr, dX, dW, M, N, K, raw(in_dt), raw(out_dt), f, seed, workspace, workspace_bytes, stream, xw_scales, saved);
+    return linear_bwd_impl(dY, nullptr, X, W, nullptr, dX, dW, M, N, K, raw(in_dt), raw(out_dt), f, seed, workspace, workspace_bytes, stream, xw_scales, saved);
+}
+
+nvfp4_status nvfp4_linear_bwd_dyq(const nvfp4_dual_operands *dY, const void *X, const void *W,
+                                  const void *w_operands, void *dX, void *dW, int64_t M, int64_t N, int64_t K,
+                                  nvfp4_dtype in_dt, nvfp4_dtype out_dt, const nvfp4_format *f, uint64_t seed,
+                                  void *workspace, size_t workspace_bytes, void *stream,
+                                  const float *xw_scales, const void *saved)
+{
+    if (!dY) return NVFP4_EINVAL;
+    return linear_bwd_impl(nullptr, dY, X, W, w_operands, dX, dW, M, N, K, raw(in_dt), raw(out_dt), f, seed, workspace, workspace_bytes, stream, xw_scales, saved);
+}
+
+size_t nvfp4_swiglu_bwd_workspace_bytes(int64_t M, int64_t F)
+{
+    (void)M;
+    (void)F;
+    return WS_HEADER + 2 * PARTIAL_SLOT;  // partial maxima of dG and of dU
+}
+
+nvfp4_status nvfp4_swiglu_bwd_quantize(const void *dH, const void *G, const void *U, nvfp4_dtype dt_, int64_t M,
+                                       int64_t F, uint64_t seed_gate, uint64_t seed_up, const nvfp4_format *f,
+                                       const nvfp4_dual_operands *dG, const nvfp4_dual_operands *dU,
+                                       void *workspace, size_t workspace_bytes, void *stream)
+{
+    const int dt = raw(dt_);
+    nvfp4_status s = check_format(f);
+    if (s != NVFP4_OK) return s;
+    if (!valid_dtype(dt) || !dH || !G || !U || !dG || !dU) return NVFP4_EINVAL;
+    if (M <= 0 || F <= 0 || M % f->block != 0 || F % f->block != 0) return NVFP4_ESHAPE;
+    const bool fmt_ok = (f->block == 16 && f->scale == NVFP4_SCALE_E4M3 && f->tensor_scale) || (f->block == 32 && f->scale == NVFP4_SCALE_E8M0);
+    if (!fmt_ok || !use_hw_convert() || !quantize_dual_fused(dt, M, F, F, f->block, true)) return NVFP4_EUNSUPPORTED;
+    if (!aligned16(dH) || !aligned16(G) || !aligned16(U)) return NVFP4_EALIGN;
+    for (const nvfp4_dual_operands *o : {dG, dU}) {
+        if (!o->codes_rows || !o->scales_rows || !o->codes_cols || !o->scales_cols || !o->g) return NVFP4_EINVAL;
+        if (o->layout & ~(NVFP4_SLAB_ROWS | NVFP4_SLAB_COLS)) return NVFP4_EINVAL;
+        if (!aligned16(o->codes_rows) || !aligned16(o->scales_rows) || !aligned16(o->codes_cols) || !aligned16(o->scales_cols)) return NVFP4_EALIGN;
+        if (((o->layout & NVFP4_SLAB_ROWS) && F % SLAB_K != 0) || ((o->layout & NVFP4_SLAB_COLS) && M % SLAB_K != 0)) return NVFP4_ESHAPE;
+    }
+    if (f->tensor_scale) {
+        if (!workspace || workspace_bytes < nvfp4_swiglu_bwd_workspace_bytes(M, F)) return NVFP4_EWORKSPACE;
+        if (!aligned16(workspace)) return NVFP4_EALIGN;
+    }
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    uint32_t *partials = f->tensor_scale ? reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(workspace) + WS_HEADER) : nullptr;
+    const int gm = f->tensor_scale ? G_FROM_AMAX : G_NONE;
+    auto plan = [&](const nvfp4_dual_operands *o, uint64_t seed) {
+        DualArgs d;
+        d.c.x = dH;
+        d.c.rows = M;
+        d.c.cols = F;
+        d.c.ld = F;
+        d.c.codes = o->codes_cols;
+        d.c.scales = o->scales_cols;
+        d.c.g_src = o->g;
+        d.c.g_out = o->g;
+        d.c.g_mode = gm;
+        d.c.seed = seed + 1;
+        d.codes_r = o->codes_rows;
+        d.scales_r = o->scales_rows;
+        d.seed_r = seed;
+        d.g_out2 = nullptr;
+        d.slab_r = (o->layout & NVFP4_SLAB_ROWS) != 0;
+        d.slab_c = (o->layout & NVFP4_SLAB_COLS) != 0;
+        d.src_g = G;
+        d.src_u = U;
+        return d;
+    };
+    DualArgs dg = plan(dG, seed_gate), du = plan(dU, seed_up);
+    return launch_swiglu_bwd_dual(dg, du, dt, f->block, f->scale, partials, partials ? partials + AMAX_DENSE_PARTIALS : nullptr, st) == hipSuccess ? NVFP4_OK : NVFP4_EHIP;
+}
+
+void nvfp4_host_swiglu_bwd(const float *dH, const float *G, const float *U, int64_t n, float *dG, float *dU)
+{
+    for (int64_t t = 0; t < n; ++t) swiglu_bwd_elem(dH[t], G[t], U[t], &dG[t], &dU[t]);
 }
 
 size_t nvfp4_weight_operands_bytes(int64_t N, int64_t K, const nvfp4_format *f)
@@ -909,7 +1000,7 @@ nvfp4_status nvfp4_linear_bwd_wq(const void *dY, const void *X, const void *w_op
                                  const void *saved)
 {
     if (!w_operands) return NVFP4_EINVAL;
-    return linear_bwd_impl(dY, X, nullptr, w_operands, dX, dW, M, N, K, raw(in_dt), raw(out_dt), f, seed, workspace, workspace_bytes, stream, xw_scales, saved);
+    return linear_bwd_impl(dY, nullptr, X, nullptr, w_operands, dX, dW, M, N, K, raw(in_dt), raw(out_dt), f, seed, workspace, workspace_bytes, stream, xw_scales, saved);
 }
 
 size_t nvfp4_quant_noise_workspace_bytes(int64_t rows, int64_t cols, int axis)

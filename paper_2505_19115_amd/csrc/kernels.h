@@ -56,6 +56,9 @@ struct DualArgs {
     int slab_r = 0;     // write the row-blocked / column-blocked output in the slab layout (below) instead
     int slab_c = 0;
     TagArgs tag;        // optional: identity of a `saved` buffer to write or to check (fused linear entries)
+    // With a SwiGLU source (launch_swiglu_bwd_dual) the tensor being quantized is never in memory: c.x is dH and
+    // these are G and U, all dense [rows, cols]; the kernel evaluates dG or dU per element as it loads.
+    const void *src_g = nullptr, *src_u = nullptr;
 };
 
 // Slab layout of a packed operand (used inside the workspaces and the saved buffer of the fused linear entries,
@@ -117,6 +120,13 @@ hipError_t launch_quantize(const QuantArgs &P, int dt, int axis, int rounding, i
 bool quantize_dual_fused(int dt, int64_t rows, int64_t cols, int64_t ld, int block, bool hw_convert);
 hipError_t launch_quantize_dual(const DualArgs &D, int dt, int rnd_rows, int rnd_cols, int block, int sf,
                                 bool hw_convert, hipStream_t st);
+// SwiGLU backward fused with the quantizers of its two results: one pass over dH, G, U leaves the partial maxima of
+// dG and dU (AMAX_DENSE_PARTIALS slots each, the counts come back in n_g / n_u; skipped without tensor scale), then one
+// dual-orientation pass per result re-evaluates it while loading.  g / u describe the outputs as for
+// launch_quantize_dual (c.x = dH, src_g, src_u set; stochastic rounding on both sides).  Formats: the ones the
+// one-pass dual kernel serves with slabs (block 16 + E4M3, block 32 + E8M0); the caller checks quantize_dual_fused().
+hipError_t launch_swiglu_bwd_dual(DualArgs &g, DualArgs &u, int dt, int block, int sf, uint32_t *partials_g,
+                                  uint32_t *partials_u, hipStream_t st);
 hipError_t launch_gemm(const GemmArgs &P, int block, int sf, int out_dt, hipStream_t st);
 hipError_t launch_gemm_mxfp4(const GemmArgs &P, int out_dt, hipStream_t st);  // block 32, E8M0
 bool mxfp4_gemm_takes_slabs(int64_t K);  // MXFP4: the codes of an operand may come as slabs (its scales stay row-major)

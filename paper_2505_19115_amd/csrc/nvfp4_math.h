@@ -107,6 +107,52 @@ NVFP4_HD uint32_t round_sr(float m, uint32_t u16)
 NVFP4_HD uint32_t sr_seed_first(uint32_t u16) { return ((~u16 & 0xFFFFu) << 16) | 0x8000u; }
 NVFP4_HD uint32_t sr_seed_second(uint32_t u16) { return ((~u16 & 0xFFFFu) << 15) | 0x4000u; }
 
+// Elementwise backward of h = silu(g) * u (the SwiGLU of the Sec. 5 model), whose results are the upstream
+// gradients of the gate and up layers in Eqs. 5-6.  The values are quantized next, so the evaluation is fixed in
+// binary32, one rounding per written operation (fused where written as fmaf), and is the same on every machine:
+//   exp(t), t <= 0 (clamped at -87): k = rint(t log2 e), r = t - k ln2 in two fused steps (12-bit head, tail),
+//   degree-6 Taylor polynomial of exp(r) in Horner form, times 2^k by an exponent-field add (exact: the result is normal);
+//   sigma = g >= 0 ? 1 / (1 + e) : e / (1 + e) with e = exp(-|g|);
+//   dG = (dH u) (sigma (1 + g (1 - sigma))),  dU = dH (g sigma).
+NVFP4_HD float exp_nonpos(float t)
+{
+    t = t < -87.0f ? -87.0f : t;
+    const float k = __builtin_rintf(t * 1.44269504f);
+    float r = __builtin_fmaf(-k, 0.693145751953125f, t);
+    r = __builtin_fmaf(-k, 1.42860677e-6f, r);
+    float p = 1.0f / 720.0f;
+    p = __builtin_fmaf(p, r, 1.0f / 120.0f);
+    p = __builtin_fmaf(p, r, 1.0f / 24.0f);
+    p = __builtin_fmaf(p, r, 1.0f / 6.0f);
+    p = __builtin_fmaf(p, r, 0.5f);
+    p = __builtin_fmaf(p, r, 1.0f);
+    p = __builtin_fmaf(p, r, 1.0f);
+    return u2f(f2u(p) + ((uint32_t)(int)k << 23));
+}
+
+NVFP4_HD void swiglu_bwd_elem(float h, float g, float u, float *dg, float *du)
+{
+    const float e = exp_nonpos(-__builtin_fabsf(g));
+    const float den = 1.0f + e;
+    const float sig = (g >= 0.0f ? 1.0f : e) / den;
+    const float a = 1.0f - sig;
+    const float b = g * a;
+    const float c = 1.0f + b;
+    const float d = sig * c;
+    const float hu = h * u;
+    const float q = g * sig;
+    *dg = hu * d;
+    *du = h * q;
+}
+
+// binary32 -> bf16 bit pattern, round to nearest even (finite inputs)
+NVFP4_HD uint32_t bf16_rne_bits(float f)
+{
+    uint32_t u = f2u(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
 // Philox4x32-10 (Salmon et al., SC'11).
 struct u32x4 {
     uint32_t x, y, z, w;

@@ -79,6 +79,20 @@ struct Chunk<NVFP4_BF16> {
         raw = make_uint4(w[0], w[1], w[2], w[3]);
     }
     __device__ __forceinline__ void zero() { raw = make_uint4(0, 0, 0, 0); }
+    // 8 binary32 values rounded to bf16 (nearest even) and packed
+    __device__ __forceinline__ void set(const float (&f)[8])
+    {
+        typedef float f2_t __attribute__((ext_vector_type(2)));
+        typedef __bf16 b2_t __attribute__((ext_vector_type(2)));
+        uint32_t w[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const f2_t p = {f[2 * t], f[2 * t + 1]};
+            const b2_t b = __builtin_convertvector(p, b2_t);
+            w[t] = __builtin_bit_cast(uint32_t, b);
+        }
+        raw = make_uint4(w[0], w[1], w[2], w[3]);
+    }
     __device__ __forceinline__ void launder() { asm volatile("" : "+v"(raw.x), "+v"(raw.y), "+v"(raw.z), "+v"(raw.w)); }
     __device__ __forceinline__ float get(int t) const
     {
@@ -110,6 +124,11 @@ struct Chunk<NVFP4_F32> {
     {
         lo = make_float4(0, 0, 0, 0);
         hi = lo;
+    }
+    __device__ __forceinline__ void set(const float (&f)[8])
+    {
+        lo = make_float4(f[0], f[1], f[2], f[3]);
+        hi = make_float4(f[4], f[5], f[6], f[7]);
     }
     __device__ __forceinline__ void launder() {}
     __device__ __forceinline__ float get(int t) const
@@ -719,6 +738,69 @@ __device__ __forceinline__ void cols_tile(const QuantArgs &P, Chunk<DT> (&v)[16]
     }
 }
 
+// ------------------------------------------------------------------ SwiGLU backward as a tile source
+
+// Where the dual quantizer's tile comes from: a tensor in memory, or dG / dU of the SwiGLU backward evaluated from
+// dH, G, U while loading (nvfp4_math.h: swiglu_bwd_elem), rounded to the element type like a stored tensor would be.
+enum { SRC_TENSOR = 0, SRC_SWIGLU_DG = 1, SRC_SWIGLU_DU = 2 };
+
+// 8 consecutive elements of dG (WHICH = SRC_SWIGLU_DG), of dU (SRC_SWIGLU_DU), or both (0: og and ou)
+template <int DT, int WHICH>
+__device__ __forceinline__ void swiglu_chunk(const void *dH, const void *G, const void *U, int64_t off, Chunk<DT> *og, Chunk<DT> *ou)
+{
+    Chunk<DT> h, g, u;
+    // (cacheable loads: the three tensors are read by the maximum pass and by both quantizer passes)
+    h.template load<false>(dH, off);
+    g.template load<false>(G, off);
+    u.template load<false>(U, off);
+    float rg[8], ru[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) swiglu_bwd_elem(h.get(t), g.get(t), u.get(t), &rg[t], &ru[t]);
+    if (WHICH != SRC_SWIGLU_DU) og->set(rg);
+    if (WHICH != SRC_SWIGLU_DG) ou->set(ru);
+}
+
+// max|dG| and max|dU| (of the values as rounded to the element type) over n = 8 * nchunk elements: one partial
+// maximum of each per workgroup, as amax_dense_kernel leaves them for a tensor in memory.
+template <int DT>
+__global__ __launch_bounds__(1024) void swiglu_amax_kernel(const void *dH, const void *G, const void *U, int64_t n,
+                                                           uint32_t *part_g, uint32_t *part_u)
+{
+    const int64_t nchunk = n >> 3;
+    const int64_t stride = (int64_t)gridDim.x * (1024 * 2);
+    float ag = 0.0f, au = 0.0f;
+    for (int64_t base = (int64_t)blockIdx.x * (1024 * 2) + threadIdx.x; base < nchunk; base += stride) {
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int64_t c = base + k * 1024;
+            if (c < nchunk) {
+                Chunk<DT> cg, cu;
+                swiglu_chunk<DT, 0>(dH, G, U, c * 8, &cg, &cu);
+                ag = fmaxf(ag, chunk_amax(cg));
+                au = fmaxf(au, chunk_amax(cu));
+            }
+        }
+    }
+    ag = group_max<16>(ag);
+    au = group_max<16>(au);
+    __shared__ uint32_t pg[64], pu[64];
+    if ((threadIdx.x & 15) == 0) {
+        pg[threadIdx.x >> 4] = f2u(ag);
+        pu[threadIdx.x >> 4] = f2u(au);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t mg = 0, mu = 0;
+#pragma unroll
+        for (int t = 0; t < 64; ++t) {
+            mg = umax(mg, pg[t]);
+            mu = umax(mu, pu[t]);
+        }
+        part_g[blockIdx.x] = mg;
+        part_u[blockIdx.x] = mu;
+    }
+}
+
 // ------------------------------------------------------------------ both orientations in one pass
 
 // Eqs. 5-6 use the output gradient twice, blocked along N for dX and along M for dW; Eqs. 4-5
@@ -734,7 +816,7 @@ __device__ __forceinline__ void cols_tile(const QuantArgs &P, Chunk<DT> (&v)[16]
 // leave in full lines although the lanes hold the data column-wise.
 // Host guarantees: rows % B == 0, cols % B == 0 (so a lane's 16 x 8 tile is entirely inside or
 // outside the tensor), 16-byte aligned rows of x.
-template <int DT, int B, int SF, int RND_R, int RND_C>
+template <int DT, int B, int SF, int RND_R, int RND_C, int SRC = SRC_TENSOR>
 __global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
 {
     using G = ColGeom<DT, 8>;
@@ -757,10 +839,12 @@ __global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
     Chunk<DT> v[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-        if (inside)
+        if (!inside)
+            v[r].zero();
+        else if (SRC == SRC_TENSOR)
             v[r].template load<true>(P.x, (row0 + r) * P.ld + col0);
         else
-            v[r].zero();
+            swiglu_chunk<DT, SRC>(P.x, D.src_g, D.src_u, (row0 + r) * P.ld + col0, &v[r], &v[r]);
     }
 
     const float g = resolve_g(P);
@@ -1032,6 +1116,42 @@ static void launch_dual_fmt(const DualArgs &D, int rnd_r, int rnd_c, int block, 
     else if (block == 16) launch_dual_rnd<DT, 16, NVFP4_SCALE_E8M0>(D, rnd_r, rnd_c, st);
     else if (sf == NVFP4_SCALE_E4M3) launch_dual_rnd<DT, 32, NVFP4_SCALE_E4M3>(D, rnd_r, rnd_c, st);
     else launch_dual_rnd<DT, 32, NVFP4_SCALE_E8M0>(D, rnd_r, rnd_c, st);
+}
+
+template <int DT, int B, int SF>
+static void launch_swiglu_dual_fmt(const DualArgs &g, const DualArgs &u, hipStream_t st)
+{
+    using G = ColGeom<DT>;
+    dim3 grid((unsigned)((g.c.cols + G::WG_COLS - 1) / G::WG_COLS), (unsigned)((g.c.rows + G::WG_ROWS - 1) / G::WG_ROWS));
+    hipLaunchKernelGGL((quantize_dual_kernel<DT, B, SF, NVFP4_SR, NVFP4_SR, SRC_SWIGLU_DG>), grid, dim3(256), 0, st, g);
+    hipLaunchKernelGGL((quantize_dual_kernel<DT, B, SF, NVFP4_SR, NVFP4_SR, SRC_SWIGLU_DU>), grid, dim3(256), 0, st, u);
+}
+
+hipError_t launch_swiglu_bwd_dual(DualArgs &g, DualArgs &u, int dt, int block, int sf, uint32_t *partials_g,
+                                  uint32_t *partials_u, hipStream_t st)
+{
+    const int64_t n = g.c.rows * g.c.cols;
+    if (g.c.g_mode == G_FROM_AMAX) {
+        int64_t gx = ((n >> 3) + 2047) / 2048;
+        gx = gx < 1 ? 1 : (gx > AMAX_DENSE_PARTIALS ? AMAX_DENSE_PARTIALS : gx);
+        if (dt == NVFP4_BF16)
+            hipLaunchKernelGGL(swiglu_amax_kernel<NVFP4_BF16>, dim3((unsigned)gx), dim3(1024), 0, st, g.c.x, g.src_g, g.src_u, n, partials_g, partials_u);
+        else
+            hipLaunchKernelGGL(swiglu_amax_kernel<NVFP4_F32>, dim3((unsigned)gx), dim3(1024), 0, st, g.c.x, g.src_g, g.src_u, n, partials_g, partials_u);
+        g.c.g_src = reinterpret_cast<const float *>(partials_g);
+        u.c.g_src = reinterpret_cast<const float *>(partials_u);
+        g.c.n_partials = u.c.n_partials = (int)gx;
+    }
+    const bool nv = block == 16 && sf == NVFP4_SCALE_E4M3, mxf = block == 32 && sf == NVFP4_SCALE_E8M0;
+    if (!nv && !mxf) return hipErrorInvalidValue;
+    if (dt == NVFP4_BF16) {
+        if (nv) launch_swiglu_dual_fmt<NVFP4_BF16, 16, NVFP4_SCALE_E4M3>(g, u, st);
+        else launch_swiglu_dual_fmt<NVFP4_BF16, 32, NVFP4_SCALE_E8M0>(g, u, st);
+    } else {
+        if (nv) launch_swiglu_dual_fmt<NVFP4_F32, 16, NVFP4_SCALE_E4M3>(g, u, st);
+        else launch_swiglu_dual_fmt<NVFP4_F32, 32, NVFP4_SCALE_E8M0>(g, u, st);
+    }
+    return launch_status();
 }
 
 bool quantize_dual_fused(int dt, int64_t rows, int64_t cols, int64_t ld, int block, bool hw_convert)

@@ -112,6 +112,48 @@ def test_weight_operand_argument_errors():
     assert bw == nv.EINVAL
 
 
+def test_swiglu_backward_scalar_step_equals_the_oracle_bit_for_bit():
+    # the kernels' own inline function for the SwiGLU backward (compiled for the host) against the oracle's fixed
+    # binary32 evaluation: every bit, over gates from deep saturation to deep saturation, zeros and signed zeros
+    rng = np.random.default_rng(3)
+    n = 200000
+    g = np.concatenate([rng.standard_normal(n // 2) * 4.0, rng.uniform(-120.0, 120.0, n // 2 - 8), [0.0, -0.0, 87.0, -87.0, 88.5, -88.5, 1e-30, -1e-30]]).astype(np.float32)
+    u = (rng.standard_normal(n) * 1.5).astype(np.float32)
+    h = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    dg, du = np.empty(n, np.float32), np.empty(n, np.float32)
+    nv.lib.nvfp4_host_swiglu_bwd(_p(h), _p(g), _p(u), n, _p(dg), _p(du))
+    og, ou = oracle.swiglu_bwd(h.reshape(1, n), g.reshape(1, n), u.reshape(1, n))
+    assert np.array_equal(dg.view(np.uint32), og.reshape(-1).view(np.uint32))
+    assert np.array_equal(du.view(np.uint32), ou.reshape(-1).view(np.uint32))
+
+
+def test_swiglu_and_dyq_argument_errors():
+    f = nv.NVFP4.c()
+    ops = nv._DualOperands(FAKE, FAKE, FAKE, FAKE, FAKE, 0)
+    sq = lambda **k: nv.lib.nvfp4_swiglu_bwd_quantize(k.get("dH", FAKE), FAKE, k.get("U", FAKE), k.get("dt", nv.BF16), k.get("M", 64), k.get("F", 64), 1, 2,
+                                                      C.byref(k.get("f", f)), C.byref(k.get("dG", ops)), C.byref(ops), k.get("ws", FAKE), k.get("wsb", 1 << 20), None)
+    assert sq(dH=None) == nv.EINVAL
+    assert sq(U=None) == nv.EINVAL
+    assert sq(dt=4) == nv.EINVAL
+    assert sq(M=72) == nv.ESHAPE
+    assert sq(F=24) == nv.ESHAPE
+    assert sq(f=nv.Format(64, nv.SCALE_E4M3, 1).c()) == nv.EUNSUPPORTED
+    assert sq(ws=None) == nv.EWORKSPACE
+    assert sq(wsb=100) == nv.EWORKSPACE
+    assert sq(dG=nv._DualOperands(FAKE, FAKE, None, FAKE, FAKE, 0)) == nv.EINVAL
+    assert sq(dG=nv._DualOperands(FAKE, FAKE, FAKE, FAKE, FAKE, 8)) == nv.EINVAL
+    assert sq(dG=nv._DualOperands(FAKE, FAKE, FAKE, FAKE, FAKE, nv.SLAB_ROWS)) == nv.ESHAPE     # F = 64: no whole K tile
+    assert sq(dG=nv._DualOperands(FAKE + 8, FAKE, FAKE, FAKE, FAKE, 0)) == nv.EALIGN
+    assert nv.lib.nvfp4_swiglu_bwd_workspace_bytes(4096, 11008) >= 4096
+    bq = lambda **k: nv.lib.nvfp4_linear_bwd_dyq(k["dy"] if "dy" in k else C.byref(ops), FAKE, FAKE, None, FAKE, FAKE, 64, k.get("N", 64), 64, nv.BF16, nv.BF16,
+                                                  C.byref(f), 0, FAKE, 1 << 30, None, None, None)
+    assert bq(dy=None) == nv.EINVAL
+    assert bq(dy=C.byref(nv._DualOperands(FAKE, FAKE, FAKE, FAKE, None, 0))) == nv.EINVAL
+    assert bq(dy=C.byref(nv._DualOperands(None, FAKE, FAKE, FAKE, FAKE, 0))) == nv.EINVAL
+    assert bq(dy=C.byref(nv._DualOperands(FAKE, FAKE, FAKE, FAKE, FAKE, nv.SLAB_ROWS))) == nv.EUNSUPPORTED  # the small GEMM takes no slabs
+    assert bq(N=72) == nv.ESHAPE
+
+
 def test_cross_check_switches_round_trip():
     before = nv.cross_check_switches()
     assert before in (0, 1, 2, 3)
