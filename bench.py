@@ -385,6 +385,30 @@ def main() -> int:
     small_forward = {"workload": "single NVFP4 linear forward, X and W fp32 [256 x 256], fp32 out: 5 kernel launches", "us_per_call": round(ms1 * 1e3, 2),
                      "GFLOP/s": round(2.0 * 256 ** 3 / (ms1 * 1e-3) / 1e9, 1)}
 
+    # ---- SwiGLU backward + the quantizers of dG and dU at the 7B shape [4096 x 11008]: fused (maxima pass + one
+    # dual pass per result, nothing stored) against the same step unfused (elementwise kernel storing dG, dU in
+    # bf16, then a maximum pass and a dual pass over each)
+    Fw = 11008
+    dHs, Gs, Us = synth.gradient_like(M, Fw, 800).to(dev), synth.normal(M, Fw, 2.0, 801).to(dev), synth.normal(M, Fw, 1.0, 802).to(dev)
+    fo = (nv.empty_dual_operands(M, Fw, nv.NVFP4, True, True), nv.empty_dual_operands(M, Fw, nv.NVFP4, True, True))
+    t_fused = event_time_ms(lambda i: nv.swiglu_bwd_quantize(dHs, Gs, Us, 10 + i, 20 + i, out=fo), 10, torch)
+    tG, tU = torch.empty_like(dHs), torch.empty_like(dHs)
+    t_stored = event_time_ms(lambda i: nv.swiglu_bwd_quantize(dHs, Gs, Us, 10 + i, 20 + i, out=fo, store=(tG, tU)), 10, torch)
+    flat = lambda o: (o.codes_rows, o.scales_rows, o.codes_cols, o.scales_cols, o.g)
+
+    def unfused(i):
+        nv.swiglu_bwd(dHs, Gs, Us, out=(tG, tU))
+        nv.quantize_dual(tG, nv.SR, 10 + i, nv.SR, 11 + i, out=flat(fo[0]), slab_rows=True, slab_cols=True)
+        nv.quantize_dual(tU, nv.SR, 20 + i, nv.SR, 21 + i, out=flat(fo[1]), slab_rows=True, slab_cols=True)
+
+    t_unfused = event_time_ms(unfused, 10, torch)
+    swiglu = {"fused_results_stored_ms": round(t_stored, 4), "fused_nothing_stored_ms": round(t_fused, 4), "unfused_ms": round(t_unfused, 4),
+              "workload": f"dH, G, U bf16 [{M} x {Fw}] -> Q_SR(dG), Q_SR(dU), both orientations, slab layout (NVFP4)",
+              "fused_results_stored": "nvfp4_swiglu_bwd_quantize with dG_store/dU_store: 1 pass evaluates, stores and leaves the maxima + 2 dual passes over the stored results",
+              "fused_nothing_stored": "nvfp4_swiglu_bwd_quantize: 1 maxima pass + 2 dual passes that evaluate the result again while loading",
+              "unfused": "nvfp4_swiglu_bwd (stores dG, dU) + 2 x nvfp4_quantize_dual (maximum pass + dual pass each)"}
+    del dHs, Gs, Us, tG, tU, fo
+
     # ---- quantizer sweep tensor (second half of the metric): bf16 [8192, 8192].
     # Four different tensors are cycled (512 MiB in total) so that the 256 MB last-level cache
     # cannot serve the reads of the next call: the rate is an HBM rate.
@@ -460,7 +484,7 @@ def main() -> int:
         "schedules": schedules,
         "frac_of_fp4_peak": round(tflops / PEAK_FP4_TFLOPS, 4),
         "roofline": roofline, "in_step_gemms": in_step, "mfma_sustained": sustained, "mxfp4_gemm": mxfp4, "mxfp4_step": mx_step,
-        "mxfp4_in_step_gemms": in_step_mx, "weights_reused_step": reuse, "forward_linears_7b": forward_linears, "small_forward": small_forward, "format_sweep": sweep,
+        "mxfp4_in_step_gemms": in_step_mx, "weights_reused_step": reuse, "forward_linears_7b": forward_linears, "small_forward": small_forward, "swiglu_bwd_quantize": swiglu, "format_sweep": sweep,
         "quantize": quant, "cpu_baseline": cpu,
     }
     print(json.dumps(line))

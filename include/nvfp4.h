@@ -337,8 +337,8 @@ typedef struct {
  * up layers' upstream gradients are dG = dH u sigma(g) (1 + g (1 - sigma(g))) and dU = dH g sigma(g), g and u the
  * two layers' forward outputs and dH the down layer's input gradient; Eqs. 5-6 then need Q_SR(dG), Q_SR(dU)
  * blocked along both axes.  This call produces those four operands from dH, G, U [M, F] (dense row-major of dt)
- * without dG or dU ever being stored: one pass leaves their maxima, one dual-orientation pass per result
- * re-evaluates it while loading.  The paper gives no arithmetic for the elementwise step; it is fixed in binary32
+ * with the tensor-maximum pass of both quantizers folded into the elementwise pass (one pass over dH, G, U leaves the
+ * maxima of dG and dU; then one dual-orientation pass per result), and optionally without dG or dU ever being stored.  The paper gives no arithmetic for the elementwise step; it is fixed in binary32
  * (one rounding per operation): e = exp(-|g|) by k = rint(t log2 e), r = t - k ln2 (two fused steps, ln2 = 0.693145751953125
  * + 1.42860677e-6), degree-6 Taylor polynomial in Horner form with fused multiply-adds, exact scaling by 2^k, t clamped
  * at -87; sigma = (g >= 0 ? 1 : e) / (1 + e); dG = (dH u)(sigma (1 + g (1 - sigma))); dU = dH (g sigma); each result
@@ -346,7 +346,13 @@ typedef struct {
  * tensors an elementwise kernel with this arithmetic would have stored.
  *   seed_gate, seed_up   SR streams: rows side seed, columns side seed + 1 (what nvfp4_linear_bwd uses for dY)
  *   dG, dU               outputs; layout bits choose row-major or slabs per side (slabs: F resp. M a multiple of 128)
- *   workspace            >= nvfp4_swiglu_bwd_workspace_bytes(M, F), 16-byte aligned (not needed without tensor scale)
+ *   dG_store, dU_store   both NULL: nothing but the operands is written (each result is evaluated in the maxima
+ *                        pass and again in its quantizer pass); both given (device, [M, F] of dt, 16-byte aligned):
+ *                        the maxima pass also stores the two results and the quantizer passes read them back -- the
+ *                        same bits out, the tensors available to the caller, and the faster form on this GPU, where
+ *                        the quantizer passes are bound by vector-ALU work rather than by memory
+ *   workspace            >= nvfp4_swiglu_bwd_workspace_bytes(M, F), 16-byte aligned (not needed without tensor scale
+ *                        unless the results are stored)
  * Formats: NVFP4 {16, E4M3, 1} and MXFP4 {32, E8M0, 0}; M and F multiples of the block size; not with the
  * software-convert cross-check switch (NVFP4_EUNSUPPORTED).  Other errors as nvfp4_quantize_dual.
  * nvfp4_linear_bwd_dyq is nvfp4_linear_bwd for an upstream gradient that is already quantized (such a pair, with
@@ -358,12 +364,17 @@ size_t nvfp4_swiglu_bwd_workspace_bytes(int64_t M, int64_t F);
 nvfp4_status nvfp4_swiglu_bwd_quantize(const void *dH, const void *G, const void *U, nvfp4_dtype dt, int64_t M,
                                        int64_t F, uint64_t seed_gate, uint64_t seed_up, const nvfp4_format *f,
                                        const nvfp4_dual_operands *dG, const nvfp4_dual_operands *dU,
+                                       void *dG_store, void *dU_store,
                                        void *workspace, size_t workspace_bytes, void *stream);
 nvfp4_status nvfp4_linear_bwd_dyq(const nvfp4_dual_operands *dY, const void *X, const void *W,
                                   const void *w_operands, void *dX, void *dW, int64_t M, int64_t N, int64_t K,
                                   nvfp4_dtype in_dt, nvfp4_dtype out_dt, const nvfp4_format *f, uint64_t seed,
                                   void *workspace, size_t workspace_bytes, void *stream,
                                   const float *xw_scales, const void *saved);
+/* The elementwise step alone, results stored: dG, dU of dt, n elements each (n a multiple of 8; all pointers device,
+ * 16-byte aligned, dense).  nvfp4_quantize_dual of these two tensors equals what nvfp4_swiglu_bwd_quantize writes. */
+nvfp4_status nvfp4_swiglu_bwd(const void *dH, const void *G, const void *U, nvfp4_dtype dt, int64_t n, void *dG,
+                              void *dU, void *stream);
 /* host evaluation of the elementwise step (the kernels' own inline function), n elements, host pointers */
 void nvfp4_host_swiglu_bwd(const float *dH, const float *G, const float *U, int64_t n, float *dG, float *dU);
 

@@ -110,9 +110,11 @@ def _load() -> C.CDLL:
     L.nvfp4_swiglu_bwd_workspace_bytes.restype = sz
     L.nvfp4_swiglu_bwd_workspace_bytes.argtypes = [i64, i64]
     L.nvfp4_swiglu_bwd_quantize.restype = ci
-    L.nvfp4_swiglu_bwd_quantize.argtypes = [vp, vp, vp, ci, i64, i64, u64, u64, fp, dp, dp, vp, sz, vp]
+    L.nvfp4_swiglu_bwd_quantize.argtypes = [vp, vp, vp, ci, i64, i64, u64, u64, fp, dp, dp, vp, vp, vp, sz, vp]
     L.nvfp4_linear_bwd_dyq.restype = ci
     L.nvfp4_linear_bwd_dyq.argtypes = [dp, vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, fp, u64, vp, sz, vp, vp, vp]
+    L.nvfp4_swiglu_bwd.restype = ci
+    L.nvfp4_swiglu_bwd.argtypes = [vp, vp, vp, ci, i64, vp, vp, vp]
     L.nvfp4_host_swiglu_bwd.restype = None
     L.nvfp4_host_swiglu_bwd.argtypes = [vp, vp, vp, i64, vp, vp]
     L.nvfp4_linear_saved_bytes.restype = sz
@@ -161,7 +163,7 @@ EXPORTS = (
     "nvfp4_host_round_rtn_n", "nvfp4_host_round_sr_n", "nvfp4_probe_mfma_rate",
     "nvfp4_quant_noise_workspace_bytes", "nvfp4_quant_noise", "nvfp4_quantize_static", "nvfp4_cross_check_switches",
     "nvfp4_weight_operands_bytes", "nvfp4_quantize_weight", "nvfp4_linear_fwd_wq", "nvfp4_linear_bwd_wq",
-    "nvfp4_swiglu_bwd_workspace_bytes", "nvfp4_swiglu_bwd_quantize", "nvfp4_linear_bwd_dyq", "nvfp4_host_swiglu_bwd",
+    "nvfp4_swiglu_bwd_workspace_bytes", "nvfp4_swiglu_bwd_quantize", "nvfp4_linear_bwd_dyq", "nvfp4_host_swiglu_bwd", "nvfp4_swiglu_bwd",
 )
 
 
@@ -430,9 +432,11 @@ def empty_dual_operands(rows: int, cols: int, fmt: Format = NVFP4, slab_rows: bo
 
 
 def swiglu_bwd_quantize(dH: torch.Tensor, G: torch.Tensor, U: torch.Tensor, seed_gate: int, seed_up: int,
-                        fmt: Format = NVFP4, slab_rows: bool = False, slab_cols: bool = False, out=None):
+                        fmt: Format = NVFP4, slab_rows: bool = False, slab_cols: bool = False, out=None, store=None):
     """nvfp4_swiglu_bwd_quantize -> (dG, dU) as DualOperands: Q_SR of the SwiGLU backward's two results, both
-    orientations each, without the results being stored.  `out` = (dG, dU) reuses caller-provided buffers."""
+    orientations each.  `out` = (dG, dU) reuses caller-provided buffers.  `store` = (dG_tensor, dU_tensor) of the
+    inputs' shape and dtype: the results are also stored there (and read back by the quantizer passes); None:
+    nothing but the operands is written."""
     _require_gpu(dH, G, U)
     assert dH.is_contiguous() and G.is_contiguous() and U.is_contiguous() and dH.shape == G.shape == U.shape
     assert dH.dtype == G.dtype == U.dtype
@@ -443,8 +447,20 @@ def swiglu_bwd_quantize(dH: torch.Tensor, G: torch.Tensor, U: torch.Tensor, seed
     ws = torch.empty(lib.nvfp4_swiglu_bwd_workspace_bytes(M, F), dtype=torch.uint8, device=dH.device)
     cg, cu = dG.c(), dU.c()
     _check(lib.nvfp4_swiglu_bwd_quantize(dH.data_ptr(), G.data_ptr(), U.data_ptr(), _dtype_tag(dH), M, F, seed_gate, seed_up,
-                                         C.byref(f), C.byref(cg), C.byref(cu), ws.data_ptr(), ws.numel(), _stream()),
+                                         C.byref(f), C.byref(cg), C.byref(cu),
+                                         None if store is None else store[0].data_ptr(), None if store is None else store[1].data_ptr(),
+                                         ws.data_ptr(), ws.numel(), _stream()),
            "nvfp4_swiglu_bwd_quantize")
+    return dG, dU
+
+
+def swiglu_bwd(dH: torch.Tensor, G: torch.Tensor, U: torch.Tensor, out=None):
+    """nvfp4_swiglu_bwd -> (dG, dU) tensors of the inputs' dtype (the elementwise step alone)."""
+    _require_gpu(dH, G, U)
+    assert dH.is_contiguous() and G.is_contiguous() and U.is_contiguous() and dH.shape == G.shape == U.shape
+    dG, dU = out if out is not None else (torch.empty_like(dH), torch.empty_like(dH))
+    _check(lib.nvfp4_swiglu_bwd(dH.data_ptr(), G.data_ptr(), U.data_ptr(), _dtype_tag(dH), dH.numel(), dG.data_ptr(),
+                                dU.data_ptr(), _stream()), "nvfp4_swiglu_bwd")
     return dG, dU
 
 

@@ -890,9 +890,12 @@ size_t nvfp4_swiglu_bwd_workspace_bytes(int64_t M, int64_t F)
 nvfp4_status nvfp4_swiglu_bwd_quantize(const void *dH, const void *G, const void *U, nvfp4_dtype dt_, int64_t M,
                                        int64_t F, uint64_t seed_gate, uint64_t seed_up, const nvfp4_format *f,
                                        const nvfp4_dual_operands *dG, const nvfp4_dual_operands *dU,
+                                       void *dG_store, void *dU_store,
                                        void *workspace, size_t workspace_bytes, void *stream)
 {
     const int dt = raw(dt_);
+    if ((dG_store == nullptr) != (dU_store == nullptr)) return NVFP4_EINVAL;
+    if (!aligned16(dG_store) || !aligned16(dU_store)) return NVFP4_EALIGN;
     nvfp4_status s = check_format(f);
     if (s != NVFP4_OK) return s;
     if (!valid_dtype(dt) || !dH || !G || !U || !dG || !dU) return NVFP4_EINVAL;
@@ -906,12 +909,13 @@ nvfp4_status nvfp4_swiglu_bwd_quantize(const void *dH, const void *G, const void
         if (!aligned16(o->codes_rows) || !aligned16(o->scales_rows) || !aligned16(o->codes_cols) || !aligned16(o->scales_cols)) return NVFP4_EALIGN;
         if (((o->layout & NVFP4_SLAB_ROWS) && F % SLAB_K != 0) || ((o->layout & NVFP4_SLAB_COLS) && M % SLAB_K != 0)) return NVFP4_ESHAPE;
     }
-    if (f->tensor_scale) {
+    const bool need_ws = f->tensor_scale || dG_store;  // (the first pass leaves its partial maxima there)
+    if (need_ws) {
         if (!workspace || workspace_bytes < nvfp4_swiglu_bwd_workspace_bytes(M, F)) return NVFP4_EWORKSPACE;
         if (!aligned16(workspace)) return NVFP4_EALIGN;
     }
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    uint32_t *partials = f->tensor_scale ? reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(workspace) + WS_HEADER) : nullptr;
+    uint32_t *partials = need_ws ? reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(workspace) + WS_HEADER) : nullptr;
     const int gm = f->tensor_scale ? G_FROM_AMAX : G_NONE;
     auto plan = [&](const nvfp4_dual_operands *o, uint64_t seed) {
         DualArgs d;
@@ -936,7 +940,19 @@ nvfp4_status nvfp4_swiglu_bwd_quantize(const void *dH, const void *G, const void
         return d;
     };
     DualArgs dg = plan(dG, seed_gate), du = plan(dU, seed_up);
-    return launch_swiglu_bwd_dual(dg, du, dt, f->block, f->scale, partials, partials ? partials + AMAX_DENSE_PARTIALS : nullptr, st) == hipSuccess ? NVFP4_OK : NVFP4_EHIP;
+    return launch_swiglu_bwd_dual(dg, du, dt, f->block, f->scale, partials, partials ? partials + AMAX_DENSE_PARTIALS : nullptr, dG_store, dU_store, st) == hipSuccess ? NVFP4_OK : NVFP4_EHIP;
+}
+
+nvfp4_status nvfp4_swiglu_bwd(const void *dH, const void *G, const void *U, nvfp4_dtype dt_, int64_t n, void *dG,
+                              void *dU, void *stream)
+{
+    const int dt = raw(dt_);
+    if (!valid_dtype(dt)) return NVFP4_EINVAL;
+    if (n < 0 || n % 8 != 0) return NVFP4_ESHAPE;
+    if (n == 0) return NVFP4_OK;
+    if (!dH || !G || !U || !dG || !dU) return NVFP4_EINVAL;
+    if (!aligned16(dH) || !aligned16(G) || !aligned16(U) || !aligned16(dG) || !aligned16(dU)) return NVFP4_EALIGN;
+    return launch_swiglu_bwd(dH, G, U, dt, n, dG, dU, reinterpret_cast<hipStream_t>(stream)) == hipSuccess ? NVFP4_OK : NVFP4_EHIP;
 }
 
 void nvfp4_host_swiglu_bwd(const float *dH, const float *G, const float *U, int64_t n, float *dG, float *dU)

@@ -125,8 +125,12 @@ hipError_t launch_quantize_dual(const DualArgs &D, int dt, int rnd_rows, int rnd
 // dual-orientation pass per result re-evaluates it while loading.  g / u describe the outputs as for
 // launch_quantize_dual (c.x = dH, src_g, src_u set; stochastic rounding on both sides).  Formats: the ones the
 // one-pass dual kernel serves with slabs (block 16 + E4M3, block 32 + E8M0); the caller checks quantize_dual_fused().
+// With dG_store / dU_store (both or neither) the first pass also stores the two results and the quantizer passes read
+// them back through the ordinary dual kernel instead of evaluating them again.
 hipError_t launch_swiglu_bwd_dual(DualArgs &g, DualArgs &u, int dt, int block, int sf, uint32_t *partials_g,
-                                  uint32_t *partials_u, hipStream_t st);
+                                  uint32_t *partials_u, void *dG_store, void *dU_store, hipStream_t st);
+// The same elementwise step with dG and dU stored as tensors of dt (n a multiple of 8).
+hipError_t launch_swiglu_bwd(const void *dH, const void *G, const void *U, int dt, int64_t n, void *dG, void *dU, hipStream_t st);
 hipError_t launch_gemm(const GemmArgs &P, int block, int sf, int out_dt, hipStream_t st);
 hipError_t launch_gemm_mxfp4(const GemmArgs &P, int out_dt, hipStream_t st);  // block 32, E8M0
 bool mxfp4_gemm_takes_slabs(int64_t K);  // MXFP4: the codes of an operand may come as slabs (its scales stay row-major)

@@ -79,6 +79,10 @@ struct Chunk<NVFP4_BF16> {
         raw = make_uint4(w[0], w[1], w[2], w[3]);
     }
     __device__ __forceinline__ void zero() { raw = make_uint4(0, 0, 0, 0); }
+    __device__ __forceinline__ void store(void *x, int64_t off) const
+    {
+        *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(x) + off) = raw;
+    }
     // 8 binary32 values rounded to bf16 (nearest even) and packed
     __device__ __forceinline__ void set(const float (&f)[8])
     {
@@ -129,6 +133,12 @@ struct Chunk<NVFP4_F32> {
     {
         lo = make_float4(f[0], f[1], f[2], f[3]);
         hi = make_float4(f[4], f[5], f[6], f[7]);
+    }
+    __device__ __forceinline__ void store(void *x, int64_t off) const
+    {
+        float *p = reinterpret_cast<float *>(x) + off;
+        *reinterpret_cast<float4 *>(p) = lo;
+        *reinterpret_cast<float4 *>(p + 4) = hi;
     }
     __device__ __forceinline__ void launder() {}
     __device__ __forceinline__ float get(int t) const
@@ -762,9 +772,11 @@ __device__ __forceinline__ void swiglu_chunk(const void *dH, const void *G, cons
 
 // max|dG| and max|dU| (of the values as rounded to the element type) over n = 8 * nchunk elements: one partial
 // maximum of each per workgroup, as amax_dense_kernel leaves them for a tensor in memory.
-template <int DT>
+// STORE: the two results are also written out as tensors (dG_out, dU_out), for quantizer passes that read them back
+// instead of evaluating them again.
+template <int DT, bool STORE>
 __global__ __launch_bounds__(1024) void swiglu_amax_kernel(const void *dH, const void *G, const void *U, int64_t n,
-                                                           uint32_t *part_g, uint32_t *part_u)
+                                                           uint32_t *part_g, uint32_t *part_u, void *dG_out, void *dU_out)
 {
     const int64_t nchunk = n >> 3;
     const int64_t stride = (int64_t)gridDim.x * (1024 * 2);
@@ -776,6 +788,10 @@ __global__ __launch_bounds__(1024) void swiglu_amax_kernel(const void *dH, const
             if (c < nchunk) {
                 Chunk<DT> cg, cu;
                 swiglu_chunk<DT, 0>(dH, G, U, c * 8, &cg, &cu);
+                if (STORE) {
+                    cg.store(dG_out, c * 8);
+                    cu.store(dU_out, c * 8);
+                }
                 ag = fmaxf(ag, chunk_amax(cg));
                 au = fmaxf(au, chunk_amax(cu));
             }
@@ -799,6 +815,29 @@ __global__ __launch_bounds__(1024) void swiglu_amax_kernel(const void *dH, const
         part_g[blockIdx.x] = mg;
         part_u[blockIdx.x] = mu;
     }
+}
+
+// dG and dU stored as tensors (the unfused form of the same step): n = 8 * nchunk elements.
+template <int DT>
+__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const void *dH, const void *G, const void *U, int64_t n, void *dG, void *dU)
+{
+    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (c >= (n >> 3)) return;
+    Chunk<DT> cg, cu;
+    swiglu_chunk<DT, 0>(dH, G, U, c * 8, &cg, &cu);
+    cg.store(dG, c * 8);
+    cu.store(dU, c * 8);
+}
+
+hipError_t launch_swiglu_bwd(const void *dH, const void *G, const void *U, int dt, int64_t n, void *dG, void *dU, hipStream_t st)
+{
+    const unsigned grid = (unsigned)(((n >> 3) + 255) / 256);
+    if (grid == 0) return hipSuccess;
+    if (dt == NVFP4_BF16)
+        hipLaunchKernelGGL(swiglu_bwd_kernel<NVFP4_BF16>, dim3(grid), dim3(256), 0, st, dH, G, U, n, dG, dU);
+    else
+        hipLaunchKernelGGL(swiglu_bwd_kernel<NVFP4_F32>, dim3(grid), dim3(256), 0, st, dH, G, U, n, dG, dU);
+    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------ both orientations in one pass
@@ -1128,22 +1167,39 @@ static void launch_swiglu_dual_fmt(const DualArgs &g, const DualArgs &u, hipStre
 }
 
 hipError_t launch_swiglu_bwd_dual(DualArgs &g, DualArgs &u, int dt, int block, int sf, uint32_t *partials_g,
-                                  uint32_t *partials_u, hipStream_t st)
+                                  uint32_t *partials_u, void *dG_store, void *dU_store, hipStream_t st)
 {
     const int64_t n = g.c.rows * g.c.cols;
-    if (g.c.g_mode == G_FROM_AMAX) {
-        int64_t gx = ((n >> 3) + 2047) / 2048;
-        gx = gx < 1 ? 1 : (gx > AMAX_DENSE_PARTIALS ? AMAX_DENSE_PARTIALS : gx);
-        if (dt == NVFP4_BF16)
-            hipLaunchKernelGGL(swiglu_amax_kernel<NVFP4_BF16>, dim3((unsigned)gx), dim3(1024), 0, st, g.c.x, g.src_g, g.src_u, n, partials_g, partials_u);
-        else
-            hipLaunchKernelGGL(swiglu_amax_kernel<NVFP4_F32>, dim3((unsigned)gx), dim3(1024), 0, st, g.c.x, g.src_g, g.src_u, n, partials_g, partials_u);
-        g.c.g_src = reinterpret_cast<const float *>(partials_g);
-        u.c.g_src = reinterpret_cast<const float *>(partials_u);
-        g.c.n_partials = u.c.n_partials = (int)gx;
-    }
     const bool nv = block == 16 && sf == NVFP4_SCALE_E4M3, mxf = block == 32 && sf == NVFP4_SCALE_E8M0;
     if (!nv && !mxf) return hipErrorInvalidValue;
+    const bool store = dG_store != nullptr;
+    if (g.c.g_mode == G_FROM_AMAX || store) {
+        int64_t gx = ((n >> 3) + 2047) / 2048;
+        gx = gx < 1 ? 1 : (gx > AMAX_DENSE_PARTIALS ? AMAX_DENSE_PARTIALS : gx);
+        const dim3 grid((unsigned)gx), wg(1024);
+        if (dt == NVFP4_BF16 && store)
+            hipLaunchKernelGGL((swiglu_amax_kernel<NVFP4_BF16, true>), grid, wg, 0, st, g.c.x, g.src_g, g.src_u, n, partials_g, partials_u, dG_store, dU_store);
+        else if (dt == NVFP4_BF16)
+            hipLaunchKernelGGL((swiglu_amax_kernel<NVFP4_BF16, false>), grid, wg, 0, st, g.c.x, g.src_g, g.src_u, n, partials_g, partials_u, dG_store, dU_store);
+        else if (store)
+            hipLaunchKernelGGL((swiglu_amax_kernel<NVFP4_F32, true>), grid, wg, 0, st, g.c.x, g.src_g, g.src_u, n, partials_g, partials_u, dG_store, dU_store);
+        else
+            hipLaunchKernelGGL((swiglu_amax_kernel<NVFP4_F32, false>), grid, wg, 0, st, g.c.x, g.src_g, g.src_u, n, partials_g, partials_u, dG_store, dU_store);
+        if (g.c.g_mode == G_FROM_AMAX) {
+            g.c.g_src = reinterpret_cast<const float *>(partials_g);
+            u.c.g_src = reinterpret_cast<const float *>(partials_u);
+            g.c.n_partials = u.c.n_partials = (int)gx;
+        }
+    }
+    if (store) {
+        // the quantizers read the stored results (the ordinary dual kernel), not dH, G, U again
+        g.c.x = dG_store;
+        u.c.x = dU_store;
+        g.src_g = g.src_u = u.src_g = u.src_u = nullptr;
+        hipError_t e = launch_quantize_dual(g, dt, NVFP4_SR, NVFP4_SR, block, sf, true, st);
+        if (e != hipSuccess) return e;
+        return launch_quantize_dual(u, dt, NVFP4_SR, NVFP4_SR, block, sf, true, st);
+    }
     if (dt == NVFP4_BF16) {
         if (nv) launch_swiglu_dual_fmt<NVFP4_BF16, 16, NVFP4_SCALE_E4M3>(g, u, st);
         else launch_swiglu_dual_fmt<NVFP4_BF16, 32, NVFP4_SCALE_E8M0>(g, u, st);

@@ -61,6 +61,21 @@ def test_fused_swiglu_backward_quantizers_match_the_oracle(fmt_name, dtype):
         for got, ref, seed, what in ((dG, oG, sg, "dG"), (dU, oU, su, "dU")):
             assert_quant_equal(got.rows, oracle.quantize(ref, 1, oracle.SR, seed, of), what + " rows")
             assert_quant_equal(got.cols, oracle.quantize(ref, 0, oracle.SR, seed + 1, of), what + " cols")
+        # the form that stores the two results in its first pass: same operands, and the stored tensors are the
+        # oracle's hand-over
+        sG, sU = torch.empty_like(dH, device="cuda"), torch.empty_like(dH, device="cuda")
+        dG2, dU2 = nv.swiglu_bwd_quantize(dH.cuda(), G.cuda(), U.cuda(), sg, su, fmt, store=(sG, sU))
+        torch.cuda.synchronize()
+        for a, b in ((dG, dG2), (dU, dU2)):
+            for x, y in zip((a.codes_rows, a.scales_rows, a.codes_cols, a.scales_cols, a.g), (b.codes_rows, b.scales_rows, b.codes_cols, b.scales_cols, b.g)):
+                assert torch.equal(x, y)
+        view0 = (lambda t: to_np(t.view(torch.int16)).view(np.uint16)) if dtype == torch.bfloat16 else to_np
+        assert np.array_equal(view0(sG), oG) and np.array_equal(view0(sU), oU)
+        # the elementwise step alone: the stored tensors are the oracle's hand-over, bit for bit
+        tG, tU = nv.swiglu_bwd(dH.cuda(), G.cuda(), U.cuda())
+        torch.cuda.synchronize()
+        view = (lambda t: to_np(t.view(torch.int16)).view(np.uint16)) if dtype == torch.bfloat16 else to_np
+        assert np.array_equal(view(tG), oG) and np.array_equal(view(tU), oU)
     # degenerate: an all-zero upstream gradient (scale 1, zero codes with the sign bits of the products)
     dH, G, U = _inputs(64, 128, dtype, 77)
     dH.zero_()

@@ -131,8 +131,10 @@ def test_swiglu_and_dyq_argument_errors():
     f = nv.NVFP4.c()
     ops = nv._DualOperands(FAKE, FAKE, FAKE, FAKE, FAKE, 0)
     sq = lambda **k: nv.lib.nvfp4_swiglu_bwd_quantize(k.get("dH", FAKE), FAKE, k.get("U", FAKE), k.get("dt", nv.BF16), k.get("M", 64), k.get("F", 64), 1, 2,
-                                                      C.byref(k.get("f", f)), C.byref(k.get("dG", ops)), C.byref(ops), k.get("ws", FAKE), k.get("wsb", 1 << 20), None)
+                                                      C.byref(k.get("f", f)), C.byref(k.get("dG", ops)), C.byref(ops), k.get("sg", None), k.get("su", None), k.get("ws", FAKE), k.get("wsb", 1 << 20), None)
     assert sq(dH=None) == nv.EINVAL
+    assert sq(sg=FAKE) == nv.EINVAL                      # the two result tensors come together or not at all
+    assert sq(sg=FAKE + 4, su=FAKE) == nv.EALIGN
     assert sq(U=None) == nv.EINVAL
     assert sq(dt=4) == nv.EINVAL
     assert sq(M=72) == nv.ESHAPE
