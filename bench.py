@@ -367,12 +367,21 @@ def main() -> int:
             nv.linear_bwd(sdY, None, None, 7000 + 3 * i, fmt, workspace=wb, out=(sdX, sdW), saved=ssaved, K=sK)
 
         ms = event_time_ms(fwd_bwd, 4, torch)
+        ms_fp4 = None
+        if fmt.block >= 64:
+            # the other exact route for these formats (unit-scale FP4 MFMA per block + binary32 rescale), for comparison
+            before = nv.cross_check_switches(nv.SWITCH_FP4_WIDE_BLOCKS)
+            ms_fp4 = event_time_ms(fwd_bwd, 4, torch)
+            nv.cross_check_switches(before)
         nx = nv.quant_noise(sX, nv.quantize(sX, 1, nv.RTN, 0, fmt), 1, fmt).cpu().numpy()
         ng = nv.quant_noise(sdY, nv.quantize(sdY, 1, nv.SR, 9, fmt), 1, fmt).cpu().numpy()
         sweep[label] = {"fwd_bwd_ms": round(ms, 4), "TFLOP/s": round(3 * 2.0 * sM * sN * sK / (ms * 1e-3) / 1e12, 1),
                         "rel_mse_activation_rtn": float(f"{nx[1] / nx[0]:.4e}"),
                         "rel_mse_gradient_sr": float(f"{ng[1] / ng[0]:.4e}"),
                         "gradient_to_noise_ratio": round(float((ng[0] / ng[1]) ** 0.5), 3)}
+        if ms_fp4 is not None:
+            sweep[label]["gemm_route"] = "operands expanded to fp16 (as NVFP4)"
+            sweep[label]["fwd_bwd_ms_fp4_mfma_rescale_route"] = round(ms_fp4, 4)
         del wf, wb
     sweep["workload"] = (f"linear fwd (RtN) + bwd (SR), down projection at 8192 tokens: M={sM} N={sN} K={sK}, bf16 in/out; "
                          "rel_mse = sum (Q(x)-x)^2 / sum x^2; ratio = ||dY|| / (sigma_q sqrt(d)), threshold sqrt(3)")

@@ -60,18 +60,23 @@ typedef struct {
 } nvfp4_format;
 
 /*
- * Two switches exist for cross-checking; neither changes a result bit.  They are taken from the environment once,
+ * Three switches exist for cross-checking; the first two change no result bit.  They are taken from the environment once,
  * by the first call that needs them, and stay fixed for the process unless nvfp4_cross_check_switches replaces them:
  *   bit 0 / NVFP4_SOFT_CONVERT=1    round elements and block scales with integer/fp32 arithmetic instead of the
  *                                   gfx950 convert instructions (then nvfp4_quantize_dual runs as two kernels, no slabs);
- *   bit 1 / NVFP4_PLAIN_OPERANDS=1  the fused linear entries keep their internal operands row-major (no slabs).
+ *   bit 1 / NVFP4_PLAIN_OPERANDS=1  the fused linear entries keep their internal operands row-major (no slabs);
+ *   bit 2 / NVFP4_FP4_WIDE_BLOCKS=1 GEMMs with E4M3 scales at blocks of 64 / 128 (K a multiple of 128) run on the FP4 matrix
+ *                                   instruction with unit scales and rescale each block's partial sum in binary32, instead
+ *                                   of expanding their operands to fp16 like NVFP4 (this one changes the accumulation
+ *                                   order, within the 1e-5 bound; measured 1.8x / 3x slower, so it is off by default).
  * nvfp4_cross_check_switches(set, value) returns the switches in force and, with set != 0, replaces them by
- * `value` (bits 0-1) for every later call of the process.  It is a test hook: call it only while no other thread is
+ * `value` (bits 0-2) for every later call of the process.  It is a test hook: call it only while no other thread is
  * inside the library, and not between a forward call that fills a `saved` buffer and its backward call
  * (nvfp4_linear_bwd refuses such a buffer with NVFP4_EINVAL).
  */
 #define NVFP4_SWITCH_SOFT_CONVERT 1u
 #define NVFP4_SWITCH_PLAIN_OPERANDS 2u
+#define NVFP4_SWITCH_FP4_WIDE_BLOCKS 4u
 uint32_t nvfp4_cross_check_switches(int set, uint32_t value);
 
 /* nvfp4_quantize flags */
@@ -190,8 +195,10 @@ nvfp4_status nvfp4_quantize_dual(const void *x, nvfp4_dtype dt, int64_t rows, in
  * accumulation is fp32.
  * K must be a multiple of the block and of 32, at most 2^23; M, N >= 1.
  * Formats: E4M3 scales with blocks 16/32/64/128 (operands expanded exactly to
- * fp16 for the matrix instruction), and E8M0 scales with block 32 (MXFP4, run
- * on the FP4 matrix instruction as stored); other pairs: NVFP4_EUNSUPPORTED.
+ * fp16 for the matrix instruction; blocks 64/128 have a second, slower route on
+ * the FP4 matrix instruction behind a cross-check switch), and E8M0 scales with
+ * block 32 (MXFP4, run on the FP4 matrix instruction as stored); other pairs:
+ * NVFP4_EUNSUPPORTED.
  */
 nvfp4_status nvfp4_gemm(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
                         const uint8_t *A_codes, const uint8_t *A_scales, const uint8_t *B_codes,

@@ -259,7 +259,7 @@ def quantize_static(x: torch.Tensor, axis: int = 1, rounding: int = RTN, seed: i
     return codes, scales, g
 
 
-SWITCH_SOFT_CONVERT, SWITCH_PLAIN_OPERANDS = 1, 2
+SWITCH_SOFT_CONVERT, SWITCH_PLAIN_OPERANDS, SWITCH_FP4_WIDE_BLOCKS = 1, 2, 4
 
 
 def cross_check_switches(value: int | None = None) -> int:

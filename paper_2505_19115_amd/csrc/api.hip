@@ -59,16 +59,21 @@ nvfp4_status check_format(const nvfp4_format *f)
 // one process).  Bit 0: round elements and block scales with the integer/fp32 formulation (the one the host probes
 // evaluate) instead of the gfx950 convert instructions.  Bit 1: keep the packed operands inside the fused linear
 // entries row-major instead of in the slab layout (kernels.h).
-constexpr uint32_t SW_SOFT_CONVERT = 1u, SW_PLAIN_OPERANDS = 2u, SW_UNREAD = 0x80000000u;
+// Bit 2: GEMMs with E4M3 scales at blocks of 64 / 128 (K a multiple of 128) run on the FP4 matrix instruction with binary32
+// rescaling of the block sums instead of expanding their operands to fp16 like NVFP4 (same results to rounding order; the
+// measured slower route, kept selectable as the reference for that measurement).
+constexpr uint32_t SW_SOFT_CONVERT = 1u, SW_PLAIN_OPERANDS = 2u, SW_FP4_WIDE_BLOCKS = 4u, SW_ALL = 7u, SW_UNREAD = 0x80000000u;
 std::atomic<uint32_t> g_switches{SW_UNREAD};
 
 uint32_t switches()
 {
     uint32_t v = g_switches.load(std::memory_order_relaxed);
     if (v == SW_UNREAD) {
-        const char *a = getenv("NVFP4_SOFT_CONVERT"), *b = getenv("NVFP4_PLAIN_OPERANDS");
-        v = ((a && a[0] == '1') ? SW_SOFT_CONVERT : 0u) | ((b && b[0] == '1') ? SW_PLAIN_OPERANDS : 0u);
+        const char *a = getenv("NVFP4_SOFT_CONVERT"), *b = getenv("NVFP4_PLAIN_OPERANDS"), *c = getenv("NVFP4_FP4_WIDE_BLOCKS");
+        v = ((a && a[0] == '1') ? SW_SOFT_CONVERT : 0u) | ((b && b[0] == '1') ? SW_PLAIN_OPERANDS : 0u) |
+            ((c && c[0] == '1') ? SW_FP4_WIDE_BLOCKS : 0u);
         g_switches.store(v, std::memory_order_relaxed);
+        set_fp4_rescale_route((v & SW_FP4_WIDE_BLOCKS) != 0);
     }
     return v;
 }
@@ -288,7 +293,10 @@ extern "C" {
 uint32_t nvfp4_cross_check_switches(int set, uint32_t value)
 {
     const uint32_t before = switches();
-    if (set) g_switches.store(value & (SW_SOFT_CONVERT | SW_PLAIN_OPERANDS), std::memory_order_relaxed);
+    if (set) {
+        g_switches.store(value & SW_ALL, std::memory_order_relaxed);
+        set_fp4_rescale_route((value & SW_FP4_WIDE_BLOCKS) != 0);
+    }
     return before;
 }
 
@@ -578,6 +586,7 @@ static nvfp4_status gemm_impl(int64_t M, int64_t N, int64_t K, const nvfp4_forma
                               const uint8_t *B_scales, const float *tensor_scales, void *out,
                               int out_dt, int64_t ldc, int a_slab, int b_slab, void *stream)
 {
+    (void)switches();  // (the GEMM route for wide E4M3 blocks follows a switch)
     nvfp4_status s = check_format(f);
     if (s != NVFP4_OK) return s;
     if (!A_codes || !A_scales || !B_codes || !B_scales || !tensor_scales || !out) return NVFP4_EINVAL;
@@ -614,6 +623,7 @@ nvfp4_status linear_fwd_impl(const void *X, const void *W, const void *w_ops, vo
                              const nvfp4_format *f, void *workspace, size_t workspace_bytes,
                              void *stream, float *xw_scales_out, void *saved, uint64_t bwd_seed)
 {
+    (void)switches();
     nvfp4_status s = check_format(f);
     if (s != NVFP4_OK) return s;
     if (!X || (!W && !w_ops) || !Y) return NVFP4_EINVAL;

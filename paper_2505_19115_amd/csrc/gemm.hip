@@ -552,12 +552,17 @@ static void launch_f16_auto(const GemmArgs &P, int out_dt, hipStream_t st)
         launch_f16<B, 2, 2, 2, 2, true>(P, out_dt, st);
 }
 
+static int g_fp4_rescale_route = 0;  // (measured slower than the fp16 route: opt-in)
+void set_fp4_rescale_route(int on) { g_fp4_rescale_route = on; }
+int fp4_rescale_route() { return g_fp4_rescale_route; }
+
 hipError_t launch_gemm(const GemmArgs &P, int block, int sf, int out_dt, hipStream_t st)
 {
     // lane offsets inside a 256-row tile are 32-bit
     if ((P.K >> 1) * 256 >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
     if ((P.a_slab || P.b_slab) && !gemm_takes_slabs(P.M, P.N, P.K, block, sf)) return hipErrorInvalidValue;
     if (sf == NVFP4_SCALE_E8M0) return block == 32 ? launch_gemm_mxfp4(P, out_dt, st) : hipErrorNotSupported;
+    if (g_fp4_rescale_route && fp4_rescale_gemm_applies(P.K, block, P)) return launch_gemm_fp4_rescale(P, block, out_dt, st);
     switch (block) {
     case 16: launch_f16_auto<16>(P, out_dt, st); break;
     case 32: launch_f16_auto<32>(P, out_dt, st); break;

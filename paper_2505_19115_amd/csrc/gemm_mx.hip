@@ -283,6 +283,160 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_kernel(GemmArgs P)
 }
 
 // ---------------------------------------------------------------------------------------------
+// E4M3 block scales at blocks of 64 and 128 on the FP4 matrix instruction (the block-size study of Sec. 3.1 / Fig. 2):
+// an E4M3 scale has a mantissa, which the instruction's power-of-two scale operand cannot carry, so the blocks are
+// multiplied with unit scales and the partial sum of each block is rescaled in binary32:
+//     acc[i, j] += P_b[i, j] * (sA[i, b] * sB[j, b]),      P_b = sum_{k in b} cA[i, k] cB[j, k].
+// P_b is exact (a multiple of 1/4 below 2^13), the product of two E4M3 values is exact (8 significant bits), and so is
+// their product with P_b (<= 23 bits): every term enters the accumulator with the one rounding of the addition, as in
+// the other kernels.  One 32 x 32 x 64 MFMA is exactly one block of 64; two chained ones are one block of 128.  The
+// cost is on the vector ALU: 16 scale products and 16 multiply-adds per 32 x 32 tile and block.
+// K tile 128 = two MFMA steps; step s of lane half g multiplies chunk 2 s + g, so a step covers elements 64 s .. 64 s + 63
+// of the tile (one block of 64, half a block of 128).  Two LDS stages, everything staged through registers; the block
+// scales are decoded to binary32 when they are staged.  K must be a multiple of 128; rows past the edge are clamped.
+namespace mxr {
+constexpr int KT = 128, ROWB = 64;
+constexpr int CODES = (mx::BM + mx::BN) * ROWB;              // 32 KB
+constexpr int STAGE = CODES + 2 * (mx::BM + mx::BN) * 4;     // + decoded scales [2 blocks][512 rows]
+constexpr int LDS_BYTES = 2 * STAGE;                         // 72 KB (>= the 64 KB the fp32 epilogue borrows)
+}  // namespace mxr
+
+template <int OUT_DT, int B>
+__global__ __launch_bounds__(256) void gemm_nt_fp4_rescale_kernel(GemmArgs P)
+{
+    using namespace mx;
+    using namespace mxr;
+    static_assert(B == 64 || B == 128, "blocks that are whole MFMA steps");
+    constexpr int NBLK = KT / B;  // blocks per K tile
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int r = lane & 31, g = lane >> 5;
+    const int ntx = (int)((P.N + BN - 1) / BN), nty = (int)((P.M + BM - 1) / BM);
+    int ty, tx;
+    tile_coords((int)blockIdx.x, ntx, nty, ty, tx);
+    const int64_t m0 = (int64_t)ty * BM, n0 = (int64_t)tx * BN;
+    const int64_t Kb = P.K >> 1, Ks = P.K / B;
+    const int nkt = (int)(P.K / KT);
+
+    float16v_t acc[TA][TB];
+#pragma unroll
+    for (int a = 0; a < TA; ++a)
+#pragma unroll
+        for (int b = 0; b < TB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+
+    // ---- global -> registers -> LDS: thread t stages chunks t, t + 256, t + 512, t + 768 (row = chunk / 4) of each operand
+    uint4 ga[4], gb[4];
+    float gsa[NBLK], gsb[NBLK];
+    const uint8_t *pA[4], *pB[4];
+    int ldsW[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int qd = tid + NT * u, row = qd >> 2, c = qd & 3;
+        const int64_t ar = m0 + row < P.M ? m0 + row : P.M - 1, br = n0 + row < P.N ? n0 + row : P.N - 1;
+        pA[u] = P.A_codes + ar * Kb + c * 16;
+        pB[u] = P.B_codes + br * Kb + c * 16;
+        ldsW[u] = row * ROWB + ((c ^ ((row >> 2) & 3)) << 4);
+    }
+    const int64_t sar = m0 + tid < P.M ? m0 + tid : P.M - 1, sbr = n0 + tid < P.N ? n0 + tid : P.N - 1;
+    auto fetch = [&](int kt) {
+        const int64_t kb = (int64_t)kt * ROWB;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            ga[u] = *reinterpret_cast<const uint4 *>(pA[u] + kb);
+            gb[u] = *reinterpret_cast<const uint4 *>(pB[u] + kb);
+        }
+#pragma unroll
+        for (int q = 0; q < NBLK; ++q) {
+            gsa[q] = e4m3_decode(P.A_scales[sar * Ks + (int64_t)kt * NBLK + q]);
+            gsb[q] = e4m3_decode(P.B_scales[sbr * Ks + (int64_t)kt * NBLK + q]);
+        }
+    };
+    auto stash = [&](int stage) {
+        uint8_t *base = lds + stage * STAGE;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            *reinterpret_cast<uint4 *>(base + ldsW[u]) = ga[u];
+            *reinterpret_cast<uint4 *>(base + BM * ROWB + ldsW[u]) = gb[u];
+        }
+        float *sS = reinterpret_cast<float *>(base + CODES);
+#pragma unroll
+        for (int q = 0; q < NBLK; ++q) {
+            sS[q * (BM + BN) + tid] = gsa[q];
+            sS[q * (BM + BN) + BM + tid] = gsb[q];
+        }
+    };
+
+    const int sw = (r >> 2) & 3;
+    // one K tile: per step the 8 fragments, per block the lane's scales (its row of each A fragment, its 16 columns of
+    // each B fragment), then 16 tiles of MFMA (+ MFMA) and rescale
+    auto tile = [&](int stage) {
+        const uint8_t *cbase = lds + stage * STAGE;
+        const float *sS = reinterpret_cast<const float *>(cbase + CODES);
+        // the A fragments of both steps stay in registers; B fragments and B scales are fetched per column of tiles
+        uint4 fa[2][TA];
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int a = 0; a < TA; ++a)
+                fa[s][a] = *reinterpret_cast<const uint4 *>(cbase + (((2 * s + g) ^ sw) << 4) + (wm * 128 + 32 * a + r) * ROWB);
+#pragma unroll
+        for (int q = 0; q < NBLK; ++q) {
+            float sa[TA];
+#pragma unroll
+            for (int a = 0; a < TA; ++a) sa[a] = sS[q * (BM + BN) + wm * 128 + 32 * a + r];
+#pragma unroll
+            for (int b = 0; b < TB; ++b) {
+                float4 sb[4];
+#pragma unroll
+                for (int c4 = 0; c4 < 4; ++c4)
+                    sb[c4] = *reinterpret_cast<const float4 *>(&sS[q * (BM + BN) + BM + wn * 128 + 32 * b + 8 * c4 + 4 * g]);
+                uint4 fb[2];
+#pragma unroll
+                for (int s = 0; s < 2; ++s)
+                    fb[s] = *reinterpret_cast<const uint4 *>(cbase + (((2 * s + g) ^ sw) << 4) + (BM + wn * 128 + 32 * b + r) * ROWB);
+#pragma unroll
+                for (int a = 0; a < TA; ++a) {
+                    float16v_t t;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) t[v] = 0.0f;
+                    // B = 128: both steps belong to the one block; B = 64: step q is block q
+#pragma unroll
+                    for (int s = (B == 128 ? 0 : q); s < (B == 128 ? 2 : q + 1); ++s) {
+                        const int8v_t va = {(int)fa[s][a].x, (int)fa[s][a].y, (int)fa[s][a].z, (int)fa[s][a].w, 0, 0, 0, 0};
+                        const int8v_t vb = {(int)fb[s].x, (int)fb[s].y, (int)fb[s].z, (int)fb[s].w, 0, 0, 0, 0};
+                        t = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(vb, va, t, 4, 4, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);
+                    }
+#pragma unroll
+                    for (int c4 = 0; c4 < 4; ++c4) {
+                        acc[a][b][4 * c4 + 0] = __builtin_fmaf(t[4 * c4 + 0], sa[a] * sb[c4].x, acc[a][b][4 * c4 + 0]);
+                        acc[a][b][4 * c4 + 1] = __builtin_fmaf(t[4 * c4 + 1], sa[a] * sb[c4].y, acc[a][b][4 * c4 + 1]);
+                        acc[a][b][4 * c4 + 2] = __builtin_fmaf(t[4 * c4 + 2], sa[a] * sb[c4].z, acc[a][b][4 * c4 + 2]);
+                        acc[a][b][4 * c4 + 3] = __builtin_fmaf(t[4 * c4 + 3], sa[a] * sb[c4].w, acc[a][b][4 * c4 + 3]);
+                    }
+                }
+            }
+        }
+    };
+
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    for (int kt = 0; kt < nkt; ++kt) {
+        const int stage = kt & 1;
+        const bool more = kt + 1 < nkt;
+        if (more) fetch(kt + 1);
+        tile(stage);
+        if (more) stash(stage ^ 1);  // the other stage: every wave finished reading it before the previous barrier
+        __syncthreads();
+    }
+    mx_store_tile<OUT_DT>(P, acc, m0, n0, lane, wave, lds);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Main kernel (K a multiple of 128 and at least 512, 16-byte aligned codes): four LDS stages of
 // 128 contraction elements, every byte written by direct global -> LDS loads, three K tiles in
 // flight, one barrier per tile, no VALU work in the loop except eight scale shifts per tile.
@@ -569,6 +723,39 @@ static void launch_mx_fallback(const GemmArgs &P, int out_dt, hipStream_t st)
         (void)once;
         hipLaunchKernelGGL(k, dim3(ntiles), dim3(256), mxf::LDS_BYTES, st, P);
     }
+}
+
+template <int B>
+static void launch_rescale(const GemmArgs &P, int out_dt, hipStream_t st)
+{
+    const unsigned ntiles = (unsigned)(((P.N + mx::BN - 1) / mx::BN) * ((P.M + mx::BM - 1) / mx::BM));
+    if (out_dt == NVFP4_F32) {
+        auto k = gemm_nt_fp4_rescale_kernel<NVFP4_F32, B>;
+        static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, mxr::LDS_BYTES), true);
+        (void)once;
+        hipLaunchKernelGGL(k, dim3(ntiles), dim3(256), mxr::LDS_BYTES, st, P);
+    } else {
+        auto k = gemm_nt_fp4_rescale_kernel<NVFP4_BF16, B>;
+        static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, mxr::LDS_BYTES), true);
+        (void)once;
+        hipLaunchKernelGGL(k, dim3(ntiles), dim3(256), mxr::LDS_BYTES, st, P);
+    }
+}
+
+// E4M3 scales at blocks of 64 / 128 on the FP4 matrix instruction with binary32 rescaling of the block sums.
+bool fp4_rescale_gemm_applies(int64_t K, int block, const GemmArgs &P)
+{
+    const uintptr_t codes = reinterpret_cast<uintptr_t>(P.A_codes) | reinterpret_cast<uintptr_t>(P.B_codes);
+    return (block == 64 || block == 128) && K % 128 == 0 && (codes & 15) == 0 && !P.a_slab && !P.b_slab;
+}
+
+hipError_t launch_gemm_fp4_rescale(const GemmArgs &P, int block, int out_dt, hipStream_t st)
+{
+    if (block == 64)
+        launch_rescale<64>(P, out_dt, st);
+    else
+        launch_rescale<128>(P, out_dt, st);
+    return hipGetLastError();
 }
 
 // The shapes the direct-to-LDS kernel serves (given 16-byte aligned codes and 4-byte aligned scales); it is also the

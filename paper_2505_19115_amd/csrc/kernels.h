@@ -133,6 +133,12 @@ hipError_t launch_swiglu_bwd_dual(DualArgs &g, DualArgs &u, int dt, int block, i
 hipError_t launch_swiglu_bwd(const void *dH, const void *G, const void *U, int dt, int64_t n, void *dG, void *dU, hipStream_t st);
 hipError_t launch_gemm(const GemmArgs &P, int block, int sf, int out_dt, hipStream_t st);
 hipError_t launch_gemm_mxfp4(const GemmArgs &P, int out_dt, hipStream_t st);  // block 32, E8M0
+// E4M3 scales at blocks of 64 / 128 as unit-scale FP4 MFMAs per block + binary32 rescale (row-major operands, K % 128 == 0)
+bool fp4_rescale_gemm_applies(int64_t K, int block, const GemmArgs &P);
+hipError_t launch_gemm_fp4_rescale(const GemmArgs &P, int block, int out_dt, hipStream_t st);
+// Which of the two exact routes launch_gemm() takes for those formats: 0 = expanded to fp16 (the NVFP4 kernel), 1 = this one
+void set_fp4_rescale_route(int on);
+int fp4_rescale_route();
 bool mxfp4_gemm_takes_slabs(int64_t K);  // MXFP4: the codes of an operand may come as slabs (its scales stay row-major)
 // Noise statistics: per-workgroup partial pairs (quant_noise_partials() of them), folded into sums[2].
 int64_t quant_noise_partials(int64_t rows, int64_t cols, int axis);

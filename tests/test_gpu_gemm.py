@@ -120,6 +120,30 @@ def test_wider_blocks(block):
     check(oracle.quantize(X, 1, 0, 0, ofmt(fmt)), oracle.quantize(W, 1, 0, 0, ofmt(fmt)), fmt, f"block{block}-real")
 
 
+@pytest.mark.parametrize("block", [64, 128])
+@pytest.mark.parametrize("shape", [(256, 256, 128), (200, 136, 384), (1, 1, 128), (130, 257, 640), (520, 300, 1024), (2900, 3000, 256)])
+def test_wide_blocks_on_the_fp4_instruction(block, shape, switches):
+    # E4M3 scales at blocks of 64 / 128: unit-scale FP4 matrix instructions per block, each block's exact partial sum
+    # scaled by sA * sB in binary32 -- against the oracle at 1e-5 (every scale byte from the smallest subnormal to
+    # 448), ragged tiles, 1 to 8 K tiles; and against the fp16 route, which must agree to rounding order
+    M, N, K = shape
+    fmt = nv.Format(block, nv.SCALE_E4M3, 1)
+    rng = np.random.default_rng(M + N + K + block)
+    A, B = random_operand(rng, M, K, block, g=0.37), random_operand(rng, N, K, block, g=2.5e-3)
+    nv.cross_check_switches(nv.SWITCH_FP4_WIDE_BLOCKS)
+    Y = check(A, B, fmt, f"fp4-rescale-b{block}")
+    Yb = check(A, B, fmt, f"fp4-rescale-b{block}-bf16", out_dtype=torch.bfloat16)
+    nv.cross_check_switches(0)
+    Y16 = check(A, B, fmt, f"f16-route-b{block}")
+    ref_abs = oracle.gemm_nt(A, B, ofmt(fmt), take_abs=True)
+    assert np.all(np.abs(to_np(Y).astype(np.float64) - to_np(Y16).astype(np.float64)) <= 2e-5 * ref_abs + 1e-300)
+    # unit scales: exact integers on this route too
+    U = (A[0], np.full_like(A[1], 0x38), 1.0), (B[0], np.full_like(B[1], 0x38), 1.0)
+    nv.cross_check_switches(nv.SWITCH_FP4_WIDE_BLOCKS)
+    Yu = to_np(nv.gemm(dev(U[0]), dev(U[1]), fmt))
+    assert np.array_equal(Yu.astype(np.float64), oracle.gemm_nt(U[0], U[1], ofmt(fmt)))
+
+
 def test_bf16_output_and_leading_dimension():
     rng = np.random.default_rng(9)
     A, B = random_operand(rng, 96, 256, lo=0x30, hi=0x40), random_operand(rng, 80, 256, lo=0x30, hi=0x40)
