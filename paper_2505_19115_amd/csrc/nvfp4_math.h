@@ -52,22 +52,17 @@ NVFP4_HD float e4m3_decode(uint32_t byte)
     return u2f(((e + 120u) << 23) | (m << 20));
 }
 
-// E8M0 shared exponent of a block with maximum a > 0 (MXFP4, Sec. 3): byte =
+// E8M0 shared exponent of a block with maximum a >= 0, finite (MXFP4, Sec. 3): byte =
 // clamp(floor(log2 a) - 2 + 127, 0, 254); *q = 2^(127 - byte) maps the block onto E2M1's range.
+// With ex the biased binary32 exponent of a, floor(log2 a) = ex - 127 for a normal a, so the byte is ex - 2;
+// ex <= 2 (which includes every subnormal a, whose logarithm is below -126, and a = 0) clamps to byte 0, and the
+// upper clamp is never reached (ex <= 254).  No branch, no leading-zero count.  q is at least 2^-125: normal.
 NVFP4_HD uint32_t e8m0_encode(float a, float *q)
 {
-    uint32_t bits = f2u(a);
-    int ex = (int)(bits >> 23);  // biased exponent; 0 for subnormal a
-    int fl;                      // floor(log2 a)
-    if (ex == 0)
-        fl = -127 - __builtin_clz(bits << 9);  // leading mantissa bit at position 22-clz
-    else
-        fl = ex - 127;
-    int biased = fl - 2 + 127;
-    biased = biased < 0 ? 0 : (biased > 254 ? 254 : biased);
-    int qe = 127 - biased + 127;  // biased exponent of q, in [0, 254]
-    *q = qe == 0 ? u2f(0x00400000u) /* 2^-127 */ : u2f((uint32_t)qe << 23);
-    return (uint32_t)biased;
+    const uint32_t ex = f2u(a) >> 23;
+    const uint32_t byte = (ex > 2u ? ex : 2u) - 2u;
+    *q = u2f((254u - byte) << 23);
+    return byte;
 }
 
 // Round-to-nearest-even of m in [0, 6] onto the E2M1 magnitudes {0,.5,1,1.5,2,3,4,6}.

@@ -98,6 +98,8 @@ struct Chunk<NVFP4_BF16> {
         raw = make_uint4(w[0], w[1], w[2], w[3]);
     }
     __device__ __forceinline__ void launder() { asm volatile("" : "+v"(raw.x), "+v"(raw.y), "+v"(raw.z), "+v"(raw.w)); }
+    // elements 2i (low half) and 2i + 1 (high half) as stored
+    __device__ __forceinline__ uint32_t word(int i) const { return i == 0 ? raw.x : i == 1 ? raw.y : i == 2 ? raw.z : raw.w; }
     __device__ __forceinline__ float get(int t) const
     {
         uint32_t w = t < 2 ? raw.x : t < 4 ? raw.y : t < 6 ? raw.z : raw.w;
@@ -141,6 +143,7 @@ struct Chunk<NVFP4_F32> {
         *reinterpret_cast<float4 *>(p + 4) = hi;
     }
     __device__ __forceinline__ void launder() {}
+    __device__ __forceinline__ uint32_t word(int) const { return 0; }  // (bf16 chunks only)
     __device__ __forceinline__ float get(int t) const
     {
         switch (t) {
@@ -163,6 +166,28 @@ __device__ __forceinline__ float chunk_amax(const Chunk<DT> &c)
 #pragma unroll
     for (int t = 0; t < 8; ++t) a = fmaxf(a, fabsf(c.get(t)));
     return a;
+}
+
+// The same on a bf16 chunk as stored: magnitudes of finite bf16 values order like their bit patterns, so the
+// maximum is taken on packed 16-bit integers, two elements per instruction, and widened once at the end.
+typedef uint16_t u16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pk_umax16(uint32_t a, uint32_t b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, a), __builtin_bit_cast(u16x2_t, b)));
+}
+// the two halves of a packed maximum as binary32 (even element, odd element)
+__device__ __forceinline__ float pk_even(uint32_t m) { return u2f(m << 16); }
+__device__ __forceinline__ float pk_odd(uint32_t m) { return u2f(m & 0xFFFF0000u); }
+template <int DT>
+__device__ __forceinline__ float chunk_amax_packed(const Chunk<DT> &c)
+{
+    if constexpr (DT == NVFP4_BF16) {
+        const uint32_t m = pk_umax16(pk_umax16(c.word(0) & 0x7FFF7FFFu, c.word(1) & 0x7FFF7FFFu),
+                                     pk_umax16(c.word(2) & 0x7FFF7FFFu, c.word(3) & 0x7FFF7FFFu));
+        return u2f(umax(m << 16, m & 0xFFFF0000u));
+    } else {
+        return chunk_amax(c);
+    }
 }
 
 // Per-tensor scale as the kernels see it: none, preset in memory, or the bit pattern of the
@@ -191,7 +216,7 @@ __device__ __forceinline__ float resolve_g(const QuantArgs &P)
 }
 
 // Block scale byte and the multiplier q that maps the block onto the E2M1 range.
-// q = 0 for a block whose magnitudes are all zero.
+// With E4M3 scales q = 0 for a block whose magnitudes are all zero.
 // HW: the E4M3 byte and its value come from the gfx950 FP8 converts (OCP E4M3, round to nearest
 // even; the input is clamped to 448 first, as in the software encode, so the convert never sees
 // an out-of-range value).  Checked against e4m3_encode / e4m3_decode on every non-negative fp32
@@ -242,10 +267,7 @@ __device__ __forceinline__ uint32_t block_scale(float a, float g, float k, float
         *q = zero ? 0.0f : r;
         return byte;
     } else {
-        if (a == 0.0f) {
-            *q = 0.0f;
-            return 0u;
-        }
+        // (an all-zero block: byte 0, and its zeros times any finite q are zeros of the same sign)
         return e8m0_encode(a, q);
     }
 }
@@ -323,6 +345,94 @@ __device__ __forceinline__ uint32_t sr_chunk_hw(const Chunk<DT> &v, float q, con
     lo = sr_elem0<3>(lo, v.get(6) * q, sr_seed0(n3, 0));
     hi = sr_elem0<3>(hi, v.get(7) * q, sr_seed0(n3, 1));
     return lo | (hi << 4);
+}
+
+// ---- MXFP4 through the converts' own scale operand.
+// The gfx950 FP4 converts divide the source by a power of two taken from the exponent field of a binary32 "scale"
+// operand before rounding.  An E8M0 block scale byte b is exactly such a power (2^(b - 127), also for b = 0), so
+// the operand is b << 23 and the element needs no multiply; a bf16 source goes in as stored, two elements per
+// register, with no unpacking either.  (With E4M3 block scales the multiplier 1 / (s g) is no power of two and
+// the elements are multiplied in binary32 first, as above.)
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float mx_scale_operand(uint32_t byte) { return u2f(byte << 23); }
+
+template <int BYTE>
+__device__ __forceinline__ uint32_t mx_pair_bf16(uint32_t acc, uint32_t w, float sc)
+{
+    return __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(acc, __builtin_bit_cast(bf16x2_t, w), sc, BYTE);
+}
+// elements 2 BYTE and 2 BYTE + 1 of a chunk -> byte BYTE of acc, round to nearest
+template <int DT, int BYTE>
+__device__ __forceinline__ uint32_t mx_rtn_pair(uint32_t acc, const Chunk<DT> &v, float sc)
+{
+    if constexpr (DT == NVFP4_BF16)
+        return mx_pair_bf16<BYTE>(acc, v.word(BYTE), sc);
+    else
+        return __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(acc, v.get(2 * BYTE), v.get(2 * BYTE + 1), sc, BYTE);
+}
+// rows R and R + 1 of column c of a lane tile -> byte BYTE of acc, round to nearest
+template <int DT, int BYTE>
+__device__ __forceinline__ uint32_t mx_rtn_rows(uint32_t acc, const Chunk<DT> &top, const Chunk<DT> &bot, int c, float sc)
+{
+    if constexpr (DT == NVFP4_BF16) {
+        const uint32_t w = __builtin_amdgcn_perm(bot.word(c >> 1), top.word(c >> 1), (c & 1) ? 0x07060302u : 0x05040100u);
+        return mx_pair_bf16<BYTE>(acc, w, sc);
+    } else {
+        return __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(acc, top.get(c), bot.get(c), sc, BYTE);
+    }
+}
+// Stochastic rounding of element t of a chunk through slot 0 of the convert (see sr_elem0) -> low nibble of byte
+// BYTE of acc.  (Inline assembly for the same reason as above: the accumulator must be tied to the destination.)
+// Always the binary32-source convert: the bf16-source form of the stochastic convert does not consume the 16
+// random bits the way the binary32 form does (measured: 0.6 % of the codes of a bf16 tensor differ, all of them
+// elements that land between 0 and 0.5), so a bf16 element is widened first; only the multiply is saved.
+template <int DT, int BYTE>
+__device__ __forceinline__ uint32_t mx_sr_elem0(uint32_t acc, const Chunk<DT> &v, int t, uint32_t seed, float sc)
+{
+    typedef float float2_t __attribute__((ext_vector_type(2)));
+    const float2_t p = float2_t{v.get(t), 0.0f};
+    if (BYTE == 0) asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, %3" : "+v"(acc) : "v"(p), "v"(seed), "v"(sc));
+    if (BYTE == 1) asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, %3 op_sel:[0,0,1,0]" : "+v"(acc) : "v"(p), "v"(seed), "v"(sc));
+    if (BYTE == 2) asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, %3 op_sel:[0,0,0,1]" : "+v"(acc) : "v"(p), "v"(seed), "v"(sc));
+    if (BYTE == 3) asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, %3 op_sel:[0,0,1,1]" : "+v"(acc) : "v"(p), "v"(seed), "v"(sc));
+    return acc;
+}
+template <int DT>
+__device__ __forceinline__ uint32_t mx_sr_chunk(const Chunk<DT> &v, float sc, const u32x4 &d)
+{
+    const uint32_t n0 = ~d.x, n1 = ~d.y, n2 = ~d.z, n3 = ~d.w;
+    uint32_t lo = 0, hi = 0;
+    lo = mx_sr_elem0<DT, 0>(lo, v, 0, sr_seed0(n0, 0), sc);
+    hi = mx_sr_elem0<DT, 0>(hi, v, 1, sr_seed0(n0, 1), sc);
+    lo = mx_sr_elem0<DT, 1>(lo, v, 2, sr_seed0(n1, 0), sc);
+    hi = mx_sr_elem0<DT, 1>(hi, v, 3, sr_seed0(n1, 1), sc);
+    lo = mx_sr_elem0<DT, 2>(lo, v, 4, sr_seed0(n2, 0), sc);
+    hi = mx_sr_elem0<DT, 2>(hi, v, 5, sr_seed0(n2, 1), sc);
+    lo = mx_sr_elem0<DT, 3>(lo, v, 6, sr_seed0(n3, 0), sc);
+    hi = mx_sr_elem0<DT, 3>(hi, v, 7, sr_seed0(n3, 1), sc);
+    return lo | (hi << 4);
+}
+// 8 elements of a row, rounding RND, MX (scale operand) or multiplier form
+template <int DT, int RND, bool MXS>
+__device__ __forceinline__ uint32_t chunk_codes_hw(const Chunk<DT> &v, float q, uint32_t seed, uint64_t ctr)
+{
+    uint32_t packed = 0;
+    if constexpr (RND == NVFP4_RTN && MXS) {
+        packed = mx_rtn_pair<DT, 0>(packed, v, q);
+        packed = mx_rtn_pair<DT, 1>(packed, v, q);
+        packed = mx_rtn_pair<DT, 2>(packed, v, q);
+        packed = mx_rtn_pair<DT, 3>(packed, v, q);
+    } else if constexpr (RND == NVFP4_RTN) {
+        packed = quant_pair_hw<0>(packed, v.get(0), v.get(1), q);
+        packed = quant_pair_hw<1>(packed, v.get(2), v.get(3), q);
+        packed = quant_pair_hw<2>(packed, v.get(4), v.get(5), q);
+        packed = quant_pair_hw<3>(packed, v.get(6), v.get(7), q);
+    } else if constexpr (MXS) {
+        packed = mx_sr_chunk(v, q, sr_draw(seed, ctr));
+    } else {
+        packed = sr_chunk_hw(v, q, sr_draw(seed, ctr));
+    }
+    return packed;
 }
 
 // ------------------------------------------------------------------ tensor maximum (Q0)
@@ -438,6 +548,7 @@ template <int DT, int B, int SF, int RND, bool HW>
 __global__ __launch_bounds__(256) void quantize_rows_kernel(QuantArgs P)
 {
     constexpr int LPB = B / 8;  // lanes per block
+    constexpr bool MXS = HW && SF == NVFP4_SCALE_E8M0;  // block scale as the convert's scale operand
     const int64_t cpr = P.cols >> 3;
     const int64_t total = P.rows * cpr;
     const int64_t base = (int64_t)blockIdx.x * (256 * ROWS_UNROLL) + threadIdx.x;
@@ -467,17 +578,13 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(QuantArgs P)
         const int64_t id = base + u * 256;
         // a whole block is in or out of range together, so the lanes exchanged below are
         // either all live or all holding zeros
-        const float a = group_max<LPB>(chunk_amax(v[u]));
+        const float a = group_max<LPB>(MXS ? chunk_amax_packed(v[u]) : chunk_amax(v[u]));
         float q;
         const uint32_t sbyte = block_scale<SF, HW, HW && SF == NVFP4_SCALE_E4M3>(a, g, k, &q);
         uint32_t packed = 0;
-        if (RND == NVFP4_RTN && HW) {
-            packed = quant_pair_hw<0>(packed, v[u].get(0), v[u].get(1), q);
-            packed = quant_pair_hw<1>(packed, v[u].get(2), v[u].get(3), q);
-            packed = quant_pair_hw<2>(packed, v[u].get(4), v[u].get(5), q);
-            packed = quant_pair_hw<3>(packed, v[u].get(6), v[u].get(7), q);
-        } else if (RND == NVFP4_SR && HW) {
-            packed = sr_chunk_hw(v[u], q, sr_draw(P.seed, (uint64_t)id));  // element index = 8*id + t
+        if (HW) {
+            if (MXS) q = mx_scale_operand(sbyte);
+            packed = chunk_codes_hw<DT, RND, MXS>(v[u], q, P.seed, (uint64_t)id);  // element index = 8*id + t
         } else {
             u32x4 d = {0, 0, 0, 0};
             if (RND == NVFP4_SR) d = sr_draw(P.seed, (uint64_t)id);  // element index = 8*id + t
@@ -536,7 +643,8 @@ __device__ __forceinline__ uint32_t col_bits(const u32x4 &d0, const u32x4 &d1, u
 // ALIGNED (every row holds a whole number of draws and the lane's 8 columns are one of them): ctr is the draw
 // counter of row row0 + R at the lane's columns and cstep = cols / 8 the distance to the next row's, both carried
 // along instead of being recomputed from 64-bit element indices for every row.
-template <int DT, int RND, bool ALIGNED, int BL, int R>
+// MXS: q holds the converts' scale operands instead of multipliers.
+template <int DT, int RND, bool ALIGNED, int BL, int R, bool MXS>
 __device__ __forceinline__ void col_sr_hw(const QuantArgs &P, Chunk<DT> (&v)[16], float (&q)[8][16 / BL],
                                           int64_t row0, int64_t col0, uint32_t (&weven)[8][2],
                                           uint32_t (&wodd)[8][2], uint64_t ctr, uint64_t cstep)
@@ -554,8 +662,13 @@ __device__ __forceinline__ void col_sr_hw(const QuantArgs &P, Chunk<DT> (&v)[16]
             const uint32_t na[4] = {~a0.x, ~a0.y, ~a0.z, ~a0.w}, nb[4] = {~b0.x, ~b0.y, ~b0.z, ~b0.w};
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
-                weven[c][R / 8] = sr_elem0<(R % 8) / 2>(weven[c][R / 8], v[R].get(c) * q[c][R / BL], sr_seed0(na[c / 2], c & 1));
-                wodd[c][R / 8] = sr_elem0<(R % 8) / 2>(wodd[c][R / 8], v[R + 1].get(c) * q[c][(R + 1) / BL], sr_seed0(nb[c / 2], c & 1));
+                if constexpr (MXS) {
+                    weven[c][R / 8] = mx_sr_elem0<DT, (R % 8) / 2>(weven[c][R / 8], v[R], c, sr_seed0(na[c / 2], c & 1), q[c][R / BL]);
+                    wodd[c][R / 8] = mx_sr_elem0<DT, (R % 8) / 2>(wodd[c][R / 8], v[R + 1], c, sr_seed0(nb[c / 2], c & 1), q[c][(R + 1) / BL]);
+                } else {
+                    weven[c][R / 8] = sr_elem0<(R % 8) / 2>(weven[c][R / 8], v[R].get(c) * q[c][R / BL], sr_seed0(na[c / 2], c & 1));
+                    wodd[c][R / 8] = sr_elem0<(R % 8) / 2>(wodd[c][R / 8], v[R + 1].get(c) * q[c][(R + 1) / BL], sr_seed0(nb[c / 2], c & 1));
+                }
             }
         } else {
 #pragma unroll
@@ -566,20 +679,24 @@ __device__ __forceinline__ void col_sr_hw(const QuantArgs &P, Chunk<DT> (&v)[16]
                                                             col_bits<ALIGNED>(b0, b1, sb, c));
             }
         }
-        col_sr_hw<DT, RND, ALIGNED, BL, R + 2>(P, v, q, row0, col0, weven, wodd, ctr + 2 * cstep, cstep);
+        col_sr_hw<DT, RND, ALIGNED, BL, R + 2, MXS>(P, v, q, row0, col0, weven, wodd, ctr + 2 * cstep, cstep);
     }
 }
 
 // Round-to-nearest of a lane's 16 x 8 tile through the hardware convert: rows R and R + 1 of a column share a
 // byte, which the convert writes in place (its byte select must be a constant, hence the recursion over row pairs).
-template <int DT, int BL, int R>
+template <int DT, int BL, int R, bool MXS>
 __device__ __forceinline__ void col_rtn_hw(Chunk<DT> (&v)[16], float (&q)[8][16 / BL], uint32_t (&words)[8][2])
 {
     if constexpr (R < 16) {
 #pragma unroll
-        for (int c = 0; c < 8; ++c)
-            words[c][R / 8] = quant_pair_hw<(R % 8) / 2>(words[c][R / 8], v[R].get(c), v[R + 1].get(c), q[c][R / BL]);
-        col_rtn_hw<DT, BL, R + 2>(v, q, words);
+        for (int c = 0; c < 8; ++c) {
+            if constexpr (MXS)
+                words[c][R / 8] = mx_rtn_rows<DT, (R % 8) / 2>(words[c][R / 8], v[R], v[R + 1], c, q[c][R / BL]);
+            else
+                words[c][R / 8] = quant_pair_hw<(R % 8) / 2>(words[c][R / 8], v[R].get(c), v[R + 1].get(c), q[c][R / BL]);
+        }
+        col_rtn_hw<DT, BL, R + 2, MXS>(v, q, words);
     }
 }
 
@@ -642,18 +759,43 @@ __device__ __forceinline__ void cols_tile(const QuantArgs &P, Chunk<DT> (&v)[16]
     const int64_t nblk = P.rows / B;
 
     // pass 1: block maxima -> scale bytes and multipliers, per column and per block part
+    // MXS: the multipliers are replaced by the converts' scale operands, and an unaligned tile (whose stochastic
+    // rounding goes through the two-slot form) keeps multipliers.
+    constexpr bool MXS = HW && SF == NVFP4_SCALE_E8M0 && (ALIGNED || RND == NVFP4_RTN);
     float q[8][NB];
     uint32_t sbytes[8][NB];
+    if constexpr (MXS && DT == NVFP4_BF16) {
+        // maxima on the packed bf16 magnitudes, two columns per instruction
 #pragma unroll
-    for (int c = 0; c < 8; ++c) {
+        for (int cp = 0; cp < 4; ++cp) {
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            float a = 0.0f;
+            for (int nb = 0; nb < NB; ++nb) {
+                uint32_t m = 0;
 #pragma unroll
-            for (int r = 0; r < BL; ++r) a = fmaxf(a, fabsf(v[nb * BL + r].get(c)));
-            a = group_max<LPB>(a);
-            sbytes[c][nb] = block_scale<SF, HW, HW && SF == NVFP4_SCALE_E4M3>(a, g, k, &q[c][nb]);
+                for (int r = 0; r < BL; ++r) m = pk_umax16(m, v[nb * BL + r].word(cp) & 0x7FFF7FFFu);
+                const float a0 = group_max<LPB>(pk_even(m)), a1 = group_max<LPB>(pk_odd(m));
+                sbytes[2 * cp][nb] = block_scale<SF, HW, false>(a0, g, k, &q[2 * cp][nb]);
+                sbytes[2 * cp + 1][nb] = block_scale<SF, HW, false>(a1, g, k, &q[2 * cp + 1][nb]);
+            }
         }
+    } else {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                float a = 0.0f;
+#pragma unroll
+                for (int r = 0; r < BL; ++r) a = fmaxf(a, fabsf(v[nb * BL + r].get(c)));
+                a = group_max<LPB>(a);
+                sbytes[c][nb] = block_scale<SF, HW, HW && SF == NVFP4_SCALE_E4M3>(a, g, k, &q[c][nb]);
+            }
+        }
+    }
+    if constexpr (MXS) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) q[c][nb] = mx_scale_operand(sbytes[c][nb]);
     }
 
     // (the empty asm makes the compiler unpack the raw registers again in pass 2 instead of
@@ -669,7 +811,7 @@ __device__ __forceinline__ void cols_tile(const QuantArgs &P, Chunk<DT> (&v)[16]
         for (int w = 0; w < RPL / 8; ++w) words[c][w] = 0;
 
     if (RND == NVFP4_RTN && HW) {
-        col_rtn_hw<DT, BL, 0>(v, q, words);
+        col_rtn_hw<DT, BL, 0, MXS>(v, q, words);
     } else if (RND == NVFP4_SR && HW) {
         // rows 2p and 2p+1 of a column share a byte: even rows go through slot 0, odd rows
         // through slot 1 of the convert, into two sets of words that are OR-ed at the end
@@ -679,7 +821,7 @@ __device__ __forceinline__ void cols_tile(const QuantArgs &P, Chunk<DT> (&v)[16]
 #pragma unroll
             for (int w = 0; w < RPL / 8; ++w) wodd[c][w] = 0;
         const uint64_t cstep = (uint64_t)P.cols >> 3;
-        col_sr_hw<DT, RND, ALIGNED, BL, 0>(P, v, q, row0, col0, words, wodd, (uint64_t)row0 * cstep + ((uint64_t)col0 >> 3), cstep);
+        col_sr_hw<DT, RND, ALIGNED, BL, 0, MXS>(P, v, q, row0, col0, words, wodd, (uint64_t)row0 * cstep + ((uint64_t)col0 >> 3), cstep);
 #pragma unroll
         for (int c = 0; c < 8; ++c)
 #pragma unroll
@@ -713,6 +855,26 @@ __device__ __forceinline__ void cols_tile(const QuantArgs &P, Chunk<DT> (&v)[16]
         }
     }
 
+    // Scale bytes, row-major [cols, rows / B]: the eight lanes stacked vertically hold consecutive bytes of a column's
+    // row (blocks of 16: one per lane, 8 per workgroup tile; blocks of 32: one per pair of lanes, 4 per tile).  Where
+    // the rows allow, four bytes are gathered into the lowest of their lanes through DPP row shifts (lane + n; every
+    // lane takes part) and leave as one aligned dword instead of single bytes.
+    constexpr bool GATHER = RPL == 16 && LV == 8 && NB == 1 && (B == 16 || B == 32);
+    constexpr int GSTEP = B == 16 ? 1 : 2;  // lanes between consecutive bytes
+    uint32_t sw[8];
+    bool wide = false, owner = false;
+    if constexpr (GATHER) {
+        // (the whole 128-row tile inside the tensor, whole dwords per tile, aligned rows of the scale matrix)
+        wide = (nblk & 3) == 0 && (reinterpret_cast<uintptr_t>(P.scales) & 3) == 0 && (row0 - lv * RPL) + G::WG_ROWS <= P.rows;
+        owner = (lv & (4 * GSTEP - 1)) == 0;  // blocks of 16: lanes 0 and 4 of the eight; blocks of 32: lane 0
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            sw[c] = sbytes[c][0];
+            sw[c] |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)sw[c], 0x100 + GSTEP, 0xF, 0xF, true) << 8;       // lane + GSTEP
+            sw[c] |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)sw[c], 0x100 + 2 * GSTEP, 0xF, 0xF, true) << 16;  // lanes + 2, + 3 GSTEP
+        }
+    }
+
     if (RPL == 16 && slab != nullptr) {
         // slab layout (the caller guarantees a lane tile entirely inside the tensor or entirely outside): a store
         // instruction of the wave writes 512 contiguous code bytes and, for blocks of 16, 64 contiguous scale
@@ -721,10 +883,13 @@ __device__ __forceinline__ void cols_tile(const QuantArgs &P, Chunk<DT> (&v)[16]
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
                 store8_stream(slab->codes + 512 * c, words[c][0], words[c][1]);
-                if (B == 16)
+                if (B == 16) {
                     slab->scales[64 * c] = (uint8_t)sbytes[c][0];
-                else if (lv % LPB == 0)
+                } else if (GATHER && wide) {
+                    if (owner) *reinterpret_cast<uint32_t *>(P.scales + (col0 + c) * nblk + row0 / B) = sw[c];
+                } else if (lv % LPB == 0) {
                     P.scales[(col0 + c) * nblk + row0 / B] = (uint8_t)sbytes[c][0];
+                }
             }
         }
         return;
@@ -738,7 +903,9 @@ __device__ __forceinline__ void cols_tile(const QuantArgs &P, Chunk<DT> (&v)[16]
             for (int h = 0; h < RPL / 16; ++h)
                 if (row0 + 16 * h < P.rows)
                     store8_stream(crow + 8 * h, words[c][2 * h], words[c][2 * h + 1]);
-            if (lv % LPB == 0) {
+            if (GATHER && wide) {
+                if (owner) *reinterpret_cast<uint32_t *>(P.scales + col * nblk + row0 / B) = sw[c];
+            } else if (lv % LPB == 0) {
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb)
                     if (row0 + nb * BL < P.rows)
@@ -855,53 +1022,31 @@ hipError_t launch_swiglu_bwd(const void *dH, const void *G, const void *U, int d
 // leave in full lines although the lanes hold the data column-wise.
 // Host guarantees: rows % B == 0, cols % B == 0 (so a lane's 16 x 8 tile is entirely inside or
 // outside the tensor), 16-byte aligned rows of x.
-template <int DT, int B, int SF, int RND_R, int RND_C, int SRC = SRC_TENSOR>
-__global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
+// One workgroup tile (128 rows x 256 columns at tile coordinates tx, ty; the lane's 16 x 8 part of it in v) through
+// both quantizers and out to memory.  Every thread of the workgroup must call it (barriers inside).
+template <int DT, int B, int SF, int RND_R, int RND_C>
+__device__ __forceinline__ void dual_tile(const DualArgs &D, Chunk<DT> (&v)[16], float g, float k, int tx, int ty,
+                                          uint32_t *lds_codes, uint8_t *lds_scales)
 {
     using G = ColGeom<DT, 8>;
-    static_assert(B == 16 || B == 32, "row blocks must fit the 8 column groups of a wave");
     constexpr int LPBR = B / 8;                  // lanes sharing one row block
+    constexpr bool MXS = SF == NVFP4_SCALE_E8M0;  // block scale as the convert's scale operand
     constexpr int ROW_BYTES = G::WG_COLS / 2;    // 128 code bytes per tile row
     constexpr int ROW_SC = G::WG_COLS / B;       // scale bytes per tile row
-    __shared__ __align__(16) uint32_t lds_codes[G::WG_ROWS * ROW_BYTES / 4];
-    __shared__ __align__(16) uint8_t lds_scales[G::WG_ROWS * 16];
-
     const QuantArgs &P = D.c;
-
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int lv = lane % G::LANES_V, lh = lane / G::LANES_V;
-    const int64_t wrow0 = (int64_t)blockIdx.y * G::WG_ROWS, wcol0 = (int64_t)blockIdx.x * G::WG_COLS;
+    const int64_t wrow0 = (int64_t)ty * G::WG_ROWS, wcol0 = (int64_t)tx * G::WG_COLS;
     const int64_t row0 = wrow0 + lv * 16;
     const int64_t col0 = wcol0 + wave * G::WAVE_COLS + lh * 8;
     const bool inside = row0 < P.rows && col0 < P.cols;
-
-    Chunk<DT> v[16];
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        if (!inside)
-            v[r].zero();
-        else if (SRC == SRC_TENSOR)
-            v[r].template load<true>(P.x, (row0 + r) * P.ld + col0);
-        else
-            swiglu_chunk<DT, SRC>(P.x, D.src_g, D.src_u, (row0 + r) * P.ld + col0, &v[r], &v[r]);
-    }
-
-    const float g = resolve_g(P);
-    const float k = 1.0f / (6.0f * g);
-    build_qtab<SF, true>(g);
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
-        // (a `saved` buffer that is not the one this call expects poisons the scale the GEMMs will multiply by)
-        const float g_gemm = tag_apply(D.tag) ? g : __builtin_nanf("");
-        *P.g_out = g_gemm;
-        if (D.g_out2) *D.g_out2 = g_gemm;
-    }
 
     // row-blocked side: one block scale and 8 codes per row of the lane tile
     const uint64_t cstep_r = (uint64_t)P.cols >> 3;
     uint64_t ctr_r = (uint64_t)row0 * cstep_r + ((uint64_t)col0 >> 3);
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-        float a = chunk_amax(v[r]);
+        float a = MXS ? chunk_amax_packed(v[r]) : chunk_amax(v[r]);
         a = dpp_max<0x128>(a);  // row_ror:8 : lane ^ 8, the neighbouring column group
         if (LPBR == 4) {
             const uint32_t o = (uint32_t)__builtin_amdgcn_ds_swizzle((int)f2u(a), 0x401F);  // lane ^ 16
@@ -909,17 +1054,10 @@ __global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
         }
         float q;
         const uint32_t sbyte = block_scale<SF, true, SF == NVFP4_SCALE_E4M3>(a, g, k, &q);
-        uint32_t packed = 0;
-        if (RND_R == NVFP4_RTN) {
-            packed = quant_pair_hw<0>(packed, v[r].get(0), v[r].get(1), q);
-            packed = quant_pair_hw<1>(packed, v[r].get(2), v[r].get(3), q);
-            packed = quant_pair_hw<2>(packed, v[r].get(4), v[r].get(5), q);
-            packed = quant_pair_hw<3>(packed, v[r].get(6), v[r].get(7), q);
-        } else {
-            // (cols is a multiple of the block, col0 of 8: the lane's 8 columns are one draw, cols / 8 draws per row)
-            packed = sr_chunk_hw(v[r], q, sr_draw(D.seed_r, ctr_r));
-            ctr_r += cstep_r;
-        }
+        if (MXS) q = mx_scale_operand(sbyte);
+        // (cols is a multiple of the block, col0 of 8: the lane's 8 columns are one draw, cols / 8 draws per row)
+        const uint32_t packed = chunk_codes_hw<DT, RND_R, MXS>(v[r], q, D.seed_r, ctr_r);
+        ctr_r += cstep_r;
         // tile row R = 16 lv + r holds 32 dwords; dword w is stored at w ^ (4 lv): the 16-byte
         // chunk c of the row sits at chunk c ^ lv, which spreads the 8 rows a wave writes at a
         // time over the banks
@@ -936,7 +1074,7 @@ __global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
     // one tile of operand rows and its 128 rows one K tile: it fills exactly one slab.
     ColSlab cs;
     if (D.slab_c) {
-        const int64_t slab = (int64_t)blockIdx.x * (P.rows / SLAB_K) + blockIdx.y;
+        const int64_t slab = (int64_t)tx * (P.rows / SLAB_K) + ty;
         cs.codes = P.codes + slab * SLAB_CODE_BYTES + wave * 4096 + lane * 8;
         cs.scales = P.scales + slab * SLAB_SCALE_BYTES + wave * 512 + lane;  // (used for blocks of 16 only)
     }
@@ -944,10 +1082,10 @@ __global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
 
     __syncthreads();
     if (D.slab_r) {
-        // slab layout: the tile is rows (wrow0 % 256) .. + 127 of two slabs (K tiles 2 blockIdx.x and + 1 of row
+        // slab layout: the tile is rows (wrow0 % 256) .. + 127 of two slabs (K tiles 2 tx and + 1 of row
         // tile wrow0 / 256).  Threads walk the slab positions q; position q holds tile row slab_row(q).
         const int64_t nkt = P.cols / SLAB_K;
-        const int64_t slab0 = (wrow0 / SLAB_ROWS) * nkt + 2 * (int64_t)blockIdx.x;
+        const int64_t slab0 = (wrow0 / SLAB_ROWS) * nkt + 2 * (int64_t)tx;
         const int half = (int)(wrow0 & 128);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -1004,6 +1142,44 @@ __global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
             }
         }
     }
+}
+
+template <int DT, int B, int SF, int RND_R, int RND_C, int SRC = SRC_TENSOR>
+__global__ __launch_bounds__(256) void quantize_dual_kernel(DualArgs D)
+{
+    using G = ColGeom<DT, 8>;
+    static_assert(B == 16 || B == 32, "row blocks must fit the 8 column groups of a wave");
+    __shared__ __align__(16) uint32_t lds_codes[G::WG_ROWS * (G::WG_COLS / 2) / 4];
+    __shared__ __align__(16) uint8_t lds_scales[G::WG_ROWS * 16];
+
+    const QuantArgs &P = D.c;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lv = lane % G::LANES_V, lh = lane / G::LANES_V;
+    const int64_t row0 = (int64_t)blockIdx.y * G::WG_ROWS + lv * 16;
+    const int64_t col0 = (int64_t)blockIdx.x * G::WG_COLS + wave * G::WAVE_COLS + lh * 8;
+    const bool inside = row0 < P.rows && col0 < P.cols;
+
+    Chunk<DT> v[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        if (!inside)
+            v[r].zero();
+        else if (SRC == SRC_TENSOR)
+            v[r].template load<true>(P.x, (row0 + r) * P.ld + col0);
+        else
+            swiglu_chunk<DT, SRC>(P.x, D.src_g, D.src_u, (row0 + r) * P.ld + col0, &v[r], &v[r]);
+    }
+
+    const float g = resolve_g(P);
+    const float k = 1.0f / (6.0f * g);
+    build_qtab<SF, true>(g);
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+        // (a `saved` buffer that is not the one this call expects poisons the scale the GEMMs will multiply by)
+        const float g_gemm = tag_apply(D.tag) ? g : __builtin_nanf("");
+        *P.g_out = g_gemm;
+        if (D.g_out2) *D.g_out2 = g_gemm;
+    }
+    dual_tile<DT, B, SF, RND_R, RND_C>(D, v, g, k, (int)blockIdx.x, (int)blockIdx.y, lds_codes, lds_scales);
 }
 
 __global__ void saved_tag_kernel(TagArgs t, float *g1, float *g2)
