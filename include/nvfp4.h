@@ -206,29 +206,32 @@ nvfp4_status nvfp4_gemm(int64_t M, int64_t N, int64_t K, const nvfp4_format *f,
                         nvfp4_dtype out_dt, int64_t ldc, void *stream);
 
 /*
- * Slab layout of an NVFP4 operand (block 16, E4M3 scales), an alternative to the
- * row-major [rows, K/2] codes and [rows, K/16] scales above.  (MXFP4 operands,
- * block 32 with E8M0 scales, can use it for their CODES only: same flags, same
- * nvfp4_slab_codes_bytes, while their scales stay row-major [rows, K/32];
- * nvfp4_gemm_takes_slabs then asks for K a multiple of 128 and at least 512.)  It holds the same
- * bytes (same quantization, Sec. 3), arranged the way the large GEMM kernel
- * fetches them: K must be a multiple of 128; the rows are padded to a multiple
- * of 256; codes are [rows/256][K/128] slabs of 16 KB, scales the same grid of
- * 2 KB slabs.  Inside a slab, row r (0..255) of the tile sits at position
+ * Slab layout of an NVFP4 operand (block 16, E4M3 scales) or an MXFP4 operand
+ * (block 32, E8M0 scales), an alternative to the row-major [rows, K/2] codes
+ * and [rows, K/block] scales above.  It holds the same bytes (same
+ * quantization, Sec. 3), arranged the way the large GEMM kernels fetch them: K
+ * must be a multiple of 128; the rows are padded to a multiple of 256; codes
+ * are [rows/256][K/128] slabs of 16 KB, scales the same grid of slabs of 2 KB
+ * (NVFP4: 8 scale bytes per row and K tile) or 1 KB (MXFP4: 4).  Inside a slab,
+ * row r (0..255) of the tile sits at position
  * p(r) = (r & ~63) | ((r & 7) << 3) | ((r >> 3) & 7) and owns 64 code bytes
- * (its 128 elements of that K tile, even element in the low nibble) or 8 scale
- * bytes.  Padding rows are never written and never reach a stored output.
+ * (its 128 elements of that K tile, even element in the low nibble) or its 8
+ * resp. 4 scale bytes.  Padding rows are never written and never reach a
+ * stored output.
  * nvfp4_quantize_dual writes it on request (NVFP4_SLAB_ROWS / NVFP4_SLAB_COLS:
  * the one-pass kernel must apply, i.e. 16-byte aligned rows of x and not SR rows
  * with RtN columns, else NVFP4_EUNSUPPORTED; cols resp. rows a multiple of 128,
- * else NVFP4_ESHAPE); the output buffers then need nvfp4_slab_codes_bytes /
- * nvfp4_slab_scales_bytes (rows = rows of the OPERAND: cols of x for the
- * column-blocked side).  nvfp4_gemm_slab is nvfp4_gemm with either operand in
- * this layout (a_slab, b_slab non-zero); it applies where
- * nvfp4_gemm_takes_slabs returns 1 (NVFP4: K a multiple of 128 and at least 128
- * output tiles of 256 x 256), otherwise NVFP4_EUNSUPPORTED.  The fused linear
- * entries below use the layout internally wherever it applies; results are
- * bit-identical either way.
+ * else NVFP4_ESHAPE); the output
+ * buffers then need nvfp4_slab_codes_bytes / nvfp4_slab_scales_bytes (rows =
+ * rows of the OPERAND: cols of x for the column-blocked side;
+ * nvfp4_slab_scales_bytes is stated for NVFP4, an MXFP4 operand uses the first
+ * half of it).  nvfp4_gemm_slab is nvfp4_gemm with either operand in this
+ * layout (a_slab, b_slab non-zero: codes AND scales of that operand); it
+ * applies where nvfp4_gemm_takes_slabs returns 1 (NVFP4: K a multiple of 128
+ * and at least 128 output tiles of 256 x 256; MXFP4: K a multiple of 128 and at
+ * least 512), otherwise NVFP4_EUNSUPPORTED.  The fused linear entries below use
+ * the layout internally wherever it applies; results are bit-identical either
+ * way.
  */
 size_t nvfp4_slab_codes_bytes(int64_t rows, int64_t K);
 size_t nvfp4_slab_scales_bytes(int64_t rows, int64_t K);

@@ -267,6 +267,12 @@ def cross_check_switches(value: int | None = None) -> int:
     return lib.nvfp4_cross_check_switches(0 if value is None else 1, 0 if value is None else value)
 
 
+def slab_scales_bytes(rows: int, K: int, fmt: Format = NVFP4) -> int:
+    """Bytes of an operand's scale slabs: nvfp4_slab_scales_bytes is stated for blocks of 16 (8 bytes per row and
+    K tile); MXFP4's slabs hold 4 bytes per row and K tile."""
+    return lib.nvfp4_slab_scales_bytes(rows, K) * 16 // fmt.block
+
+
 def quantize_dual(x: torch.Tensor, rounding_rows: int = RTN, seed_rows: int = 0, rounding_cols: int = RTN,
                   seed_cols: int = 0, fmt: Format = NVFP4, tensor_scale: torch.Tensor | None = None, out=None,
                   slab_rows: bool = False, slab_cols: bool = False):
@@ -275,7 +281,7 @@ def quantize_dual(x: torch.Tensor, rounding_rows: int = RTN, seed_rows: int = 0,
 
     `out` = (codes_rows, scales_rows, codes_cols, scales_cols, g) reuses caller-provided tensors.
     slab_rows / slab_cols: that side comes back in the slab layout instead (flat byte tensors of
-    nvfp4_slab_codes_bytes / nvfp4_slab_scales_bytes), for gemm(..., slabs=...).
+    nvfp4_slab_codes_bytes / slab_scales_bytes), for gemm(..., slabs=...).
     """
     _require_gpu(x, tensor_scale)
     assert x.dim() == 2 and (x.stride(1) == 1 or x.shape[1] <= 1)
@@ -289,12 +295,10 @@ def quantize_dual(x: torch.Tensor, rounding_rows: int = RTN, seed_rows: int = 0,
         sc = torch.empty((cols, rows // fmt.block), dtype=torch.uint8, device=x.device)
         if slab_rows:
             cr = torch.empty(lib.nvfp4_slab_codes_bytes(rows, cols), dtype=torch.uint8, device=x.device)
-            if fmt.block == 16:  # (MXFP4 keeps its scales row-major)
-                sr = torch.empty(lib.nvfp4_slab_scales_bytes(rows, cols), dtype=torch.uint8, device=x.device)
+            sr = torch.empty(slab_scales_bytes(rows, cols, fmt), dtype=torch.uint8, device=x.device)
         if slab_cols:
             cc = torch.empty(lib.nvfp4_slab_codes_bytes(cols, rows), dtype=torch.uint8, device=x.device)
-            if fmt.block == 16:
-                sc = torch.empty(lib.nvfp4_slab_scales_bytes(cols, rows), dtype=torch.uint8, device=x.device)
+            sc = torch.empty(slab_scales_bytes(cols, rows, fmt), dtype=torch.uint8, device=x.device)
         g = torch.empty(1, dtype=torch.float32, device=x.device) if tensor_scale is None else tensor_scale
     else:
         cr, sr, cc, sc, g = out
@@ -423,10 +427,8 @@ def empty_dual_operands(rows: int, cols: int, fmt: Format = NVFP4, slab_rows: bo
     u8 = dict(dtype=torch.uint8, device=device)
     cr = torch.empty(lib.nvfp4_slab_codes_bytes(rows, cols), **u8) if slab_rows else torch.empty((rows, cols // 2), **u8)
     cc = torch.empty(lib.nvfp4_slab_codes_bytes(cols, rows), **u8) if slab_cols else torch.empty((cols, rows // 2), **u8)
-    sr = (torch.empty(lib.nvfp4_slab_scales_bytes(rows, cols), **u8) if slab_rows and fmt.block == 16
-          else torch.empty((rows, cols // fmt.block), **u8))
-    sc = (torch.empty(lib.nvfp4_slab_scales_bytes(cols, rows), **u8) if slab_cols and fmt.block == 16
-          else torch.empty((cols, rows // fmt.block), **u8))
+    sr = torch.empty(slab_scales_bytes(rows, cols, fmt), **u8) if slab_rows else torch.empty((rows, cols // fmt.block), **u8)
+    sc = torch.empty(slab_scales_bytes(cols, rows, fmt), **u8) if slab_cols else torch.empty((cols, rows // fmt.block), **u8)
     return DualOperands(cr, sr, cc, sc, torch.empty(1, dtype=torch.float32, device=device),
                         (SLAB_ROWS if slab_rows else 0) | (SLAB_COLS if slab_cols else 0))
 

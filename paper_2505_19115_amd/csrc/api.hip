@@ -497,7 +497,7 @@ nvfp4_status nvfp4_quantize_dual(const void *x, nvfp4_dtype dt_, int64_t rows, i
         return NVFP4_EALIGN;
     const bool slab_r = (flags & NVFP4_SLAB_ROWS) != 0, slab_c = (flags & NVFP4_SLAB_COLS) != 0;
     if (slab_r || slab_c) {
-        // only the one-pass kernel writes slabs, and only NVFP4 operands are read back from them
+        // only the one-pass kernel writes slabs
         const bool slab_format = (f->block == 16 && f->scale == NVFP4_SCALE_E4M3) || (f->block == 32 && f->scale == NVFP4_SCALE_E8M0);
         if (!slab_format || !use_hw_convert() ||
             !quantize_dual_fused(dt, rows, cols, ld, f->block, true) || (rounding_rows == NVFP4_SR && rounding_cols == NVFP4_RTN))

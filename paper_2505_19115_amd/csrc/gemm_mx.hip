@@ -454,6 +454,16 @@ __global__ __launch_bounds__(256) void gemm_nt_fp4_rescale_kernel(GemmArgs P)
 // chunk 2 g + s of the tile: the lane shifts the tile's scale dword right by 16 g once and the
 // instruction's byte select is the compile-time s.
 //
+// An operand in the slab layout (A_SLAB / B_SLAB) brings its scales as slabs too: 256 positions x 4 bytes per K
+// tile, contiguous, so ONE instruction of one wave fetches the scales of a whole K tile (wave 0: A, wave 1: B), they
+// travel with the codes of their tile through four 1 KB stages (which take the place of that operand's part of the
+// first scale buffer), and a lane reads its row's dword at position slab_row(row): 32 consecutive rows are 32
+// different banks.  (Row-major scales lie 16 bytes apart in LDS, so 32 rows share 16 banks and those reads conflict.)
+//
+// Every wave issues the same ten direct-to-LDS instructions per K tile, which the counted waits rely on: 4 + 4
+// codes, one slot for a row-major scale group and one for a scale slab; a slot with nothing to fetch issues a
+// one-request filler.
+//
 // The MFMA's first operand is the B (N-side) tile, so a lane's accumulator holds four consecutive
 // output COLUMNS of one row: the epilogue is one packed convert pair and one 8-byte (bf16) or
 // 16-byte (fp32) store per four outputs.
@@ -463,10 +473,10 @@ constexpr int STAGE = (mx::BM + mx::BN) * ROWB;        // 32 KB of codes
 constexpr int SBUF = (mx::BM + mx::BN) * 16;           // 8 KB: the scales of four K tiles
 constexpr int SCALES0 = NS * STAGE, DUMP0 = SCALES0 + 2 * SBUF;
 constexpr int LDS_BYTES = DUMP0 + 4096;
-constexpr int PER_TILE = 9;  // direct-to-LDS instructions per wave per K tile: 4 + 4 codes, 1 scales or filler
+constexpr int PER_TILE = 10;  // direct-to-LDS instructions per wave per K tile: 4 + 4 codes, 2 scale slots
 }  // namespace mxd
 
-template <int OUT_DT>
+template <int OUT_DT, bool A_SLAB, bool B_SLAB>
 __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
 {
     using namespace mx;
@@ -503,8 +513,8 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
         const int row = (wave * 4 + u) * 16 + (lane >> 2);
         const int c = (lane & 3) ^ ((lane >> 4) & 3);
         // (an operand in the slab layout has all 256 rows of the tile, 64 bytes apart, in slab order)
-        offA[u] = P.a_slab ? (uint32_t)(slab_row(row) * 64 + c * 16) : (uint32_t)((row < mrows ? row : mrows - 1) * Kb + c * 16);
-        offB[u] = P.b_slab ? (uint32_t)(slab_row(row) * 64 + c * 16) : (uint32_t)((row < nrows ? row : nrows - 1) * Kb + c * 16);
+        offA[u] = A_SLAB ? (uint32_t)(slab_row(row) * 64 + c * 16) : (uint32_t)((row < mrows ? row : mrows - 1) * Kb + c * 16);
+        offB[u] = B_SLAB ? (uint32_t)(slab_row(row) * 64 + c * 16) : (uint32_t)((row < nrows ? row : nrows - 1) * Kb + c * 16);
     }
     const int srow = wave * 64 + lane;
     const uint32_t offSA = (uint32_t)((srow < mrows ? srow : mrows - 1) * Ks);
@@ -527,10 +537,12 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(voff), "s"(base) : "memory");
     };
     // codes of K tile kt: tile + kt * step (row-major: 64 bytes further along every row; slabs: the next 16 KB slab)
-    const uint8_t *tileA = P.a_slab ? P.A_codes + (int64_t)ty * nkt * SLAB_CODE_BYTES : P.A_codes + m0 * Kb;
-    const uint8_t *tileB = P.b_slab ? P.B_codes + (int64_t)tx * nkt * SLAB_CODE_BYTES : P.B_codes + n0 * Kb;
-    const int64_t stepA = P.a_slab ? SLAB_CODE_BYTES : ROWB, stepB = P.b_slab ? SLAB_CODE_BYTES : ROWB;
-    const uint8_t *tileSA = P.A_scales + m0 * Ks, *tileSB = P.B_scales + n0 * Ks;
+    const uint8_t *tileA = A_SLAB ? P.A_codes + (int64_t)ty * nkt * SLAB_CODE_BYTES : P.A_codes + m0 * Kb;
+    const uint8_t *tileB = B_SLAB ? P.B_codes + (int64_t)tx * nkt * SLAB_CODE_BYTES : P.B_codes + n0 * Kb;
+    constexpr int64_t stepA = A_SLAB ? SLAB_CODE_BYTES : ROWB, stepB = B_SLAB ? SLAB_CODE_BYTES : ROWB;
+    // scales: the tile's rows in the row-major matrix, or the tile row's scale slabs (one per K tile)
+    const uint8_t *tileSA = A_SLAB ? P.A_scales + (int64_t)ty * nkt * SLAB_MX_SCALE_BYTES : P.A_scales + m0 * Ks;
+    const uint8_t *tileSB = B_SLAB ? P.B_scales + (int64_t)tx * nkt * SLAB_MX_SCALE_BYTES : P.B_scales + n0 * Ks;
     auto dma_codes = [&](int kt) {
         const uint32_t st = (uint32_t)(kt & (NS - 1)) * STAGE;
         const uint8_t *pa = uniform_ptr(tileA + kt * stepA), *pb = uniform_ptr(tileB + kt * stepB);
@@ -543,13 +555,28 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
     // Scale group G = the 16 scale bytes of a row that cover K tiles 4 G .. 4 G + 3; the window of the
     // last group is moved back to end with the row (Ks >= 16), so no load passes the end of a row.
     auto group_start = [&](int G) -> int { return 16 * G + 16 <= Ks ? 16 * G : (int)Ks - 16; };
-    // part 0: this wave's 64 A rows, part 1: its 64 B rows
+    // keeps the number of loads per tile constant (the counted waits rely on it): one request, lands in the dump
+    // (the first bytes of A's codes: a valid address in both layouts)
+    auto dma_filler = [&]() { dma16(dump_dst, 0u, uniform_ptr(tileA)); };
+    // row-major scales, group G.  part 0: this wave's 64 A rows, part 1: its 64 B rows
     auto dma_scales = [&](int G, int part) {
+        if ((part == 0 && A_SLAB) || (part == 1 && B_SLAB)) {
+            dma_filler();
+            return;
+        }
         const uint8_t *base = (part ? tileSB : tileSA) + group_start(G);
         dma16(scale_dst + (G & 1) * SBUF + part * (BM * 16), part ? offSB : offSA, uniform_ptr(base));
     };
-    // keeps the number of loads per tile constant (the counted waits rely on it): one request, lands in the dump
-    auto dma_filler = [&]() { dma16(dump_dst, 0u, uniform_ptr(tileSA)); };
+    // scale slabs of K tile kt (real: kt < nkt): wave 0 fetches A's, wave 1 B's, 16 bytes per lane, into stage
+    // kt % 4 of that operand's part of the first scale buffer; the other waves (and a wave whose operand is
+    // row-major) fill in
+    const uint32_t slab_scale_dst = __builtin_amdgcn_readfirstlane(lds0 + SCALES0 + (wave == 1 ? BM * 16 : 0));
+    const bool slab_loader = __builtin_amdgcn_readfirstlane((wave == 0 && A_SLAB) || (wave == 1 && B_SLAB));
+    auto dma_scale_slab = [&](int kt, bool real) {
+        const bool go = slab_loader && real;
+        const uint8_t *base = go ? (wave == 0 ? tileSA : tileSB) + (int64_t)kt * SLAB_MX_SCALE_BYTES : tileA;
+        dma16(go ? slab_scale_dst + (uint32_t)(kt & (NS - 1)) * 1024 : dump_dst, go ? (uint32_t)lane * 16 : 0u, uniform_ptr(base));
+    };
 
     // ---- LDS -> registers
     struct Frags {
@@ -560,7 +587,17 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
     };
     const int sw = (r >> 2) & 3;
     const int rdA = (wm * 128 + r) * ROWB, rdB = (BM + wn * 128 + r) * ROWB;
-    const int rdS = SCALES0 + (wm * 128 + r) * 16, rdT = SCALES0 + (BM + wn * 128 + r) * 16;
+    // scale dword of fragment i (rows 32 i + r of the wave's part): row-major image [row][16 bytes], or the slab
+    // image [position][4 bytes] with the row at position slab_row(row) (for row 128 w + 32 i + r that is
+    // 128 w + 64 (i / 2) + 8 (r % 8) + 4 (i % 2) + r / 8: a lane part plus a constant per fragment)
+    const int rdS = SCALES0 + (A_SLAB ? slab_row(wm * 128 + r) * 4 : (wm * 128 + r) * 16);
+    const int rdT = SCALES0 + BM * 16 + (B_SLAB ? slab_row(wn * 128 + r) * 4 : (wn * 128 + r) * 16);
+    auto frag_off = [](bool slab, int i) -> int { return slab ? 256 * (i >> 1) + 16 * (i & 1) : 512 * i; };
+    // where in the scale area the dwords of K tile kt start
+    auto tile_off = [&](bool slab, int kt) -> int {
+        const int G = kt >> 2;
+        return slab ? (kt & (NS - 1)) * 1024 : (G & 1) * SBUF + (4 * kt - group_start(G));
+    };
     const int sh = 16 * g;
     // fragment i of both operands (rows 32 i + r of the wave's A and B parts) for MFMA step s of tile kt
     auto load_frag = [&](int kt, int s, Frags &F, int i) {
@@ -570,10 +607,8 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
     };
     // raw scale dwords of a tile (all four E8M0 bytes of the row); shifted into place when the tile starts
     auto load_scale = [&](int kt, Scales &R, int i) {
-        const int G = kt >> 2;
-        const uint8_t *p = lds + (G & 1) * SBUF + (4 * kt - group_start(G));
-        R.a[i] = *reinterpret_cast<const uint32_t *>(p + rdS + 512 * i);
-        R.b[i] = *reinterpret_cast<const uint32_t *>(p + rdT + 512 * i);
+        R.a[i] = *reinterpret_cast<const uint32_t *>(lds + tile_off(A_SLAB, kt) + rdS + frag_off(A_SLAB, i));
+        R.b[i] = *reinterpret_cast<const uint32_t *>(lds + tile_off(B_SLAB, kt) + rdT + frag_off(B_SLAB, i));
     };
     auto shift_scales = [&](const Scales &R, Scales &S) {
 #pragma unroll
@@ -599,15 +634,18 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
 
     Frags F0, F1;
     Scales S, R;
-    // nine loads per batch, three batches: scale group 0 rides with tile 0
+    // ten loads per batch, three batches: scale group 0 rides with tile 0 (eleven loads)
     dma_scales(0, 0);
     dma_scales(0, 1);
     dma_codes(0);
+    dma_scale_slab(0, true);
     dma_codes(1);
     dma_filler();
+    dma_scale_slab(1, true);
     dma_codes(2);
     dma_filler();
-    NVFP4_MXD_WAIT(2 * PER_TILE)  // batch 0 (ten loads) has landed
+    dma_scale_slab(2, true);
+    NVFP4_MXD_WAIT(2 * PER_TILE)  // batch 0 has landed
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -630,8 +668,8 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
         const bool more = kt + 3 < nkt;
         const uint32_t lanes = more ? ~0u : 0u;
         const uint32_t dst3 = code_dst + (uint32_t)((kt + 3) & (NS - 1)) * STAGE;
-        const uint8_t *pa = uniform_ptr(more ? tileA + (kt + 3) * stepA : tileSA);
-        const uint8_t *pb = uniform_ptr(more ? tileB + (kt + 3) * stepB : tileSA);
+        const uint8_t *pa = uniform_ptr(more ? tileA + (kt + 3) * stepA : tileA);
+        const uint8_t *pb = uniform_ptr(more ? tileB + (kt + 3) * stepB : tileA);
         shift_scales(R, S);
         NVFP4_MXD_FENCE
         // step 0: MFMAs 0-7 each shadow one fragment read of step 1 (B fragments first: every row of
@@ -654,10 +692,13 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
             }
         }
         {
+            // slot of the row-major scale groups: halves of the next group ride with tiles 0 and 1 of this one
             const int Gn = (kt >> 2) + 1, part = kt & 1;
-            const bool real = (kt & 3) < 2 && 4 * Gn < nkt;
-            const uint8_t *base = real ? (part ? tileSB : tileSA) + group_start(Gn) : tileSA;
+            const bool real = (kt & 3) < 2 && 4 * Gn < nkt && !(part ? B_SLAB : A_SLAB);
+            const uint8_t *base = real ? (part ? tileSB : tileSA) + group_start(Gn) : tileA;
             dma16(real ? scale_dst + (Gn & 1) * SBUF + part * (BM * 16) : dump_dst, real ? (part ? offSB : offSA) : 0u, uniform_ptr(base));
+            // slot of the scale slabs: those of tile kt + 3, next to its codes
+            dma_scale_slab(kt + 3, more);
         }
         NVFP4_MXD_WAIT(2 * PER_TILE)
         __syncthreads();
@@ -665,15 +706,14 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
         // step 1: MFMAs 0-7 shadow the scale reads of tile kt + 1, MFMAs 8-15 its first fragments
         {
             const uint8_t *p = lds + ((kt + 1) & (NS - 1)) * STAGE + (((2 * g) ^ sw) << 4);
-            const int G = (kt + 1) >> 2;
-            const uint8_t *q = lds + (G & 1) * SBUF + (4 * (kt + 1) - group_start(G));
+            const uint8_t *qa = lds + tile_off(A_SLAB, kt + 1) + rdS, *qb = lds + tile_off(B_SLAB, kt + 1) + rdT;
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
                 NVFP4_MXD_MMA(F1, S, 1, j >> 2, j & 3)
                 if (j < 4)
-                    R.a[j] = *reinterpret_cast<const uint32_t *>(q + rdS + 512 * j);
+                    R.a[j] = *reinterpret_cast<const uint32_t *>(qa + frag_off(A_SLAB, j));
                 else if (j < 8)
-                    R.b[j - 4] = *reinterpret_cast<const uint32_t *>(q + rdT + 512 * (j - 4));
+                    R.b[j - 4] = *reinterpret_cast<const uint32_t *>(qb + frag_off(B_SLAB, j - 4));
                 else if (j < 12)
                     F0.b[j - 8] = *reinterpret_cast<const uint4 *>(p + rdB + 32 * (j - 8) * ROWB);
                 else
@@ -693,20 +733,31 @@ __global__ __launch_bounds__(256) void gemm_nt_mxfp4_dma_kernel(GemmArgs P)
     mx_store_tile<OUT_DT>(P, acc, m0, n0, lane, wave, lds);
 }
 
-static void launch_mx_dma(const GemmArgs &P, int out_dt, hipStream_t st)
+template <int OUT_DT, bool A_SLAB, bool B_SLAB>
+static void launch_mx_dma_as(const GemmArgs &P, hipStream_t st)
 {
     const unsigned ntiles = (unsigned)(((P.N + mx::BN - 1) / mx::BN) * ((P.M + mx::BM - 1) / mx::BM));
-    if (out_dt == NVFP4_F32) {
-        auto k = gemm_nt_mxfp4_dma_kernel<NVFP4_F32>;
-        static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, mxd::LDS_BYTES), true);
-        (void)once;
-        hipLaunchKernelGGL(k, dim3(ntiles), dim3(256), mxd::LDS_BYTES, st, P);
-    } else {
-        auto k = gemm_nt_mxfp4_dma_kernel<NVFP4_BF16>;
-        static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, mxd::LDS_BYTES), true);
-        (void)once;
-        hipLaunchKernelGGL(k, dim3(ntiles), dim3(256), mxd::LDS_BYTES, st, P);
-    }
+    auto k = gemm_nt_mxfp4_dma_kernel<OUT_DT, A_SLAB, B_SLAB>;
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, mxd::LDS_BYTES), true);
+    (void)once;
+    hipLaunchKernelGGL(k, dim3(ntiles), dim3(256), mxd::LDS_BYTES, st, P);
+}
+
+template <int OUT_DT>
+static void launch_mx_dma_out(const GemmArgs &P, hipStream_t st)
+{
+    if (P.a_slab && P.b_slab) launch_mx_dma_as<OUT_DT, true, true>(P, st);
+    else if (P.a_slab) launch_mx_dma_as<OUT_DT, true, false>(P, st);
+    else if (P.b_slab) launch_mx_dma_as<OUT_DT, false, true>(P, st);
+    else launch_mx_dma_as<OUT_DT, false, false>(P, st);
+}
+
+static void launch_mx_dma(const GemmArgs &P, int out_dt, hipStream_t st)
+{
+    if (out_dt == NVFP4_F32)
+        launch_mx_dma_out<NVFP4_F32>(P, st);
+    else
+        launch_mx_dma_out<NVFP4_BF16>(P, st);
 }
 
 static void launch_mx_fallback(const GemmArgs &P, int out_dt, hipStream_t st)

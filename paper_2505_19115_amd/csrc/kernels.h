@@ -68,9 +68,10 @@ struct DualArgs {
 // at position slab_row(r), which swaps the two 3-bit fields of r below bit 6: the column-blocked quantizer holds
 // rows 8 cx + j (lane group cx, column j of the lane) and with this order each of its store instructions writes
 // 512 contiguous bytes.  The scales follow the same scheme with 8 bytes per row (slabs of 2 KB).
-// MXFP4 operands (block 32, E8M0) use the same slabs for their codes and keep their scales row-major: the FP4 GEMM
-// fetches 16 scale bytes = four K tiles of a row at a time.
-constexpr int64_t SLAB_ROWS = 256, SLAB_K = 128, SLAB_CODE_BYTES = 16384, SLAB_SCALE_BYTES = 2048;
+// MXFP4 operands (block 32, E8M0) use the same slabs for their codes, and scale slabs of 256 positions x 4 bytes
+// (the four E8M0 bytes of a row's K tile; 1 KB, same position rule): one direct-to-LDS instruction of the FP4 GEMM
+// fetches a whole one, and its image in LDS is read 4 bytes per lane at a 4-byte stride, free of bank conflicts.
+constexpr int64_t SLAB_ROWS = 256, SLAB_K = 128, SLAB_CODE_BYTES = 16384, SLAB_SCALE_BYTES = 2048, SLAB_MX_SCALE_BYTES = 1024;
 __host__ __device__ inline int slab_row(int r) { return (r & ~63) | ((r & 7) << 3) | ((r >> 3) & 7); }
 inline int64_t slab_rows_padded(int64_t rows) { return (rows + SLAB_ROWS - 1) / SLAB_ROWS * SLAB_ROWS; }
 

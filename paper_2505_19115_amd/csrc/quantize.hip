@@ -701,7 +701,8 @@ __device__ __forceinline__ void col_rtn_hw(Chunk<DT> (&v)[16], float (&q)[8][16 
 }
 
 // Where a lane's column-blocked outputs go in the slab layout: column c of the lane stores its 8 code bytes at
-// codes + 512 c and its scale byte at scales + 64 c (the lane index is folded into the two pointers).
+// codes + 512 c and its scale byte at scales + 64 c (blocks of 16) or, from the lowest of the eight stacked lanes,
+// the column's four scale bytes at scales + 32 c (blocks of 32); the lane index is folded into the two pointers.
 struct ColSlab {
     uint8_t *codes, *scales;
 };
@@ -876,19 +877,18 @@ __device__ __forceinline__ void cols_tile(const QuantArgs &P, Chunk<DT> (&v)[16]
     }
 
     if (RPL == 16 && slab != nullptr) {
-        // slab layout (the caller guarantees a lane tile entirely inside the tensor or entirely outside): a store
-        // instruction of the wave writes 512 contiguous code bytes and, for blocks of 16, 64 contiguous scale
-        // bytes; wider blocks keep their scales row-major
+        // slab layout (the caller guarantees a lane tile entirely inside the tensor or entirely outside, blocks of
+        // 16 or 32): a store instruction of the wave writes 512 contiguous code bytes and 64 contiguous scale bytes
+        // (blocks of 16) or 32 contiguous scale bytes from its eight owner lanes (blocks of 32)
         if (ncol == 8) {
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
                 store8_stream(slab->codes + 512 * c, words[c][0], words[c][1]);
                 if (B == 16) {
                     slab->scales[64 * c] = (uint8_t)sbytes[c][0];
-                } else if (GATHER && wide) {
-                    if (owner) *reinterpret_cast<uint32_t *>(P.scales + (col0 + c) * nblk + row0 / B) = sw[c];
-                } else if (lv % LPB == 0) {
-                    P.scales[(col0 + c) * nblk + row0 / B] = (uint8_t)sbytes[c][0];
+                } else if (GATHER) {
+                    // blocks of 32: the lowest of the eight stacked lanes holds the column's four bytes of this K tile
+                    if (owner) *reinterpret_cast<uint32_t *>(slab->scales + 32 * c) = sw[c];
                 }
             }
         }
@@ -1076,7 +1076,9 @@ __device__ __forceinline__ void dual_tile(const DualArgs &D, Chunk<DT> (&v)[16],
     if (D.slab_c) {
         const int64_t slab = (int64_t)tx * (P.rows / SLAB_K) + ty;
         cs.codes = P.codes + slab * SLAB_CODE_BYTES + wave * 4096 + lane * 8;
-        cs.scales = P.scales + slab * SLAB_SCALE_BYTES + wave * 512 + lane;  // (used for blocks of 16 only)
+        // (tile column 64 wave + 8 lh + c sits at position 64 wave + 8 c + lh)
+        cs.scales = B == 16 ? P.scales + slab * SLAB_SCALE_BYTES + wave * 512 + lane
+                            : P.scales + slab * SLAB_MX_SCALE_BYTES + wave * 256 + lh * 4;
     }
     cols_tile<DT, B, SF, RND_C, true, true, 8>(P, v, g, k, row0, col0, inside ? 8 : 0, lv, D.slab_c ? &cs : nullptr);
 
@@ -1096,16 +1098,23 @@ __device__ __forceinline__ void dual_tile(const DualArgs &D, Chunk<DT> (&v)[16],
                 __builtin_nontemporal_store(o, reinterpret_cast<u32x4_t *>(D.codes_r + (slab0 + (c >> 2)) * SLAB_CODE_BYTES + (half + q) * 64 + (c & 3) * 16));
             }
         }
-        if (B == 16 && threadIdx.x < G::WG_ROWS) {
+        if (threadIdx.x < G::WG_ROWS) {
             const int q = threadIdx.x, R = slab_row(q);
             if (wrow0 + R < P.rows) {
                 const uint32_t *src = reinterpret_cast<const uint32_t *>(&lds_scales[R * 16]);
-                uint8_t *dst = D.scales_r + slab0 * SLAB_SCALE_BYTES + (half + q) * 8;
-                store8_stream(dst, src[0], src[1]);
-                if (wcol0 + 128 < P.cols) store8_stream(dst + SLAB_SCALE_BYTES, src[2], src[3]);
+                if (B == 16) {
+                    uint8_t *dst = D.scales_r + slab0 * SLAB_SCALE_BYTES + (half + q) * 8;
+                    store8_stream(dst, src[0], src[1]);
+                    if (wcol0 + 128 < P.cols) store8_stream(dst + SLAB_SCALE_BYTES, src[2], src[3]);
+                } else {
+                    // blocks of 32: four bytes per row and K tile
+                    uint8_t *dst = D.scales_r + slab0 * SLAB_MX_SCALE_BYTES + (half + q) * 4;
+                    store4_stream(dst, src[0]);
+                    if (wcol0 + 128 < P.cols) store4_stream(dst + SLAB_MX_SCALE_BYTES, src[1]);
+                }
             }
         }
-        if (B == 16) return;
+        return;
     }
     const int64_t cpr = P.cols >> 1;
     const bool wide = (cpr & 15) == 0;  // rows of the code matrix are 16-byte aligned

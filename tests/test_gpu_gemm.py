@@ -785,11 +785,10 @@ def test_slab_outputs_of_the_dual_quantizer_and_slab_gemm(rounding, fmt_name):
     assert cr.numel() == 12 * 25 * 16384 and cc.numel() == 13 * 23 * 16384
     assert np.array_equal(_slab_to_plain(to_np(cr), rows, cols, 64), to_np(pr))
     assert np.array_equal(_slab_to_plain(to_np(cc), cols, rows, 64), to_np(pc))
-    if fmt.block == 16:
-        assert np.array_equal(_slab_to_plain(to_np(sr), rows, cols, 8), to_np(psr))
-        assert np.array_equal(_slab_to_plain(to_np(sc), cols, rows, 8), to_np(psc))
-    else:  # MXFP4: only the codes move; the scales stay row-major
-        assert torch.equal(sr, psr) and torch.equal(sc, psc)
+    per_row = 128 // fmt.block   # scale bytes per row and K tile: 8 (NVFP4) or 4 (MXFP4)
+    assert sr.numel() == 12 * 25 * 256 * per_row and sc.numel() == 13 * 23 * 256 * per_row
+    assert np.array_equal(_slab_to_plain(to_np(sr), rows, cols, per_row), to_np(psr))
+    assert np.array_equal(_slab_to_plain(to_np(sc), cols, rows, per_row), to_np(psc))
     assert float(g) == float(pg)
     xc = x.cpu()
     assert_quant_equal((pr, psr, pg), oracle.quantize(xc, 1, rr, 11, ofmt(fmt)), "rows side")

@@ -108,8 +108,8 @@ def test_fused_swiglu_slab_outputs_and_prequantized_backward(fmt_name):
     assert_quant_equal(pU.cols, oracle.quantize(oU, 0, oracle.SR, su + 1, of), "dU cols")
     assert np.array_equal(_slab_to_plain(to_np(dGq.codes_rows), T, F, 64), to_np(pG.codes_rows))
     assert np.array_equal(_slab_to_plain(to_np(dUq.codes_cols), F, T, 64), to_np(pU.codes_cols))
-    if fmt.block == 16:
-        assert np.array_equal(_slab_to_plain(to_np(dGq.scales_cols), F, T, 8), to_np(pG.scales_cols))
+    assert np.array_equal(_slab_to_plain(to_np(dGq.scales_cols), F, T, 128 // fmt.block), to_np(pG.scales_cols))
+    assert np.array_equal(_slab_to_plain(to_np(dUq.scales_rows), T, F, 128 // fmt.block), to_np(pU.scales_rows))
     dG_t = _as_torch(oG, torch.bfloat16).cuda()
     want = nv.linear_bwd(dG_t, X, Wg, sg, fmt, out_dtype=torch.bfloat16)
     for q, what in ((dGq, "slabs"), (pG, "row-major")):
