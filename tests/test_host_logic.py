@@ -178,7 +178,7 @@ def test_quantize_dual_argument_errors():
     assert dual(rnd=2) == nv.EINVAL
     assert dual(k2=5) == nv.EINVAL
     assert dual(flags=8) == nv.EINVAL
-    # slab outputs: NVFP4 only, through the one-pass kernel only, whole K tiles of 128 only
+    # slab outputs: NVFP4 and MXFP4 only, through the one-pass kernel only, whole K tiles of 128 only
     assert dual(flags=nv.SLAB_ROWS) == nv.ESHAPE                      # cols = 64
     assert dual(flags=nv.SLAB_COLS, cols=128, ld=128) == nv.ESHAPE    # rows = 64
     assert dual(flags=nv.SLAB_ROWS, fmt=nv.Format(32, nv.SCALE_E4M3, 1), rows=128, cols=128, ld=128) == nv.EUNSUPPORTED
@@ -221,6 +221,8 @@ def test_gemm_and_linear_argument_errors():
     assert nv.lib.nvfp4_slab_codes_bytes(256, 128) == 16384 and nv.lib.nvfp4_slab_scales_bytes(256, 128) == 2048
     assert nv.lib.nvfp4_slab_codes_bytes(257, 256) == 2 * 2 * 16384 and nv.lib.nvfp4_slab_scales_bytes(1, 128) == 2048
     assert nv.lib.nvfp4_slab_codes_bytes(0, 128) == 0
+    # (MXFP4: 4 scale bytes per row and K tile, half of what the query states)
+    assert nv.slab_scales_bytes(257, 256, nv.MXFP4) == 2 * 2 * 1024 and nv.slab_scales_bytes(257, 256) == 2 * 2 * 2048
     fw = lambda **k: nv.lib.nvfp4_linear_fwd(k.get("X", FAKE), FAKE, FAKE, k.get("M", 64), 64, k.get("K", 64), nv.BF16,
                                              nv.F32, C.byref(f), k.get("ws", FAKE), k.get("wsb", 1 << 30), None, None,
                                              k.get("saved"), 0)
